@@ -1,0 +1,186 @@
+/*
+ * xrl.h -- C ABI of the MI355X state encoder for graph-rewrite reinforcement learning
+ * (X-RLflow, arXiv 2304.14698).
+ *
+ * A state is the current computation graph plus every candidate graph produced by an applicable
+ * rewrite rule; the action picks one candidate or No-Op (Section 3.3.2). The library batches all
+ * graphs of one or many states into one meta-graph, embeds every graph with the three-stage GNN
+ * of Section 3.4 and evaluates the policy head (masked categorical over slots) and the value head
+ * of Section 3.3.2, forward and backward (one back-propagation through heads and GNN, Section
+ * 3.3.4).
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, borrowed for the duration of the call only.
+ *   - "device" pointers are GPU memory owned by the caller (any HIP allocation, e.g. a torch
+ *     tensor's data_ptr); the library never frees or resizes them.
+ *   - Every GPU call is enqueued on the HIP stream given to xrl_create and returns without
+ *     synchronising; outputs are valid once that stream has reached the call.
+ *   - Every function returns XRL_OK (0) or a negative xrl_status; it never aborts or throws. After
+ *     an error no output may be trusted. xrl_last_error() gives a message for the calling thread.
+ *   - All matrices are row-major; an affine layer is y = x W + b with W stored [in, out].
+ */
+#ifndef XRL_H
+#define XRL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  XRL_OK = 0,
+  XRL_ERR_NULL = -1,        /* a required pointer is NULL */
+  XRL_ERR_SHAPE = -2,       /* negative count, non-monotone or inconsistent ptr array */
+  XRL_ERR_INDEX = -3,       /* edge endpoint outside its graph, op id outside [0, n_op_types) */
+  XRL_ERR_VALUE = -4,       /* NaN or Inf in a feature or weight */
+  XRL_ERR_MASK = -5,        /* a state's No-Op slot (its first graph) is masked out */
+  XRL_ERR_STATE = -6,       /* call order: batch not uploaded, backward without saved forward */
+  XRL_ERR_UNSUPPORTED = -7, /* model dimensions the kernels do not cover */
+  XRL_ERR_OOM = -8,         /* host or device allocation failed */
+  XRL_ERR_HIP = -9          /* a HIP runtime call failed (no usable GPU, launch error) */
+} xrl_status;
+
+enum { XRL_READOUT_SUM = 0, XRL_READOUT_MEAN = 1 };
+enum { XRL_PREC_FP32 = 0,      /* fp32 operands, fp32 accumulate                              */
+       XRL_PREC_BF16 = 1 };    /* bf16 MFMA operands (weights, stored activations), fp32
+                                  accumulate, bias, ReLU, segment sums, readout and heads     */
+
+/* Model dimensions. Encoder (Section 3.4): node-update layer, `rounds` message-passing layers
+ * (k = 5 in the paper's appendix), global-update layer; every learned transform is an MLP of
+ * `mlp_layers` affine layers, ReLU after each. Heads (Section 3.3.2): hidden sizes head_hidden
+ * ([256, 64] in the appendix) with ReLU, then a linear output of width 1. */
+typedef struct xrl_model_desc {
+  int32_t n_op_types;     /* T: width of the one-hot operator attribute                       */
+  int32_t n_node_dense;   /* extra dense node attributes after the one-hot (may be 0)         */
+  int32_t d_edge;         /* edge attribute width (tensor-shape attributes)                    */
+  int32_t d_global;       /* global attribute width (initialised to 0 by the paper)           */
+  int32_t hidden;         /* H: 64, 128 or 256                                                */
+  int32_t rounds;         /* number of message-passing layers, >= 0                           */
+  int32_t mlp_layers;     /* affine layers per encoder transform; the GPU path supports 2     */
+  int32_t head_hidden[2];
+  int32_t readout;        /* XRL_READOUT_SUM (the paper's sum) or XRL_READOUT_MEAN            */
+  int32_t precision;      /* XRL_PREC_FP32 or XRL_PREC_BF16                                   */
+} xrl_model_desc;
+
+/* One or many states, all host memory. Graphs are listed state by state; the first graph of a
+ * state is the current graph and doubles as the No-Op slot, the others are its candidates
+ * (Section 3.3.2). Edge endpoints are node indices local to the edge's graph; edges may come in
+ * any order; multi-edges and cycles are accepted. */
+typedef struct xrl_state_desc {
+  int32_t n_states;
+  const int32_t *state_graph_ptr; /* [S+1] graph range of each state, starts at 0             */
+  const int32_t *graph_node_ptr;  /* [G+1] node range of each graph, starts at 0              */
+  const int32_t *graph_edge_ptr;  /* [G+1] edge range of each graph, starts at 0              */
+  const int32_t *node_op;         /* [N] operator id                                          */
+  const float *node_dense;        /* [N, n_node_dense] (NULL allowed if n_node_dense == 0)    */
+  const int32_t *edge_src;        /* [E] sender, local index                                  */
+  const int32_t *edge_dst;        /* [E] receiver, local index                                */
+  const float *edge_feat;         /* [E, d_edge]                                              */
+  const float *graph_global;      /* [G, d_global] or NULL for zeros                          */
+  const uint8_t *slot_mask;       /* [G] 1 = slot may be chosen; each state's first must be 1 */
+} xrl_state_desc;
+
+/* Read-only view of a packed batch's host arrays (valid until xrl_batch_free). Edges are stored
+ * sorted by global receiver id, ties in input order ("receiver order"). */
+typedef struct xrl_packed_view {
+  int64_t S, G, N, E;
+  const int32_t *state_graph_ptr; /* [S+1]                                                    */
+  const int32_t *graph_node_ptr;  /* [G+1] global node offsets                                */
+  const int32_t *in_ptr;          /* [N+1] receiver-order edge range of each receiver         */
+  const int32_t *in_src;          /* [E] global sender id, receiver order                     */
+  const int32_t *in_dst;          /* [E] global receiver id, receiver order (non-decreasing)  */
+  const int32_t *in_eid;          /* [E] index of the edge in the caller's edge arrays        */
+  const int32_t *out_ptr;         /* [N+1] out-edge range of each sender                      */
+  const int32_t *out_pos;         /* [E] receiver-order position of each out-edge, by sender  */
+  const int32_t *node_graph;      /* [N] graph id of each node                                */
+  const float *edge_feat;         /* [E, d_edge] in receiver order                            */
+} xrl_packed_view;
+
+typedef struct xrl_ctx xrl_ctx;     /* device weights + workspaces, bound to one HIP stream    */
+typedef struct xrl_batch xrl_batch; /* one packed meta-batch (host copy + device copy)         */
+
+/* ---- weights -------------------------------------------------------------------------------
+ * One flat fp32 vector. Tensor order: embed MLP (input [sum of incoming edge attrs | one-hot op
+ * | dense attrs], the node-update layer of Section 3.4); per round r: edge MLP (input [h_sender |
+ * h_receiver | edge attrs]) then node MLP (input [h | received sum]) (message-passing layers of
+ * Section 3.4); readout MLP (input [sum or mean of node states | global attrs], the global-update
+ * layer); policy head; value head (Section 3.3.2). Each MLP lists, per layer, W [in, out] then
+ * b [out]. */
+int64_t xrl_weight_count(const xrl_model_desc *model);        /* total floats, <0 on error     */
+int32_t xrl_weight_tensor_count(const xrl_model_desc *model); /* number of tensors, <0 on error */
+/* Tensor `index`: name (e.g. "edge3.W0") copied into name[name_cap]; vectors report cols = 0. */
+int xrl_weight_tensor(const xrl_model_desc *model, int32_t index, char *name, size_t name_cap,
+                      int64_t *offset, int64_t *rows, int64_t *cols);
+
+/* ---- packing (host only; never touches the GPU) ---------------------------------------------
+ * Batches current + candidate graphs into one meta-graph with its slot mask (Section 3.3.2):
+ * validates, converts endpoints to global node ids, sorts edges by receiver (stable) and builds
+ * the sender-side index. Errors: NULL, SHAPE, INDEX, VALUE (non-finite attribute), MASK. */
+int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *state, xrl_batch **out);
+int xrl_batch_dims(const xrl_batch *b, int64_t *S, int64_t *G, int64_t *N, int64_t *E);
+int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *view);
+int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is accepted          */
+
+/* ---- context --------------------------------------------------------------------------------
+ * weights_host: xrl_weight_count floats. hip_stream: a hipStream_t (NULL = default stream).
+ * Errors: NULL, UNSUPPORTED (hidden not in {64,128,256}, mlp_layers != 2, ...), VALUE, HIP, OOM. */
+int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip_stream,
+               xrl_ctx **out);
+int xrl_set_weights(xrl_ctx *ctx, const float *weights_host);
+int xrl_destroy(xrl_ctx *ctx);
+/* Copies the packed arrays to the GPU (async on the ctx stream). Must precede the calls below. */
+int xrl_batch_upload(xrl_ctx *ctx, xrl_batch *b);
+
+/* ---- forward --------------------------------------------------------------------------------
+ * xrl_encode: the GNN of Section 3.4 on every graph of the batch. d_emb: device [G, hidden]
+ * fp32, the graph representations. save_for_backward != 0 keeps the per-round node states and
+ * received sums inside ctx for xrl_encode_backward (overwritten by the next xrl_encode). */
+int xrl_encode(xrl_ctx *ctx, const xrl_batch *b, float *d_emb, int save_for_backward);
+
+/* xrl_policy_value: heads of Section 3.3.2 on the embeddings. Per slot j: logit = policy MLP of
+ * emb[j]; per state, over its valid slots only (invalid-action masking): d_logp [G] = log
+ * softmax (-inf at masked slots), d_entropy [S], d_action [S] = slot index inside the state of
+ * the largest valid logit, lowest index on ties (0 = No-Op), d_value [S] = value MLP of the mean
+ * embedding of the valid slots. All device pointers; d_logit [G] may be NULL. */
+int xrl_policy_value(xrl_ctx *ctx, const xrl_batch *b, const float *d_emb, float *d_logp,
+                     float *d_value, float *d_entropy, int32_t *d_action, float *d_logit);
+
+/* ---- backward (Section 3.3.4: one back-propagation through heads and GNN) -------------------
+ * For a scalar J with dJ/dlogp = d_dlogp [G] (entries at masked slots are ignored), dJ/dvalue =
+ * d_dvalue [S], dJ/dentropy = d_dentropy [S]:
+ * xrl_policy_value_backward writes d_demb [G, hidden] = dJ/demb (exactly 0 at masked slots) and
+ * ADDS the head weight gradients into d_dweights [xrl_weight_count] fp32 (flat layout above).
+ * xrl_encode_backward ADDS the encoder weight gradients for upstream d_demb into d_dweights; it
+ * needs the batch's last xrl_encode to have been called with save_for_backward != 0 (else STATE).
+ * Results are run-to-run deterministic (no floating-point atomics). */
+int xrl_policy_value_backward(xrl_ctx *ctx, const xrl_batch *b, const float *d_emb,
+                              const float *d_dlogp, const float *d_dvalue,
+                              const float *d_dentropy, float *d_demb, float *d_dweights);
+int xrl_encode_backward(xrl_ctx *ctx, const xrl_batch *b, const float *d_demb, float *d_dweights);
+
+/* ---- building blocks exposed for measurement and per-step checks ----------------------------
+ * xrl_segment_sum: out[i, :] = sum of values[r, :] over rows r in [d_ptr[i], d_ptr[i+1]) -- the
+ * receiver-side aggregation of Section 3.4's first two equations on receiver-ordered rows, and
+ * the per-graph sum of its third. d_values: device [n_rows, width] fp32; d_ptr: device [n_seg+1]
+ * int32, non-decreasing, d_ptr[0] = 0, d_ptr[n_seg] = n_rows; d_out: device [n_seg, width] fp32.
+ * width must be a multiple of 4 and at most 256. */
+int xrl_segment_sum(xrl_ctx *ctx, const float *d_values, const int32_t *d_ptr, int64_t n_rows,
+                    int64_t n_seg, int32_t width, float *d_out);
+
+/* Copies one saved activation of the last xrl_encode(save_for_backward=1) into d_out as fp32:
+ * what = "a0" [N, d_edge] (sum of incoming edge attrs), "h" [N, hidden] (node states after the
+ * node-update layer for round = 0, after message-passing round r for round = r), "agg" [N,
+ * hidden] (received sums of round r >= 1; rows of receivers without in-edges are 0), "pool"
+ * [G, hidden] (per-graph sum or mean). */
+int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32_t round,
+                       float *d_out);
+
+const char *xrl_last_error(void);
+const char *xrl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XRL_H */

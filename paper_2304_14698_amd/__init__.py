@@ -1,0 +1,280 @@
+"""Python binding of libxrl (see include/xrl.h): argument marshalling only.
+
+Every step of the path runs inside the HIP library; torch is used for device buffers and the
+stream handle. There is no CPU fallback: if the library is missing, load_library() raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxrl.so")
+_lib = None
+
+PRECISION = {"fp32": 0, "bf16": 1}
+READOUT = {"sum": 0, "mean": 1}
+
+
+class XrlError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"xrl error {code}: {msg}")
+        self.code = code
+
+
+ERR = dict(NULL=-1, SHAPE=-2, INDEX=-3, VALUE=-4, MASK=-5, STATE=-6, UNSUPPORTED=-7, OOM=-8, HIP=-9)
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("n_op_types", C.c_int32), ("n_node_dense", C.c_int32), ("d_edge", C.c_int32),
+                ("d_global", C.c_int32), ("hidden", C.c_int32), ("rounds", C.c_int32),
+                ("mlp_layers", C.c_int32), ("head_hidden", C.c_int32 * 2),
+                ("readout", C.c_int32), ("precision", C.c_int32)]
+
+
+class StateDesc(C.Structure):
+    _fields_ = [("n_states", C.c_int32),
+                ("state_graph_ptr", C.c_void_p), ("graph_node_ptr", C.c_void_p),
+                ("graph_edge_ptr", C.c_void_p), ("node_op", C.c_void_p),
+                ("node_dense", C.c_void_p), ("edge_src", C.c_void_p), ("edge_dst", C.c_void_p),
+                ("edge_feat", C.c_void_p), ("graph_global", C.c_void_p), ("slot_mask", C.c_void_p)]
+
+
+class PackedView(C.Structure):
+    _fields_ = [("S", C.c_int64), ("G", C.c_int64), ("N", C.c_int64), ("E", C.c_int64),
+                ("state_graph_ptr", C.c_void_p), ("graph_node_ptr", C.c_void_p),
+                ("in_ptr", C.c_void_p), ("in_src", C.c_void_p), ("in_dst", C.c_void_p),
+                ("in_eid", C.c_void_p), ("out_ptr", C.c_void_p), ("out_pos", C.c_void_p),
+                ("node_graph", C.c_void_p), ("edge_feat", C.c_void_p)]
+
+
+EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
+           "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
+           "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
+           "xrl_policy_value_backward", "xrl_encode_backward", "xrl_segment_sum",
+           "xrl_get_activation", "xrl_last_error", "xrl_version"]
+
+
+def load_library():
+    """Loads libxrl.so (built by __graft_entry__.build()); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise OSError(f"{LIB_PATH} not found: run `python __graft_entry__.py` to build it")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.xrl_weight_count.restype = i64
+    lib.xrl_weight_count.argtypes = [C.POINTER(ModelDesc)]
+    lib.xrl_weight_tensor_count.restype = i32
+    lib.xrl_weight_tensor_count.argtypes = [C.POINTER(ModelDesc)]
+    lib.xrl_weight_tensor.argtypes = [C.POINTER(ModelDesc), i32, C.c_char_p, C.c_size_t,
+                                      C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.xrl_pack_state.argtypes = [C.POINTER(ModelDesc), C.POINTER(StateDesc), C.POINTER(vp)]
+    lib.xrl_batch_dims.argtypes = [vp] + [C.POINTER(i64)] * 4
+    lib.xrl_batch_host_view.argtypes = [vp, C.POINTER(PackedView)]
+    lib.xrl_batch_free.argtypes = [vp]
+    lib.xrl_create.argtypes = [C.POINTER(ModelDesc), vp, vp, C.POINTER(vp)]
+    lib.xrl_set_weights.argtypes = [vp, vp]
+    lib.xrl_destroy.argtypes = [vp]
+    lib.xrl_batch_upload.argtypes = [vp, vp]
+    lib.xrl_encode.argtypes = [vp, vp, vp, C.c_int]
+    lib.xrl_policy_value.argtypes = [vp] * 8
+    lib.xrl_policy_value_backward.argtypes = [vp] * 8
+    lib.xrl_encode_backward.argtypes = [vp] * 4
+    lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+    lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
+    lib.xrl_last_error.restype = C.c_char_p
+    lib.xrl_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc < 0:
+        raise XrlError(int(rc), load_library().xrl_last_error().decode())
+    return rc
+
+
+def model_desc(model):
+    hh = model.get("head_hidden", (256, 64))
+    prec, ro = model.get("precision", "fp32"), model.get("readout", "sum")
+    return ModelDesc(model["n_op_types"], model["n_node_dense"], model["d_edge"], model["d_global"],
+                     model["hidden"], model["rounds"], model.get("mlp_layers", 2),
+                     (C.c_int32 * 2)(int(hh[0]), int(hh[1])),
+                     READOUT[ro] if isinstance(ro, str) else int(ro),
+                     PRECISION[prec] if isinstance(prec, str) else int(prec))
+
+
+def weight_count(model):
+    return _check(load_library().xrl_weight_count(C.byref(model_desc(model))))
+
+
+def weight_layout(model):
+    """[(name, shape)] in flat-vector order, as the library lays the weights out."""
+    lib, md = load_library(), model_desc(model)
+    n = _check(lib.xrl_weight_tensor_count(C.byref(md)))
+    out, expect = [], 0
+    for i in range(n):
+        name = C.create_string_buffer(64)
+        off, rows, cols = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib.xrl_weight_tensor(C.byref(md), i, name, 64, C.byref(off), C.byref(rows), C.byref(cols)))
+        assert off.value == expect
+        shape = (rows.value, cols.value) if cols.value else (rows.value,)
+        expect += int(np.prod(shape))
+        out.append((name.value.decode(), shape))
+    return out
+
+
+def _arr(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data
+
+
+class Batch:
+    """A packed meta-batch (host side; device side after Encoder.upload)."""
+
+    def __init__(self, model, state):
+        lib = load_library()
+        self._keep = dict(
+            sgp=_arr(state["state_graph_ptr"], np.int32), gnp=_arr(state["graph_node_ptr"], np.int32),
+            gep=_arr(state["graph_edge_ptr"], np.int32), op=_arr(state["node_op"], np.int32),
+            dense=_arr(state.get("node_dense"), np.float32), src=_arr(state["edge_src"], np.int32),
+            dst=_arr(state["edge_dst"], np.int32), ef=_arr(state["edge_feat"], np.float32),
+            gg=_arr(state.get("graph_global"), np.float32), mask=_arr(state["slot_mask"], np.uint8))
+        k = self._keep
+        sd = StateDesc(int(state["n_states"]), _ptr(k["sgp"]), _ptr(k["gnp"]), _ptr(k["gep"]),
+                       _ptr(k["op"]), _ptr(k["dense"]), _ptr(k["src"]), _ptr(k["dst"]),
+                       _ptr(k["ef"]), _ptr(k["gg"]), _ptr(k["mask"]))
+        self.handle = C.c_void_p()
+        self.model = dict(model)
+        _check(lib.xrl_pack_state(C.byref(model_desc(model)), C.byref(sd), C.byref(self.handle)))
+        self._keep = None                      # host inputs are only borrowed during the call
+        d = [C.c_int64() for _ in range(4)]
+        _check(lib.xrl_batch_dims(self.handle, *[C.byref(x) for x in d]))
+        self.S, self.G, self.N, self.E = (int(x.value) for x in d)
+
+    def host_view(self):
+        """Copies of the packed host arrays as numpy arrays."""
+        v = PackedView()
+        _check(load_library().xrl_batch_host_view(self.handle, C.byref(v)))
+        De = self.model["d_edge"]
+
+        def grab(p, n, ct=C.c_int32, dt=np.int32):
+            if n == 0:
+                return np.zeros(0, dtype=dt)
+            return np.ctypeslib.as_array(C.cast(p, C.POINTER(ct)), shape=(n,)).astype(dt, copy=True)
+        return dict(state_graph_ptr=grab(v.state_graph_ptr, self.S + 1),
+                    graph_node_ptr=grab(v.graph_node_ptr, self.G + 1),
+                    in_ptr=grab(v.in_ptr, self.N + 1), in_src=grab(v.in_src, self.E),
+                    in_dst=grab(v.in_dst, self.E), in_eid=grab(v.in_eid, self.E),
+                    out_ptr=grab(v.out_ptr, self.N + 1), out_pos=grab(v.out_pos, self.E),
+                    node_graph=grab(v.node_graph, self.N),
+                    edge_feat=grab(v.edge_feat, self.E * De, C.c_float, np.float32).reshape(self.E, De))
+
+    def free(self):
+        if self.handle:
+            load_library().xrl_batch_free(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pack_state(model, state):
+    return Batch(model, state)
+
+
+class Encoder:
+    """Device context: weights + workspaces on the current torch CUDA stream."""
+
+    def __init__(self, model, weights, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("xrl needs a GPU: torch.cuda.is_available() is False")
+        self.torch = torch
+        self.model = dict(model)
+        self.lib = load_library()
+        self.H = model["hidden"]
+        self.n_weights = weight_count(model)
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        if w.size != self.n_weights:
+            raise ValueError(f"weights has {w.size} entries, the model needs {self.n_weights}")
+        self.stream = torch.cuda.current_stream() if stream is None else stream
+        self.handle = C.c_void_p()
+        _check(self.lib.xrl_create(C.byref(model_desc(model)), w.ctypes.data,
+                                   C.c_void_p(self.stream.cuda_stream), C.byref(self.handle)))
+
+    def set_weights(self, weights):
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        assert w.size == self.n_weights
+        _check(self.lib.xrl_set_weights(self.handle, w.ctypes.data))
+
+    def upload(self, batch):
+        _check(self.lib.xrl_batch_upload(self.handle, batch.handle))
+        return batch
+
+    def pack(self, state):
+        return self.upload(Batch(self.model, state))
+
+    def _empty(self, shape, dtype=None):
+        t = self.torch
+        return t.empty(shape, dtype=dtype or t.float32, device="cuda")
+
+    def encode(self, batch, save_for_backward=False, out=None):
+        emb = self._empty((batch.G, self.H)) if out is None else out
+        _check(self.lib.xrl_encode(self.handle, batch.handle, emb.data_ptr(), int(save_for_backward)))
+        return emb
+
+    def policy_value(self, batch, emb, out=None):
+        t = self.torch
+        o = out or dict(logp=self._empty((batch.G,)), value=self._empty((batch.S,)),
+                        entropy=self._empty((batch.S,)), action=self._empty((batch.S,), t.int32),
+                        logit=self._empty((batch.G,)))
+        _check(self.lib.xrl_policy_value(self.handle, batch.handle, emb.data_ptr(), o["logp"].data_ptr(),
+                                         o["value"].data_ptr(), o["entropy"].data_ptr(),
+                                         o["action"].data_ptr(), o["logit"].data_ptr()))
+        return o
+
+    def policy_value_backward(self, batch, emb, dlogp, dvalue, dentropy, dweights):
+        demb = self._empty((batch.G, self.H))
+        _check(self.lib.xrl_policy_value_backward(self.handle, batch.handle, emb.data_ptr(),
+                                                  dlogp.data_ptr(), dvalue.data_ptr(),
+                                                  dentropy.data_ptr(), demb.data_ptr(),
+                                                  dweights.data_ptr()))
+        return demb
+
+    def encode_backward(self, batch, demb, dweights):
+        _check(self.lib.xrl_encode_backward(self.handle, batch.handle, demb.data_ptr(), dweights.data_ptr()))
+        return dweights
+
+    def segment_sum(self, values, ptr, out=None):
+        n_rows, width = values.shape
+        n_seg = ptr.numel() - 1
+        o = self._empty((n_seg, width)) if out is None else out
+        _check(self.lib.xrl_segment_sum(self.handle, values.data_ptr(), ptr.data_ptr(), n_rows, n_seg,
+                                        width, o.data_ptr()))
+        return o
+
+    def get_activation(self, batch, what, rnd=0):
+        shape = {"a0": (batch.N, self.model["d_edge"]), "pool": (batch.G, self.H)}.get(what, (batch.N, self.H))
+        o = self._empty(shape)
+        _check(self.lib.xrl_get_activation(self.handle, batch.handle, what.encode(), rnd, o.data_ptr()))
+        return o
+
+    def close(self):
+        if self.handle:
+            self.lib.xrl_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,158 @@
+// Deterministic segment sum over consecutive rows: out[s, :] = sum of rows [ptr[s], ptr[s+1]).
+// Used for the receiver-side sum of incoming edge attributes (node-update layer, Section 3.4),
+// the per-graph sum of node states (global-update layer) and, in the backward pass, the sums over
+// a receiver's in-edges and over a sender's out-edges (through a row permutation).
+//
+// Rows are cut into fixed sub-tiles of RT rows; D / VEC lanes own one sub-tile, each lane a
+// 16-byte column slice. A lane walks its sub-tile in row order, so every sum has a fixed order
+// (no atomics). A segment lying entirely inside a sub-tile is written directly; the piece of a
+// segment that started in an earlier sub-tile goes to carry[st][0], the piece of one that
+// continues into a later sub-tile to carry[st][1]; segsum_fixup adds the pieces in row order.
+#pragma once
+#include "mma.hip.h"
+
+template <typename T, int VEC>
+struct RowVec;
+template <>
+struct RowVec<float, 4> {
+  static __device__ __forceinline__ void load(const float *p, float *v) {
+    f32x4 x = *(const f32x4 *)p;
+    v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+  }
+};
+template <>
+struct RowVec<float, 1> {
+  static __device__ __forceinline__ void load(const float *p, float *v) { v[0] = *p; }
+};
+template <>
+struct RowVec<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const bf16_t *p, float *v) {
+    bf16x8 x = *(const bf16x8 *)p;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = (float)x[j];
+  }
+};
+
+template <typename TO>
+__device__ __forceinline__ void store_out(TO *p, float v);
+template <>
+__device__ __forceinline__ void store_out<float>(float *p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_out<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)v; }
+
+// largest s in [0, n_seg) with ptr[s] <= row < ptr[s+1]; requires 0 <= row < ptr[n_seg]
+__device__ __forceinline__ int seg_of_row(const int32_t *ptr, int64_t n_seg, int64_t row) {
+  int64_t lo = 0, hi = n_seg;  // invariant: ptr[lo] <= row < ptr[hi]
+  while (hi - lo > 1) {
+    int64_t mid = (lo + hi) >> 1;
+    if (ptr[mid] <= row) lo = mid; else hi = mid;
+  }
+  return (int)lo;
+}
+
+struct SegsumArgs {
+  const void *vals;     // [*, D] rows, type TIn
+  const int32_t *perm;  // nullable: row r of the reduction reads vals row perm[r]
+  const int32_t *ptr;   // [n_seg + 1]
+  int64_t n_rows, n_seg;
+  int D, RT;
+  void *out;            // [n_seg, D], type TOut
+  float *carry;         // [n_subtiles, 2, D]
+};
+
+template <typename TIn, typename TOut, int VEC, int RT>
+__global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
+  const int lpr = a.D / VEC;                                   // lanes per row
+  const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t st = gt / lpr;
+  const int c = (int)(gt - st * lpr) * VEC;
+  const int64_t r0 = st * RT;
+  if (r0 >= a.n_rows) return;
+  const int nv = (int)((a.n_rows - r0) < RT ? (a.n_rows - r0) : RT);
+  const TIn *vals = (const TIn *)a.vals;
+  TOut *out = (TOut *)a.out;
+  float v[RT][VEC];
+#pragma unroll
+  for (int i = 0; i < RT; ++i) {
+    if (i < nv) {
+      int64_t r = a.perm ? (int64_t)a.perm[r0 + i] : (r0 + i);
+      RowVec<TIn, VEC>::load(vals + (size_t)r * a.D + c, v[i]);
+    }
+  }
+  int seg = seg_of_row(a.ptr, a.n_seg, r0);
+  if (st == 0)                                                  // empty segments before row 0
+    for (int s = 0; s < seg; ++s)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)s * a.D + c + j, 0.f);
+  float acc[VEC];
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+  bool first = true;
+  int64_t seg_end = a.ptr[seg + 1];
+#pragma unroll
+  for (int i = 0; i < RT; ++i) {
+    if (i < nv) {
+      const int64_t row = r0 + i;
+      while (row >= seg_end) {                                  // close finished (or empty) segments
+        if (first && (int64_t)a.ptr[seg] < r0) {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) a.carry[((size_t)st * 2) * a.D + c + j] = acc[j];
+        } else {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)seg * a.D + c + j, acc[j]);
+        }
+        first = false;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+        ++seg;
+        seg_end = a.ptr[seg + 1];
+      }
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc[j] += v[i][j];
+    }
+  }
+  // last open segment of the sub-tile
+  const int64_t tile_end = r0 + RT;                              // exclusive end of a full sub-tile
+  if (first && (int64_t)a.ptr[seg] < r0) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) a.carry[((size_t)st * 2) * a.D + c + j] = acc[j];
+  } else if (seg_end > tile_end) {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) a.carry[((size_t)st * 2 + 1) * a.D + c + j] = acc[j];
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)seg * a.D + c + j, acc[j]);
+  }
+  // empty segments sitting exactly at this sub-tile's end (incl. trailing ones at n_rows)
+  const int64_t here = r0 + nv;
+  if (seg_end == here) {
+    int s = seg + 1;
+    while (s < a.n_seg && (int64_t)a.ptr[s + 1] == here) {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)s * a.D + c + j, 0.f);
+      ++s;
+    }
+  }
+}
+
+// One 64-thread block per sub-tile: if the sub-tile's last segment starts inside it and runs on,
+// add its pieces in row order and write the segment's sum. row_seg (nullable) gives the segment
+// of each row directly; otherwise it is found by binary search in ptr.
+template <typename TOut>
+__global__ __launch_bounds__(64) void segsum_fixup(const int32_t *ptr, const int32_t *row_seg,
+                                                   int64_t n_rows, int64_t n_seg, int D, int RT,
+                                                   const float *carry, TOut *out) {
+  const int64_t st = blockIdx.x;
+  const int64_t r0 = st * RT;
+  if (r0 >= n_rows) return;
+  const int64_t nv = (n_rows - r0) < RT ? (n_rows - r0) : RT;
+  const int64_t last = r0 + nv - 1;
+  const int seg = row_seg ? row_seg[last] : seg_of_row(ptr, n_seg, last);
+  const int64_t beg = ptr[seg], end = ptr[seg + 1];
+  if (beg < r0 || end <= r0 + RT) return;
+  for (int f = threadIdx.x; f < D; f += 64) {
+    float sum = carry[((size_t)st * 2 + 1) * D + f];
+    for (int64_t t = st + 1; t * RT < end; ++t) sum += carry[((size_t)t * 2) * D + f];
+    store_out<TOut>(out + (size_t)seg * D + f, sum);
+  }
+}

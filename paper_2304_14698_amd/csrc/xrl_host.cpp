@@ -1,0 +1,282 @@
+// Host side of the library: weight layout, validation and packing of states into the
+// receiver-sorted meta-batch. Nothing in this file calls the GPU runtime.
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "xrl_internal.h"
+
+namespace xrl {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static void add_mlp(Layout &L, MlpRef &ref, const std::string &prefix, int d_in,
+                    const std::vector<int> &widths) {
+  ref.n_layers = (int)widths.size();
+  int d = d_in;
+  for (size_t i = 0; i < widths.size(); ++i) {
+    int w = widths[i];
+    ref.d_in[i] = d;
+    ref.d_out[i] = w;
+    ref.w[i] = L.total;
+    L.tensors.push_back({prefix + ".W" + std::to_string(i), L.total, d, w});
+    L.total += (int64_t)d * w;
+    ref.b[i] = L.total;
+    L.tensors.push_back({prefix + ".b" + std::to_string(i), L.total, w, 0});
+    L.total += w;
+    d = w;
+  }
+}
+
+int build_layout(const xrl_model_desc &m, Layout &L) {
+  if (m.n_op_types < 1 || m.n_node_dense < 0 || m.d_edge < 1 || m.d_global < 0 || m.hidden < 1 ||
+      m.rounds < 0 || m.mlp_layers < 1 || m.mlp_layers > 3 || m.head_hidden[0] < 1 ||
+      m.head_hidden[1] < 1)
+    return fail(XRL_ERR_SHAPE, "model: non-positive or out-of-range dimension");
+  if (m.n_op_types > 4096 || m.n_node_dense > 4096 || m.d_edge > 4096 || m.d_global > 4096 ||
+      m.hidden > 4096 || m.rounds > 1024 || m.head_hidden[0] > 4096 || m.head_hidden[1] > 4096)
+    return fail(XRL_ERR_SHAPE, "model: dimension above 4096 (rounds above 1024)");
+  if (m.readout != XRL_READOUT_SUM && m.readout != XRL_READOUT_MEAN)
+    return fail(XRL_ERR_SHAPE, "model: readout must be XRL_READOUT_SUM or XRL_READOUT_MEAN");
+  if (m.precision != XRL_PREC_FP32 && m.precision != XRL_PREC_BF16)
+    return fail(XRL_ERR_SHAPE, "model: precision must be XRL_PREC_FP32 or XRL_PREC_BF16");
+  L = Layout();
+  const int H = m.hidden;
+  std::vector<int> enc(m.mlp_layers, H);
+  add_mlp(L, L.embed, "embed", m.d_edge + m.n_op_types + m.n_node_dense, enc);
+  L.edge.resize(m.rounds);
+  L.node.resize(m.rounds);
+  for (int r = 0; r < m.rounds; ++r) {
+    add_mlp(L, L.edge[r], "edge" + std::to_string(r), 2 * H + m.d_edge, enc);
+    add_mlp(L, L.node[r], "node" + std::to_string(r), 2 * H, enc);
+  }
+  add_mlp(L, L.readout, "readout", H + m.d_global, enc);
+  std::vector<int> head = {m.head_hidden[0], m.head_hidden[1], 1};
+  add_mlp(L, L.policy, "policy", H, head);
+  add_mlp(L, L.value, "value", H, head);
+  return XRL_OK;
+}
+
+}  // namespace xrl
+
+using namespace xrl;
+
+extern "C" {
+
+const char *xrl_last_error(void) { return g_err; }
+const char *xrl_version(void) { return "xrl 0.1 (gfx950)"; }
+
+int64_t xrl_weight_count(const xrl_model_desc *model) {
+  if (!model) return fail(XRL_ERR_NULL, "xrl_weight_count: model is NULL");
+  Layout L;
+  int rc = build_layout(*model, L);
+  return rc ? rc : L.total;
+}
+
+int32_t xrl_weight_tensor_count(const xrl_model_desc *model) {
+  if (!model) return fail(XRL_ERR_NULL, "xrl_weight_tensor_count: model is NULL");
+  Layout L;
+  int rc = build_layout(*model, L);
+  return rc ? rc : (int32_t)L.tensors.size();
+}
+
+int xrl_weight_tensor(const xrl_model_desc *model, int32_t index, char *name, size_t name_cap,
+                      int64_t *offset, int64_t *rows, int64_t *cols) {
+  if (!model) return fail(XRL_ERR_NULL, "xrl_weight_tensor: model is NULL");
+  Layout L;
+  int rc = build_layout(*model, L);
+  if (rc) return rc;
+  if (index < 0 || index >= (int32_t)L.tensors.size())
+    return fail(XRL_ERR_INDEX, "xrl_weight_tensor: index %d outside [0, %zu)", index,
+                L.tensors.size());
+  const WeightTensor &t = L.tensors[index];
+  if (name && name_cap) {
+    strncpy(name, t.name.c_str(), name_cap - 1);
+    name[name_cap - 1] = 0;
+  }
+  if (offset) *offset = t.offset;
+  if (rows) *rows = t.rows;
+  if (cols) *cols = t.cols;
+  return XRL_OK;
+}
+
+static int check_ptr(const int32_t *p, int64_t n, const char *what) {
+  if (p[0] != 0) return fail(XRL_ERR_SHAPE, "%s[0] = %d, must be 0", what, p[0]);
+  for (int64_t i = 0; i < n; ++i)
+    if (p[i + 1] < p[i])
+      return fail(XRL_ERR_SHAPE, "%s decreases at %lld (%d -> %d)", what, (long long)i, p[i],
+                  p[i + 1]);
+  return XRL_OK;
+}
+
+static bool all_finite(const float *p, int64_t n, int64_t *where) {
+  for (int64_t i = 0; i < n; ++i)
+    if (!std::isfinite(p[i])) {
+      *where = i;
+      return false;
+    }
+  return true;
+}
+
+int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_batch **out) {
+  if (!model || !st || !out) return fail(XRL_ERR_NULL, "xrl_pack_state: NULL argument");
+  *out = nullptr;
+  Layout L;
+  int rc = build_layout(*model, L);
+  if (rc) return rc;
+  const int64_t S = st->n_states;
+  if (S < 0) return fail(XRL_ERR_SHAPE, "n_states = %lld is negative", (long long)S);
+  if (!st->state_graph_ptr || !st->graph_node_ptr || !st->graph_edge_ptr || !st->slot_mask)
+    return fail(XRL_ERR_NULL, "xrl_pack_state: a ptr array or slot_mask is NULL");
+  if ((rc = check_ptr(st->state_graph_ptr, S, "state_graph_ptr"))) return rc;
+  const int64_t G = st->state_graph_ptr[S];
+  for (int64_t s = 0; s < S; ++s)
+    if (st->state_graph_ptr[s + 1] == st->state_graph_ptr[s])
+      return fail(XRL_ERR_SHAPE, "state %lld has no graph (needs its current graph)", (long long)s);
+  if ((rc = check_ptr(st->graph_node_ptr, G, "graph_node_ptr"))) return rc;
+  if ((rc = check_ptr(st->graph_edge_ptr, G, "graph_edge_ptr"))) return rc;
+  const int64_t N = st->graph_node_ptr[G], E = st->graph_edge_ptr[G];
+  const int Dd = model->n_node_dense, De = model->d_edge, Dg = model->d_global;
+  if (N > 0 && (!st->node_op || (Dd > 0 && !st->node_dense)))
+    return fail(XRL_ERR_NULL, "node_op or node_dense is NULL");
+  if (E > 0 && (!st->edge_src || !st->edge_dst || !st->edge_feat))
+    return fail(XRL_ERR_NULL, "edge_src, edge_dst or edge_feat is NULL");
+  for (int64_t s = 0; s < S; ++s)
+    if (st->slot_mask[st->state_graph_ptr[s]] == 0)
+      return fail(XRL_ERR_MASK, "state %lld masks its No-Op slot (its first graph)", (long long)s);
+  for (int64_t i = 0; i < N; ++i)
+    if (st->node_op[i] < 0 || st->node_op[i] >= model->n_op_types)
+      return fail(XRL_ERR_INDEX, "node %lld: op id %d outside [0, %d)", (long long)i,
+                  st->node_op[i], model->n_op_types);
+  for (int64_t g = 0; g < G; ++g) {
+    const int32_t n = st->graph_node_ptr[g + 1] - st->graph_node_ptr[g];
+    for (int64_t e = st->graph_edge_ptr[g]; e < st->graph_edge_ptr[g + 1]; ++e)
+      if (st->edge_src[e] < 0 || st->edge_src[e] >= n || st->edge_dst[e] < 0 ||
+          st->edge_dst[e] >= n)
+        return fail(XRL_ERR_INDEX, "edge %lld of graph %lld: endpoint (%d -> %d) outside [0, %d)",
+                    (long long)e, (long long)g, st->edge_src[e], st->edge_dst[e], n);
+  }
+  int64_t bad = 0;
+  if (Dd > 0 && !all_finite(st->node_dense, N * Dd, &bad))
+    return fail(XRL_ERR_VALUE, "node_dense[%lld] is not finite", (long long)bad);
+  if (!all_finite(st->edge_feat, E * De, &bad))
+    return fail(XRL_ERR_VALUE, "edge_feat[%lld] is not finite", (long long)bad);
+  if (st->graph_global && !all_finite(st->graph_global, G * Dg, &bad))
+    return fail(XRL_ERR_VALUE, "graph_global[%lld] is not finite", (long long)bad);
+
+  xrl_batch *b = new (std::nothrow) xrl_batch();
+  if (!b) return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
+  try {
+    static std::atomic<uint64_t> next_id{1};
+    b->id = next_id++;
+    b->model = *model;
+    b->S = S; b->G = G; b->N = N; b->E = E;
+    b->state_graph_ptr.assign(st->state_graph_ptr, st->state_graph_ptr + S + 1);
+    b->graph_node_ptr.assign(st->graph_node_ptr, st->graph_node_ptr + G + 1);
+    b->node_op.assign(st->node_op, st->node_op + N);
+    b->node_dense.assign(st->node_dense, st->node_dense + (Dd > 0 ? N * Dd : 0));
+    b->mask.resize(G);
+    for (int64_t g = 0; g < G; ++g) b->mask[g] = st->slot_mask[g] ? 1 : 0;
+    if (st->graph_global)
+      b->graph_global.assign(st->graph_global, st->graph_global + G * Dg);
+    else
+      b->graph_global.assign((size_t)(G * Dg), 0.0f);
+    for (int64_t s = 0; s < S; ++s) {
+      int32_t c = st->state_graph_ptr[s + 1] - st->state_graph_ptr[s];
+      if (c > b->max_slots) b->max_slots = c;
+    }
+    b->node_graph.resize(N);
+    for (int64_t g = 0; g < G; ++g)
+      for (int32_t i = st->graph_node_ptr[g]; i < st->graph_node_ptr[g + 1]; ++i)
+        b->node_graph[i] = (int32_t)g;
+
+    // receiver order: stable counting sort of the edges by global receiver id
+    b->in_ptr.assign(N + 1, 0);
+    b->out_ptr.assign(N + 1, 0);
+    std::vector<int32_t> gsrc(E), gdst(E);
+    for (int64_t g = 0; g < G; ++g) {
+      const int32_t base = st->graph_node_ptr[g];
+      for (int64_t e = st->graph_edge_ptr[g]; e < st->graph_edge_ptr[g + 1]; ++e) {
+        gsrc[e] = base + st->edge_src[e];
+        gdst[e] = base + st->edge_dst[e];
+        b->in_ptr[gdst[e] + 1]++;
+        b->out_ptr[gsrc[e] + 1]++;
+      }
+    }
+    for (int64_t i = 0; i < N; ++i) {
+      b->in_ptr[i + 1] += b->in_ptr[i];
+      b->out_ptr[i + 1] += b->out_ptr[i];
+    }
+    b->in_src.resize(E); b->in_dst.resize(E); b->in_eid.resize(E); b->out_pos.resize(E);
+    b->edge_feat.resize((size_t)E * De);
+    {
+      std::vector<int32_t> cur(b->in_ptr.begin(), b->in_ptr.end() - 1);
+      for (int64_t e = 0; e < E; ++e) {
+        const int32_t p = cur[gdst[e]]++;
+        b->in_src[p] = gsrc[e];
+        b->in_dst[p] = gdst[e];
+        b->in_eid[p] = (int32_t)e;
+        memcpy(&b->edge_feat[(size_t)p * De], &st->edge_feat[(size_t)e * De], sizeof(float) * De);
+      }
+    }
+    {  // sender-side index: receiver-order positions grouped by sender, ascending position
+      std::vector<int32_t> cur(b->out_ptr.begin(), b->out_ptr.end() - 1);
+      for (int64_t p = 0; p < E; ++p) b->out_pos[cur[b->in_src[p]]++] = (int32_t)p;
+    }
+  } catch (const std::bad_alloc &) {
+    delete b;
+    return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
+  }
+  *out = b;
+  return XRL_OK;
+}
+
+int xrl_batch_dims(const xrl_batch *b, int64_t *S, int64_t *G, int64_t *N, int64_t *E) {
+  if (!b) return fail(XRL_ERR_NULL, "xrl_batch_dims: batch is NULL");
+  if (S) *S = b->S;
+  if (G) *G = b->G;
+  if (N) *N = b->N;
+  if (E) *E = b->E;
+  return XRL_OK;
+}
+
+int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *v) {
+  if (!b || !v) return fail(XRL_ERR_NULL, "xrl_batch_host_view: NULL argument");
+  v->S = b->S; v->G = b->G; v->N = b->N; v->E = b->E;
+  v->state_graph_ptr = b->state_graph_ptr.data();
+  v->graph_node_ptr = b->graph_node_ptr.data();
+  v->in_ptr = b->in_ptr.data();
+  v->in_src = b->in_src.data();
+  v->in_dst = b->in_dst.data();
+  v->in_eid = b->in_eid.data();
+  v->out_ptr = b->out_ptr.data();
+  v->out_pos = b->out_pos.data();
+  v->node_graph = b->node_graph.data();
+  v->edge_feat = b->edge_feat.data();
+  return XRL_OK;
+}
+
+int xrl_batch_free(xrl_batch *b) {
+  if (!b) return XRL_OK;
+  xrl_batch_release_device(b);
+  delete b;
+  return XRL_OK;
+}
+
+}  // extern "C"

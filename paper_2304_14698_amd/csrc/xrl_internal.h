@@ -1,0 +1,67 @@
+// Internal declarations shared by the host-side packer and the device-side runtime.
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "xrl.h"
+
+namespace xrl {
+
+void set_error(const char *fmt, ...);
+int fail(int code, const char *fmt, ...);
+
+// One tensor of the flat weight vector (order documented in xrl.h).
+struct WeightTensor {
+  std::string name;
+  int64_t offset, rows, cols;  // cols == 0 for a bias vector of length rows
+};
+
+// Offsets of one MLP inside the flat vector: per layer (W offset, b offset, in, out).
+struct MlpRef {
+  int n_layers = 0;
+  int64_t w[3] = {0, 0, 0}, b[3] = {0, 0, 0};
+  int32_t d_in[3] = {0, 0, 0}, d_out[3] = {0, 0, 0};
+};
+
+struct Layout {
+  std::vector<WeightTensor> tensors;
+  int64_t total = 0;
+  MlpRef embed, readout, policy, value;
+  std::vector<MlpRef> edge, node;  // per round
+};
+
+// Validates the dimensions that every part of the library relies on (positive widths, ...)
+// and fills the layout. Returns XRL_OK or an error code (message set).
+int build_layout(const xrl_model_desc &m, Layout &out);
+
+}  // namespace xrl
+
+// Device-side copies of a packed batch (all owned by one hipMalloc block).
+struct xrl_batch_device {
+  void *block = nullptr;
+  size_t bytes = 0;
+  int32_t *state_graph_ptr = nullptr, *graph_node_ptr = nullptr, *node_op = nullptr;
+  int32_t *in_ptr = nullptr, *in_src = nullptr, *in_dst = nullptr;
+  int32_t *out_ptr = nullptr, *out_pos = nullptr, *node_graph = nullptr;
+  float *node_dense = nullptr, *edge_feat = nullptr, *graph_global = nullptr;
+  uint8_t *mask = nullptr;
+};
+
+struct xrl_batch {
+  xrl_model_desc model;
+  int64_t S = 0, G = 0, N = 0, E = 0;
+  int32_t max_slots = 0;  // largest number of slots in one state
+  std::vector<int32_t> state_graph_ptr, graph_node_ptr, node_op;
+  std::vector<int32_t> in_ptr, in_src, in_dst, in_eid, out_ptr, out_pos, node_graph;
+  std::vector<float> node_dense, edge_feat, graph_global;
+  std::vector<uint8_t> mask;
+  xrl_batch_device dev;
+  bool uploaded = false;
+  uint64_t id = 0;  // unique per packed batch; ties saved activations to their batch
+};
+
+// Implemented in the device translation unit; frees dev.block if any.
+extern "C" void xrl_batch_release_device(xrl_batch *b);
