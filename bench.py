@@ -1,0 +1,140 @@
+"""Throughput of the state encoder + heads on one MI355X, with roofline and CPU-oracle baseline.
+
+One step = one forward pass of the whole path (sum of incoming edge attributes, embed MLP,
+R x (edge MLP + per-receiver sum, node MLP), per-graph readout, policy/value heads) over one
+packed synthetic meta-batch that is already resident in HBM. Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def oracle_baseline(model, state, w, budget_s=20.0):
+    """The float64 oracle timed on the host cores over whole graphs of the same workload."""
+    import numpy as np
+    from oracle import xrl_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    om = O.default_model(**{k: model[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
+                                                  "hidden", "rounds", "mlp_layers", "head_hidden", "readout")})
+    G = len(state["graph_node_ptr"]) - 1
+    t0 = time.perf_counter()
+    done = 0
+    embs = []
+    for g in range(G):
+        embs.append(O.encode(om, w, state, graphs=[g])[0])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    if done == G:
+        O.policy_value(om, w, np.stack(embs), state)
+    dt = time.perf_counter() - t0
+    return dict(value=done / dt, unit="graphs/s", cores=int(cores), kind="oracle",
+                sample=f"{done} of {G} graphs of the same meta-batch, float64 numpy, {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="synthetic configuration (2 = headline)")
+    ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
+    ap.add_argument("--states", type=int, default=None, help="override the number of states")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2304_14698_amd as xrl
+    import synth
+    xrl.load_library()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+
+    model, state = synth.make_config(args.config, n_states=args.states)
+    if args.precision:
+        model["precision"] = args.precision
+    rng = np.random.Generator(np.random.PCG64(synth.BASE_SEED))
+    w = synth.init_weights(rng, xrl.weight_layout(model), bias_range=0.1)
+    enc = xrl.Encoder(model, w)
+    batch = enc.pack(state)                       # pack + upload happen before the timed region
+    S, G, N, E = batch.S, batch.G, batch.N, batch.E
+    H, R, De = model["hidden"], model["rounds"], model["d_edge"]
+    emb = torch.empty((G, H), dtype=torch.float32, device="cuda")
+    outs = dict(logp=torch.empty(G, device="cuda"), value=torch.empty(S, device="cuda"),
+                entropy=torch.empty(S, device="cuda"), action=torch.empty(S, dtype=torch.int32, device="cuda"),
+                logit=torch.empty(G, device="cuda"))
+
+    def step():
+        enc.encode(batch, out=emb)
+        enc.policy_value(batch, emb, out=outs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+
+    # the dominant kernel (edge MLP + per-receiver sum), timed with HIP events on the library's
+    # stream over the same number of steps
+    enc.set_timing(True)
+    for _ in range(args.steps):
+        step()
+    kern = {}
+    for k in ("embed", "edge", "edge_fixup", "node", "pool", "readout", "heads"):
+        tot, n = enc.read_timing(k)
+        kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)
+    enc.set_timing(False)
+    edge_flops = 2.0 * E * H * (3 * H + De)       # edge L1 (2H+De -> H) + edge L2 (H -> H), per launch
+    edge_s = kern["edge"]["avg_us"] * 1e-6
+    bf16 = model["precision"] == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    achieved = edge_flops / edge_s / 1e12 if edge_s > 0 else 0.0
+    b = 2 if bf16 else 4
+    pool_bytes = N * H * b + 4 * (G + 1) + G * H * 4
+    pool_s = kern["pool"]["avg_us"] * 1e-6
+
+    res = dict(
+        metric="candidate graphs encoded/sec on 1 MI355X", value=G / (ms * 1e-3), unit="graphs/s",
+        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms, higher_is_better=True,
+        scaling="weak", vs_baseline=None, dtype=model["precision"], data="synthetic",
+        config=dict(workload=f"config {args.config} ({synth.CONFIGS[args.config]['name']}): {S} state(s), "
+                             f"{G} graphs, {N} nodes, {E} edges, hidden {H}, {R} rounds, forward "
+                             f"(encode + policy/value heads)",
+                    states=S, graphs=G, nodes=N, edges=E, hidden=H, rounds=R),
+        edges_per_s=E * R / (ms * 1e-3),
+        roofline=dict(bound="mfma", kernel="edge MLP + per-receiver sum (one launch per round)",
+                      achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak, traffic=None,
+                      flops_per_launch=edge_flops, avg_launch_us=kern["edge"]["avg_us"]),
+        hbm_kernel=dict(kernel="per-graph readout sum", bytes_per_launch=pool_bytes,
+                        achieved=(pool_bytes / pool_s / 1e9 if pool_s > 0 else 0.0), peak=PEAK_HBM_GBS,
+                        unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
+        kernels_us=kern,
+    )
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = oracle_baseline(model, state, w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -177,6 +177,14 @@ int xrl_segment_sum(xrl_ctx *ctx, const float *d_values, const int32_t *d_ptr, i
 int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32_t round,
                        float *d_out);
 
+/* Per-kernel timing for roofline measurement. While enabled, every launch group of the forward
+ * path is bracketed by HIP events on the ctx stream. xrl_read_timing synchronises the stream,
+ * returns the summed duration and launch count recorded since the last read for `kernel` in
+ * {"embed", "edge", "edge_fixup", "node", "pool", "readout", "heads"} (the steps of
+ * Section 3.4 / 3.3.2 in execution order) and forgets them. Errors: NULL, INDEX, HIP. */
+int xrl_set_timing(xrl_ctx *ctx, int enabled);
+int xrl_read_timing(xrl_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
+
 const char *xrl_last_error(void);
 const char *xrl_version(void);
 

@@ -110,14 +110,18 @@ def mlp_forward(x, layers, last_relu):
     return x, cache
 
 
-def mlp_backward(dy, layers, cache, last_relu):
-    """Reverse of mlp_forward: returns dx and [(dW, db)] in layer order."""
+def mlp_backward(dy, layers, cache, last_relu, bound=None):
+    """Reverse of mlp_forward: returns dx and [(dW, db)] in layer order. If `bound` is a list,
+    it receives per layer (|x|^T |dz|, sum |dz|): the sums of absolute terms of each gradient
+    entry, i.e. the quantity a rounding-error bound of that entry is proportional to."""
     grads = [None] * len(layers)
     for i in reversed(range(len(layers))):
         Wm, _ = layers[i]
         x, z = cache[i]
         dz = dy * (z > 0.0) if (last_relu or i + 1 < len(layers)) else dy
         grads[i] = (x.T @ dz, dz.sum(axis=0))
+        if bound is not None:
+            bound.insert(0, (np.abs(x).T @ np.abs(dz), np.abs(dz).sum(axis=0)))
         dy = dz @ Wm.T
     return dy, grads
 
@@ -256,7 +260,7 @@ def zero_grads(model):
     return {name: np.zeros(shape, dtype=F) for name, shape in weight_layout(model)}
 
 
-def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy):
+def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound=None):
     """Gradient of L = sum_valid dlogp_j logp_j + sum_s dvalue_s value_s + sum_s dentropy_s
     entropy_s w.r.t. the embeddings [G, H] and the head weights (flat vector, zero elsewhere).
     Masked slots get exactly zero everywhere (invalid-action masking, Section 3.3.2)."""
@@ -267,7 +271,8 @@ def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy):
     dlogit = np.zeros(G)
     dz = np.zeros_like(fw["z"])
     dv = np.asarray(dvalue, dtype=F).reshape(S, 1)
-    dzs, g_v = mlp_backward(dv, _layers(W, "value"), fw["c_v"], False)
+    b_v, b_pi = ([], []) if bound is not None else (None, None)
+    dzs, g_v = mlp_backward(dv, _layers(W, "value"), fw["c_v"], False, b_v)
     demb = np.zeros_like(np.asarray(emb, dtype=F))
     for s in range(S):
         j0, j1 = int(sgp[s]), int(sgp[s + 1])
@@ -276,41 +281,48 @@ def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy):
         pv, lpv = fw["p"][valid], fw["logp"][valid]
         dlogit[valid] = c - pv * c.sum() - dentropy[s] * pv * (lpv + fw["entropy"][s])
         demb[valid] += dzs[s] / len(valid)
-    dx, g_pi = mlp_backward(dlogit[:, None], _layers(W, "policy"), fw["c_pi"], False)
+    dx, g_pi = mlp_backward(dlogit[:, None], _layers(W, "policy"), fw["c_pi"], False, b_pi)
     demb += dx          # rows of masked slots stay exactly zero: their dlogit is zero
     grads = zero_grads(model)
     _put(grads, model, "policy", g_pi)
     _put(grads, model, "value", g_v)
+    if bound is not None:
+        _put(bound, model, "policy", b_pi)
+        _put(bound, model, "value", b_v)
     return demb, flatten(model, grads)
 
 
-def encode_graph_backward(model, W, inter, demb_g, src, dst, grads):
-    """Accumulates into `grads` the gradient through one graph's encoder given d/d emb."""
+def encode_graph_backward(model, W, inter, demb_g, src, dst, grads, bound=None):
+    """Accumulates into `grads` the gradient through one graph's encoder given d/d emb (and into
+    `bound`, a dict like grads, the sums of absolute terms; see mlp_backward)."""
+    def back(dy, prefix, cache):
+        bl = [] if bound is not None else None
+        dx, g = mlp_backward(dy, _layers(W, prefix), cache, True, bl)
+        _put(grads, model, prefix, g)
+        if bound is not None:
+            _put(bound, model, prefix, bl)
+        return dx
     if model.get("round_kind", "mlp") != "mlp":
         raise NotImplementedError("backward is written for round_kind='mlp'")
     n, H = inter["h"][0].shape[0], model["hidden"]
-    dgin, g = mlp_backward(np.asarray(demb_g, dtype=F)[None, :], _layers(W, "readout"),
-                           inter["c_readout"], True)
-    _put(grads, model, "readout", g)
+    dgin = back(np.asarray(demb_g, dtype=F)[None, :], "readout", inter["c_readout"])
     dpool = dgin[0, :H]
     if model["readout"] == "mean":
         dpool = dpool / max(n, 1)
     dh = np.tile(dpool, (n, 1))
     for r in reversed(range(model["rounds"])):
-        dxin, g = mlp_backward(dh, _layers(W, f"node{r}"), inter["c_node"][r], True)
-        _put(grads, model, f"node{r}", g)
+        dxin = back(dh, f"node{r}", inter["c_node"][r])
         dh, dagg = dxin[:, :H].copy(), dxin[:, H:]
         dm = dagg[dst]                                   # reverse of the sum at the receiver
-        dxe, g = mlp_backward(dm, _layers(W, f"edge{r}"), inter["c_edge"][r], True)
-        _put(grads, model, f"edge{r}", g)
+        dxe = back(dm, f"edge{r}", inter["c_edge"][r])
         np.add.at(dh, src, dxe[:, :H])                   # reverse of the gather by sender
         np.add.at(dh, dst, dxe[:, H:2 * H])              # reverse of the gather by receiver
-    _, g = mlp_backward(dh, _layers(W, "embed"), inter["c_embed"], True)
-    _put(grads, model, "embed", g)
+    back(dh, "embed", inter["c_embed"])
 
 
-def encode_backward(model, w, state, demb, graphs=None):
-    """Flat weight gradient (zero on head weights) of sum_g <demb_g, emb_g>."""
+def encode_backward(model, w, state, demb, graphs=None, bound=None):
+    """Flat weight gradient (zero on head weights) of sum_g <demb_g, emb_g>. `bound`: optional
+    dict from zero_grads() that receives the sums of absolute terms."""
     W = unflatten(model, w)
     grads = zero_grads(model)
     G = len(state["graph_node_ptr"]) - 1
@@ -320,11 +332,11 @@ def encode_backward(model, w, state, demb, graphs=None):
         if gg is None:
             gg = np.zeros(model["d_global"])
         inter = encode_graph(model, W, op, dense, src, dst, xe, gg)
-        encode_graph_backward(model, W, inter, demb[k], src, dst, grads)
+        encode_graph_backward(model, W, inter, demb[k], src, dst, grads, bound)
     return flatten(model, grads)
 
 
-def loss_and_grad(model, w, state, dlogp, dvalue, dentropy):
+def loss_and_grad(model, w, state, dlogp, dvalue, dentropy, bound=None):
     """L (see policy_value_backward) and dL/dw through heads and encoder."""
     emb = encode(model, w, state)
     fw = policy_value(model, w, emb, state)
@@ -332,5 +344,5 @@ def loss_and_grad(model, w, state, dlogp, dvalue, dentropy):
     L = (np.asarray(dlogp, dtype=F)[valid] * fw["logp"][valid]).sum() \
         + (np.asarray(dvalue, dtype=F) * fw["value"]).sum() \
         + (np.asarray(dentropy, dtype=F) * fw["entropy"]).sum()
-    demb, gh = policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy)
-    return L, gh + encode_backward(model, w, state, demb), demb
+    demb, gh = policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound)
+    return L, gh + encode_backward(model, w, state, demb, bound=bound), demb

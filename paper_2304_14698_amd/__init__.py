@@ -52,7 +52,8 @@ EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "
            "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_segment_sum",
-           "xrl_get_activation", "xrl_last_error", "xrl_version"]
+           "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_last_error",
+           "xrl_version"]
 
 
 def load_library():
@@ -84,6 +85,8 @@ def load_library():
     lib.xrl_encode_backward.argtypes = [vp] * 4
     lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
+    lib.xrl_set_timing.argtypes = [vp, C.c_int]
+    lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.xrl_last_error.restype = C.c_char_p
     lib.xrl_version.restype = C.c_char_p
     _lib = lib
@@ -267,6 +270,15 @@ class Encoder:
         o = self._empty(shape)
         _check(self.lib.xrl_get_activation(self.handle, batch.handle, what.encode(), rnd, o.data_ptr()))
         return o
+
+    def set_timing(self, enabled):
+        _check(self.lib.xrl_set_timing(self.handle, int(enabled)))
+
+    def read_timing(self, kernel):
+        """(total milliseconds, launches) recorded for `kernel` since the last read."""
+        ms, n = C.c_double(), C.c_int64()
+        _check(self.lib.xrl_read_timing(self.handle, kernel.encode(), C.byref(ms), C.byref(n)))
+        return ms.value, int(n.value)
 
     def close(self):
         if self.handle:

@@ -6,7 +6,8 @@
 #include <math.h>
 #include <stdint.h>
 
-#define ROWMLP_ROWS 8  // rows per block: every weight read is reused 8 times
+// Rows per block of the row-MLP kernels: 8 reuses every weight read eight times (large batches);
+// 1 gives one block per row so that small batches still spread over the chip.
 
 // Up to three affine layers over rows of [in1 | in2]; ReLU after every layer except, when
 // relu_last == 0, the last. Optionally stores every layer's output (post-activation) for the
@@ -22,6 +23,7 @@ struct RowMlpArgs {
   float *act[3];           // nullable each
 };
 
+template <int ROWMLP_ROWS>
 __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
   extern __shared__ float sm[];          // two buffers of ROWMLP_ROWS * dmax floats
   int dmax = a.d_in[0];
@@ -44,6 +46,7 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
       const float bv = a.b[l][f];
 #pragma unroll
       for (int r = 0; r < ROWMLP_ROWS; ++r) acc[r] = bv;
+#pragma unroll 8
       for (int k = 0; k < din; ++k) {
         const float w = a.W[l][(size_t)k * dout + f];
 #pragma unroll
@@ -137,10 +140,25 @@ __global__ __launch_bounds__(256) void state_policy_kernel(
   }
   ent = block_sum(ent, red);
   if (t == 0) { entropy[s] = ent; action[s] = arg - j0; }
-  for (int f = t; f < H; f += 256) {
-    float acc = 0.f;
-    for (int j = j0; j < j1; ++j)
-      if (mask[j]) acc += emb[(size_t)j * H + f];
+  // mean embedding of the valid slots: 256 / H groups of threads take every (256/H)-th slot,
+  // four independent partial sums each; partials are combined in a fixed order
+  const int ng = 256 / H, f = t % H, q = t / H;     // H is 64, 128 or 256
+  float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+  int j = j0 + q;
+  for (; j + 3 * ng < j1; j += 4 * ng) {
+    const float v0 = emb[(size_t)j * H + f], v1 = emb[(size_t)(j + ng) * H + f];
+    const float v2 = emb[(size_t)(j + 2 * ng) * H + f], v3 = emb[(size_t)(j + 3 * ng) * H + f];
+    p0 += mask[j] ? v0 : 0.f;
+    p1 += mask[j + ng] ? v1 : 0.f;
+    p2 += mask[j + 2 * ng] ? v2 : 0.f;
+    p3 += mask[j + 3 * ng] ? v3 : 0.f;
+  }
+  for (; j < j1; j += ng) p0 += mask[j] ? emb[(size_t)j * H + f] : 0.f;
+  red[t] = (p0 + p1) + (p2 + p3);
+  __syncthreads();
+  if (q == 0) {
+    float acc = red[f];
+    for (int k = 1; k < ng; ++k) acc += red[k * H + f];
     zmean[(size_t)s * H + f] = acc / nvalid;
   }
 }
@@ -185,6 +203,7 @@ struct RowMlpBwdArgs {
   float *dx;             // [n_rows, d_in[0]] nullable
 };
 
+template <int ROWMLP_ROWS>
 __global__ __launch_bounds__(256) void rowmlp_bwd_kernel(const RowMlpBwdArgs a) {
   extern __shared__ float sm[];
   int dmax = a.d_in[0];
@@ -217,6 +236,7 @@ __global__ __launch_bounds__(256) void rowmlp_bwd_kernel(const RowMlpBwdArgs a) 
 #pragma unroll
       for (int r = 0; r < ROWMLP_ROWS; ++r) acc[r] = 0.f;
       const float *wrow = a.W[l] + (size_t)k * dout;
+#pragma unroll 8
       for (int f = 0; f < dout; ++f) {
         const float w = wrow[f];
 #pragma unroll

@@ -2,6 +2,7 @@
 // activation never leaving registers. One kernel template serves the three learned transforms of
 // the encoder (Section 3.4):
 //   EMBED  rows = nodes,  x = [sum of incoming edge attrs | one-hot op | dense attrs]   -> h0
+//          (the sum over the node's in-edges is formed in the prologue)
 //   EDGE   rows = edges in receiver order, x = [h_sender | h_receiver | edge attrs]
 //          -> ReLU MLP -> summed per receiver (the message-passing sum)                 -> agg
 //   NODE   rows = nodes,  x = [h | agg]                                                 -> h'
@@ -27,11 +28,10 @@ struct Mlp2Args {
   int nslab1;              // slabs of layer 1's (zero-padded) input width
   const void *h;           // [N, H] operand type            (EDGE, NODE)
   const void *agg;         // [N, H] operand type            (NODE)
-  const int32_t *in_ptr;   // [N + 1]                        (EDGE, NODE)
+  const int32_t *in_ptr;   // [N + 1]                        (all kinds)
   const int32_t *in_src;   // [E]                            (EDGE)
   const int32_t *in_dst;   // [E]                            (EDGE)
-  const float *edge_feat;  // [E, De]                        (EDGE)
-  const float *a0;         // [N, De]                        (EMBED)
+  const float *edge_feat;  // [E, De] receiver order         (EDGE, EMBED)
   const int32_t *node_op;  // [N]                            (EMBED)
   const float *node_dense; // [N, Dd]                        (EMBED)
   int De, Tn, Dd;
@@ -122,16 +122,28 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
       mma_slab<T, H>(W1 + (size_t)(HS + s) * MB * 64, x, acc1);
     }
   } else {
-    const float *a0 = a.a0 + (size_t)row * a.De;
+    // the sum of the node's incoming edge attributes is formed here, from the node's contiguous
+    // receiver-order edge range, in edge order
     const float *dn = a.node_dense + (size_t)row * a.Dd;
     const int op = a.node_op[row];
+    const int e0 = a.in_ptr[row], e1 = a.in_ptr[row + 1];
     for (int s = 0; s < a.nslab1; ++s) {
+      float a0[V1];
+#pragma unroll
+      for (int j = 0; j < V1; ++j) a0[j] = 0.f;
+      if (s * SL1 + g * V1 < a.De)
+        for (int e = e0; e < e1; ++e) {
+          const float *xe = a.edge_feat + (size_t)e * a.De + s * SL1 + g * V1;
+#pragma unroll
+          for (int j = 0; j < V1; ++j)
+            if (s * SL1 + g * V1 + j < a.De) a0[j] += xe[j];
+        }
       vec1 x;
 #pragma unroll
       for (int j = 0; j < V1; ++j) {
         const int k = s * SL1 + g * V1 + j;
         float v = 0.f;
-        if (k < a.De) v = a0[k];
+        if (k < a.De) v = a0[j];
         else if (k < a.De + a.Tn) v = (k - a.De == op) ? 1.f : 0.f;
         else if (k < a.De + a.Tn + a.Dd) v = dn[k - a.De - a.Tn];
         x[j] = Opd1::from_float(v);

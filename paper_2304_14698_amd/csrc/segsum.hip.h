@@ -21,10 +21,6 @@ struct RowVec<float, 4> {
   }
 };
 template <>
-struct RowVec<float, 1> {
-  static __device__ __forceinline__ void load(const float *p, float *v) { v[0] = *p; }
-};
-template <>
 struct RowVec<bf16_t, 8> {
   static __device__ __forceinline__ void load(const bf16_t *p, float *v) {
     bf16x8 x = *(const bf16x8 *)p;
@@ -39,6 +35,18 @@ template <>
 __device__ __forceinline__ void store_out<float>(float *p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_out<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)v; }
+
+// Output policy of the segment-sum kernels: plain store (empty segments get zeros) or
+// accumulate (out[s] += sum; each segment has exactly one writer, so the order stays fixed).
+struct PutStore {
+  template <typename TO>
+  static __device__ __forceinline__ void put(TO *p, float v) { store_out<TO>(p, v); }
+  static constexpr bool kZeroEmpty = true;
+};
+struct PutAdd {
+  static __device__ __forceinline__ void put(float *p, float v) { *p += v; }
+  static constexpr bool kZeroEmpty = false;
+};
 
 // largest s in [0, n_seg) with ptr[s] <= row < ptr[s+1]; requires 0 <= row < ptr[n_seg]
 __device__ __forceinline__ int seg_of_row(const int32_t *ptr, int64_t n_seg, int64_t row) {
@@ -60,7 +68,7 @@ struct SegsumArgs {
   float *carry;         // [n_subtiles, 2, D]
 };
 
-template <typename TIn, typename TOut, int VEC, int RT>
+template <typename TIn, typename TOut, int VEC, int RT, typename Put = PutStore>
 __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
   const int lpr = a.D / VEC;                                   // lanes per row
   const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
     }
   }
   int seg = seg_of_row(a.ptr, a.n_seg, r0);
-  if (st == 0)                                                  // empty segments before row 0
+  if (Put::kZeroEmpty && st == 0)                               // empty segments before row 0
     for (int s = 0; s < seg; ++s)
 #pragma unroll
       for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)s * a.D + c + j, 0.f);
@@ -97,9 +105,9 @@ __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
         if (first && (int64_t)a.ptr[seg] < r0) {
 #pragma unroll
           for (int j = 0; j < VEC; ++j) a.carry[((size_t)st * 2) * a.D + c + j] = acc[j];
-        } else {
+        } else if (Put::kZeroEmpty || (int64_t)a.ptr[seg] < seg_end) {
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)seg * a.D + c + j, acc[j]);
+          for (int j = 0; j < VEC; ++j) Put::put(out + (size_t)seg * a.D + c + j, acc[j]);
         }
         first = false;
 #pragma unroll
@@ -121,11 +129,11 @@ __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
     for (int j = 0; j < VEC; ++j) a.carry[((size_t)st * 2 + 1) * a.D + c + j] = acc[j];
   } else {
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) store_out<TOut>(out + (size_t)seg * a.D + c + j, acc[j]);
+    for (int j = 0; j < VEC; ++j) Put::put(out + (size_t)seg * a.D + c + j, acc[j]);
   }
   // empty segments sitting exactly at this sub-tile's end (incl. trailing ones at n_rows)
   const int64_t here = r0 + nv;
-  if (seg_end == here) {
+  if (Put::kZeroEmpty && seg_end == here) {
     int s = seg + 1;
     while (s < a.n_seg && (int64_t)a.ptr[s + 1] == here) {
 #pragma unroll
@@ -135,14 +143,18 @@ __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
   }
 }
 
-// One 64-thread block per sub-tile: if the sub-tile's last segment starts inside it and runs on,
-// add its pieces in row order and write the segment's sum. row_seg (nullable) gives the segment
-// of each row directly; otherwise it is found by binary search in ptr.
-template <typename TOut>
-__global__ __launch_bounds__(64) void segsum_fixup(const int32_t *ptr, const int32_t *row_seg,
-                                                   int64_t n_rows, int64_t n_seg, int D, int RT,
-                                                   const float *carry, TOut *out) {
-  const int64_t st = blockIdx.x;
+// One thread per (sub-tile, 4-column slice): if the sub-tile's last segment starts inside it and
+// runs on into later sub-tiles, add that segment's pieces in row order and write its sum.
+// Loads are issued eight sub-tiles at a time; the additions keep the row order. row_seg
+// (nullable) gives the segment of each row directly; otherwise it is found by binary search.
+template <typename TOut, typename Put = PutStore>
+__global__ __launch_bounds__(256) void segsum_fixup(const int32_t *ptr, const int32_t *row_seg,
+                                                    int64_t n_rows, int64_t n_seg, int D, int RT,
+                                                    const float *carry, TOut *out) {
+  const int cpr = D / 4;                                        // column slices per sub-tile
+  const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t st = gt / cpr;
+  const int c = (int)(gt - st * cpr) * 4;
   const int64_t r0 = st * RT;
   if (r0 >= n_rows) return;
   const int64_t nv = (n_rows - r0) < RT ? (n_rows - r0) : RT;
@@ -150,9 +162,17 @@ __global__ __launch_bounds__(64) void segsum_fixup(const int32_t *ptr, const int
   const int seg = row_seg ? row_seg[last] : seg_of_row(ptr, n_seg, last);
   const int64_t beg = ptr[seg], end = ptr[seg + 1];
   if (beg < r0 || end <= r0 + RT) return;
-  for (int f = threadIdx.x; f < D; f += 64) {
-    float sum = carry[((size_t)st * 2 + 1) * D + f];
-    for (int64_t t = st + 1; t * RT < end; ++t) sum += carry[((size_t)t * 2) * D + f];
-    store_out<TOut>(out + (size_t)seg * D + f, sum);
+  f32x4 sum = *(const f32x4 *)(carry + ((size_t)st * 2 + 1) * D + c);
+  const int64_t t_end = (end + RT - 1) / RT;                    // first sub-tile past the segment
+  int64_t t = st + 1;
+  for (; t + 8 <= t_end; t += 8) {
+    f32x4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *(const f32x4 *)(carry + ((size_t)(t + i) * 2) * D + c);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += v[i];
   }
+  for (; t < t_end; ++t) sum += *(const f32x4 *)(carry + ((size_t)t * 2) * D + c);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) Put::put(out + (size_t)seg * D + c + j, sum[j]);
 }

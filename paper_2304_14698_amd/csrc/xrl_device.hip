@@ -8,6 +8,8 @@
 
 #include "heads.hip.h"
 #include "mlp2.hip.h"
+#include "mlp2_bwd.hip.h"
+#include "wgrad.hip.h"
 #include "segsum.hip.h"
 #include "xrl_internal.h"
 
@@ -51,29 +53,37 @@ void swizzle_l1(const float *W, int K, int H, int V, std::vector<T> &out) {
         }
 }
 
-// Layer-2 weights W [H, H] -> [chunk][feature block][lane][j]: the contraction index follows the
-// accumulator layout of layer 1: element j of chunk c in lane group g is input feature
-// 2V*c + 8*(j/4) + 4*g + j%4; lane l addresses output feature 32*nb + l%32.
+// "Chain" order for a weight whose contraction index is fed from an accumulator tile:
+// Wt [Kc, M] (row = contraction index, column = the index a lane addresses) ->
+// [chunk][column block][lane][j]; element j of chunk c in lane group g is contraction index
+// 2V*c + 8*(j/4) + 4*g + j%4 (the accumulator layout), lane l addresses column 32*b + l%32.
+// Used for the forward's layer 2 (Wt = W2) and for the backward's W2^T and W1^T products.
 template <typename T>
-void swizzle_l2(const float *W, int H, int V, std::vector<T> &out) {
-  const int SL = 2 * V, MB = H / 32, nc = H / SL;
-  out.assign((size_t)nc * MB * 64 * V, HostCvt<T>::cvt(0.f));
+void swizzle_chain(const float *Wt, int Kc, int M, int ld, int V, std::vector<T> &out) {
+  const int SL = 2 * V, MBk = M / 32, nc = Kc / SL;
+  out.assign((size_t)nc * MBk * 64 * V, HostCvt<T>::cvt(0.f));
   for (int c = 0; c < nc; ++c)
-    for (int nb = 0; nb < MB; ++nb)
+    for (int b = 0; b < MBk; ++b)
       for (int l = 0; l < 64; ++l)
         for (int j = 0; j < V; ++j) {
-          const int g = l / 32, f = SL * c + 8 * (j / 4) + 4 * g + j % 4, f2 = 32 * nb + l % 32;
-          out[(((size_t)c * MB + nb) * 64 + l) * V + j] = HostCvt<T>::cvt(W[(size_t)f * H + f2]);
+          const int g = l / 32, k = SL * c + 8 * (j / 4) + 4 * g + j % 4, m = 32 * b + l % 32;
+          out[(((size_t)c * MBk + b) * 64 + l) * V + j] = HostCvt<T>::cvt(Wt[(size_t)k * ld + m]);
         }
 }
 
 struct EncMlp {           // device pointers of one encoder MLP
   const void *W1s = nullptr, *W2s = nullptr;
+  const void *W2bt = nullptr, *W1bt = nullptr;   // backward: contraction over the weight's columns
   const float *b1 = nullptr, *b2 = nullptr;
   int nslab1 = 0;
 };
 
 }  // namespace
+
+// kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
+enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_COUNT };
+static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup",
+                                                  "node", "pool", "readout", "heads"};
 
 struct xrl_ctx {
   xrl_model_desc m;
@@ -90,12 +100,39 @@ struct xrl_ctx {
   size_t ws_bytes = 0;
   char *hws = nullptr;
   size_t hws_bytes = 0;
+  char *bws = nullptr;          // backward scratch
+  size_t bws_bytes = 0;
   // buffers of the last encode (inside ws)
   uint64_t enc_batch = 0;
   bool enc_saved = false;
-  float *a0 = nullptr, *pool = nullptr, *carry = nullptr, *ro_act[2] = {nullptr, nullptr};
+  float *pool = nullptr, *carry = nullptr, *ro_act[2] = {nullptr, nullptr};
   std::vector<void *> h, agg;   // h[0..R], agg[1..R] (index 0 unused)
+  // optional per-kernel timing
+  bool timing = false;
+  struct Span { int kind; hipEvent_t a, b; };
+  std::vector<Span> spans;
+  std::vector<hipEvent_t> free_events;
 };
+
+namespace {
+// Brackets the launches made during its lifetime with two events on the ctx stream.
+struct Timed {
+  xrl_ctx *c;
+  int idx = -1;
+  Timed(xrl_ctx *ctx, int kind) : c(ctx) {
+    if (!c->timing) return;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!c->free_events.empty()) { ev[i] = c->free_events.back(); c->free_events.pop_back(); }
+      else if (hipEventCreate(&ev[i]) != hipSuccess) return;
+    }
+    c->spans.push_back({kind, ev[0], ev[1]});
+    idx = (int)c->spans.size() - 1;
+    (void)hipEventRecord(ev[0], c->stream);
+  }
+  ~Timed() { if (idx >= 0) (void)hipEventRecord(c->spans[idx].b, c->stream); }
+};
+}  // namespace
 
 extern "C" void xrl_batch_release_device(xrl_batch *b) {
   if (b && b->dev.block) {
@@ -114,7 +151,7 @@ int upload_weights(xrl_ctx *c, const float *w) {
   const int V = c->elem == 2 ? 8 : 4, H = m.hidden;
   // build the fragment-ordered blob on the host
   std::vector<char> blob;
-  struct Ref { size_t w1, w2; int ns; };
+  struct Ref { size_t w1, w2, w2bt, w1bt; int ns; };
   std::vector<Ref> refs;
   auto add = [&](const MlpRef &r, bool l1_fp32) {
     Ref ref;
@@ -126,6 +163,14 @@ int upload_weights(xrl_ctx *c, const float *w) {
       memcpy(blob.data() + o, p, n);
       return o;
     };
+    // transposed copies for the backward products: W2^T [H, H] and (W1^T)[:, :2H] [H, 2H]
+    std::vector<float> w2t((size_t)H * H), w1t((size_t)H * 2 * H, 0.f);
+    for (int f = 0; f < H; ++f)
+      for (int f2 = 0; f2 < H; ++f2) w2t[(size_t)f2 * H + f] = w[r.w[1] + (size_t)f * H + f2];
+    const bool has_dx = r.d_in[0] >= 2 * H;            // edge and node MLPs; not the embed MLP
+    if (has_dx)
+      for (int k = 0; k < 2 * H; ++k)
+        for (int f = 0; f < H; ++f) w1t[(size_t)f * 2 * H + k] = w[r.w[0] + (size_t)k * H + f];
     if (c->elem == 2) {
       std::vector<uint16_t> t;
       if (l1_fp32) {
@@ -136,14 +181,22 @@ int upload_weights(xrl_ctx *c, const float *w) {
         swizzle_l1<uint16_t>(w + r.w[0], r.d_in[0], H, V, t);
         ref.w1 = put(t.data(), t.size() * 2);
       }
-      swizzle_l2<uint16_t>(w + r.w[1], H, V, t);
+      swizzle_chain<uint16_t>(w + r.w[1], H, H, H, V, t);
       ref.w2 = put(t.data(), t.size() * 2);
+      swizzle_chain<uint16_t>(w2t.data(), H, H, H, V, t);
+      ref.w2bt = put(t.data(), t.size() * 2);
+      swizzle_chain<uint16_t>(w1t.data(), H, 2 * H, 2 * H, V, t);
+      ref.w1bt = put(t.data(), t.size() * 2);
     } else {
       std::vector<float> t;
       swizzle_l1<float>(w + r.w[0], r.d_in[0], H, V, t);
       ref.w1 = put(t.data(), t.size() * 4);
-      swizzle_l2<float>(w + r.w[1], H, V, t);
+      swizzle_chain<float>(w + r.w[1], H, H, H, V, t);
       ref.w2 = put(t.data(), t.size() * 4);
+      swizzle_chain<float>(w2t.data(), H, H, H, V, t);
+      ref.w2bt = put(t.data(), t.size() * 4);
+      swizzle_chain<float>(w1t.data(), H, 2 * H, 2 * H, V, t);
+      ref.w1bt = put(t.data(), t.size() * 4);
     }
     refs.push_back(ref);
   };
@@ -162,6 +215,8 @@ int upload_weights(xrl_ctx *c, const float *w) {
   auto bind = [&](EncMlp &e, const Ref &ref, const MlpRef &r) {
     e.W1s = c->d_swz + ref.w1;
     e.W2s = c->d_swz + ref.w2;
+    e.W2bt = c->d_swz + ref.w2bt;
+    e.W1bt = c->d_swz + ref.w1bt;
     e.b1 = c->d_w + r.b[0];
     e.b2 = c->d_w + r.b[1];
     e.nslab1 = ref.ns;
@@ -194,20 +249,22 @@ int ensure_ws(xrl_ctx *c, size_t bytes) {
   return XRL_OK;
 }
 
-int ensure_hws(xrl_ctx *c, size_t bytes) {
-  if (bytes <= c->hws_bytes) return XRL_OK;
+int ensure_buf(xrl_ctx *c, char **buf, size_t *have, size_t bytes, const char *what) {
+  if (bytes <= *have) return XRL_OK;
   HIP_TRY(hipStreamSynchronize(c->stream));
-  if (c->hws) HIP_TRY(hipFree(c->hws));
-  c->hws = nullptr;
-  c->hws_bytes = 0;
-  hipError_t e = hipMalloc((void **)&c->hws, bytes);
+  if (*buf) HIP_TRY(hipFree(*buf));
+  *buf = nullptr;
+  *have = 0;
+  hipError_t e = hipMalloc((void **)buf, bytes);
   if (e != hipSuccess) {
     (void)hipGetLastError();
-    return fail(XRL_ERR_OOM, "head workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    return fail(XRL_ERR_OOM, "%s of %zu bytes: %s", what, bytes, hipGetErrorString(e));
   }
-  c->hws_bytes = bytes;
+  *have = bytes;
   return XRL_OK;
 }
+int ensure_hws(xrl_ctx *c, size_t bytes) { return ensure_buf(c, &c->hws, &c->hws_bytes, bytes, "head workspace"); }
+int ensure_bws(xrl_ctx *c, size_t bytes) { return ensure_buf(c, &c->bws, &c->bws_bytes, bytes, "backward workspace"); }
 
 __global__ void fill_zero_kernel(float *p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -235,11 +292,10 @@ int check_batch(const xrl_ctx *c, const xrl_batch *b, const char *who) {
 }
 
 // ---------------------------------------------------------------- launch helpers
-template <typename TIn, typename TOut, int VEC>
-int launch_segsum(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
-                  const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, void *out,
-                  float *carry) {
-  constexpr int RT = 16;
+template <typename TIn, typename TOut, int VEC, int RT>
+int launch_segsum_rt(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
+                     const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, void *out,
+                     float *carry) {
   if (n_seg == 0) return XRL_OK;
   if (n_rows == 0) {
     static_assert(sizeof(TOut) == 4, "zero fill below writes fp32 words");
@@ -255,13 +311,46 @@ int launch_segsum(xrl_ctx *c, const void *vals, const int32_t *perm, const int32
   const int64_t threads = nsub * (D / VEC);
   const int64_t blocks = (threads + 255) / 256;
   segsum_kernel<TIn, TOut, VEC, RT><<<dim3((unsigned)blocks), dim3(256), 0, c->stream>>>(a);
-  segsum_fixup<TOut><<<dim3((unsigned)nsub), dim3(64), 0, c->stream>>>(ptr, row_seg, n_rows, n_seg, D,
-                                                                      RT, carry, (TOut *)out);
+  const int64_t fthreads = nsub * (D / 4);
+  segsum_fixup<TOut><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
+      ptr, row_seg, n_rows, n_seg, D, RT, carry, (TOut *)out);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
 
-size_t segsum_carry_floats(int64_t n_rows, int D) { return (size_t)((n_rows + 15) / 16) * 2 * D; }
+// Rows per sub-tile: 16 keeps sixteen 16-byte loads in flight per lane; tiny inputs (under 1 MB)
+// use 4 so that they still produce a few waves per compute unit.
+inline int segsum_rt(int64_t n_rows, int D, size_t elem) { return (size_t)n_rows * D * elem < ((size_t)1 << 20) ? 4 : 16; }
+
+template <typename TIn, typename TOut, int VEC>
+int launch_segsum(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
+                  const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, void *out,
+                  float *carry) {
+  if (segsum_rt(n_rows, D, sizeof(TIn)) == 4)
+    return launch_segsum_rt<TIn, TOut, VEC, 4>(c, vals, perm, ptr, row_seg, n_rows, n_seg, D, out, carry);
+  return launch_segsum_rt<TIn, TOut, VEC, 16>(c, vals, perm, ptr, row_seg, n_rows, n_seg, D, out, carry);
+}
+
+// out[s, :] += segment sums (fp32 out, RT = 16); perm as in SegsumArgs
+template <typename TIn, int VEC>
+int launch_segsum_add(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
+                      const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, float *out, float *carry) {
+  constexpr int RT = 16;
+  if (n_seg == 0 || n_rows == 0) return XRL_OK;
+  SegsumArgs a;
+  a.vals = vals; a.perm = perm; a.ptr = ptr; a.n_rows = n_rows; a.n_seg = n_seg;
+  a.D = D; a.RT = RT; a.out = out; a.carry = carry;
+  const int64_t nsub = (n_rows + RT - 1) / RT;
+  const int64_t threads = nsub * (D / VEC);
+  segsum_kernel<TIn, float, VEC, RT, PutAdd><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(a);
+  const int64_t fthreads = nsub * (D / 4);
+  segsum_fixup<float, PutAdd><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
+      ptr, row_seg, n_rows, n_seg, D, RT, carry, out);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+size_t segsum_carry_floats(int64_t n_rows, int D) { return (size_t)((n_rows + 3) / 4) * 2 * D; }
 
 template <typename T, int H>
 int launch_mlp2_h(xrl_ctx *c, int kind, const Mlp2Args &a) {
@@ -302,9 +391,12 @@ int launch_rowmlp(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1,
     if (r.d_out[l] > dmax) dmax = r.d_out[l];
   }
   a.in1 = in1; a.in2 = in2; a.w1 = w1; a.w2 = w2; a.n_rows = n_rows; a.out = out;
-  const size_t shm = (size_t)2 * ROWMLP_ROWS * dmax * sizeof(float);
-  const unsigned blocks = (unsigned)((n_rows + ROWMLP_ROWS - 1) / ROWMLP_ROWS);
-  rowmlp_kernel<<<dim3(blocks), dim3(256), shm, c->stream>>>(a);
+  if (n_rows <= 4096) {
+    rowmlp_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)2 * dmax * sizeof(float), c->stream>>>(a);
+  } else {
+    const unsigned blocks = (unsigned)((n_rows + 7) / 8);
+    rowmlp_kernel<8><<<dim3(blocks), dim3(256), (size_t)2 * 8 * dmax * sizeof(float), c->stream>>>(a);
+  }
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
@@ -320,6 +412,234 @@ __global__ void export_rows_kernel(const T *src, const int32_t *in_ptr, int64_t 
   dst[i] = v;
 }
 
+
+template <typename T, int H>
+int launch_mlp2_bwd_h(xrl_ctx *c, int kind, const Mlp2BwdArgs &a) {
+  if (a.n_rows <= 0) return XRL_OK;
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) / 8) * 8);
+  if (kind == KIND_EMBED) mlp2_bwd_kernel<float, T, H, KIND_EMBED><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
+  else if (kind == KIND_EDGE) mlp2_bwd_kernel<T, T, H, KIND_EDGE><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
+  else mlp2_bwd_kernel<T, T, H, KIND_NODE><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+template <typename T>
+int launch_mlp2_bwd(xrl_ctx *c, int kind, Mlp2BwdArgs &a) {
+  a.n_blocks = (a.n_rows + 127) / 128;
+  switch (c->m.hidden) {
+    case 64: return launch_mlp2_bwd_h<T, 64>(c, kind, a);
+    case 128: return launch_mlp2_bwd_h<T, 128>(c, kind, a);
+    case 256: return launch_mlp2_bwd_h<T, 256>(c, kind, a);
+  }
+  return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
+}
+
+// rows per chunk / number of chunks of the weight-gradient kernels
+inline void wgrad_chunks(int64_t n_rows, int *rows_per_chunk, int *n_chunks) {
+  int64_t nc = (n_rows + 511) / 512;
+  if (nc > 512) nc = 512;
+  if (nc < 1) nc = 1;
+  int64_t rpc = (n_rows + nc - 1) / nc;
+  rpc = (rpc + 63) / 64 * 64;
+  *rows_per_chunk = (int)rpc;
+  *n_chunks = (int)((n_rows + rpc - 1) / rpc);
+  if (*n_chunks < 1) *n_chunks = 1;
+}
+inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H) {
+  int rpc, nc;
+  wgrad_chunks(n_rows, &rpc, &nc);
+  return (size_t)nc * ((Ka + 1 + 63) / 64 * 64) * H;
+}
+
+template <typename T, int H>
+int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
+  if (a.n_rows <= 0) return XRL_OK;
+  wgrad_chunks(a.n_rows, &a.rows_per_chunk, &a.n_chunks);
+  const int kt = (a.Ka + 1 + 63) / 64;
+  dim3 grid((unsigned)kt, (unsigned)a.n_chunks);
+  if (kind == WG_PLAIN) wgrad_kernel<T, H, WG_PLAIN><<<grid, dim3(256), 0, c->stream>>>(a);
+  else if (kind == WG_EDGE) wgrad_kernel<T, H, WG_EDGE><<<grid, dim3(256), 0, c->stream>>>(a);
+  else if (kind == WG_NODE) wgrad_kernel<T, H, WG_NODE><<<grid, dim3(256), 0, c->stream>>>(a);
+  else wgrad_kernel<T, H, WG_EMBED><<<grid, dim3(256), 0, c->stream>>>(a);
+  const int64_t n = (int64_t)(a.Ka + 1) * H;
+  wgrad_reduce_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream>>>(
+      a.partial, a.n_chunks, kt * 64, a.Ka, H, dW, db);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+template <typename T>
+int launch_wgrad(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
+  switch (c->m.hidden) {
+    case 64: return launch_wgrad_h<T, 64>(c, kind, a, dW, db);
+    case 128: return launch_wgrad_h<T, 128>(c, kind, a, dW, db);
+    case 256: return launch_wgrad_h<T, 256>(c, kind, a, dW, db);
+  }
+  return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
+}
+
+int launch_rowmlp_bwd(xrl_ctx *c, const MlpRef &r, bool relu_last, float *const *act, const float *dout,
+                      int64_t n_rows, float *const *dz, float *dx) {
+  if (n_rows <= 0) return XRL_OK;
+  RowMlpBwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n_layers = r.n_layers;
+  a.relu_last = relu_last ? 1 : 0;
+  int dmax = r.d_in[0];
+  for (int l = 0; l < r.n_layers; ++l) {
+    a.W[l] = c->d_w + r.w[l];
+    a.d_in[l] = r.d_in[l];
+    a.d_out[l] = r.d_out[l];
+    a.act[l] = act[l];
+    a.dz[l] = dz[l];
+    if (r.d_out[l] > dmax) dmax = r.d_out[l];
+  }
+  a.dout = dout; a.n_rows = n_rows; a.dx = dx;
+  if (n_rows <= 4096) {
+    rowmlp_bwd_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)2 * dmax * sizeof(float), c->stream>>>(a);
+  } else {
+    const unsigned blocks = (unsigned)((n_rows + 7) / 8);
+    rowmlp_bwd_kernel<8><<<dim3(blocks), dim3(256), (size_t)2 * 8 * dmax * sizeof(float), c->stream>>>(a);
+  }
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+// dW, db of every layer of a small row-MLP: x of layer 0 is [x1 | x2], of layer l > 0 act[l-1]
+int launch_small_wgrads(xrl_ctx *c, const MlpRef &r, const float *x1, int w1, const float *x2, int w2,
+                        float *const *act, float *const *dz, int64_t n_rows, float *dweights) {
+  if (n_rows <= 0) return XRL_OK;
+  for (int l = 0; l < r.n_layers; ++l) {
+    const int64_t n = (int64_t)(r.d_in[l] + 1) * r.d_out[l];
+    const float *a1 = l == 0 ? x1 : act[l - 1];
+    const int aw1 = l == 0 ? w1 : r.d_in[l];
+    small_wgrad_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream>>>(
+        a1, aw1, l == 0 ? x2 : nullptr, l == 0 ? w2 : 0, dz[l], n_rows, r.d_in[l], r.d_out[l],
+        dweights + r.w[l], dweights + r.b[l]);
+  }
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+// demb[j, :] = mask[j] ? demb[j, :] + dz[s, :] * inv_n[s] : 0 for the slots j of state s
+__global__ void demb_combine_kernel(float *demb, const float *dzs, const float *inv_n, const uint8_t *mask,
+                                    const int32_t *state_graph_ptr, int H) {
+  const int s = blockIdx.x;
+  const int j0 = state_graph_ptr[s], j1 = state_graph_ptr[s + 1];
+  const float w = inv_n[s];
+  for (int64_t i = threadIdx.x; i < (int64_t)(j1 - j0) * H; i += blockDim.x) {
+    const int j = j0 + (int)(i / H), f = (int)(i % H);
+    const size_t o = (size_t)j * H + f;
+    demb[o] = mask[j] ? demb[o] + dzs[(size_t)s * H + f] * w : 0.f;
+  }
+}
+
+// dh[i, :] = dx[graph(i), :H] (divided by the graph's node count for the mean readout)
+__global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *node_graph,
+                                       const int32_t *graph_node_ptr, int mean, int64_t N, int H, float *dh) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N * H) return;
+  const int64_t n = i / H;
+  const int f = (int)(i - n * H), gph = node_graph[n];
+  float v = dx[(size_t)gph * ldx + f];
+  if (mean) {
+    const int cnt = graph_node_ptr[gph + 1] - graph_node_ptr[gph];
+    v /= (float)(cnt > 1 ? cnt : 1);
+  }
+  dh[i] = v;
+}
+
+template <typename T>
+int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, float *dweights) {
+  const xrl_model_desc &m = c->m;
+  const int H = m.hidden, R = m.rounds, De = m.d_edge, Dg = m.d_global;
+  const int64_t N = b->N, E = b->E, G = b->G;
+  const int64_t M = N > E ? N : E;
+  const xrl_batch_device &d = b->dev;
+  // ---- scratch plan
+  size_t need = 0;
+  auto acc = [&](size_t bytes) { need += align_up(bytes); };
+  for (int i = 0; i < 3; ++i) acc((size_t)M * H * sizeof(T));      // z1, dz1, dz2
+  for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
+  for (int i = 0; i < 3; ++i) acc((size_t)N * H * 4);              // dh (two buffers), dagg
+  const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H), wgrad_partial_floats(M, H, H));
+  acc(part * 4);
+  const size_t carry_floats = segsum_carry_floats(E, H);
+  acc(carry_floats * 4);
+  acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
+  int rc = ensure_bws(c, need);
+  if (rc) return rc;
+  Bump bump{c->bws};
+  T *z1 = bump.take<T>((size_t)M * H), *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
+  T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)E * H);
+  float *dhA = bump.take<float>((size_t)N * H), *dhB = bump.take<float>((size_t)N * H);
+  float *dagg = bump.take<float>((size_t)N * H);
+  float *partial = bump.take<float>(part);
+  float *carry = bump.take<float>(carry_floats);
+  float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
+  float *rdx = bump.take<float>((size_t)G * (H + Dg));
+
+  // ---- global-update layer backward
+  float *ract[3] = {c->ro_act[0], c->ro_act[1], nullptr};
+  if ((rc = launch_rowmlp_bwd(c, c->L.readout, true, ract, d_demb, G, rdz, rdx))) return rc;
+  if ((rc = launch_small_wgrads(c, c->L.readout, c->pool, H, d.graph_global, Dg, ract, rdz, G, dweights))) return rc;
+  if (N > 0)
+    broadcast_dpool_kernel<<<dim3((unsigned)((N * H + 255) / 256)), dim3(256), 0, c->stream>>>(
+        rdx, H + Dg, d.node_graph, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, N, H, dhA);
+
+  Mlp2BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.De = De; a.Tn = m.n_op_types; a.Dd = m.n_node_dense;
+  a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
+  a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
+  a.z1 = z1; a.dz1 = dz1; a.dz2 = dz2;
+  WgradArgs wa;
+  memset(&wa, 0, sizeof(wa));
+  wa.in_ptr = d.in_ptr; wa.in_src = d.in_src; wa.in_dst = d.in_dst; wa.edge_feat = d.edge_feat;
+  wa.node_op = d.node_op; wa.node_dense = d.node_dense; wa.De = De; wa.Tn = m.n_op_types; wa.Dd = m.n_node_dense;
+  wa.partial = partial;
+  auto set_w = [&](const EncMlp &e) {
+    a.W1s = e.W1s; a.W2s = e.W2s; a.W2bt = e.W2bt; a.W1bt = e.W1bt; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
+  };
+  auto wgrads = [&](int kind, int64_t rows, int Ka, const MlpRef &r) -> int {
+    wa.n_rows = rows; wa.Ka = Ka; wa.dZ = dz1; wa.A = nullptr;
+    int rc2 = launch_wgrad<T>(c, kind, wa, dweights + r.w[0], dweights + r.b[0]);
+    if (rc2) return rc2;
+    wa.Ka = H; wa.dZ = dz2; wa.A = z1;
+    return launch_wgrad<T>(c, WG_PLAIN, wa, dweights + r.w[1], dweights + r.b[1]);
+  };
+  constexpr int PV = 16 / sizeof(T);
+  for (int r = R - 1; r >= 0; --r) {
+    // node MLP of round r+1: inputs h[r], agg[r+1]; output h[r+1]; upstream dhA
+    set_w(c->node[r]);
+    a.n_rows = N; a.h = c->h[r]; a.agg = c->agg[r + 1]; a.y = c->h[r + 1]; a.dy = dhA;
+    a.dx_a = dhB; a.dx_b = dagg;
+    if ((rc = launch_mlp2_bwd<T>(c, KIND_NODE, a))) return rc;
+    wa.h = c->h[r]; wa.agg = c->agg[r + 1];
+    if ((rc = wgrads(WG_NODE, N, 2 * H, c->L.node[r]))) return rc;
+    // edge MLP of round r+1: upstream = dagg gathered by receiver
+    set_w(c->edge[r]);
+    a.n_rows = E; a.h = c->h[r]; a.agg = nullptr; a.y = nullptr; a.dy = dagg;
+    a.dx_a = dsrc; a.dx_b = ddst;
+    if ((rc = launch_mlp2_bwd<T>(c, KIND_EDGE, a))) return rc;
+    if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r]))) return rc;
+    // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
+    if (E > 0) {
+      if ((rc = launch_segsum_add<T, PV>(c, ddst, nullptr, d.in_ptr, d.in_dst, E, N, H, dhB, carry))) return rc;
+      if ((rc = launch_segsum_add<T, PV>(c, dsrc, d.out_pos, d.out_ptr, nullptr, E, N, H, dhB, carry))) return rc;
+    }
+    std::swap(dhA, dhB);
+  }
+  // ---- node-update layer backward (weights only: its inputs are data)
+  set_w(c->embed);
+  a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
+  if ((rc = launch_mlp2_bwd<T>(c, KIND_EMBED, a))) return rc;
+  if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed))) return rc;
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
 template <typename T>
 int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   const xrl_model_desc &m = c->m;
@@ -329,7 +649,6 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   const int nh = save ? R + 1 : (R > 0 ? 2 : 1), nagg = save ? R : (R > 0 ? 1 : 0);
   size_t need = 0;
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
-  acc((size_t)N * De * 4);
   for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));
   const size_t carry_floats = std::max(std::max(segsum_carry_floats(E, De), segsum_carry_floats(N, H)),
                                        (size_t)((E + 31) / 32) * 2 * H);
@@ -340,7 +659,6 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   int rc = ensure_ws(c, need);
   if (rc) return rc;
   Bump bump{c->ws};
-  c->a0 = bump.take<float>((size_t)N * De);
   c->h.assign(R + 1, nullptr);
   c->agg.assign(R + 1, nullptr);
   std::vector<T *> hb(nh), ab(std::max(nagg, 1), nullptr);
@@ -354,22 +672,18 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   c->enc_saved = save != 0;
   const xrl_batch_device &d = b->dev;
 
-  // ---- node-update layer: sum incoming edge attrs, then the embed MLP
-  if (De % 4 == 0)
-    rc = launch_segsum<float, float, 4>(c, d.edge_feat, nullptr, d.in_ptr, d.in_dst, E, N, De, c->a0, c->carry);
-  else
-    rc = launch_segsum<float, float, 1>(c, d.edge_feat, nullptr, d.in_ptr, d.in_dst, E, N, De, c->a0, c->carry);
-  if (rc) return rc;
+  // ---- node-update layer: the embed MLP (it sums each node's incoming edge attrs itself)
   Mlp2Args a;
   memset(&a, 0, sizeof(a));
   a.De = De; a.Tn = m.n_op_types; a.Dd = m.n_node_dense;
   a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
-  a.edge_feat = d.edge_feat; a.a0 = c->a0; a.node_op = d.node_op; a.node_dense = d.node_dense;
+  a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
   a.carry = c->carry;
   auto set_w = [&](const EncMlp &e) { a.W1s = e.W1s; a.W2s = e.W2s; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1; };
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
-  if ((rc = launch_mlp2<T>(c, KIND_EMBED, a))) return rc;
+  { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
+  if (rc) return rc;
   c->h[0] = hb[0];
   T *hcur = hb[0];
   // ---- message-passing rounds
@@ -378,26 +692,32 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     T *hnext = save ? hb[r + 1] : hb[(r + 1) & 1];
     set_w(c->edge[r]);
     a.n_rows = E; a.h = hcur; a.out = aggb;
-    if ((rc = launch_mlp2<T>(c, KIND_EDGE, a))) return rc;
+    { Timed t(c, TK_EDGE); rc = launch_mlp2<T>(c, KIND_EDGE, a); }
+    if (rc) return rc;
     if (E > 0) {
+      Timed t(c, TK_EDGE_FIXUP);
       const int64_t nwt = (E + 31) / 32;
-      segsum_fixup<T><<<dim3((unsigned)nwt), dim3(64), 0, c->stream>>>(d.in_ptr, d.in_dst, E, N, H, 32,
-                                                                    c->carry, aggb);
+      const int64_t fthreads = nwt * (H / 4);
+      segsum_fixup<T><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
+          d.in_ptr, d.in_dst, E, N, H, 32, c->carry, aggb);
     }
     set_w(c->node[r]);
     a.n_rows = N; a.h = hcur; a.agg = aggb; a.out = hnext;
-    if ((rc = launch_mlp2<T>(c, KIND_NODE, a))) return rc;
+    { Timed t(c, TK_NODE); rc = launch_mlp2<T>(c, KIND_NODE, a); }
+    if (rc) return rc;
     c->h[r + 1] = hnext;
     c->agg[r + 1] = aggb;
     hcur = hnext;
   }
   // ---- global-update layer: per-graph sum (or mean), then the readout MLP
   constexpr int PV = 16 / sizeof(T);
-  rc = launch_segsum<T, float, PV>(c, hcur, nullptr, d.graph_node_ptr, d.node_graph, N, G, H, c->pool, c->carry);
+  { Timed t(c, TK_POOL);
+    rc = launch_segsum<T, float, PV>(c, hcur, nullptr, d.graph_node_ptr, d.node_graph, N, G, H, c->pool, c->carry); }
   if (rc) return rc;
   if (m.readout == XRL_READOUT_MEAN && G > 0)
     mean_scale_kernel<<<dim3((unsigned)((G * H + 255) / 256)), dim3(256), 0, c->stream>>>(c->pool, d.graph_node_ptr, G, H, 0);
-  rc = launch_rowmlp(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb, c->ro_act);
+  { Timed t(c, TK_READOUT);
+    rc = launch_rowmlp(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb, c->ro_act); }
   if (rc) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
@@ -418,6 +738,8 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
     return fail(XRL_ERR_UNSUPPORTED, "hidden = %d: the kernels cover 64, 128 and 256", model->hidden);
   if (model->mlp_layers != 2)
     return fail(XRL_ERR_UNSUPPORTED, "mlp_layers = %d: the kernels cover 2", model->mlp_layers);
+  if (model->d_edge % 4 != 0)
+    return fail(XRL_ERR_UNSUPPORTED, "d_edge = %d: the kernels need a multiple of 4", model->d_edge);
   if (model->head_hidden[0] > 512 || model->head_hidden[1] > 512 || model->d_global > 256 ||
       model->d_edge > 256 || model->n_op_types + model->n_node_dense > 1024)
     return fail(XRL_ERR_UNSUPPORTED, "head/global/edge/node attribute width beyond the kernels' range");
@@ -459,6 +781,9 @@ int xrl_destroy(xrl_ctx *c) {
   if (c->d_swz) (void)hipFree(c->d_swz);
   if (c->ws) (void)hipFree(c->ws);
   if (c->hws) (void)hipFree(c->hws);
+  if (c->bws) (void)hipFree(c->bws);
+  for (auto &sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  for (auto &e : c->free_events) (void)hipEventDestroy(e);
   delete c;
   return XRL_OK;
 }
@@ -541,6 +866,7 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   if (rc) return rc;
   float *logit = d_logit ? d_logit : (float *)c->hws;
   float *zmean = (float *)(c->hws + align_up((size_t)b->G * 4));
+  Timed t(c, TK_HEADS);
   rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, nullptr);
   if (rc) return rc;
   state_policy_kernel<<<dim3((unsigned)b->S), dim3(256), 0, c->stream>>>(
@@ -554,17 +880,92 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
 int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb,
                               const float *d_dlogp, const float *d_dvalue,
                               const float *d_dentropy, float *d_demb, float *d_dweights) {
-  (void)d_emb; (void)d_dlogp; (void)d_dvalue; (void)d_dentropy; (void)d_demb; (void)d_dweights;
   int rc = check_batch(c, b, "xrl_policy_value_backward");
   if (rc) return rc;
-  return fail(XRL_ERR_UNSUPPORTED, "xrl_policy_value_backward: not built yet");
+  if (b->S == 0) return XRL_OK;
+  if (!d_emb || !d_dlogp || !d_dvalue || !d_dentropy || !d_demb || !d_dweights)
+    return fail(XRL_ERR_NULL, "xrl_policy_value_backward: NULL device pointer");
+  const int H = c->m.hidden, h0 = c->m.head_hidden[0], h1 = c->m.head_hidden[1];
+  const int64_t G = b->G, S = b->S;
+  size_t need = 0;
+  auto acc = [&](size_t n) { need += align_up(n * 4); };
+  acc(G); acc(G); acc(S); acc(S * H); acc(S); acc(S);                 // logit logp ent zmean action value
+  acc(G * h0); acc(G * h1); acc(G);                                   // policy activations
+  acc(S * h0); acc(S * h1); acc(S);                                   // value activations
+  acc(G); acc(S);                                                     // dlogit, 1/|valid|
+  acc(G * h0); acc(G * h1); acc(G);                                   // policy dz
+  acc(S * h0); acc(S * h1); acc(S); acc(S * H);                       // value dz, dz_mean
+  if ((rc = ensure_hws(c, need))) return rc;
+  Bump bump{c->hws};
+  float *logit = bump.take<float>(G), *logp = bump.take<float>(G), *ent = bump.take<float>(S);
+  float *zmean = bump.take<float>(S * H);
+  int32_t *action = bump.take<int32_t>(S);
+  float *value = bump.take<float>(S);
+  float *pact[3] = {bump.take<float>(G * h0), bump.take<float>(G * h1), bump.take<float>(G)};
+  float *vact[3] = {bump.take<float>(S * h0), bump.take<float>(S * h1), bump.take<float>(S)};
+  float *dlogit = bump.take<float>(G), *inv_n = bump.take<float>(S);
+  float *pdz[3] = {bump.take<float>(G * h0), bump.take<float>(G * h1), bump.take<float>(G)};
+  float *vdz[3] = {bump.take<float>(S * h0), bump.take<float>(S * h1), bump.take<float>(S)};
+  float *dzs = bump.take<float>(S * H);
+  const xrl_batch_device &d = b->dev;
+  // forward of the heads, keeping every layer's output
+  if ((rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, G, logit, pact))) return rc;
+  state_policy_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(logit, d.mask, d.state_graph_ptr, d_emb,
+                                                                    H, logp, ent, action, zmean);
+  if ((rc = launch_rowmlp(c, c->L.value, false, zmean, H, nullptr, 0, S, value, vact))) return rc;
+  // backward
+  state_policy_bwd_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(logp, ent, d.mask, d.state_graph_ptr,
+                                                                        d_dlogp, d_dentropy, dlogit, inv_n);
+  if ((rc = launch_rowmlp_bwd(c, c->L.policy, false, pact, dlogit, G, pdz, d_demb))) return rc;
+  if ((rc = launch_rowmlp_bwd(c, c->L.value, false, vact, d_dvalue, S, vdz, dzs))) return rc;
+  demb_combine_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(d_demb, dzs, inv_n, d.mask,
+                                                                    d.state_graph_ptr, H);
+  if ((rc = launch_small_wgrads(c, c->L.policy, d_emb, H, nullptr, 0, pact, pdz, G, d_dweights))) return rc;
+  if ((rc = launch_small_wgrads(c, c->L.value, zmean, H, nullptr, 0, vact, vdz, S, d_dweights))) return rc;
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
 }
 
 int xrl_encode_backward(xrl_ctx *c, const xrl_batch *b, const float *d_demb, float *d_dweights) {
-  (void)d_demb; (void)d_dweights;
   int rc = check_batch(c, b, "xrl_encode_backward");
   if (rc) return rc;
-  return fail(XRL_ERR_UNSUPPORTED, "xrl_encode_backward: not built yet");
+  if (b->G == 0) return XRL_OK;
+  if (!d_demb || !d_dweights) return fail(XRL_ERR_NULL, "xrl_encode_backward: NULL device pointer");
+  if (!c->enc_saved || c->enc_batch != b->id)
+    return fail(XRL_ERR_STATE, "xrl_encode_backward: the batch's last xrl_encode did not save for backward");
+  return c->elem == 2 ? encode_backward_impl<bf16_t>(c, b, d_demb, d_dweights)
+                      : encode_backward_impl<float>(c, b, d_demb, d_dweights);
+}
+
+int xrl_set_timing(xrl_ctx *c, int enabled) {
+  if (!c) return fail(XRL_ERR_NULL, "xrl_set_timing: ctx is NULL");
+  c->timing = enabled != 0;
+  return XRL_OK;
+}
+
+int xrl_read_timing(xrl_ctx *c, const char *kernel, double *total_ms, int64_t *launches) {
+  if (!c || !kernel || !total_ms || !launches) return fail(XRL_ERR_NULL, "xrl_read_timing: NULL argument");
+  int kind = -1;
+  for (int k = 0; k < TK_COUNT; ++k)
+    if (!strcmp(kernel, kTimedNames[k])) kind = k;
+  if (kind < 0) return fail(XRL_ERR_INDEX, "xrl_read_timing: unknown kernel '%s'", kernel);
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  double tot = 0.0;
+  int64_t n = 0;
+  std::vector<xrl_ctx::Span> keep;
+  for (const auto &sp : c->spans) {
+    if (sp.kind != kind) { keep.push_back(sp); continue; }
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+    tot += ms;
+    ++n;
+    c->free_events.push_back(sp.a);
+    c->free_events.push_back(sp.b);
+  }
+  c->spans.swap(keep);
+  *total_ms = tot;
+  *launches = n;
+  return XRL_OK;
 }
 
 int xrl_segment_sum(xrl_ctx *c, const float *d_values, const int32_t *d_ptr, int64_t n_rows,
@@ -593,7 +994,10 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
   int64_t rows = N;
   int D = H;
   bool typed = true, mask_rows = false;
-  if (!strcmp(what, "a0")) { src = c->a0; D = c->m.d_edge; typed = false; }
+  if (!strcmp(what, "a0")) {   // not kept by the forward pass: recomputed with the segment-sum kernel
+    return launch_segsum<float, float, 4>(c, b->dev.edge_feat, nullptr, b->dev.in_ptr, b->dev.in_dst, b->E, N,
+                                          c->m.d_edge, d_out, c->carry);
+  }
   else if (!strcmp(what, "pool")) { src = c->pool; rows = G; typed = false; }
   else if (!strcmp(what, "h")) {
     if (round < 0 || round > R) return fail(XRL_ERR_INDEX, "h: round %d outside [0, %d]", round, R);

@@ -361,6 +361,19 @@ def test_backward_matches_central_differences(seed, readout):
     assert np.abs(grad).max() > 1e-3
 
 
+def test_absolute_term_bound_dominates_gradient():
+    """The optional bound is the same sum with every term replaced by its absolute value: it
+    dominates |grad| entry by entry and equals it where all terms share a sign (last-layer bias
+    of the value head: d value / d b = sum of d_s, here made all positive)."""
+    model, w, st, c, d, f = fd_case(25)
+    b = O.zero_grads(model)
+    _, g, _ = O.loss_and_grad(model, w, st, c, np.abs(d), f, bound=b)
+    B = O.flatten(model, b)
+    assert np.all(B >= np.abs(g) * (1 - 1e-12)) and np.all(B >= 0)
+    np.testing.assert_allclose(b["value.b2"], np.abs(d).sum(), rtol=1e-13)
+    np.testing.assert_allclose(b["value.b2"], O.unflatten(model, g)["value.b2"], rtol=1e-13)
+
+
 def test_masked_slots_get_exactly_zero_gradient():
     model, w, st, c, d, f = fd_case(23)
     emb = O.encode(model, w, st)
