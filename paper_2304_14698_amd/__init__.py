@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libxrl.so")
+LIB_PATH = os.environ.get("XRL_LIBRARY") or os.path.join(_HERE, "libxrl.so")
 _lib = None
 
 PRECISION = {"fp32": 0, "bf16": 1}

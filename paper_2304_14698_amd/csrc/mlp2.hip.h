@@ -39,6 +39,35 @@ struct Mlp2Args {
   float *carry;            // [ceil(E / 32), 2, H]           (EDGE)
 };
 
+// Raw (fp32) piece of one row's trailing attributes that lane group g feeds to slab `ts` of the
+// tail: columns [ts*2V + g*V, +V) of a row of `width` floats (width a multiple of 4), zeros
+// beyond. The loads are unconditional (out-of-range pieces re-read the row's first columns and
+// are zeroed afterwards) so that no branch or early wait separates them from other loads.
+template <int V>
+struct TailRaw {
+  f32x4 q[V / 4];
+};
+template <int V>
+__device__ __forceinline__ TailRaw<V> load_tail(const float *rowp, int width, int ts, int g) {
+  TailRaw<V> r;
+#pragma unroll
+  for (int i = 0; i < V / 4; ++i) {
+    const int k = ts * 2 * V + g * V + 4 * i;
+    const bool ok = k + 4 <= width;
+    const f32x4 v = *(const f32x4 *)(rowp + (ok ? k : 0));
+    r.q[i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  return r;
+}
+template <typename T>
+__device__ __forceinline__ typename Operand<T>::vec tail_to_operand(const TailRaw<Operand<T>::V> &r);
+template <>
+__device__ __forceinline__ f32x4 tail_to_operand<float>(const TailRaw<4> &r) { return r.q[0]; }
+template <>
+__device__ __forceinline__ bf16x8 tail_to_operand<bf16_t>(const TailRaw<8> &r) {
+  return pack_bf16x8(r.q[0][0], r.q[0][1], r.q[0][2], r.q[0][3], r.q[1][0], r.q[1][1], r.q[1][2], r.q[1][3]);
+}
+
 template <typename T, int H>
 __device__ __forceinline__ void mma_slab(const typename Operand<T>::vec *wp,
                                          const typename Operand<T>::vec &x, f32x16 *acc) {
@@ -46,6 +75,80 @@ __device__ __forceinline__ void mma_slab(const typename Operand<T>::vec *wp,
   for (int mb = 0; mb < H / 32; ++mb) {
     typename Operand<T>::vec w = wp[mb * 64];
     Operand<T>::mma(w, x, acc[mb]);
+  }
+}
+
+// Receivers of the 32 edges of a wave tile, plus those of the edges just outside it.
+struct EdgeTileMeta {
+  int dst;      // receiver of this lane's edge (lanes 32..63 mirror 0..31; rows past the end are
+                // clamped to the last edge)
+  int prev_d;   // receiver of the edge before the tile, -1 if there is none
+  int next_d;   // receiver of the edge after the tile, -1 if there is none
+};
+__device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, int64_t n_rows, int64_t row0,
+                                                       int l32) {
+  EdgeTileMeta m;
+  int64_t row = row0 + l32;
+  if (row >= n_rows) row = n_rows - 1;
+  m.dst = in_dst[row];
+  m.prev_d = row0 > 0 ? in_dst[row0 - 1] : -1;
+  m.next_d = row0 + 32 < n_rows ? in_dst[row0 + 32] : -1;
+  return m;
+}
+
+// Per-receiver sum of a wave tile of messages held as features x rows accumulators (lane = edge,
+// registers = features; edges are in receiver order, so a receiver's edges are adjacent lanes).
+// ReLU, then a segmented suffix sum across lanes by doubling: after the step of distance d a lane
+// holds the sum of its own and the next 2d - 1 edges of its receiver, so the first lane of every
+// receiver ends with the receiver's total after ceil(log2(longest run)) steps (none at all when
+// every receiver of the tile has one in-edge, one when none has more than two). The order of
+// the additions is fixed by the positions in the tile alone. The first lane of each run then
+// writes 4 consecutive features per store: to out[receiver] when the run lies inside the tile, to
+// carry[wt][0] when it began before the tile, to carry[wt][1] when it goes on after it (a run
+// covering the whole tile and open on both sides counts as begun before); segsum_fixup adds the
+// carried pieces in tile order.
+template <typename T, int H>
+__device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeTileMeta &m, int64_t wt,
+                                               int64_t n_rows, int lane, T *out, float *carry) {
+  constexpr int MB = H / 32;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int64_t row0 = wt * 32;
+  const int64_t left = n_rows - row0;
+  const int nv = left < 32 ? (int)left : 32;                    // >= 1: the caller skips empty tiles
+  const bool valid = l32 < nv;
+  const int up = __shfl_up(m.dst, 1);                           // lane 32 reads lane 31, but is a head anyway
+  const bool head = valid && (l32 == 0 || up != m.dst);
+  const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << nv);
+  // number of edges after this one that have the same receiver and lie in the tile
+  const int rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nb][r] = relu_f32(acc[nb][r]);
+  for (int d = 1; __any(rem >= d); d <<= 1) {
+    const bool take = rem >= d;
+    const int from = ((lane + d) & 63) << 2;
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        // (a copy first: bit-casting the vector-element lvalue itself reads element 0)
+        const float v = acc[nb][r];
+        const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
+        acc[nb][r] = v + (take ? t : 0.f);
+      }
+  }
+  const bool ends_tile = l32 + rem == nv - 1;
+  const bool to_c0 = head && l32 == 0 && m.prev_d == m.dst;
+  const bool to_c1 = head && !to_c0 && ends_tile && m.next_d == m.dst;
+  if (head && !to_c0 && !to_c1) {
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) store_tile_rows<T, H>(out, m.dst, true, nb, g, acc[nb]);
+  }
+  if (to_c0 || to_c1) {
+    const int64_t crow = wt * 2 + (to_c1 ? 1 : 0);
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) store_tile_rows<float, H>(carry, crow, true, nb, g, acc[nb]);
   }
 }
 
@@ -62,7 +165,6 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   using vec1 = typename Opd1::vec;
   constexpr int V1 = Opd1::V, SL1 = 2 * V1;
   static_assert(KIND == KIND_EMBED || sizeof(T1) == sizeof(T), "only EMBED mixes operand types");
-  __shared__ float zb[KIND == KIND_EDGE ? 4 : 1][32][64];
 
   // consecutive tiles stay on one XCD (blocks are dealt round-robin to the 8 XCDs), so the rows
   // a tile gathers are mostly in that XCD's L2 already
@@ -84,42 +186,53 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
     for (int r = 0; r < 16; ++r) acc1[mb][r] = a.b1[32 * mb + acc_row(r, g)];
   const vec1 *W1 = (const vec1 *)a.W1s + lane;
 
-  if constexpr (KIND == KIND_EDGE) {
-    const T *hs = (const T *)a.h + (size_t)a.in_src[row] * H + g * V;
-    const T *hd = (const T *)a.h + (size_t)a.in_dst[row] * H + g * V;
-#pragma unroll 2
-    for (int s = 0; s < HS; ++s) {
-      vec x = *(const vec *)(hs + s * SL);
-      mma_slab<T, H>(W1 + (size_t)s * MB * 64, x, acc1);
+  if constexpr (KIND == KIND_EDGE || KIND == KIND_NODE) {
+    // both H-wide parts of the input row are requested up front (one exposed latency instead
+    // of one per slab); the weight fragments are requested one slab ahead of their MFMAs
+    const T *pa, *pb;
+    bool has_b = true;
+    if constexpr (KIND == KIND_EDGE) {
+      pa = (const T *)a.h + (size_t)a.in_src[row] * H + g * V;
+      pb = (const T *)a.h + (size_t)a.in_dst[row] * H + g * V;
+    } else {
+      pa = (const T *)a.h + (size_t)row * H + g * V;
+      pb = (const T *)a.agg + (size_t)row * H + g * V;
+      has_b = a.in_ptr[row + 1] > a.in_ptr[row];                // agg rows of source nodes are unwritten
     }
-#pragma unroll 2
-    for (int s = 0; s < HS; ++s) {
-      vec x = *(const vec *)(hd + s * SL);
-      mma_slab<T, H>(W1 + (size_t)(HS + s) * MB * 64, x, acc1);
-    }
-    const float *xe = a.edge_feat + (size_t)row * a.De;
-    for (int s = 2 * HS; s < a.nslab1; ++s) {
-      vec x;
+    vec xa[HS], xb[HS];
 #pragma unroll
-      for (int j = 0; j < V; ++j) {
-        const int k = (s - 2 * HS) * SL + g * V + j;
-        x[j] = Opd::from_float(k < a.De ? xe[k] : 0.f);
+    for (int s = 0; s < HS; ++s) xa[s] = *(const vec *)(pa + s * SL);
+#pragma unroll
+    for (int s = 0; s < HS; ++s) xb[s] = *(const vec *)(pb + s * SL);
+    [[maybe_unused]] TailRaw<V> xt;
+    if constexpr (KIND == KIND_EDGE) xt = load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, 0, g);
+    vec wc[MB], wn[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) wc[mb] = W1[mb * 64];
+#pragma unroll
+    for (int s = 0; s < 2 * HS; ++s) {
+      if (s + 1 < a.nslab1) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) wn[mb] = W1[((size_t)(s + 1) * MB + mb) * 64];
       }
-      mma_slab<T, H>(W1 + (size_t)s * MB * 64, x, acc1);
+      vec x = s < HS ? xa[s < HS ? s : 0] : xb[s < HS ? 0 : s - HS];
+      if (s >= HS && !has_b) x = Opd::zero();
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) Opd::mma(wc[mb], x, acc1[mb]);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) wc[mb] = wn[mb];
     }
-  } else if constexpr (KIND == KIND_NODE) {
-    const T *hp = (const T *)a.h + (size_t)row * H + g * V;
-    const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
-    const bool has_in = a.in_ptr[row + 1] > a.in_ptr[row];      // agg rows of source nodes are unwritten
-#pragma unroll 2
-    for (int s = 0; s < HS; ++s) {
-      vec x = *(const vec *)(hp + s * SL);
-      mma_slab<T, H>(W1 + (size_t)s * MB * 64, x, acc1);
-    }
-#pragma unroll 2
-    for (int s = 0; s < HS; ++s) {
-      vec x = has_in ? *(const vec *)(ap + s * SL) : Opd::zero();
-      mma_slab<T, H>(W1 + (size_t)(HS + s) * MB * 64, x, acc1);
+    if constexpr (KIND == KIND_EDGE) {
+      const float *xe = a.edge_feat + (size_t)row * a.De;
+      for (int s = 2 * HS; s < a.nslab1; ++s) {                 // edge attributes
+        const vec x = tail_to_operand<T>(s == 2 * HS ? xt : load_tail<V>(xe, a.De, s - 2 * HS, g));
+        if (s > 2 * HS) {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) wc[mb] = W1[((size_t)s * MB + mb) * 64];
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) Opd::mma(wc[mb], x, acc1[mb]);
+      }
     }
   } else {
     // the sum of the node's incoming edge attributes is formed here, from the node's contiguous
@@ -152,28 +265,32 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
     }
   }
 
-  // ---------------- layer 2: acc2[nb] = relu(z1) W2 tile, rows x features, bias pre-loaded
+  // ---------------- layer 2, transposed as well: acc2[nb] = (W2^T relu(z1)^T) tile, features x
+  // rows, bias pre-loaded. Lane = row, and a lane's register quads are four consecutive features
+  // of its row: 8- or 16-byte stores, and for EDGE a per-receiver sum across adjacent lanes.
   f32x16 acc2[MB];
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) {
-    const float bv = a.b2[32 * nb + l32];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc2[nb][r] = bv;
+    for (int r = 0; r < 16; ++r) acc2[nb][r] = a.b2[32 * nb + acc_row(r, g)];
   }
   const vec *W2 = (const vec *)a.W2s + lane;
+  {
+    constexpr int QB = 32 / SL, NC2 = MB * QB;
+    vec wc[MB], wn[MB];
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
+    for (int nb = 0; nb < MB; ++nb) wc[nb] = W2[nb * 64];
 #pragma unroll
-    for (int q = 0; q < 32 / SL; ++q) {
-      vec z;
+    for (int c = 0; c < NC2; ++c) {
+      if (c + 1 < NC2) {
 #pragma unroll
-      for (int j = 0; j < V; ++j) z[j] = Opd::from_float(fmaxf(acc1[mb][q * V + j], 0.f));
-      const vec *wp = W2 + (size_t)(mb * (32 / SL) + q) * MB * 64;
-#pragma unroll
-      for (int nb = 0; nb < MB; ++nb) {
-        vec w = wp[nb * 64];
-        Opd::mma(z, w, acc2[nb]);
+        for (int nb = 0; nb < MB; ++nb) wn[nb] = W2[((size_t)(c + 1) * MB + nb) * 64];
       }
+      const vec z = relu_operand<T>(acc1[c / QB], c % QB);
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) Opd::mma(wc[nb], z, acc2[nb]);
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) wc[nb] = wn[nb];
     }
   }
 
@@ -182,44 +299,11 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   if constexpr (KIND != KIND_EDGE) {
 #pragma unroll
     for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t rr = row0 + acc_row(r, g);
-        if (rr < a.n_rows) out[(size_t)rr * H + 32 * nb + l32] = Opd::from_float(fmaxf(acc2[nb][r], 0.f));
-      }
+      store_tile_rows_relu<T, H>(out, row0 + l32, row0 + l32 < a.n_rows, nb, g, acc2[nb]);
   } else {
-    const int dstv = a.in_dst[row];
-    const int64_t left = a.n_rows - row0;
-    const int nv = left < 32 ? (int)left : 32;                  // <= 0 for a wave past the end
-#pragma unroll
-    for (int ch = 0; ch < H / 64; ++ch) {
-#pragma unroll
-      for (int nbl = 0; nbl < 2; ++nbl)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          zb[wave][acc_row(r, g)][32 * nbl + l32] = fmaxf(acc2[2 * ch + nbl][r], 0.f);
-      __syncthreads();
-      if (nv > 0) {
-        const int f = 64 * ch + lane;
-        float sum = 0.f;
-        int prev = __builtin_amdgcn_readlane(dstv, 0);
-        bool first = true;
-        for (int i = 0; i < nv; ++i) {
-          const int cur = __builtin_amdgcn_readlane(dstv, i);
-          if (cur != prev) {                                    // receiver `prev` is finished
-            if (first && (int64_t)a.in_ptr[prev] < row0) a.carry[((size_t)wt * 2) * H + f] = sum;
-            else out[(size_t)prev * H + f] = Opd::from_float(sum);
-            first = false;
-            sum = 0.f;
-            prev = cur;
-          }
-          sum += zb[wave][i][lane];
-        }
-        if (first && (int64_t)a.in_ptr[prev] < row0) a.carry[((size_t)wt * 2) * H + f] = sum;
-        else if ((int64_t)a.in_ptr[prev + 1] > row0 + 32) a.carry[((size_t)wt * 2 + 1) * H + f] = sum;
-        else out[(size_t)prev * H + f] = Opd::from_float(sum);
-      }
-      __syncthreads();
+    if (row0 < a.n_rows) {
+      const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, l32);
+      edge_tile_sum<T, H>(acc2, m, wt, a.n_rows, lane, out, a.carry);
     }
   }
 }

@@ -33,55 +33,17 @@ struct Mlp2BwdArgs {
                              // NODE: d h, d agg [N, H] fp32
 };
 
-// four consecutive features of one row, starting at feature f0, as floats
-template <typename T>
-__device__ __forceinline__ void load4(const T *p, float *v);
-template <>
-__device__ __forceinline__ void load4<float>(const float *p, float *v) {
-  f32x4 x = *(const f32x4 *)p;
-  v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
-}
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-template <>
-__device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, float *v) {
-  bf16x4 x = *(const bf16x4 *)p;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) v[j] = (float)x[j];
-}
-template <typename T>
-__device__ __forceinline__ void store4(T *p, const float *v);
-template <>
-__device__ __forceinline__ void store4<float>(float *p, const float *v) {
-  *(f32x4 *)p = f32x4{v[0], v[1], v[2], v[3]};
-}
-template <>
-__device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float *v) {
-  bf16x4 x;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) x[j] = (bf16_t)v[j];
-  *(bf16x4 *)p = x;
-}
-
 // Accumulator tile (features x rows) -> the 32 / (2V) operand slabs of its 32 features.
 template <typename T>
-__device__ __forceinline__ typename Operand<T>::vec acc_slab(const f32x16 &acc, int q) {
-  typename Operand<T>::vec z;
-#pragma unroll
-  for (int j = 0; j < Operand<T>::V; ++j) z[j] = Operand<T>::from_float(acc[q * Operand<T>::V + j]);
-  return z;
+__device__ __forceinline__ typename Operand<T>::vec acc_slab(const f32x16 &acc, int q);
+template <>
+__device__ __forceinline__ f32x4 acc_slab<float>(const f32x16 &acc, int q) {
+  return f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
 }
-
-// Writes a features x rows accumulator tile (feature block fb) to a row-major [rows, H] array:
-// lane = row, register quads = four consecutive features.
-template <typename TO, int H>
-__device__ __forceinline__ void store_tile_rows(TO *base, int64_t row, bool valid, int fb, int g,
-                                                const f32x16 &acc) {
-  if (!valid) return;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    float v[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-    store4<TO>(base + (size_t)row * H + 32 * fb + 8 * q + 4 * g, v);
-  }
+template <>
+__device__ __forceinline__ bf16x8 acc_slab<bf16_t>(const f32x16 &acc, int q) {
+  return pack_bf16x8(acc[8 * q], acc[8 * q + 1], acc[8 * q + 2], acc[8 * q + 3], acc[8 * q + 4],
+                     acc[8 * q + 5], acc[8 * q + 6], acc[8 * q + 7]);
 }
 
 template <typename T1, typename T, int H, int KIND>
@@ -127,12 +89,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     }
     const float *xe = a.edge_feat + (size_t)row * a.De;
     for (int s = 2 * HS; s < a.nslab1; ++s) {
-      vec x;
-#pragma unroll
-      for (int j = 0; j < V; ++j) {
-        const int k = (s - 2 * HS) * SL + g * V + j;
-        x[j] = Opd::from_float(k < a.De ? xe[k] : 0.f);
-      }
+      const vec x = tail_to_operand<T>(load_tail<V>(xe, a.De, s - 2 * HS, g));
       mma_slab<T, H>(W1 + (size_t)s * MB * 64, x, acc1);
     }
   } else if constexpr (KIND == KIND_NODE) {

@@ -1,0 +1,209 @@
+// Persistent variant of the fused two-layer MLP (edge and node kinds) for operand widths whose
+// fragment-ordered weights fit in LDS (bf16, H <= 128: at most 104 KB of the CU's 160 KB):
+// one block of NW waves per CU copies both weight matrices into LDS once and then walks over
+// wave tiles of 32 rows, so the steady state reads weights from LDS only and rows from memory.
+// Wave tiles are dealt to waves one at a time (not in block-sized groups), so a problem of only a
+// few tiles per CU still spreads evenly.
+//
+// Each wave loads the rows of its tile, computes and stores; the two waves that share a SIMD
+// overlap one's loads and epilogue with the other's MFMAs, and the row indices of a wave's next
+// tile are requested a tile ahead. (Requesting the next tile's rows ahead as well costs about 50
+// registers and measured slower; more than 8 waves per CU do not fit the register file at H = 128
+// without spilling and measured slower too.)
+// Inside a layer the weight fragments of the next contraction slab are read from LDS while the
+// MFMAs of the current slab run. Math, operand layouts and epilogues are those of mlp2_kernel.
+#pragma once
+#include "mlp2.hip.h"
+
+template <typename T, int H>
+struct TileRows {
+  using vec = typename Operand<T>::vec;
+  static constexpr int NX = 2 * (H / (2 * Operand<T>::V));   // slabs of the two H-wide parts
+  vec x[NX];
+  TailRaw<Operand<T>::V> xe;   // EDGE: the single zero-padded slab of edge attributes, raw
+  int has_in;                  // NODE: receiver has in-edges (else its agg row is unwritten)
+};
+
+struct TileIndex {
+  int src;          // EDGE: sender of this lane's edge
+  EdgeTileMeta m;   // EDGE: receivers
+};
+
+template <int KIND>
+__device__ __forceinline__ TileIndex load_index(const Mlp2Args &a, int64_t wt, int l32) {
+  TileIndex ix;
+  if constexpr (KIND == KIND_EDGE) {
+    int64_t row = wt * 32 + l32;
+    if (row >= a.n_rows) row = a.n_rows - 1;
+    ix.src = a.in_src[row];
+    ix.m = load_edge_meta(a.in_dst, a.n_rows, wt * 32, l32);
+  }
+  return ix;
+}
+
+// Issues every row load of a wave tile; all loads are unconditional (clamped) so none waits on
+// another.
+template <typename T, int H, int KIND>
+__device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32, int g, const TileIndex &ix,
+                                          TileRows<T, H> &in) {
+  using Opd = Operand<T>;
+  using vec = typename Opd::vec;
+  constexpr int V = Opd::V, SL = 2 * V, HS = H / SL;
+  int64_t row = wt * 32 + l32;
+  if (row >= a.n_rows) row = a.n_rows - 1;
+  if constexpr (KIND == KIND_EDGE) {
+    const T *hs = (const T *)a.h + (size_t)ix.src * H + g * V;
+    const T *hd = (const T *)a.h + (size_t)ix.m.dst * H + g * V;
+#pragma unroll
+    for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hs + k * SL);
+#pragma unroll
+    for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(hd + k * SL);
+    in.xe = load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, 0, g);
+  } else {
+    const T *hp = (const T *)a.h + (size_t)row * H + g * V;
+    const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
+    in.has_in = a.in_ptr[row + 1] - a.in_ptr[row];
+#pragma unroll
+    for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hp + k * SL);
+#pragma unroll
+    for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(ap + k * SL);
+  }
+}
+
+template <typename T, int H, int KIND, int NW>
+__global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
+  using Opd = Operand<T>;
+  using vec = typename Opd::vec;
+  constexpr int V = Opd::V, SL = 2 * V, MB = H / 32, HS = H / SL, QB = 32 / SL;
+  constexpr int NS1 = 2 * HS + (KIND == KIND_EDGE ? 1 : 0);   // slabs of layer 1
+  constexpr int NC2 = MB * QB;                                // chunks of layer 2
+  static_assert(KIND == KIND_EDGE || KIND == KIND_NODE, "embed keeps the streaming kernel");
+  extern __shared__ __align__(16) char smem[];
+  vec *W1l = (vec *)smem;                                  // [NS1][MB][64]
+  vec *W2l = W1l + (size_t)NS1 * MB * 64;                  // [NC2][MB][64]
+  float(*b1l)[2][16] = (float(*)[2][16])(W2l + (size_t)NC2 * MB * 64);   // [MB][lane group][16]
+  float(*b2l)[2][16] = b1l + MB;                                         // same for layer 2
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  // the wave tiles of one XCD are contiguous (blocks are dealt round-robin to the 8 XCDs); inside
+  // the XCD, tile j of a pass goes to wave j / nbx of block j % nbx
+  const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
+  const int64_t n_wt = (a.n_rows + 31) / 32;
+  const int64_t per_xcd = (n_wt + 7) / 8;
+  const int64_t t_begin = xcd * per_xcd;
+  const int64_t t_end = (t_begin + per_xcd) < n_wt ? (t_begin + per_xcd) : n_wt;
+  const int64_t stride = (int64_t)nbx * NW;
+  int64_t wt = t_begin + (int64_t)wave * nbx + lid;
+
+  // Start-up: request the first tile's indices, then all of this thread's share of the weights
+  // in one batch of loads (a load-store loop would pay one memory round trip per 8 KB), and only
+  // then move the weights into LDS.
+  TileIndex ix;
+  if (wt < t_end) ix = load_index<KIND>(a, wt, l32);
+  {
+    constexpr int NT = 64 * NW, N1 = NS1 * MB * 64, N2 = NC2 * MB * 64;
+    constexpr int C1 = (N1 + NT - 1) / NT, C2 = (N2 + NT - 1) / NT;
+    const vec *s1 = (const vec *)a.W1s, *s2 = (const vec *)a.W2s;
+    vec t1[C1], t2[C2];
+#pragma unroll
+    for (int c = 0; c < C1; ++c) t1[c] = s1[tid + c * NT < N1 ? tid + c * NT : 0];
+#pragma unroll
+    for (int c = 0; c < C2; ++c) t2[c] = s2[tid + c * NT < N2 ? tid + c * NT : 0];
+    float bb1 = 0.f, bb2 = 0.f;
+    if (tid < MB * 32) {                                     // biases in accumulator order
+      bb1 = a.b1[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+      bb2 = a.b2[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+    }
+#pragma unroll
+    for (int c = 0; c < C1; ++c)
+      if (tid + c * NT < N1) W1l[tid + c * NT] = t1[c];
+#pragma unroll
+    for (int c = 0; c < C2; ++c)
+      if (tid + c * NT < N2) W2l[tid + c * NT] = t2[c];
+    if (tid < MB * 32) {
+      b1l[tid / 32][(tid / 16) % 2][tid % 16] = bb1;
+      b2l[tid / 32][(tid / 16) % 2][tid % 16] = bb2;
+    }
+  }
+  __syncthreads();
+
+  for (; wt < t_end; wt += stride) {
+    // the weights in LDS never change, but keeping all their fragments in registers across
+    // tiles would not fit: make the compiler re-read them from LDS in every tile
+    asm volatile("" ::: "memory");
+    TileRows<T, H> in;
+    load_rows<T, H, KIND>(a, wt, l32, g, ix, in);
+    [[maybe_unused]] const EdgeTileMeta meta = ix.m;
+    ix = load_index<KIND>(a, wt + stride < t_end ? wt + stride : wt, l32);
+    // ---------------- layer 1 (features x rows)
+    f32x16 acc1[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
+    if constexpr (KIND == KIND_NODE) {
+      if (in.has_in == 0)
+#pragma unroll
+        for (int k = 0; k < HS; ++k) in.x[HS + k] = Opd::zero();
+    }
+    [[maybe_unused]] vec xe;
+    if constexpr (KIND == KIND_EDGE) xe = tail_to_operand<T>(in.xe);
+    {
+      vec wc[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) wc[mb] = W1l[mb * 64 + lane];
+#pragma unroll
+      for (int s = 0; s < NS1; ++s) {
+        vec wn[MB];
+        if (s + 1 < NS1) {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) wn[mb] = W1l[((s + 1) * MB + mb) * 64 + lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          if (KIND == KIND_EDGE && s == 2 * HS) Opd::mma(wc[mb], xe, acc1[mb]);
+          else Opd::mma(wc[mb], in.x[s < 2 * HS ? s : 0], acc1[mb]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 1 < NS1) {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) wc[mb] = wn[mb];
+        }
+      }
+    }
+    // ---------------- layer 2 (features x rows)
+    f32x16 acc2[MB];
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) acc2[nb] = *(const f32x16 *)&b2l[nb][g][0];
+    {
+      vec wc[MB];
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) wc[nb] = W2l[nb * 64 + lane];
+#pragma unroll
+      for (int c = 0; c < NC2; ++c) {
+        vec wn[MB];
+        if (c + 1 < NC2) {
+#pragma unroll
+          for (int nb = 0; nb < MB; ++nb) wn[nb] = W2l[((c + 1) * MB + nb) * 64 + lane];
+        }
+        const vec z = relu_operand<T>(acc1[c / QB], c % QB);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb) Opd::mma(wc[nb], z, acc2[nb]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (c + 1 < NC2) {
+#pragma unroll
+          for (int nb = 0; nb < MB; ++nb) wc[nb] = wn[nb];
+        }
+      }
+    }
+    // ---------------- epilogue
+    T *out = (T *)a.out;
+    if constexpr (KIND == KIND_NODE) {
+      const int64_t row = wt * 32 + l32;
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) store_tile_rows_relu<T, H>(out, row, row < a.n_rows, nb, g, acc2[nb]);
+    } else {
+      edge_tile_sum<T, H>(acc2, meta, wt, a.n_rows, lane, out, a.carry);
+    }
+  }
+}

@@ -49,3 +49,108 @@ struct Operand<bf16_t> {
 
 // row of accumulator register r inside its 32x32 tile, for lane group g
 __device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// ReLU + conversion of V consecutive accumulator registers (chunk q of a 32x32 tile) into one
+// MFMA operand. For bf16 the values are converted first and the ReLU is taken on the packed
+// pairs as 16-bit integers (a negative bf16 has its sign bit set, i.e. is a negative int16;
+// max(x, 0) maps it -- and -0 -- to +0 and leaves non-negative values untouched): half the
+// instructions of ReLU-then-convert.
+// max(x, 0) as a single integer max on the bit pattern (a negative float is a negative int32;
+// -0 becomes +0). fmaxf costs a second instruction that quiets a possible signalling NaN first.
+__device__ __forceinline__ float relu_f32(float x) {
+  const int b = __float_as_int(x);
+  return __int_as_float(b > 0 ? b : 0);
+}
+
+template <typename T>
+__device__ __forceinline__ typename Operand<T>::vec relu_operand(const f32x16 &acc, int q);
+template <>
+__device__ __forceinline__ f32x4 relu_operand<float>(const f32x16 &acc, int q) {
+  f32x4 z;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) z[j] = relu_f32(acc[4 * q + j]);
+  return z;
+}
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Two floats -> two bf16 (round to nearest even), `lo` in bits 15..0, `hi` in bits 31..16. Written
+// as a two-element vector conversion, which the compiler selects as a single v_cvt_pk_bf16_f32
+// (element-wise conversions of longer vectors cost one instruction per element plus a byte
+// permute per pair). Deliberately not inline assembly: the compiler does not see the registers
+// an asm statement reads, and so would not insert the wait states the hardware needs between a
+// matrix instruction and the first read of its result.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned cvt_pk_bf16(float lo, float hi) {
+  const f32x2 f = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+__device__ __forceinline__ bf16x8 pack_bf16x8(float x0, float x1, float x2, float x3, float x4, float x5,
+                                              float x6, float x7) {
+  const u32x4 u = {cvt_pk_bf16(x0, x1), cvt_pk_bf16(x2, x3), cvt_pk_bf16(x4, x5), cvt_pk_bf16(x6, x7)};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+template <>
+__device__ __forceinline__ bf16x8 relu_operand<bf16_t>(const f32x16 &acc, int q) {
+  const bf16x8 z = pack_bf16x8(acc[8 * q], acc[8 * q + 1], acc[8 * q + 2], acc[8 * q + 3], acc[8 * q + 4],
+                               acc[8 * q + 5], acc[8 * q + 6], acc[8 * q + 7]);
+  s16x8 s = __builtin_bit_cast(s16x8, z);
+  const s16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  s = __builtin_elementwise_max(s, zero);
+  return __builtin_bit_cast(bf16x8, s);
+}
+
+// four consecutive features of one row, starting at feature f0, as floats
+template <typename T>
+__device__ __forceinline__ void load4(const T *p, float *v);
+template <>
+__device__ __forceinline__ void load4<float>(const float *p, float *v) {
+  f32x4 x = *(const f32x4 *)p;
+  v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+}
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+template <>
+__device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, float *v) {
+  bf16x4 x = *(const bf16x4 *)p;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = (float)x[j];
+}
+template <typename T>
+__device__ __forceinline__ void store4(T *p, const float *v);
+template <>
+__device__ __forceinline__ void store4<float>(float *p, const float *v) {
+  *(f32x4 *)p = f32x4{v[0], v[1], v[2], v[3]};
+}
+template <>
+__device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float *v) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  *(u32x2 *)p = u32x2{cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3])};
+}
+
+// Writes a features x rows accumulator tile (feature block fb) to a row-major [rows, H] array:
+// lane = row, register quads = four consecutive features.
+template <typename TO, int H>
+__device__ __forceinline__ void store_tile_rows(TO *base, int64_t row, bool valid, int fb, int g,
+                                                const f32x16 &acc) {
+  if (!valid) return;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float v[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+    store4<TO>(base + (size_t)row * H + 32 * fb + 8 * q + 4 * g, v);
+  }
+}
+
+// Same with ReLU applied on the way out.
+template <typename TO, int H>
+__device__ __forceinline__ void store_tile_rows_relu(TO *base, int64_t row, bool valid, int fb, int g,
+                                                     const f32x16 &acc) {
+  if (!valid) return;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float v[4] = {relu_f32(acc[4 * q]), relu_f32(acc[4 * q + 1]), relu_f32(acc[4 * q + 2]),
+                  relu_f32(acc[4 * q + 3])};
+    store4<TO>(base + (size_t)row * H + 32 * fb + 8 * q + 4 * g, v);
+  }
+}

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -9,6 +10,7 @@
 #include "heads.hip.h"
 #include "mlp2.hip.h"
 #include "mlp2_bwd.hip.h"
+#include "mlp2p.hip.h"
 #include "wgrad.hip.h"
 #include "segsum.hip.h"
 #include "xrl_internal.h"
@@ -90,6 +92,10 @@ struct xrl_ctx {
   Layout L;
   hipStream_t stream = nullptr;
   int elem = 4;                 // bytes per stored activation / operand
+  int n_cu = 256;               // compute units of the device
+  int max_lds = 65536;          // LDS bytes one block may use
+  bool use_persistent = true;   // LDS-resident-weights MLP kernels where they apply
+  int64_t p_min_rows = 0;       // development switch: smallest row count for the persistent kernels
   float *d_w = nullptr;         // flat fp32 weights
   char *d_swz = nullptr;        // fragment-ordered encoder weights
   size_t swz_bytes = 0;
@@ -363,8 +369,51 @@ int launch_mlp2_h(xrl_ctx *c, int kind, const Mlp2Args &a) {
   return XRL_OK;
 }
 
+// Persistent LDS-resident-weights variant (bf16, H <= 128, edge and node kinds).
+inline size_t mlp2p_lds_bytes(int H, int nslab1) {
+  const int MB = H / 32, HS = H / 16;
+  return ((size_t)nslab1 * MB + (size_t)HS * MB) * 1024 + (size_t)MB * 256;
+}
+
+constexpr int kPersistWaves = 8;
+
+template <int H, int KIND>
+int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
+  constexpr int NW = kPersistWaves;
+  auto kern = mlp2p_kernel<bf16_t, H, KIND, NW>;
+  static bool attr_set = false;          // one attribute per kernel instantiation
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const int64_t n_wt = (a.n_rows + 31) / 32;
+  a.n_blocks = n_wt;
+  int64_t grid = ((n_wt + NW - 1) / NW + 7) / 8 * 8;
+  const int64_t cap = (int64_t)c->n_cu / 8 * 8;
+  if (grid > cap) grid = cap;
+  kern<<<dim3((unsigned)grid), dim3(64 * NW), lds, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+template <int H>
+int launch_mlp2p(xrl_ctx *c, int kind, Mlp2Args &a) {
+  const size_t lds = mlp2p_lds_bytes(H, a.nslab1);
+  if (kind == KIND_EDGE) return launch_mlp2p_k<H, KIND_EDGE>(c, a, lds);
+  return launch_mlp2p_k<H, KIND_NODE>(c, a, lds);
+}
+
+inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
+  const int H = c->m.hidden;
+  if (c->elem != 2 || kind == KIND_EMBED || H > 128 || a.n_rows <= 0 || !c->use_persistent) return false;
+  if (a.n_rows < c->p_min_rows) return false;
+  if (kind == KIND_EDGE && a.nslab1 != 2 * (H / 16) + 1) return false;   // edge attrs must fit one slab
+  return mlp2p_lds_bytes(H, a.nslab1) <= (size_t)c->max_lds;
+}
+
 template <typename T>
 int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
+  if (mlp2p_applies(c, kind, a)) return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
   a.n_blocks = (a.n_rows + 127) / 128;
   switch (c->m.hidden) {
     case 64: return launch_mlp2_h<T, 64>(c, kind, a);
@@ -755,6 +804,16 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   c->L = L;
   c->stream = (hipStream_t)hip_stream;
   c->elem = model->precision == XRL_PREC_BF16 ? 2 : 4;
+  if (const char *e = getenv("XRL_NO_PERSISTENT")) c->use_persistent = !(e[0] == '1');
+  c->p_min_rows = 8192;
+  if (const char *e = getenv("XRL_P_MIN_ROWS")) c->p_min_rows = atoll(e);
+  {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) c->n_cu = v;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) c->max_lds = v;
+    }
+  }
   e = hipMalloc((void **)&c->d_w, sizeof(float) * L.total);
   if (e != hipSuccess) {
     delete c;
