@@ -96,6 +96,10 @@ typedef struct xrl_packed_view {
   const int32_t *out_pos;         /* [E] receiver-order position of each out-edge, by sender  */
   const int32_t *node_graph;      /* [N] graph id of each node                                */
   const float *edge_feat;         /* [E, d_edge] in receiver order                            */
+  int64_t n_tiles;                /* edge tiles of the message kernels                        */
+  const int32_t *tile_ptr;        /* [n_tiles+1] first receiver-order edge of each tile: 1..32
+                                     edges per tile, cut at receiver boundaries except inside a
+                                     receiver with more than 32 in-edges                      */
 } xrl_packed_view;
 
 typedef struct xrl_ctx xrl_ctx;     /* device weights + workspaces, bound to one HIP stream    */

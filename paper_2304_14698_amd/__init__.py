@@ -45,7 +45,8 @@ class PackedView(C.Structure):
                 ("state_graph_ptr", C.c_void_p), ("graph_node_ptr", C.c_void_p),
                 ("in_ptr", C.c_void_p), ("in_src", C.c_void_p), ("in_dst", C.c_void_p),
                 ("in_eid", C.c_void_p), ("out_ptr", C.c_void_p), ("out_pos", C.c_void_p),
-                ("node_graph", C.c_void_p), ("edge_feat", C.c_void_p)]
+                ("node_graph", C.c_void_p), ("edge_feat", C.c_void_p),
+                ("n_tiles", C.c_int64), ("tile_ptr", C.c_void_p)]
 
 
 EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
@@ -176,6 +177,7 @@ class Batch:
                     in_dst=grab(v.in_dst, self.E), in_eid=grab(v.in_eid, self.E),
                     out_ptr=grab(v.out_ptr, self.N + 1), out_pos=grab(v.out_pos, self.E),
                     node_graph=grab(v.node_graph, self.N),
+                    tile_ptr=grab(v.tile_ptr, int(v.n_tiles) + 1),
                     edge_feat=grab(v.edge_feat, self.E * De, C.c_float, np.float32).reshape(self.E, De))
 
     def free(self):

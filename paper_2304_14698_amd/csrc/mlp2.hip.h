@@ -36,7 +36,9 @@ struct Mlp2Args {
   const float *node_dense; // [N, Dd]                        (EMBED)
   int De, Tn, Dd;
   void *out;               // [N, H] operand type
-  float *carry;            // [ceil(E / 32), 2, H]           (EDGE)
+  float *carry;            // [n_tiles, 2, H]                (EDGE)
+  const int32_t *tile_ptr; // [n_tiles + 1] first edge of each edge tile (EDGE)
+  int64_t n_tiles;         //                                (EDGE)
 };
 
 // Raw (fp32) piece of one row's trailing attributes that lane group g feeds to slab `ts` of the
@@ -78,21 +80,20 @@ __device__ __forceinline__ void mma_slab(const typename Operand<T>::vec *wp,
   }
 }
 
-// Receivers of the 32 edges of a wave tile, plus those of the edges just outside it.
+// Receivers of the edges of a wave tile (edges [e0, e0 + nv), nv <= 32, from the packer's tile
+// table), plus those of the edges just outside it.
 struct EdgeTileMeta {
-  int dst;      // receiver of this lane's edge (lanes 32..63 mirror 0..31; rows past the end are
-                // clamped to the last edge)
+  int dst;      // receiver of this lane's edge (lanes 32..63 mirror 0..31; lanes past the tile's
+                // last edge repeat it)
   int prev_d;   // receiver of the edge before the tile, -1 if there is none
   int next_d;   // receiver of the edge after the tile, -1 if there is none
 };
-__device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, int64_t n_rows, int64_t row0,
+__device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, int64_t n_rows, int64_t e0, int nv,
                                                        int l32) {
   EdgeTileMeta m;
-  int64_t row = row0 + l32;
-  if (row >= n_rows) row = n_rows - 1;
-  m.dst = in_dst[row];
-  m.prev_d = row0 > 0 ? in_dst[row0 - 1] : -1;
-  m.next_d = row0 + 32 < n_rows ? in_dst[row0 + 32] : -1;
+  m.dst = in_dst[e0 + (l32 < nv ? l32 : nv - 1)];
+  m.prev_d = e0 > 0 ? in_dst[e0 - 1] : -1;
+  m.next_d = e0 + nv < n_rows ? in_dst[e0 + nv] : -1;
   return m;
 }
 
@@ -108,14 +109,11 @@ __device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, in
 // covering the whole tile and open on both sides counts as begun before); segsum_fixup adds the
 // carried pieces in tile order.
 template <typename T, int H>
-__device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeTileMeta &m, int64_t wt,
-                                               int64_t n_rows, int lane, T *out, float *carry) {
+__device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeTileMeta &m, int64_t wt, int nv,
+                                               int lane, T *out, float *carry) {
   constexpr int MB = H / 32;
   const int l32 = lane & 31, g = lane >> 5;
-  const int64_t row0 = wt * 32;
-  const int64_t left = n_rows - row0;
-  const int nv = left < 32 ? (int)left : 32;                    // >= 1: the caller skips empty tiles
-  const bool valid = l32 < nv;
+  const bool valid = l32 < nv;                                  // nv >= 1
   const int up = __shfl_up(m.dst, 1);                           // lane 32 reads lane 31, but is a head anyway
   const bool head = valid && (l32 == 0 || up != m.dst);
   const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << nv);
@@ -173,9 +171,15 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   if (tile >= a.n_blocks) return;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
-  const int64_t wt = tile * 4 + wave;                           // wave tile = 32 rows
-  const int64_t row0 = wt * 32;
-  int64_t row = row0 + l32;
+  const int64_t wt = tile * 4 + wave;                           // wave tile: 32 rows, or an edge tile
+  int64_t row0 = wt * 32;
+  [[maybe_unused]] int nv = 32;
+  if constexpr (KIND == KIND_EDGE) {
+    if (wt >= a.n_tiles) return;
+    row0 = a.tile_ptr[wt];
+    nv = a.tile_ptr[wt + 1] - (int)row0;
+  }
+  int64_t row = row0 + (l32 < nv ? l32 : nv - 1);
   if (row >= a.n_rows) row = a.n_rows - 1;                      // clamp loads; stores are guarded
 
   // ---------------- layer 1: acc1[mb] = (W1^T x^T) tile, features x rows, bias pre-loaded
@@ -301,9 +305,7 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
     for (int nb = 0; nb < MB; ++nb)
       store_tile_rows_relu<T, H>(out, row0 + l32, row0 + l32 < a.n_rows, nb, g, acc2[nb]);
   } else {
-    if (row0 < a.n_rows) {
-      const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, l32);
-      edge_tile_sum<T, H>(acc2, m, wt, a.n_rows, lane, out, a.carry);
-    }
+    const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, nv, l32);
+    edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry);
   }
 }

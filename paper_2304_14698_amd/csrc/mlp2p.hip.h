@@ -25,6 +25,7 @@ struct TileRows {
 };
 
 struct TileIndex {
+  int e0, nv;       // EDGE: the tile's edges are [e0, e0 + nv)
   int src;          // EDGE: sender of this lane's edge
   EdgeTileMeta m;   // EDGE: receivers
 };
@@ -33,10 +34,10 @@ template <int KIND>
 __device__ __forceinline__ TileIndex load_index(const Mlp2Args &a, int64_t wt, int l32) {
   TileIndex ix;
   if constexpr (KIND == KIND_EDGE) {
-    int64_t row = wt * 32 + l32;
-    if (row >= a.n_rows) row = a.n_rows - 1;
-    ix.src = a.in_src[row];
-    ix.m = load_edge_meta(a.in_dst, a.n_rows, wt * 32, l32);
+    ix.e0 = a.tile_ptr[wt];
+    ix.nv = a.tile_ptr[wt + 1] - ix.e0;
+    ix.src = a.in_src[ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1)];
+    ix.m = load_edge_meta(a.in_dst, a.n_rows, ix.e0, ix.nv, l32);
   }
   return ix;
 }
@@ -49,9 +50,8 @@ __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32
   using Opd = Operand<T>;
   using vec = typename Opd::vec;
   constexpr int V = Opd::V, SL = 2 * V, HS = H / SL;
-  int64_t row = wt * 32 + l32;
-  if (row >= a.n_rows) row = a.n_rows - 1;
   if constexpr (KIND == KIND_EDGE) {
+    const int64_t row = ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1);
     const T *hs = (const T *)a.h + (size_t)ix.src * H + g * V;
     const T *hd = (const T *)a.h + (size_t)ix.m.dst * H + g * V;
 #pragma unroll
@@ -60,6 +60,8 @@ __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32
     for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(hd + k * SL);
     in.xe = load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, 0, g);
   } else {
+    int64_t row = wt * 32 + l32;
+    if (row >= a.n_rows) row = a.n_rows - 1;
     const T *hp = (const T *)a.h + (size_t)row * H + g * V;
     const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
     in.has_in = a.in_ptr[row + 1] - a.in_ptr[row];
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   // the wave tiles of one XCD are contiguous (blocks are dealt round-robin to the 8 XCDs); inside
   // the XCD, tile j of a pass goes to wave j / nbx of block j % nbx
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
-  const int64_t n_wt = (a.n_rows + 31) / 32;
+  const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
   const int64_t per_xcd = (n_wt + 7) / 8;
   const int64_t t_begin = xcd * per_xcd;
   const int64_t t_end = (t_begin + per_xcd) < n_wt ? (t_begin + per_xcd) : n_wt;
@@ -134,6 +136,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     TileRows<T, H> in;
     load_rows<T, H, KIND>(a, wt, l32, g, ix, in);
     [[maybe_unused]] const EdgeTileMeta meta = ix.m;
+    [[maybe_unused]] const int nv = ix.nv;
     ix = load_index<KIND>(a, wt + stride < t_end ? wt + stride : wt, l32);
     // ---------------- layer 1 (features x rows)
     f32x16 acc1[MB];
@@ -203,7 +206,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
 #pragma unroll
       for (int nb = 0; nb < MB; ++nb) store_tile_rows_relu<T, H>(out, row, row < a.n_rows, nb, g, acc2[nb]);
     } else {
-      edge_tile_sum<T, H>(acc2, meta, wt, a.n_rows, lane, out, a.carry);
+      edge_tile_sum<T, H>(acc2, meta, wt, nv, lane, out, a.carry);
     }
   }
 }

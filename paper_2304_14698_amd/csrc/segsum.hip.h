@@ -176,3 +176,26 @@ __global__ __launch_bounds__(256) void segsum_fixup(const int32_t *ptr, const in
 #pragma unroll
   for (int j = 0; j < 4; ++j) Put::put(out + (size_t)seg * D + c + j, sum[j]);
 }
+
+// The same fix-up for the message kernels' edge tiles, whose boundaries come from the packer's
+// tile table: one thread per (tile, 4-column slice). Only receivers with more than 32 in-edges are
+// ever cut by a tile boundary, so this kernel is launched only for batches that have one.
+template <typename TOut>
+__global__ __launch_bounds__(256) void edge_tile_fixup(const int32_t *tile_ptr, int64_t n_tiles,
+                                                       const int32_t *in_ptr, const int32_t *in_dst, int D,
+                                                       const float *carry, TOut *out) {
+  const int cpr = D / 4;
+  const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t st = gt / cpr;
+  const int c = (int)(gt - st * cpr) * 4;
+  if (st >= n_tiles) return;
+  const int64_t r0 = tile_ptr[st], r1 = tile_ptr[st + 1];
+  const int seg = in_dst[r1 - 1];
+  const int64_t beg = in_ptr[seg], end = in_ptr[seg + 1];
+  if (beg < r0 || end <= r1) return;
+  f32x4 sum = *(const f32x4 *)(carry + ((size_t)st * 2 + 1) * D + c);
+  for (int64_t t = st + 1; t < n_tiles && tile_ptr[t] < end; ++t)
+    sum += *(const f32x4 *)(carry + ((size_t)t * 2) * D + c);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) store_out<TOut>(out + (size_t)seg * D + c + j, sum[j]);
+}

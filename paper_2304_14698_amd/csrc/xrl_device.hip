@@ -386,7 +386,7 @@ int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  const int64_t n_wt = (a.n_rows + 31) / 32;
+  const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
   a.n_blocks = n_wt;
   int64_t grid = ((n_wt + NW - 1) / NW + 7) / 8 * 8;
   const int64_t cap = (int64_t)c->n_cu / 8 * 8;
@@ -414,7 +414,7 @@ inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
 template <typename T>
 int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
   if (mlp2p_applies(c, kind, a)) return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
-  a.n_blocks = (a.n_rows + 127) / 128;
+  a.n_blocks = kind == KIND_EDGE ? (a.n_tiles + 3) / 4 : (a.n_rows + 127) / 128;
   switch (c->m.hidden) {
     case 64: return launch_mlp2_h<T, 64>(c, kind, a);
     case 128: return launch_mlp2_h<T, 128>(c, kind, a);
@@ -694,13 +694,14 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   const xrl_model_desc &m = c->m;
   const int H = m.hidden, R = m.rounds, De = m.d_edge;
   const int64_t N = b->N, E = b->E, G = b->G;
+  const int64_t n_tiles = (int64_t)b->tile_ptr.size() - 1;
   // ---- workspace plan
   const int nh = save ? R + 1 : (R > 0 ? 2 : 1), nagg = save ? R : (R > 0 ? 1 : 0);
   size_t need = 0;
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
   for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));
   const size_t carry_floats = std::max(std::max(segsum_carry_floats(E, De), segsum_carry_floats(N, H)),
-                                       (size_t)((E + 31) / 32) * 2 * H);
+                                       (size_t)n_tiles * 2 * H);
   acc(carry_floats * 4);
   acc((size_t)G * H * 4);
   acc((size_t)G * H * 4);
@@ -727,7 +728,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   a.De = De; a.Tn = m.n_op_types; a.Dd = m.n_node_dense;
   a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
   a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
-  a.carry = c->carry;
+  a.carry = c->carry; a.tile_ptr = d.tile_ptr; a.n_tiles = n_tiles;
   auto set_w = [&](const EncMlp &e) { a.W1s = e.W1s; a.W2s = e.W2s; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1; };
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
@@ -743,12 +744,11 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     a.n_rows = E; a.h = hcur; a.out = aggb;
     { Timed t(c, TK_EDGE); rc = launch_mlp2<T>(c, KIND_EDGE, a); }
     if (rc) return rc;
-    if (E > 0) {
+    if (b->n_split_tiles > 0) {         // only a receiver with more than 32 in-edges spans tiles
       Timed t(c, TK_EDGE_FIXUP);
-      const int64_t nwt = (E + 31) / 32;
-      const int64_t fthreads = nwt * (H / 4);
-      segsum_fixup<T><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
-          d.in_ptr, d.in_dst, E, N, H, 32, c->carry, aggb);
+      const int64_t fthreads = n_tiles * (H / 4);
+      edge_tile_fixup<T><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
+          d.tile_ptr, n_tiles, d.in_ptr, d.in_dst, H, c->carry, aggb);
     }
     set_w(c->node[r]);
     a.n_rows = N; a.h = hcur; a.agg = aggb; a.out = hnext;
@@ -858,7 +858,8 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
                o_inp = plan((N + 1) * 4), o_ins = plan(E * 4), o_ind = plan(E * 4),
                o_outp = plan((N + 1) * 4), o_outpos = plan(E * 4), o_ng = plan(N * 4),
                o_nd = plan((size_t)N * Dd * 4), o_ef = plan((size_t)E * De * 4),
-               o_gg = plan((size_t)G * Dg * 4), o_mask = plan(G);
+               o_gg = plan((size_t)G * Dg * 4), o_mask = plan(G),
+               o_tile = plan(b->tile_ptr.size() * 4);
   char *blk = nullptr;
   hipError_t e = hipMalloc((void **)&blk, off);
   if (e != hipSuccess) {
@@ -886,6 +887,7 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   HIP_TRY(cp(o_ef, b->edge_feat.data(), (size_t)E * De * 4));
   HIP_TRY(cp(o_gg, b->graph_global.data(), (size_t)G * Dg * 4));
   HIP_TRY(cp(o_mask, b->mask.data(), G));
+  HIP_TRY(cp(o_tile, b->tile_ptr.data(), b->tile_ptr.size() * 4));
   HIP_TRY(hipStreamSynchronize(c->stream));
   d.state_graph_ptr = (int32_t *)(blk + o_sgp);
   d.graph_node_ptr = (int32_t *)(blk + o_gnp);
@@ -900,6 +902,7 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   d.edge_feat = (float *)(blk + o_ef);
   d.graph_global = (float *)(blk + o_gg);
   d.mask = (uint8_t *)(blk + o_mask);
+  d.tile_ptr = (int32_t *)(blk + o_tile);
   b->uploaded = true;
   return XRL_OK;
 }

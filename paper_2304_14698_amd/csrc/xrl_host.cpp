@@ -239,6 +239,30 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
       std::vector<int32_t> cur(b->out_ptr.begin(), b->out_ptr.end() - 1);
       for (int64_t p = 0; p < E; ++p) b->out_pos[cur[b->in_src[p]]++] = (int32_t)p;
     }
+    {  // Edge tiles of the message kernels: consecutive receiver-order edges, at most 32 per tile,
+       // cut at receiver boundaries so that a receiver's in-edges share a tile. Only a receiver
+       // with more than 32 in-edges is split (into full tiles plus a remainder that later
+       // receivers may join); its pieces are recombined by the carry fix-up.
+      b->tile_ptr.clear();
+      b->tile_ptr.push_back(0);
+      b->n_split_tiles = 0;
+      int32_t fill = 0;                 // edges in the open tile
+      for (int64_t n = 0; n < N; ++n) {
+        int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
+        if (d == 0) continue;
+        if (fill + d > 32 && fill > 0) {
+          b->tile_ptr.push_back(b->in_ptr[n]);
+          fill = 0;
+        }
+        while (d > 32) {                // fill == 0 here
+          b->tile_ptr.push_back(b->tile_ptr.back() + 32);
+          b->n_split_tiles++;
+          d -= 32;
+        }
+        fill += d;
+      }
+      if (fill > 0) b->tile_ptr.push_back((int32_t)E);
+    }
   } catch (const std::bad_alloc &) {
     delete b;
     return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
@@ -269,6 +293,8 @@ int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *v) {
   v->out_pos = b->out_pos.data();
   v->node_graph = b->node_graph.data();
   v->edge_feat = b->edge_feat.data();
+  v->n_tiles = (int64_t)b->tile_ptr.size() - 1;
+  v->tile_ptr = b->tile_ptr.data();
   return XRL_OK;
 }
 

@@ -45,7 +45,7 @@ struct xrl_batch_device {
   size_t bytes = 0;
   int32_t *state_graph_ptr = nullptr, *graph_node_ptr = nullptr, *node_op = nullptr;
   int32_t *in_ptr = nullptr, *in_src = nullptr, *in_dst = nullptr;
-  int32_t *out_ptr = nullptr, *out_pos = nullptr, *node_graph = nullptr;
+  int32_t *out_ptr = nullptr, *out_pos = nullptr, *node_graph = nullptr, *tile_ptr = nullptr;
   float *node_dense = nullptr, *edge_feat = nullptr, *graph_global = nullptr;
   uint8_t *mask = nullptr;
 };
@@ -56,6 +56,8 @@ struct xrl_batch {
   int32_t max_slots = 0;  // largest number of slots in one state
   std::vector<int32_t> state_graph_ptr, graph_node_ptr, node_op;
   std::vector<int32_t> in_ptr, in_src, in_dst, in_eid, out_ptr, out_pos, node_graph;
+  std::vector<int32_t> tile_ptr;  // [n_tiles + 1] edge tiles of the message kernels (see the packer)
+  int64_t n_split_tiles = 0;      // tiles that end inside a receiver's in-edge range
   std::vector<float> node_dense, edge_feat, graph_global;
   std::vector<uint8_t> mask;
   xrl_batch_device dev;

@@ -83,6 +83,45 @@ def test_pack_edge_cases():
     assert v["in_src"].tolist() == [3, 2, 2, 4] and v["in_eid"].tolist() == [3, 0, 1, 2]
 
 
+def check_tiles(v):
+    """Edge tiles: a partition of the receiver-order edges into runs of 1..32 edges whose
+    boundaries fall between receivers, except inside a receiver with more than 32 in-edges; such a
+    receiver starts a tile and is cut every 32 edges."""
+    tp, in_ptr, in_dst = v["tile_ptr"], v["in_ptr"], v["in_dst"]
+    E = len(in_dst)
+    assert tp[0] == 0 and tp[-1] == E and (E > 0 or len(tp) == 1)
+    sizes = np.diff(tp)
+    assert np.all(sizes >= 1) and np.all(sizes <= 32)
+    for t in tp[1:-1]:
+        if in_dst[t - 1] == in_dst[t]:                       # the boundary cuts a receiver's range
+            beg = in_ptr[in_dst[t]]
+            assert in_ptr[in_dst[t] + 1] - beg > 32 and (t - beg) % 32 == 0
+    # greedy: a tile is closed only when the next receiver's edges would not fit
+    for i in range(len(tp) - 2):
+        nxt = in_dst[tp[i + 1]]
+        if in_dst[tp[i + 1] - 1] != nxt:
+            deg = in_ptr[nxt + 1] - in_ptr[nxt]
+            assert sizes[i] + min(deg, 32) > 32 or deg > 32
+
+
+def test_edge_tiles():
+    model, st = synth.make_config(1)
+    check_tiles(xrl.pack_state(model, st).host_view())
+    model, st = synth.make_config(2, n_cand=6)
+    check_tiles(xrl.pack_state(model, st).host_view())
+    rng = np.random.Generator(np.random.PCG64(5))
+    for n_hub in (31, 32, 33, 64, 65, 300):                  # receivers of high in-degree
+        n = n_hub + 40
+        src = np.concatenate([np.arange(1, n_hub + 1), rng.integers(0, n, 60)]).astype(np.int32)
+        dst = np.concatenate([np.full(n_hub, 7), rng.integers(0, n, 60)]).astype(np.int32)
+        st = dict(n_states=1, state_graph_ptr=[0, 1], graph_node_ptr=[0, n], graph_edge_ptr=[0, len(src)],
+                  node_op=np.zeros(n, np.int32), node_dense=np.zeros((n, 4)), edge_src=src, edge_dst=dst,
+                  edge_feat=np.zeros((len(src), 8)), graph_global=None, slot_mask=[1])
+        v = xrl.pack_state(base_model(), st).host_view()
+        check_tiles(v)
+        assert len(v["tile_ptr"]) - 1 >= -(-len(src) // 32)
+
+
 def _mutate(st, **kw):
     out = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in st.items()}
     out.update(kw)
