@@ -126,7 +126,7 @@ def main():
         roofline=dict(bound="mfma", kernel="edge MLP + per-receiver sum (one launch per round)",
                       achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak, traffic=None,
                       flops_per_launch=edge_flops, avg_launch_us=kern["edge"]["avg_us"]),
-        hbm_kernel=dict(kernel="per-graph readout sum", bytes_per_launch=pool_bytes,
+        hbm_kernel=dict(kernel="per-graph readout sum (fused with the readout MLP)", bytes_per_launch=pool_bytes,
                         achieved=(pool_bytes / pool_s / 1e9 if pool_s > 0 else 0.0), peak=PEAK_HBM_GBS,
                         unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
         kernels_us=kern,

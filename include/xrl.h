@@ -32,7 +32,7 @@ extern "C" {
 typedef enum {
   XRL_OK = 0,
   XRL_ERR_NULL = -1,        /* a required pointer is NULL */
-  XRL_ERR_SHAPE = -2,       /* negative count, non-monotone or inconsistent ptr array */
+  XRL_ERR_SHAPE = -2,       /* negative count, non-monotone or inconsistent ptr array, misaligned buffer */
   XRL_ERR_INDEX = -3,       /* edge endpoint outside its graph, op id outside [0, n_op_types) */
   XRL_ERR_VALUE = -4,       /* NaN or Inf in a feature or weight */
   XRL_ERR_MASK = -5,        /* a state's No-Op slot (its first graph) is masked out */
@@ -147,7 +147,8 @@ int xrl_encode(xrl_ctx *ctx, const xrl_batch *b, float *d_emb, int save_for_back
  * emb[j]; per state, over its valid slots only (invalid-action masking): d_logp [G] = log
  * softmax (-inf at masked slots), d_entropy [S], d_action [S] = slot index inside the state of
  * the largest valid logit, lowest index on ties (0 = No-Op), d_value [S] = value MLP of the mean
- * embedding of the valid slots. All device pointers; d_logit [G] may be NULL. */
+ * embedding of the valid slots. All device pointers (d_emb 16-byte aligned); d_logit [G] may be
+ * NULL. Errors: NULL, SHAPE (alignment), STATE, HIP. */
 int xrl_policy_value(xrl_ctx *ctx, const xrl_batch *b, const float *d_emb, float *d_logp,
                      float *d_value, float *d_entropy, int32_t *d_action, float *d_logit);
 

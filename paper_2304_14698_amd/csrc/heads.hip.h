@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include "segsum.hip.h"
 
 // Rows per block of the row-MLP kernels: 8 reuses every weight read eight times (large batches);
 // 1 gives one block per row so that small batches still spread over the chip.
@@ -23,9 +24,64 @@ struct RowMlpArgs {
   float *act[3];           // nullable each
 };
 
+// One row through the layers of `a`, all 256 threads of the block cooperating. The contraction of
+// a layer narrower than the block is split over 256 / d_out thread groups (each thread then has
+// d_in * d_out / 256 weights to fetch, all requested before the first is used -- these kernels
+// are bound by memory latency, not bandwidth); the groups' partial sums are added in group order.
+// cur holds the input row (d_in[0] floats) on entry; cur/nxt: >= widest layer; part: 256 floats.
+// `row` indexes the stores to a.act[l] and a.out.
+__device__ __forceinline__ void block_row_mlp(const RowMlpArgs &a, float *cur, float *nxt, float *part,
+                                              int64_t row) {
+  const int t = threadIdx.x;
+  for (int l = 0; l < a.n_layers; ++l) {
+    const int din = a.d_in[l], dout = a.d_out[l];
+    const bool relu = a.relu_last || (l + 1 < a.n_layers);
+    int fw = 256;                                         // outputs handled per pass
+    while (fw / 2 >= dout && 256 / (fw / 2) <= din) fw /= 2;
+    const int KQ = 256 / fw;                              // thread groups splitting the contraction
+    const int kc = (din + KQ - 1) / KQ;
+    const int fl = t % fw, kq = t / fw;
+    const int k0 = kq * kc, k1 = (k0 + kc) < din ? (k0 + kc) : din;
+    const float *W = a.W[l];
+    for (int f0 = 0; f0 < dout; f0 += fw) {
+      const int f = f0 + fl;
+      float acc = 0.f;
+      if (f < dout) {
+        int k = k0;
+        for (; k + 16 <= k1; k += 16) {
+          float w[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) w[i] = W[(size_t)(k + i) * dout + f];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc = fmaf(cur[k + i], w[i], acc);
+        }
+        for (; k < k1; ++k) acc = fmaf(cur[k], W[(size_t)k * dout + f], acc);
+      }
+      if (KQ > 1) {
+        part[t] = acc;
+        __syncthreads();
+        if (kq == 0) {
+          acc = part[fl];
+          for (int q = 1; q < KQ; ++q) acc += part[q * fw + fl];
+        }
+      }
+      if (kq == 0 && f < dout) {
+        acc += a.b[l][f];
+        const float y = relu ? fmaxf(acc, 0.f) : acc;
+        nxt[f] = y;
+        if (a.act[l]) a.act[l][row * dout + f] = y;
+        if (l + 1 == a.n_layers) a.out[row * dout + f] = y;
+      }
+      if (KQ > 1) __syncthreads();
+    }
+    __syncthreads();
+    float *tmp = cur; cur = nxt; nxt = tmp;
+  }
+}
+
 template <int ROWMLP_ROWS>
 __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
-  extern __shared__ float sm[];          // two buffers of ROWMLP_ROWS * dmax floats
+  extern __shared__ float sm[];          // two buffers of ROWMLP_ROWS * dmax floats (+ 256 for one row)
   int dmax = a.d_in[0];
   for (int l = 0; l < a.n_layers; ++l) dmax = a.d_out[l] > dmax ? a.d_out[l] : dmax;
   float *cur = sm, *nxt = sm + ROWMLP_ROWS * dmax;
@@ -38,6 +94,10 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
     cur[r * dmax + k] = v;
   }
   __syncthreads();
+  if constexpr (ROWMLP_ROWS == 1) {
+    block_row_mlp(a, cur, nxt, sm + 2 * dmax, row0);
+    return;
+  }
   for (int l = 0; l < a.n_layers; ++l) {
     const int din = a.d_in[l], dout = a.d_out[l];
     const bool relu = a.relu_last || (l + 1 < a.n_layers);
@@ -46,7 +106,7 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
       const float bv = a.b[l][f];
 #pragma unroll
       for (int r = 0; r < ROWMLP_ROWS; ++r) acc[r] = bv;
-#pragma unroll 8
+#pragma unroll 16
       for (int k = 0; k < din; ++k) {
         const float w = a.W[l][(size_t)k * dout + f];
 #pragma unroll
@@ -66,6 +126,58 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
     __syncthreads();
     float *t = cur; cur = nxt; nxt = t;
   }
+}
+
+// Global-update layer (Section 3.4) for one graph per block: the sum (or mean) of the graph's node
+// states, then the readout MLP on [pool | global attrs], without leaving the block. The 256
+// threads form 256 / (H / VEC) row groups, each lane owning a 16-byte column slice; a group
+// takes every (number of groups)-th node with eight loads in flight, and the groups' partial
+// sums are added in group order, so the result does not depend on timing. pool [G, H] is also
+// stored (it is an input of the backward pass). Meant for batches of many graphs of moderate
+// size; a few huge graphs go through the generic segment-sum kernels instead.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const int32_t *graph_node_ptr, int H,
+                                                            int mean, float *pool, const RowMlpArgs mlp) {
+  extern __shared__ __align__(16) float sm[];   // [256 * VEC] partial sums, then the MLP's buffers
+  const int g = blockIdx.x, t = threadIdx.x;
+  const int tpr = H / VEC, ng = 256 / tpr, c0 = (t % tpr) * VEC, q = t / tpr;
+  const int n0 = graph_node_ptr[g], n1 = graph_node_ptr[g + 1];
+  float acc[VEC];
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+  int n = n0 + q;
+  for (; n + 7 * ng < n1; n += 8 * ng) {
+    float v[8][VEC];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) RowVec<T, VEC>::load(h + (size_t)(n + i * ng) * H + c0, v[i]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc[j] += v[i][j];
+  }
+  for (; n < n1; n += ng) {
+    float v[VEC];
+    RowVec<T, VEC>::load(h + (size_t)n * H + c0, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+  }
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) sm[(q * tpr + t % tpr) * VEC + j] = acc[j];
+  __syncthreads();
+  int dmax = mlp.d_in[0];
+  for (int l = 0; l < mlp.n_layers; ++l) dmax = mlp.d_out[l] > dmax ? mlp.d_out[l] : dmax;
+  float *cur = sm + 256 * VEC, *nxt = cur + dmax, *part = nxt + dmax;
+  const float scale = mean ? 1.f / (float)(n1 - n0 > 1 ? n1 - n0 : 1) : 1.f;
+  for (int f = t; f < H; f += 256) {
+    float a = sm[f];
+    for (int k = 1; k < ng; ++k) a += sm[k * H + f];
+    a *= scale;
+    pool[(size_t)g * H + f] = a;
+    cur[f] = a;
+  }
+  for (int k = t; k < mlp.w2; k += 256) cur[H + k] = mlp.in2[(size_t)g * mlp.w2 + k];
+  __syncthreads();
+  block_row_mlp(mlp, cur, nxt, part, g);
 }
 
 // pool[g, :] /= max(n_g, 1)  (mean readout)
@@ -93,12 +205,14 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
 }
 
 // One block per state: masked log-softmax over the state's slots, entropy, first-max action,
-// and the mean embedding of the valid slots (input of the value head).
+// the mean embedding of the valid slots and, on it, the value head (value.n_layers == 0 skips it).
 __global__ __launch_bounds__(256) void state_policy_kernel(
     const float *logit, const uint8_t *mask, const int32_t *state_graph_ptr, const float *emb,
-    int H, float *logp, float *entropy, int32_t *action, float *zmean) {
+    int H, float *logp, float *entropy, int32_t *action, float *zmean, const RowMlpArgs value) {
   __shared__ float red[256];
   __shared__ int redi[256];
+  __shared__ __align__(16) float zbuf[1024];                      // partial sums of the mean embedding
+  __shared__ __align__(16) float vcur[512], vnxt[512];            // value head: layer input / output
   const int s = blockIdx.x, t = threadIdx.x;
   const int j0 = state_graph_ptr[s], j1 = state_graph_ptr[s + 1];
   // max valid logit and the lowest slot index attaining it
@@ -140,27 +254,41 @@ __global__ __launch_bounds__(256) void state_policy_kernel(
   }
   ent = block_sum(ent, red);
   if (t == 0) { entropy[s] = ent; action[s] = arg - j0; }
-  // mean embedding of the valid slots: 256 / H groups of threads take every (256/H)-th slot,
-  // four independent partial sums each; partials are combined in a fixed order
-  const int ng = 256 / H, f = t % H, q = t / H;     // H is 64, 128 or 256
-  float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+  // mean embedding of the valid slots: H / 4 threads cover a row with 16-byte loads, the 1024 / H
+  // thread groups take every (1024/H)-th slot, eight loads in flight each; the groups' partial
+  // sums are combined in group order
+  const int tpr = H / 4, ng = 256 / tpr, c4 = (t % tpr) * 4, q = t / tpr;     // H is 64, 128 or 256
+  float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
   int j = j0 + q;
-  for (; j + 3 * ng < j1; j += 4 * ng) {
-    const float v0 = emb[(size_t)j * H + f], v1 = emb[(size_t)(j + ng) * H + f];
-    const float v2 = emb[(size_t)(j + 2 * ng) * H + f], v3 = emb[(size_t)(j + 3 * ng) * H + f];
-    p0 += mask[j] ? v0 : 0.f;
-    p1 += mask[j + ng] ? v1 : 0.f;
-    p2 += mask[j + 2 * ng] ? v2 : 0.f;
-    p3 += mask[j + 3 * ng] ? v3 : 0.f;
+  for (; j + 7 * ng < j1; j += 8 * ng) {
+    float4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *(const float4 *)(emb + (size_t)(j + i * ng) * H + c4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (mask[j + i * ng]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; }
   }
-  for (; j < j1; j += ng) p0 += mask[j] ? emb[(size_t)j * H + f] : 0.f;
-  red[t] = (p0 + p1) + (p2 + p3);
+  for (; j < j1; j += ng)
+    if (mask[j]) {
+      const float4 v = *(const float4 *)(emb + (size_t)j * H + c4);
+      p.x += v.x; p.y += v.y; p.z += v.z; p.w += v.w;
+    }
+  float4 *zp = (float4 *)zbuf;                                   // [ng][H / 4]
+  zp[t] = p;
   __syncthreads();
-  if (q == 0) {
-    float acc = red[f];
-    for (int k = 1; k < ng; ++k) acc += red[k * H + f];
-    zmean[(size_t)s * H + f] = acc / nvalid;
+  if (t < tpr) {
+    float4 acc = zp[t];
+    for (int k = 1; k < ng; ++k) {
+      const float4 o = zp[k * tpr + t];
+      acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+    }
+    acc.x /= nvalid; acc.y /= nvalid; acc.z /= nvalid; acc.w /= nvalid;
+    *(float4 *)(zmean + (size_t)s * H + c4) = acc;
+    *(float4 *)(vcur + c4) = acc;
   }
+  __syncthreads();
+  // value head on the mean embedding (Section 3.3.2), in the same block
+  if (value.n_layers > 0) block_row_mlp(value, vcur, vnxt, red, s);
 }
 
 // dJ/dlogit per slot from (dlogp, dentropy) and the forward's logp/entropy; one block per state.

@@ -423,9 +423,8 @@ int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
 
-int launch_rowmlp(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1, int w1,
-                  const float *in2, int w2, int64_t n_rows, float *out, float *const *act) {
-  if (n_rows <= 0) return XRL_OK;
+RowMlpArgs rowmlp_args(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1, int w1, const float *in2,
+                       int w2, int64_t n_rows, float *out, float *const *act, int *dmax_out = nullptr) {
   RowMlpArgs a;
   memset(&a, 0, sizeof(a));
   a.n_layers = r.n_layers;
@@ -440,8 +439,17 @@ int launch_rowmlp(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1,
     if (r.d_out[l] > dmax) dmax = r.d_out[l];
   }
   a.in1 = in1; a.in2 = in2; a.w1 = w1; a.w2 = w2; a.n_rows = n_rows; a.out = out;
+  if (dmax_out) *dmax_out = dmax;
+  return a;
+}
+
+int launch_rowmlp(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1, int w1,
+                  const float *in2, int w2, int64_t n_rows, float *out, float *const *act) {
+  if (n_rows <= 0) return XRL_OK;
+  int dmax = 0;
+  const RowMlpArgs a = rowmlp_args(c, r, relu_last, in1, w1, in2, w2, n_rows, out, act, &dmax);
   if (n_rows <= 4096) {
-    rowmlp_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)2 * dmax * sizeof(float), c->stream>>>(a);
+    rowmlp_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)(2 * dmax + 256) * sizeof(float), c->stream>>>(a);
   } else {
     const unsigned blocks = (unsigned)((n_rows + 7) / 8);
     rowmlp_kernel<8><<<dim3(blocks), dim3(256), (size_t)2 * 8 * dmax * sizeof(float), c->stream>>>(a);
@@ -760,6 +768,18 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   }
   // ---- global-update layer: per-graph sum (or mean), then the readout MLP
   constexpr int PV = 16 / sizeof(T);
+  if (N <= 4096 * G) {
+    // many graphs of moderate size: one block per graph sums its nodes and runs the readout MLP
+    Timed t(c, TK_POOL);
+    int dmax = 0;
+    const RowMlpArgs ra = rowmlp_args(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb,
+                                      c->ro_act, &dmax);
+    const size_t lds = (size_t)(256 * PV + 2 * dmax + 256) * sizeof(float);
+    graph_readout_kernel<T, PV><<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(
+        hcur, d.graph_node_ptr, H, m.readout == XRL_READOUT_MEAN ? 1 : 0, c->pool, ra);
+    HIP_TRY(hipGetLastError());
+    return XRL_OK;
+  }
   { Timed t(c, TK_POOL);
     rc = launch_segsum<T, float, PV>(c, hcur, nullptr, d.graph_node_ptr, d.node_graph, N, G, H, c->pool, c->carry); }
   if (rc) return rc;
@@ -923,6 +943,7 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   if (b->S == 0) return XRL_OK;
   if (!d_emb || !d_logp || !d_value || !d_entropy || !d_action)
     return fail(XRL_ERR_NULL, "xrl_policy_value: NULL device pointer");
+  if ((uintptr_t)d_emb & 15) return fail(XRL_ERR_SHAPE, "xrl_policy_value: d_emb must be 16-byte aligned");
   const int H = c->m.hidden;
   rc = ensure_hws(c, align_up((size_t)b->G * 4) + align_up((size_t)b->S * H * 4));
   if (rc) return rc;
@@ -932,9 +953,8 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, nullptr);
   if (rc) return rc;
   state_policy_kernel<<<dim3((unsigned)b->S), dim3(256), 0, c->stream>>>(
-      logit, b->dev.mask, b->dev.state_graph_ptr, d_emb, H, d_logp, d_entropy, d_action, zmean);
-  rc = launch_rowmlp(c, c->L.value, false, zmean, H, nullptr, 0, b->S, d_value, nullptr);
-  if (rc) return rc;
+      logit, b->dev.mask, b->dev.state_graph_ptr, d_emb, H, d_logp, d_entropy, d_action, zmean,
+      rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, b->S, d_value, nullptr));
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
@@ -947,6 +967,8 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   if (b->S == 0) return XRL_OK;
   if (!d_emb || !d_dlogp || !d_dvalue || !d_dentropy || !d_demb || !d_dweights)
     return fail(XRL_ERR_NULL, "xrl_policy_value_backward: NULL device pointer");
+  if ((uintptr_t)d_emb & 15)
+    return fail(XRL_ERR_SHAPE, "xrl_policy_value_backward: d_emb must be 16-byte aligned");
   const int H = c->m.hidden, h0 = c->m.head_hidden[0], h1 = c->m.head_hidden[1];
   const int64_t G = b->G, S = b->S;
   size_t need = 0;
@@ -972,9 +994,9 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   const xrl_batch_device &d = b->dev;
   // forward of the heads, keeping every layer's output
   if ((rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, G, logit, pact))) return rc;
-  state_policy_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(logit, d.mask, d.state_graph_ptr, d_emb,
-                                                                    H, logp, ent, action, zmean);
-  if ((rc = launch_rowmlp(c, c->L.value, false, zmean, H, nullptr, 0, S, value, vact))) return rc;
+  state_policy_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(
+      logit, d.mask, d.state_graph_ptr, d_emb, H, logp, ent, action, zmean,
+      rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, S, value, vact));
   // backward
   state_policy_bwd_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(logp, ent, d.mask, d.state_graph_ptr,
                                                                         d_dlogp, d_dentropy, dlogit, inv_n);
