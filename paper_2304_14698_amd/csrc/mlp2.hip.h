@@ -103,14 +103,15 @@ __device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, in
 // holds the sum of its own and the next 2d - 1 edges of its receiver, so the first lane of every
 // receiver ends with the receiver's total after ceil(log2(longest run)) steps (none at all when
 // every receiver of the tile has one in-edge, one when none has more than two). The order of
-// the additions is fixed by the positions in the tile alone. The first lane of each run then
-// writes 4 consecutive features per store: to out[receiver] when the run lies inside the tile, to
+// the additions is fixed by the positions in the tile alone. The total held by the first lane of
+// each run then goes to out[receiver] (whole rows, through the staging buffer) when the run lies
+// inside the tile, to
 // carry[wt][0] when it began before the tile, to carry[wt][1] when it goes on after it (a run
 // covering the whole tile and open on both sides counts as begun before); segsum_fixup adds the
 // carried pieces in tile order.
 template <typename T, int H>
 __device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeTileMeta &m, int64_t wt, int nv,
-                                               int lane, T *out, float *carry) {
+                                               int lane, T *out, float *carry, char *stage) {
   constexpr int MB = H / 32;
   const int l32 = lane & 31, g = lane >> 5;
   const bool valid = l32 < nv;                                  // nv >= 1
@@ -139,10 +140,11 @@ __device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeT
   const bool ends_tile = l32 + rem == nv - 1;
   const bool to_c0 = head && l32 == 0 && m.prev_d == m.dst;
   const bool to_c1 = head && !to_c0 && ends_tile && m.next_d == m.dst;
-  if (head && !to_c0 && !to_c1) {
-#pragma unroll
-    for (int nb = 0; nb < MB; ++nb) store_tile_rows<T, H>(out, m.dst, true, nb, g, acc[nb]);
-  }
+  const int dsel = (head && !to_c0 && !to_c1) ? m.dst : -1;      // row this lane's total goes to
+  store_rows_via_lds<T, H, false>(acc, stage, lane, [&](int r) -> T * {
+    const int d = __shfl(dsel, r);
+    return d >= 0 ? out + (size_t)d * H : nullptr;
+  });
   if (to_c0 || to_c1) {
     const int64_t crow = wt * 2 + (to_c1 ? 1 : 0);
 #pragma unroll
@@ -163,6 +165,7 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   using vec1 = typename Opd1::vec;
   constexpr int V1 = Opd1::V, SL1 = 2 * V1;
   static_assert(KIND == KIND_EMBED || sizeof(T1) == sizeof(T), "only EMBED mixes operand types");
+  __shared__ __align__(16) char stage[4][RowStage<T, H>::BYTES];  // per-wave staging of output rows
 
   // consecutive tiles stay on one XCD (blocks are dealt round-robin to the 8 XCDs), so the rows
   // a tile gathers are mostly in that XCD's L2 already
@@ -301,11 +304,11 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   // ---------------- epilogue
   T *out = (T *)a.out;
   if constexpr (KIND != KIND_EDGE) {
-#pragma unroll
-    for (int nb = 0; nb < MB; ++nb)
-      store_tile_rows_relu<T, H>(out, row0 + l32, row0 + l32 < a.n_rows, nb, g, acc2[nb]);
+    store_rows_via_lds<T, H, true>(acc2, stage[wave], lane, [&](int r) -> T * {
+      return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
+    });
   } else {
     const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, nv, l32);
-    edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry);
+    edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry, stage[wave]);
   }
 }

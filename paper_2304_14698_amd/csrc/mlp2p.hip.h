@@ -85,6 +85,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   vec *W2l = W1l + (size_t)NS1 * MB * 64;                  // [NC2][MB][64]
   float(*b1l)[2][16] = (float(*)[2][16])(W2l + (size_t)NC2 * MB * 64);   // [MB][lane group][16]
   float(*b2l)[2][16] = b1l + MB;                                         // same for layer 2
+  char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * RowStage<T, H>::BYTES;   // this wave's output staging
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   // the wave tiles of one XCD are contiguous (blocks are dealt round-robin to the 8 XCDs); inside
@@ -202,11 +203,12 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     // ---------------- epilogue
     T *out = (T *)a.out;
     if constexpr (KIND == KIND_NODE) {
-      const int64_t row = wt * 32 + l32;
-#pragma unroll
-      for (int nb = 0; nb < MB; ++nb) store_tile_rows_relu<T, H>(out, row, row < a.n_rows, nb, g, acc2[nb]);
+      const int64_t row0 = wt * 32;
+      store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
+        return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
+      });
     } else {
-      edge_tile_sum<T, H>(acc2, meta, wt, nv, lane, out, a.carry);
+      edge_tile_sum<T, H>(acc2, meta, wt, nv, lane, out, a.carry, stage);
     }
   }
 }

@@ -154,3 +154,57 @@ __device__ __forceinline__ void store_tile_rows_relu(TO *base, int64_t row, bool
     store4<TO>(base + (size_t)row * H + 32 * fb + 8 * q + 4 * g, v);
   }
 }
+
+// Row-major store of a features x rows accumulator set (lane = row of a 32-row wave tile) through
+// a wave-private LDS staging buffer, so that every global store instruction writes whole rows:
+// a lane holds its own row, and storing from that layout directly would touch 32 different rows
+// (cache lines) with every instruction. The tile goes through the buffer RP rows at a time: the
+// lanes owning those rows write their register quads (padded row stride, bank-conflict free),
+// then all 64 lanes read the rows back 16 bytes per lane, H * sizeof(T) / 16 lanes per row, and
+// store them. row_dst(r) gives the destination of tile row r (nullptr: skip); it is called by all
+// lanes together, so it may use cross-lane operations.
+template <typename T, int H>
+struct RowStage {
+  static constexpr int RS = H * (int)sizeof(T) + 16;                  // padded row stride, bytes
+  static constexpr int RP = H * (int)sizeof(T) >= 1024 ? 8 : 16;      // rows per pass
+  static constexpr int BYTES = RP * RS;                               // per wave
+  static constexpr int LPR = H * (int)sizeof(T) / 16;                 // lanes per row on the way out
+  static constexpr int RPI = 64 / LPR;                                // rows per store instruction
+};
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T, int H, bool RELU, typename RowDst>
+__device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[H / 32], char *stage, int lane,
+                                                   RowDst row_dst) {
+  using S = RowStage<T, H>;
+  const int l32 = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int p = 0; p < 32 / S::RP; ++p) {
+    if (l32 / S::RP == p) {
+      char *wp = stage + (l32 % S::RP) * S::RS + 4 * g * (int)sizeof(T);
+#pragma unroll
+      for (int nb = 0; nb < H / 32; ++nb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = RELU ? relu_f32(acc[nb][4 * q + j]) : acc[nb][4 * q + j];
+          store4<T>((T *)(wp + (32 * nb + 8 * q) * (int)sizeof(T)), v);
+        }
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int k = 0; k < S::RP / S::RPI; ++k) {
+      const int rr = k * S::RPI + lane / S::LPR;                      // row inside the pass
+      const f32x4 v = *(const f32x4 *)(stage + rr * S::RS + (lane % S::LPR) * 16);
+      T *dst = row_dst(p * S::RP + rr);
+      if (dst) *(f32x4 *)((char *)dst + (lane % S::LPR) * 16) = v;
+    }
+    wave_lds_fence();
+  }
+}

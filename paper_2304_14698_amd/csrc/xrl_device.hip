@@ -370,12 +370,12 @@ int launch_mlp2_h(xrl_ctx *c, int kind, const Mlp2Args &a) {
 }
 
 // Persistent LDS-resident-weights variant (bf16, H <= 128, edge and node kinds).
+constexpr int kPersistWaves = 8;
 inline size_t mlp2p_lds_bytes(int H, int nslab1) {
   const int MB = H / 32, HS = H / 16;
-  return ((size_t)nslab1 * MB + (size_t)HS * MB) * 1024 + (size_t)MB * 256;
+  return ((size_t)nslab1 * MB + (size_t)HS * MB) * 1024 + (size_t)MB * 256 +
+         (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;   // staging sized for the widest H served
 }
-
-constexpr int kPersistWaves = 8;
 
 template <int H, int KIND>
 int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
