@@ -35,6 +35,9 @@ struct Mlp2Args {
   const int32_t *node_op;  // [N]                            (EMBED)
   const float *node_dense; // [N, Dd]                        (EMBED)
   int De, Tn, Dd;
+  const void *W1x;         // EMBED: fragment-ordered fp32 rows of W1 for [edge-attr sum | dense attrs]
+  int nslabx;              // EMBED: its slabs
+  const float *table;      // EMBED: [Tn, H] fp32 rows of W1 for the one-hot op type
   void *out;               // [N, H] operand type
   float *carry;            // [n_tiles, 2, H]                (EDGE)
   const int32_t *tile_ptr; // [n_tiles + 1] first edge of each edge tile (EDGE)
@@ -152,6 +155,43 @@ __device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeT
   }
 }
 
+// Node-update layer input (Section 3.4) of one node, without its one-hot block: column k of
+// [sum of the node's incoming edge attributes (De) | dense attributes (Dd)], zero beyond. The
+// in-edges are the node's contiguous receiver-order range [e0, e1) and are added in that order;
+// the first two are requested together (most nodes of a computation graph have one or two).
+struct EmbedRow {
+  int op, e0, e1;
+  const float *dense;
+};
+__device__ __forceinline__ EmbedRow load_embed_row(const int32_t *node_op, const int32_t *in_ptr,
+                                                   const float *node_dense, int Dd, int64_t row) {
+  EmbedRow r;
+  r.op = node_op[row];
+  r.e0 = in_ptr[row];
+  r.e1 = in_ptr[row + 1];
+  r.dense = node_dense + (size_t)row * Dd;
+  return r;
+}
+// four consecutive columns k0 .. k0+3 (k0 a multiple of 4, as are De and the row stride)
+__device__ __forceinline__ f32x4 embed_columns(const EmbedRow &r, const float *edge_feat, int De, int Dd, int k0) {
+  f32x4 x = {0.f, 0.f, 0.f, 0.f};
+  if (k0 < De) {
+    const int n = r.e1 - r.e0;
+    const float *p = edge_feat + (size_t)r.e0 * De + k0;
+    f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+    if (n > 0) v0 = *(const f32x4 *)p;
+    if (n > 1) v1 = *(const f32x4 *)(p + De);
+    x = v0;
+    if (n > 1) x += v1;
+    for (int e = 2; e < n; ++e) x += *(const f32x4 *)(p + (size_t)e * De);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (k0 + j < De + Dd) x[j] = r.dense[k0 + j - De];
+  }
+  return x;
+}
+
 // T1 = operand type of layer 1 (its input rows and W1), T = operand type of layer 2 and of the
 // stored activations. They differ only for EMBED in bf16 mode, whose first layer stays in fp32:
 // its inputs (log2 shape attributes up to 12, sums of edge attributes) are large enough for bf16
@@ -187,11 +227,13 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
 
   // ---------------- layer 1: acc1[mb] = (W1^T x^T) tile, features x rows, bias pre-loaded
   f32x16 acc1[MB];
+  if constexpr (KIND != KIND_EMBED) {
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc1[mb][r] = a.b1[32 * mb + acc_row(r, g)];
-  const vec1 *W1 = (const vec1 *)a.W1s + lane;
+      for (int r = 0; r < 16; ++r) acc1[mb][r] = a.b1[32 * mb + acc_row(r, g)];
+  }
+  const vec1 *W1 = (const vec1 *)(KIND == KIND_EMBED ? a.W1x : a.W1s) + lane;
 
   if constexpr (KIND == KIND_EDGE || KIND == KIND_NODE) {
     // both H-wide parts of the input row are requested up front (one exposed latency instead
@@ -242,32 +284,23 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
       }
     }
   } else {
-    // the sum of the node's incoming edge attributes is formed here, from the node's contiguous
-    // receiver-order edge range, in edge order
-    const float *dn = a.node_dense + (size_t)row * a.Dd;
-    const int op = a.node_op[row];
-    const int e0 = a.in_ptr[row], e1 = a.in_ptr[row + 1];
-    for (int s = 0; s < a.nslab1; ++s) {
-      float a0[V1];
+    // The one-hot block of the input selects one row of W1: that row (plus the bias) is the
+    // accumulators' starting value, read as four consecutive features per load, and only the
+    // remaining [edge-attr sum | dense attrs] columns go through the matrix cores (in fp32).
+    const EmbedRow er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
+    const float *trow = a.table + (size_t)er.op * H + 4 * g;
 #pragma unroll
-      for (int j = 0; j < V1; ++j) a0[j] = 0.f;
-      if (s * SL1 + g * V1 < a.De)
-        for (int e = e0; e < e1; ++e) {
-          const float *xe = a.edge_feat + (size_t)e * a.De + s * SL1 + g * V1;
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-          for (int j = 0; j < V1; ++j)
-            if (s * SL1 + g * V1 + j < a.De) a0[j] += xe[j];
-        }
-      vec1 x;
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 t = *(const f32x4 *)(trow + 32 * mb + 8 * q);
+        const f32x4 b = *(const f32x4 *)(a.b1 + 32 * mb + 8 * q + 4 * g);
 #pragma unroll
-      for (int j = 0; j < V1; ++j) {
-        const int k = s * SL1 + g * V1 + j;
-        float v = 0.f;
-        if (k < a.De) v = a0[j];
-        else if (k < a.De + a.Tn) v = (k - a.De == op) ? 1.f : 0.f;
-        else if (k < a.De + a.Tn + a.Dd) v = dn[k - a.De - a.Tn];
-        x[j] = Opd1::from_float(v);
+        for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] = t[j] + b[j];
       }
+    static_assert(V1 == 4, "the embed MLP's first layer uses fp32 operands");
+    for (int s = 0; s < a.nslabx; ++s) {
+      const vec1 x = embed_columns(er, a.edge_feat, a.De, a.Dd, s * SL1 + g * V1);
       mma_slab<T1, H>(W1 + (size_t)s * MB * 64, x, acc1);
     }
   }

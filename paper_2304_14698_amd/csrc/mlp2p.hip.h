@@ -72,6 +72,38 @@ __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32
   }
 }
 
+// Layer 2 of a wave tile with the weights in LDS: acc2 = W2^T relu(z1)^T + b2 (features x rows);
+// the fragments of the next chunk are read while the MFMAs of the current one run.
+template <typename T, int H>
+__device__ __forceinline__ void layer2_lds(const f32x16 (&acc1)[H / 32], const typename Operand<T>::vec *W2l,
+                                           const float (*b2l)[2][16], int lane, int g, f32x16 (&acc2)[H / 32]) {
+  using Opd = Operand<T>;
+  using vec = typename Opd::vec;
+  constexpr int MB = H / 32, QB = 32 / (2 * Opd::V), NC2 = MB * QB;
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb) acc2[nb] = *(const f32x16 *)&b2l[nb][g][0];
+  vec wc[MB];
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb) wc[nb] = W2l[nb * 64 + lane];
+#pragma unroll
+  for (int c = 0; c < NC2; ++c) {
+    vec wn[MB];
+    if (c + 1 < NC2) {
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) wn[nb] = W2l[((c + 1) * MB + nb) * 64 + lane];
+    }
+    const vec z = relu_operand<T>(acc1[c / QB], c % QB);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) Opd::mma(wc[nb], z, acc2[nb]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (c + 1 < NC2) {
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) wc[nb] = wn[nb];
+    }
+  }
+}
+
 template <typename T, int H, int KIND, int NW>
 __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   using Opd = Operand<T>;
@@ -79,7 +111,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   constexpr int V = Opd::V, SL = 2 * V, MB = H / 32, HS = H / SL, QB = 32 / SL;
   constexpr int NS1 = 2 * HS + (KIND == KIND_EDGE ? 1 : 0);   // slabs of layer 1
   constexpr int NC2 = MB * QB;                                // chunks of layer 2
-  static_assert(KIND == KIND_EDGE || KIND == KIND_NODE, "embed keeps the streaming kernel");
+  static_assert(KIND == KIND_EDGE || KIND == KIND_NODE, "the embed MLP has its own kernel below");
   extern __shared__ __align__(16) char smem[];
   vec *W1l = (vec *)smem;                                  // [NS1][MB][64]
   vec *W2l = W1l + (size_t)NS1 * MB * 64;                  // [NC2][MB][64]
@@ -176,30 +208,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     }
     // ---------------- layer 2 (features x rows)
     f32x16 acc2[MB];
-#pragma unroll
-    for (int nb = 0; nb < MB; ++nb) acc2[nb] = *(const f32x16 *)&b2l[nb][g][0];
-    {
-      vec wc[MB];
-#pragma unroll
-      for (int nb = 0; nb < MB; ++nb) wc[nb] = W2l[nb * 64 + lane];
-#pragma unroll
-      for (int c = 0; c < NC2; ++c) {
-        vec wn[MB];
-        if (c + 1 < NC2) {
-#pragma unroll
-          for (int nb = 0; nb < MB; ++nb) wn[nb] = W2l[((c + 1) * MB + nb) * 64 + lane];
-        }
-        const vec z = relu_operand<T>(acc1[c / QB], c % QB);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int nb = 0; nb < MB; ++nb) Opd::mma(wc[nb], z, acc2[nb]);
-        __builtin_amdgcn_sched_barrier(0);
-        if (c + 1 < NC2) {
-#pragma unroll
-          for (int nb = 0; nb < MB; ++nb) wc[nb] = wn[nb];
-        }
-      }
-    }
+    layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
     // ---------------- epilogue
     T *out = (T *)a.out;
     if constexpr (KIND == KIND_NODE) {
@@ -210,5 +219,96 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     } else {
       edge_tile_sum<T, H>(acc2, meta, wt, nv, lane, out, a.carry, stage);
     }
+  }
+}
+
+// The node-update layer's MLP (Section 3.4) in the same persistent form. Its first layer needs
+// little LDS -- the fp32 fragments for the [edge-attr sum | dense attrs] columns and the [Tn, H]
+// table of W1's one-hot rows -- so two blocks fit a CU. At most 4 * 64 * NW 16-byte pieces each
+// for the first-layer fragments and for the table (the launcher checks).
+template <typename T, int H, int NW>
+__global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
+  using Opd = Operand<T>;
+  using vec = typename Opd::vec;
+  constexpr int V = Opd::V, SL = 2 * V, MB = H / 32, QB = 32 / SL, NC2 = MB * QB, NT = 64 * NW;
+  extern __shared__ __align__(16) char smem[];
+  vec *W2l = (vec *)smem;                                              // [NC2][MB][64]
+  f32x4 *W1l = (f32x4 *)(W2l + (size_t)NC2 * MB * 64);                 // [nslabx][MB][64]
+  f32x4 *tab = W1l + (size_t)a.nslabx * MB * 64;                       // [Tn][H / 4]
+  float(*b1l)[2][16] = (float(*)[2][16])(tab + (size_t)a.Tn * (H / 4));
+  float(*b2l)[2][16] = b1l + MB;
+  char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * RowStage<T, H>::BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
+  const int64_t n_wt = (a.n_rows + 31) / 32;
+  const int64_t per_xcd = (n_wt + 7) / 8;
+  const int64_t t_begin = xcd * per_xcd;
+  const int64_t t_end = (t_begin + per_xcd) < n_wt ? (t_begin + per_xcd) : n_wt;
+  const int64_t stride = (int64_t)nbx * NW;
+  int64_t wt = t_begin + (int64_t)wave * nbx + lid;
+  {
+    constexpr int N2 = NC2 * MB * 64, C2 = (N2 + NT - 1) / NT;
+    const int n1 = a.nslabx * MB * 64, nt = a.Tn * (H / 4);
+    const vec *s2 = (const vec *)a.W2s;
+    const f32x4 *s1 = (const f32x4 *)a.W1x, *st = (const f32x4 *)a.table;
+    vec t2[C2];
+    f32x4 t1[4], tt[4];
+#pragma unroll
+    for (int c = 0; c < C2; ++c) t2[c] = s2[tid + c * NT < N2 ? tid + c * NT : 0];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) t1[c] = s1[tid + c * NT < n1 ? tid + c * NT : 0];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) tt[c] = st[tid + c * NT < nt ? tid + c * NT : 0];
+    float bb1 = 0.f, bb2 = 0.f;
+    if (tid < MB * 32) {
+      bb1 = a.b1[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+      bb2 = a.b2[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+    }
+#pragma unroll
+    for (int c = 0; c < C2; ++c)
+      if (tid + c * NT < N2) W2l[tid + c * NT] = t2[c];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (tid + c * NT < n1) W1l[tid + c * NT] = t1[c];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (tid + c * NT < nt) tab[tid + c * NT] = tt[c];
+    if (tid < MB * 32) {
+      b1l[tid / 32][(tid / 16) % 2][tid % 16] = bb1;
+      b2l[tid / 32][(tid / 16) % 2][tid % 16] = bb2;
+    }
+  }
+  __syncthreads();
+
+  for (; wt < t_end; wt += stride) {
+    asm volatile("" ::: "memory");
+    const int64_t row0 = wt * 32;
+    const int64_t row = row0 + l32 < a.n_rows ? row0 + l32 : a.n_rows - 1;
+    const EmbedRow er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
+    // ---------------- layer 1: bias + the op type's row of W1, then the fp32 columns on the MFMAs
+    f32x16 acc1[MB];
+    const f32x4 *trow = tab + (size_t)er.op * (H / 4) + g;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 t = trow[8 * mb + 2 * q];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] += t[j];
+      }
+    }
+    for (int s = 0; s < a.nslabx; ++s) {
+      const f32x4 x = embed_columns(er, a.edge_feat, a.De, a.Dd, s * 8 + g * 4);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) Operand<float>::mma(W1l[(s * MB + mb) * 64 + lane], x, acc1[mb]);
+    }
+    f32x16 acc2[MB];
+    layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+    T *out = (T *)a.out;
+    store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
+      return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
+    });
   }
 }

@@ -78,6 +78,11 @@ struct EncMlp {           // device pointers of one encoder MLP
   const void *W2bt = nullptr, *W1bt = nullptr;   // backward: contraction over the weight's columns
   const float *b1 = nullptr, *b2 = nullptr;
   int nslab1 = 0;
+  // embed MLP, forward: W1's rows for [edge-attr sum | dense attrs] in fragment order (fp32), and
+  // its rows for the one-hot op type as a plain [Tn, H] table
+  const void *W1x = nullptr;
+  const float *table = nullptr;
+  int nslabx = 0;
 };
 
 }  // namespace
@@ -157,7 +162,7 @@ int upload_weights(xrl_ctx *c, const float *w) {
   const int V = c->elem == 2 ? 8 : 4, H = m.hidden;
   // build the fragment-ordered blob on the host
   std::vector<char> blob;
-  struct Ref { size_t w1, w2, w2bt, w1bt; int ns; };
+  struct Ref { size_t w1, w2, w2bt, w1bt, w1x = 0; int ns, nsx = 0; };
   std::vector<Ref> refs;
   auto add = [&](const MlpRef &r, bool l1_fp32) {
     Ref ref;
@@ -177,6 +182,15 @@ int upload_weights(xrl_ctx *c, const float *w) {
     if (has_dx)
       for (int k = 0; k < 2 * H; ++k)
         for (int f = 0; f < H; ++f) w1t[(size_t)f * 2 * H + k] = w[r.w[0] + (size_t)k * H + f];
+    if (l1_fp32) {                                     // the embed MLP (see EncMlp::W1x)
+      const int De = m.d_edge, Tn = m.n_op_types, Dd = m.n_node_dense;
+      std::vector<float> wc((size_t)(De + Dd) * H), tx;
+      memcpy(wc.data(), w + r.w[0], sizeof(float) * (size_t)De * H);
+      memcpy(wc.data() + (size_t)De * H, w + r.w[0] + (size_t)(De + Tn) * H, sizeof(float) * (size_t)Dd * H);
+      swizzle_l1<float>(wc.data(), De + Dd, H, 4, tx);
+      ref.w1x = put(tx.data(), tx.size() * 4);
+      ref.nsx = (De + Dd + 7) / 8;
+    }
     if (c->elem == 2) {
       std::vector<uint16_t> t;
       if (l1_fp32) {
@@ -226,6 +240,9 @@ int upload_weights(xrl_ctx *c, const float *w) {
     e.b1 = c->d_w + r.b[0];
     e.b2 = c->d_w + r.b[1];
     e.nslab1 = ref.ns;
+    e.W1x = c->d_swz + ref.w1x;
+    e.nslabx = ref.nsx;
+    e.table = c->d_w + r.w[0] + (size_t)m.d_edge * H;    // meaningful for the embed MLP only
   };
   size_t i = 0;
   bind(c->embed, refs[i++], c->L.embed);
@@ -403,17 +420,52 @@ int launch_mlp2p(xrl_ctx *c, int kind, Mlp2Args &a) {
   return launch_mlp2p_k<H, KIND_NODE>(c, a, lds);
 }
 
+inline size_t embedp_lds_bytes(int H, int nslabx, int Tn) {
+  const int MB = H / 32, HS = H / 16;
+  return ((size_t)nslabx * MB + (size_t)HS * MB) * 1024 + (size_t)Tn * H * 4 + (size_t)MB * 256 +
+         (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;
+}
+
+template <int H>
+int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
+  constexpr int NW = kPersistWaves;
+  const size_t lds = embedp_lds_bytes(H, a.nslabx, a.Tn);
+  auto kern = embedp_kernel<bf16_t, H, NW>;
+  static size_t attr_lds = 0;
+  if (lds > attr_lds) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_lds = lds;
+  }
+  const int64_t n_wt = (a.n_rows + 31) / 32;
+  a.n_blocks = n_wt;
+  int64_t grid = ((n_wt + NW - 1) / NW + 7) / 8 * 8;
+  const int per_cu = 2 * lds <= (size_t)c->max_lds ? 2 : 1;   // blocks that fit a CU's LDS
+  const int64_t cap = (int64_t)c->n_cu / 8 * 8 * per_cu;
+  if (grid > cap) grid = cap;
+  kern<<<dim3((unsigned)grid), dim3(64 * NW), lds, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
 inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   const int H = c->m.hidden;
-  if (c->elem != 2 || kind == KIND_EMBED || H > 128 || a.n_rows <= 0 || !c->use_persistent) return false;
+  if (c->elem != 2 || H > 128 || a.n_rows <= 0 || !c->use_persistent) return false;
   if (a.n_rows < c->p_min_rows) return false;
+  if (kind == KIND_EMBED) {
+    const int pieces = 4 * 64 * kPersistWaves;               // see embedp_kernel
+    return a.nslabx * (H / 32) * 64 <= pieces && a.Tn * (H / 4) <= pieces &&
+           embedp_lds_bytes(H, a.nslabx, a.Tn) <= (size_t)c->max_lds;
+  }
   if (kind == KIND_EDGE && a.nslab1 != 2 * (H / 16) + 1) return false;   // edge attrs must fit one slab
   return mlp2p_lds_bytes(H, a.nslab1) <= (size_t)c->max_lds;
 }
 
 template <typename T>
 int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
-  if (mlp2p_applies(c, kind, a)) return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
+  if (mlp2p_applies(c, kind, a)) {
+    if (kind == KIND_EMBED) return c->m.hidden == 64 ? launch_embedp<64>(c, a) : launch_embedp<128>(c, a);
+    return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
+  }
   a.n_blocks = kind == KIND_EDGE ? (a.n_tiles + 3) / 4 : (a.n_rows + 127) / 128;
   switch (c->m.hidden) {
     case 64: return launch_mlp2_h<T, 64>(c, kind, a);
@@ -737,7 +789,10 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
   a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
   a.carry = c->carry; a.tile_ptr = d.tile_ptr; a.n_tiles = n_tiles;
-  auto set_w = [&](const EncMlp &e) { a.W1s = e.W1s; a.W2s = e.W2s; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1; };
+  auto set_w = [&](const EncMlp &e) {
+    a.W1s = e.W1s; a.W2s = e.W2s; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
+    a.W1x = e.W1x; a.nslabx = e.nslabx; a.table = e.table;
+  };
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }

@@ -9,6 +9,10 @@ tensor and elementwise:   |g - ref| <= 1e-4 |ref| + 1e-4 scale + 3e-4 B
   The candidates of a state are near-copies of its current graph and softmax gradients sum to
   zero per state, so in the policy-driven gradients B exceeds |ref| by 1e2..1e4; the forward's
   1e-5 relative bound cannot hold for such entries in fp32.
+  Up to max(2, 5e-5 of the tensor's entries) may exceed that bound, by at most a factor 5: a
+  pre-activation that lies within fp32 rounding of zero (a few among the 1e7 of a case) takes the
+  other ReLU mask than in the float64 oracle, and its whole term -- about B / rows, not
+  eps * B -- then differs.
 bf16 path: the backward pass multiplies by ReLU masks taken from the bf16 forward. A
   pre-activation that lies within the forward's rounding error of zero (about 0.4 % of them) gets
   the opposite mask from the float64 oracle, and each flipped term enters the gradient in full;
@@ -56,8 +60,9 @@ def check_grads(got, ref, bound, model, only=None):
             continue
         g, r, B = got[sl].astype(np.float64), ref[sl], bound[sl]
         scale = max(float(np.abs(r).max()), 1e-3 * gscale)
-        err = np.abs(g - r) - (1e-4 * np.abs(r) + 1e-4 * scale + 3e-4 * B)
-        if err.max() > 0:
+        tol = 1e-4 * np.abs(r) + 1e-4 * scale + 3e-4 * B
+        err = np.abs(g - r) - tol
+        if (err > 0).sum() > max(2, 5e-5 * g.size) or np.any(np.abs(g - r) > 5 * tol):
             i = int(np.argmax(err))
             bad.append(f"{name}: {(err > 0).sum()}/{g.size} outside tolerance, worst [{i}] got {g[i]:.6g} "
                        f"ref {r[i]:.6g} scale {scale:.3g} B {B[i]:.3g}")
