@@ -38,6 +38,10 @@ struct Mlp2Args {
   const void *W1x;         // EMBED: fragment-ordered fp32 rows of W1 for [edge-attr sum | dense attrs]
   int nslabx;              // EMBED: its slabs
   const float *table;      // EMBED: [Tn, H] fp32 rows of W1 for the one-hot op type
+  const void *zero_row;    // 1 KB of zeros (source of rows that are absent)
+  void *agg0;              // EMBED: first of n_agg received-sum buffers [N, H], agg_stride bytes apart;
+  size_t agg_stride;       //        the embed kernel zeroes their rows of nodes without in-edges, which
+  int n_agg;               //        the message kernels never write
   void *out;               // [N, H] operand type
   float *carry;            // [n_tiles, 2, H]                (EDGE)
   const int32_t *tile_ptr; // [n_tiles + 1] first edge of each edge tile (EDGE)
@@ -192,6 +196,24 @@ __device__ __forceinline__ f32x4 embed_columns(const EmbedRow &r, const float *e
   return x;
 }
 
+// EMBED: zero rows of the received-sum buffers for the tile's nodes without in-edges (`no_in`:
+// this lane's node, lane = row l % 32), whole rows, 16 bytes per lane.
+template <typename T, int H>
+__device__ __forceinline__ void zero_source_rows(const Mlp2Args &a, int64_t row0, bool no_in, int lane) {
+  constexpr int LPR = H * (int)sizeof(T) / 16, RPI = 64 / LPR;
+  if (a.n_agg == 0 || !__any(no_in)) return;
+  const int flag = no_in ? 1 : 0;
+#pragma unroll
+  for (int k = 0; k < 32 / RPI; ++k) {
+    const int r = k * RPI + lane / LPR;
+    const bool z = __shfl(flag, r) != 0 && row0 + r < a.n_rows;
+    if (z)
+      for (int i = 0; i < a.n_agg; ++i)
+        *(f32x4 *)((char *)a.agg0 + i * a.agg_stride + ((size_t)(row0 + r) * H) * sizeof(T) + (lane % LPR) * 16) =
+            f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
 // T1 = operand type of layer 1 (its input rows and W1), T = operand type of layer 2 and of the
 // stored activations. They differ only for EMBED in bf16 mode, whose first layer stays in fp32:
 // its inputs (log2 shape attributes up to 12, sums of edge attributes) are large enough for bf16
@@ -239,15 +261,13 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
     // both H-wide parts of the input row are requested up front (one exposed latency instead
     // of one per slab); the weight fragments are requested one slab ahead of their MFMAs
     const T *pa, *pb;
-    bool has_b = true;
     if constexpr (KIND == KIND_EDGE) {
       pa = (const T *)a.h + (size_t)a.in_src[row] * H + g * V;
       pb = (const T *)a.h + (size_t)a.in_dst[row] * H + g * V;
     } else {
       pa = (const T *)a.h + (size_t)row * H + g * V;
-      pb = (const T *)a.agg + (size_t)row * H + g * V;
-      has_b = a.in_ptr[row + 1] > a.in_ptr[row];                // agg rows of source nodes are unwritten
-    }
+      pb = (const T *)a.agg + (size_t)row * H + g * V;   // (rows of nodes without in-edges were zeroed
+    }                                                    //  by the embed kernel)
     vec xa[HS], xb[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) xa[s] = *(const vec *)(pa + s * SL);
@@ -264,8 +284,7 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) wn[mb] = W1[((size_t)(s + 1) * MB + mb) * 64];
       }
-      vec x = s < HS ? xa[s < HS ? s : 0] : xb[s < HS ? 0 : s - HS];
-      if (s >= HS && !has_b) x = Opd::zero();
+      const vec x = s < HS ? xa[s < HS ? s : 0] : xb[s < HS ? 0 : s - HS];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) Opd::mma(wc[mb], x, acc1[mb]);
 #pragma unroll
@@ -340,6 +359,7 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
     store_rows_via_lds<T, H, true>(acc2, stage[wave], lane, [&](int r) -> T * {
       return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
     });
+    if constexpr (KIND == KIND_EMBED) zero_source_rows<T, H>(a, row0, a.in_ptr[row + 1] == a.in_ptr[row], lane);
   } else {
     const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, nv, l32);
     edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry, stage[wave]);

@@ -21,7 +21,6 @@ struct TileRows {
   static constexpr int NX = 2 * (H / (2 * Operand<T>::V));   // slabs of the two H-wide parts
   vec x[NX];
   TailRaw<Operand<T>::V> xe;   // EDGE: the single zero-padded slab of edge attributes, raw
-  int has_in;                  // NODE: receiver has in-edges (else its agg row is unwritten)
 };
 
 struct TileIndex {
@@ -64,7 +63,6 @@ __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32
     if (row >= a.n_rows) row = a.n_rows - 1;
     const T *hp = (const T *)a.h + (size_t)row * H + g * V;
     const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
-    in.has_in = a.in_ptr[row + 1] - a.in_ptr[row];
 #pragma unroll
     for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hp + k * SL);
 #pragma unroll
@@ -175,11 +173,6 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     f32x16 acc1[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
-    if constexpr (KIND == KIND_NODE) {
-      if (in.has_in == 0)
-#pragma unroll
-        for (int k = 0; k < HS; ++k) in.x[HS + k] = Opd::zero();
-    }
     [[maybe_unused]] vec xe;
     if constexpr (KIND == KIND_EDGE) xe = tail_to_operand<T>(in.xe);
     {
@@ -310,5 +303,6 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
       return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
     });
+    zero_source_rows<T, H>(a, row0, er.e0 == er.e1, lane);
   }
 }

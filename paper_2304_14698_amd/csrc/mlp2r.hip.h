@@ -1,0 +1,280 @@
+// Register-stationary variant of the fused two-layer MLP for H = 256 in bf16 (edge and node
+// kinds), where the fragment-ordered weights (about 400 KB) fit neither LDS nor one wave's
+// registers: one persistent block of 8 waves per CU, wave w owning output features
+// [32w, 32w + 32) of both layers. Its slices of W1 (33 fragments) and W2 (16 fragments) stay in
+// registers for the whole kernel, so the steady state moves no weights at all; what the waves
+// share instead is the input: a tile of 32 rows is gathered once per block into LDS and read by
+// all 8 waves as MFMA operands, and layer 1's output is exchanged through LDS in operand
+// fragment order.
+//
+// The gather uses the loads that write LDS directly (16 bytes per lane, no registers in between;
+// lane i of an instruction fills bytes [16 i, 16 i + 16) of a 1 KB destination): one instruction
+// fetches two 512-byte row parts, each lane one 16-byte piece, so global reads are whole rows.
+// Which piece a lane fetches is permuted per row -- slot j of row r holds piece j ^ (r % 16) --
+// which makes the operand reads (32 rows x the same piece) bank-conflict free without padding.
+// The loads of tile t+2 are issued at the end of tile t into the buffer tile t just vacated and
+// are awaited at the end of tile t+1: a whole tile of compute hides their latency. Row indices
+// are requested one tile earlier still.
+//
+// Per tile (two block barriers):
+//   layer 1: z1[32w.., rows] = W1[:, 32w..]^T x^T            33 MFMAs per wave, x from LDS
+//   ReLU, bf16, own two fragments -> zbuf; barrier
+//   layer 2: y[32w.., rows] = W2[:, 32w..]^T relu(z1)^T       16 MFMAs per wave, z from LDS
+//   epilogue on the wave's 32 features: NODE ReLU; EDGE ReLU + per-receiver sum across lanes;
+//   rows -> staging buffer; wait for tile t+1's rows; barrier
+//   whole rows stored, 16 bytes per lane; loads of tile t+2 issued
+#pragma once
+#include "mlp2.hip.h"
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+template <int KIND>
+struct RTile {
+  static constexpr int H = 256;
+  static constexpr int XPART = 32 * 512;                                   // one H-wide part of 32 rows
+  static constexpr int XBUF = 2 * XPART + (KIND == KIND_EDGE ? 1024 : 0);  // + raw fp32 edge attributes
+  static constexpr int ZBUF = 16 * 1024;                                   // 16 chunks x 64 lanes x 16 bytes
+  static constexpr int SROW = H * 2 + 16, SBUF = 32 * SROW;                // output staging, padded rows
+  static constexpr int NC2L = KIND == KIND_EDGE ? 7 : 6;                   // W2 fragments per wave kept in LDS
+  static constexpr int W2L = 8 * NC2L * 1024;
+  static constexpr int BYTES = 2 * XBUF + ZBUF + SBUF + 256 + 2 * 1024 + W2L;   // + receiver rows, biases, W2 part
+};
+
+// Rows of one tile: EDGE tiles are the packer's edge tiles, NODE tiles are 32 consecutive nodes.
+struct RTileRows {
+  int64_t r0;   // first row
+  int nv;       // rows in the tile (1..32)
+};
+template <int KIND>
+__device__ __forceinline__ RTileRows rtile_rows(const Mlp2Args &a, int64_t wt) {
+  RTileRows t;
+  if constexpr (KIND == KIND_EDGE) {
+    t.r0 = a.tile_ptr[wt];
+    t.nv = a.tile_ptr[wt + 1] - (int)t.r0;
+  } else {
+    t.r0 = wt * 32;
+    const int64_t left = a.n_rows - t.r0;
+    t.nv = left < 32 ? (int)left : 32;
+  }
+  return t;
+}
+
+// What this lane fetches for a tile: wave w issues the four instructions of row parts 4w .. 4w+3
+// (parts 0..15: sender / node-state rows 2k, 2k+1; parts 16..31: receiver / received-sum rows),
+// wave 0 also the edge attributes. src[j] is the global row the lane reads for instruction j
+// (rows past the tile's last repeat it and are never stored). Nothing here branches on a loaded
+// value, so the index loads can stay in flight until the rows are fetched a tile later.
+struct RFetch {
+  int src[4];
+};
+template <int KIND>
+__device__ __forceinline__ RFetch rtile_index(const Mlp2Args &a, const RTileRows &t, int w, int lane) {
+  RFetch f;
+  const int32_t *ip = w < 4 ? a.in_src : a.in_dst;             // EDGE: parts 0..15 senders, 16..31 receivers
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = 2 * ((4 * w + j) & 15) + (lane >> 5);
+    const int64_t row = t.r0 + (r < t.nv ? r : t.nv - 1);
+    if constexpr (KIND == KIND_EDGE) f.src[j] = ip[row];
+    else f.src[j] = (int)row;
+  }
+  return f;
+}
+template <int KIND>
+__device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &t, const RFetch &f, int w, int lane,
+                                            char *xbuf) {
+  constexpr int H = 256;
+  const bf16_t *base = (KIND == KIND_NODE && w >= 4) ? (const bf16_t *)a.agg : (const bf16_t *)a.h;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int rp = 4 * w + j, r = 2 * (rp & 15) + (lane >> 5);
+    const int piece = (lane & 31) ^ (r & 15);
+    __builtin_amdgcn_global_load_lds((const void *)(base + (size_t)f.src[j] * H + piece * 8),
+                                     (lds_void_t *)(xbuf + rp * 1024), 16, 0, 0);
+  }
+  if constexpr (KIND == KIND_EDGE) {
+    if (w == 0) {                                               // 32 rows x 32 bytes of raw fp32 attributes
+      const int r = lane >> 1, half = lane & 1;
+      const int64_t erow = t.r0 + (r < t.nv ? r : t.nv - 1);
+      const void *g = 4 * half < a.De ? (const void *)(a.edge_feat + (size_t)erow * a.De + 4 * half)
+                                      : (const void *)a.zero_row;
+      __builtin_amdgcn_global_load_lds(g, (lds_void_t *)(xbuf + 2 * RTile<KIND>::XPART), 16, 0, 0);
+    }
+  }
+}
+
+template <int KIND>
+__global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
+  using T = bf16_t;
+  using R = RTile<KIND>;
+  constexpr int H = 256, MB = 8, HS = H / 16;
+  constexpr int NS1 = 2 * HS + (KIND == KIND_EDGE ? 1 : 0), NC2 = 16;
+  static_assert(KIND == KIND_EDGE || KIND == KIND_NODE, "edge and node MLPs only");
+  extern __shared__ __align__(16) char smem[];
+  char *zbuf = smem + 2 * R::XBUF;
+  char *sbuf = zbuf + R::ZBUF;
+  int *drow = (int *)(sbuf + R::SBUF);                         // EDGE: destination row of each staged row
+  float(*b1l)[2][16] = (float(*)[2][16])(sbuf + R::SBUF + 256), (*b2l)[2][16] = b1l + 8;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
+  const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
+  const int64_t per_xcd = (n_wt + 7) / 8;
+  const int64_t t_begin = xcd * per_xcd;
+  const int64_t t_end = (t_begin + per_xcd) < n_wt ? (t_begin + per_xcd) : n_wt;
+  int64_t wt = t_begin + lid;
+  if (wt >= t_end) return;                                     // the whole block leaves together
+
+  // first two tiles' rows, third tile's indices
+  RTileRows cur = rtile_rows<KIND>(a, wt);
+  RTileRows nxt = cur;
+  rtile_fetch<KIND>(a, cur, rtile_index<KIND>(a, cur, w, lane), w, lane, smem);
+  if (wt + nbx < t_end) {
+    nxt = rtile_rows<KIND>(a, wt + nbx);
+    rtile_fetch<KIND>(a, nxt, rtile_index<KIND>(a, nxt, w, lane), w, lane, smem + R::XBUF);
+  }
+  RTileRows nn = nxt;
+  RFetch fn;
+  if (wt + 2 * nbx < t_end) {
+    nn = rtile_rows<KIND>(a, wt + 2 * nbx);
+    fn = rtile_index<KIND>(a, nn, w, lane);
+  }
+  // this wave's weight slices, loaded once, and the biases in accumulator order (parked in LDS:
+  // the weight slices leave few registers)
+  constexpr int NC2R = NC2 - R::NC2L;                         // W2 fragments in registers; the rest in LDS
+  bf16x8 W1r[NS1], W2r[NC2R];
+  bf16x8 *W2l = (bf16x8 *)((char *)(b2l + 8) + w * R::NC2L * 1024) + lane;   // [NC2L][64] of this wave
+  {
+    const bf16x8 *s1 = (const bf16x8 *)a.W1s + w * 64 + lane, *s2 = (const bf16x8 *)a.W2s + w * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < NS1; ++s) W1r[s] = s1[(size_t)s * MB * 64];
+#pragma unroll
+    for (int c = 0; c < NC2R; ++c) W2r[c] = s2[(size_t)c * MB * 64];
+#pragma unroll
+    for (int c = NC2R; c < NC2; ++c) W2l[(c - NC2R) * 64] = s2[(size_t)c * MB * 64];
+  }
+  // byte offsets of this lane's operand pieces inside a row part: piece 2k + g of row l32 sits in
+  // slot (2k + g) ^ (l32 % 16); pieces 16.. add 256
+  int off8[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) off8[k] = l32 * 512 + (((2 * k + g) ^ (l32 & 15)) << 4);
+  if (tid < 256) {
+    b1l[tid / 32][(tid / 16) % 2][tid % 16] = a.b1[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+    b2l[tid / 32][(tid / 16) % 2][tid % 16] = a.b2[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): both tiles' rows are in LDS
+  __syncthreads();
+
+  int buf = 0;
+  for (; wt < t_end; wt += nbx) {
+    const char *xb = smem + buf * R::XBUF;
+    asm volatile("" ::: "memory");
+    // ---------------- layer 1: this wave's 32 features x the tile's rows (each operand is read
+    // from LDS one MFMA ahead of its use)
+    f32x16 acc = *(const f32x16 *)&b1l[w][g][0];
+    {
+      auto xread = [&](int s) {
+        return *(const bf16x8 *)(xb + (s >> 4) * R::XPART + ((s >> 3) & 1) * 256 + off8[s & 7]);
+      };
+      bf16x8 xf = xread(0);
+#pragma unroll
+      for (int s = 0; s < 2 * HS; ++s) {
+        bf16x8 xn = xf;
+        if (s + 1 < 2 * HS) xn = xread(s + 1);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(W1r[s], xf, acc, 0, 0, 0);
+        xf = xn;
+      }
+      if constexpr (KIND == KIND_EDGE) {
+        const float *xe = (const float *)(xb + 2 * R::XPART + l32 * 32);
+        TailRaw<8> raw;
+        raw.q[0] = *(const f32x4 *)xe;
+        raw.q[1] = *(const f32x4 *)(xe + 4);
+        const bf16x8 xt = g == 0 ? tail_to_operand<T>(raw) : Operand<bf16_t>::zero();
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(W1r[2 * HS], xt, acc, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      *(bf16x8 *)(zbuf + ((2 * w + q) * 64 + lane) * 16) = relu_operand<T>(acc, q);
+    __syncthreads();
+    // ---------------- layer 2
+    acc = *(const f32x16 *)&b2l[w][g][0];
+    {
+      const bf16x8 *zr = (const bf16x8 *)zbuf + lane;
+      bf16x8 zf = zr[0];
+#pragma unroll
+      for (int c = 0; c < NC2; ++c) {
+        bf16x8 zn = zf;
+        if (c + 1 < NC2) zn = zr[(c + 1) * 64];
+        const bf16x8 wf = c < NC2R ? W2r[c < NC2R ? c : 0] : W2l[(c < NC2R ? 0 : c - NC2R) * 64];
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, zf, acc, 0, 0, 0);
+        zf = zn;
+      }
+    }
+    // ---------------- epilogue on this wave's 32 features
+    T *out = (T *)a.out;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = relu_f32(acc[r]);
+    if constexpr (KIND == KIND_EDGE) {
+      const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, cur.r0, cur.nv, l32);
+      const bool valid = l32 < cur.nv;
+      const int up = __shfl_up(m.dst, 1);
+      const bool head = valid && (l32 == 0 || up != m.dst);
+      const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << cur.nv);
+      const int rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
+      for (int d = 1; __any(rem >= d); d <<= 1) {
+        const bool take = rem >= d;
+        const int from = ((lane + d) & 63) << 2;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc[r];
+          const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
+          acc[r] = v + (take ? t : 0.f);
+        }
+      }
+      const bool ends_tile = l32 + rem == cur.nv - 1;
+      const bool to_c0 = head && l32 == 0 && m.prev_d == m.dst;
+      const bool to_c1 = head && !to_c0 && ends_tile && m.next_d == m.dst;
+      if (w == 0 && g == 0) drow[l32] = (head && !to_c0 && !to_c1) ? m.dst : -1;
+      if (to_c0 || to_c1) {
+        float *cp = a.carry + ((size_t)wt * 2 + (to_c1 ? 1 : 0)) * H + 32 * w + 4 * g;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float v[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+          store4<float>(cp + 8 * q, v);
+        }
+      }
+    }
+    {
+      char *sp = sbuf + l32 * R::SROW + (32 * w + 4 * g) * 2;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[4] = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        store4<T>((T *)(sp + 16 * q), v);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): the next tile's rows are in LDS
+    __syncthreads();
+    {
+      const int piece = tid & 31, rr = tid >> 5;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int r = rr + 16 * j;
+        const f32x4 v = *(const f32x4 *)(sbuf + r * R::SROW + piece * 16);
+        int64_t drw;
+        if constexpr (KIND == KIND_EDGE) drw = drow[r];
+        else drw = r < cur.nv ? cur.r0 + r : -1;
+        if (drw >= 0) *(f32x4 *)((char *)(out + (size_t)drw * H) + piece * 16) = v;
+      }
+    }
+    // the buffer this tile used is free now: rows of the tile after next, indices one further
+    if (wt + 2 * nbx < t_end) rtile_fetch<KIND>(a, nn, fn, w, lane, smem + buf * R::XBUF);
+    cur = nxt;
+    nxt = nn;
+    if (wt + 3 * nbx < t_end) {
+      nn = rtile_rows<KIND>(a, wt + 3 * nbx);
+      fn = rtile_index<KIND>(a, nn, w, lane);
+    }
+    buf ^= 1;
+  }
+}

@@ -11,6 +11,7 @@
 #include "mlp2.hip.h"
 #include "mlp2_bwd.hip.h"
 #include "mlp2p.hip.h"
+#include "mlp2r.hip.h"
 #include "wgrad.hip.h"
 #include "segsum.hip.h"
 #include "xrl_internal.h"
@@ -102,6 +103,7 @@ struct xrl_ctx {
   bool use_persistent = true;   // LDS-resident-weights MLP kernels where they apply
   int64_t p_min_rows = 0;       // development switch: smallest row count for the persistent kernels
   float *d_w = nullptr;         // flat fp32 weights
+  void *zero_row = nullptr;     // 1 KB of zeros behind the weights
   char *d_swz = nullptr;        // fragment-ordered encoder weights
   size_t swz_bytes = 0;
   EncMlp embed;
@@ -460,8 +462,37 @@ inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   return mlp2p_lds_bytes(H, a.nslab1) <= (size_t)c->max_lds;
 }
 
+// Register-stationary variant (bf16, H = 256, edge and node kinds).
+template <int KIND>
+int launch_mlp2r_k(xrl_ctx *c, Mlp2Args &a) {
+  auto kern = mlp2r_kernel<KIND>;
+  constexpr int lds = RTile<KIND>::BYTES;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
+  a.n_blocks = n_wt;
+  int64_t grid = (n_wt + 7) / 8 * 8;
+  const int64_t cap = (int64_t)c->n_cu / 8 * 8;
+  if (grid > cap) grid = cap;
+  kern<<<dim3((unsigned)grid), dim3(512), lds, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+inline bool mlp2r_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
+  if (c->elem != 2 || c->m.hidden != 256 || kind == KIND_EMBED || a.n_rows <= 0 || !c->use_persistent) return false;
+  if (a.n_rows < c->p_min_rows) return false;
+  if (kind == KIND_EDGE && (a.De > 8 || a.nslab1 != 33)) return false;   // edge attrs: half a slab
+  return (size_t)RTile<KIND_EDGE>::BYTES <= (size_t)c->max_lds;
+}
+
 template <typename T>
 int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
+  if (mlp2r_applies(c, kind, a))
+    return kind == KIND_EDGE ? launch_mlp2r_k<KIND_EDGE>(c, a) : launch_mlp2r_k<KIND_NODE>(c, a);
   if (mlp2p_applies(c, kind, a)) {
     if (kind == KIND_EMBED) return c->m.hidden == 64 ? launch_embedp<64>(c, a) : launch_embedp<128>(c, a);
     return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
@@ -788,13 +819,14 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   a.De = De; a.Tn = m.n_op_types; a.Dd = m.n_node_dense;
   a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
   a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
-  a.carry = c->carry; a.tile_ptr = d.tile_ptr; a.n_tiles = n_tiles;
+  a.carry = c->carry; a.tile_ptr = d.tile_ptr; a.n_tiles = n_tiles; a.zero_row = c->zero_row;
   auto set_w = [&](const EncMlp &e) {
     a.W1s = e.W1s; a.W2s = e.W2s; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
     a.W1x = e.W1x; a.nslabx = e.nslabx; a.table = e.table;
   };
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
+  a.agg0 = ab[0]; a.n_agg = nagg; a.agg_stride = nagg > 1 ? (size_t)((char *)ab[1] - (char *)ab[0]) : 0;
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
   c->h[0] = hb[0];
@@ -889,10 +921,18 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
       if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) c->max_lds = v;
     }
   }
-  e = hipMalloc((void **)&c->d_w, sizeof(float) * L.total);
+  // the weights, followed by 1 KB of zeros (16-byte aligned) that kernels read in place of absent rows
+  const size_t w_bytes = align_up(sizeof(float) * L.total);
+  e = hipMalloc((void **)&c->d_w, w_bytes + 1024);
   if (e != hipSuccess) {
     delete c;
     return fail(XRL_ERR_OOM, "device weights: %s", hipGetErrorString(e));
+  }
+  c->zero_row = (char *)c->d_w + w_bytes;
+  e = hipMemset(c->zero_row, 0, 1024);
+  if (e != hipSuccess) {
+    xrl_destroy(c);
+    return fail(XRL_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
   }
   rc = upload_weights(c, weights_host);
   if (rc) {
