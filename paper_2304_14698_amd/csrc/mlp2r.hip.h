@@ -26,7 +26,21 @@
 #pragma once
 #include "mlp2.hip.h"
 
-typedef __attribute__((address_space(3))) void lds_void_t;
+// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at LDS byte
+// lds_base + 16 i (lds_base uniform across the wave). Written as inline assembly on purpose:
+// the compiler makes every later LDS access wait for its own LDS-direct loads, whichever
+// buffer they target, which would serialise the prefetch with the compute it is meant to
+// overlap. Whoever reads the destination must wait for vmcnt(0) and a barrier first.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void lds_direct_load16(const void *g, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ unsigned lds_address(const void *p) {
+  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
+}
 
 template <int KIND>
 struct RTile {
@@ -89,8 +103,8 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
   for (int j = 0; j < 4; ++j) {
     const int rp = 4 * w + j, r = 2 * (rp & 15) + (lane >> 5);
     const int piece = (lane & 31) ^ (r & 15);
-    __builtin_amdgcn_global_load_lds((const void *)(base + (size_t)f.src[j] * H + piece * 8),
-                                     (lds_void_t *)(xbuf + rp * 1024), 16, 0, 0);
+    lds_direct_load16(base + (size_t)f.src[j] * H + piece * 8,
+                      __builtin_amdgcn_readfirstlane(lds_address(xbuf) + rp * 1024));
   }
   if constexpr (KIND == KIND_EDGE) {
     if (w == 0) {                                               // 32 rows x 32 bytes of raw fp32 attributes
@@ -98,7 +112,7 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
       const int64_t erow = t.r0 + (r < t.nv ? r : t.nv - 1);
       const void *g = 4 * half < a.De ? (const void *)(a.edge_feat + (size_t)erow * a.De + 4 * half)
                                       : (const void *)a.zero_row;
-      __builtin_amdgcn_global_load_lds(g, (lds_void_t *)(xbuf + 2 * RTile<KIND>::XPART), 16, 0, 0);
+      lds_direct_load16(g, __builtin_amdgcn_readfirstlane(lds_address(xbuf) + 2 * RTile<KIND>::XPART));
     }
   }
 }
@@ -153,11 +167,11 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
 #pragma unroll
     for (int c = NC2R; c < NC2; ++c) W2l[(c - NC2R) * 64] = s2[(size_t)c * MB * 64];
   }
-  // byte offsets of this lane's operand pieces inside a row part: piece 2k + g of row l32 sits in
-  // slot (2k + g) ^ (l32 % 16); pieces 16.. add 256
-  int off8[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) off8[k] = l32 * 512 + (((2 * k + g) ^ (l32 & 15)) << 4);
+  // This lane's operand piece 2k + g of row l32 sits in slot (2k + g) ^ (l32 % 16) of its row part,
+  // i.e. at byte xrow + ((k ^ xk) << 5); pieces 16.. add 256. (Recomputed per read: two VALU
+  // instructions are cheaper here than eight more live registers.)
+  const int xk = (l32 & 15) >> 1;
+  const int xrow = l32 * 512 + (((l32 ^ g) & 1) << 4);
   if (tid < 256) {
     b1l[tid / 32][(tid / 16) % 2][tid % 16] = a.b1[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
     b2l[tid / 32][(tid / 16) % 2][tid % 16] = a.b2[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
@@ -169,12 +183,16 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
   for (; wt < t_end; wt += nbx) {
     const char *xb = smem + buf * R::XBUF;
     asm volatile("" ::: "memory");
+    [[maybe_unused]] EdgeTileMeta m;
+    if constexpr (KIND == KIND_EDGE) m = load_edge_meta(a.in_dst, a.n_rows, cur.r0, cur.nv, l32);
     // ---------------- layer 1: this wave's 32 features x the tile's rows (each operand is read
     // from LDS one MFMA ahead of its use)
     f32x16 acc = *(const f32x16 *)&b1l[w][g][0];
     {
+      int xk_t = xk;
+      asm volatile("" : "+v"(xk_t));                             // keeps the eight offsets out of registers
       auto xread = [&](int s) {
-        return *(const bf16x8 *)(xb + (s >> 4) * R::XPART + ((s >> 3) & 1) * 256 + off8[s & 7]);
+        return *(const bf16x8 *)(xb + (s >> 4) * R::XPART + ((s >> 3) & 1) * 256 + xrow + (((s & 7) ^ xk_t) << 5));
       };
       bf16x8 xf = xread(0);
 #pragma unroll
@@ -216,7 +234,6 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = relu_f32(acc[r]);
     if constexpr (KIND == KIND_EDGE) {
-      const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, cur.r0, cur.nv, l32);
       const bool valid = l32 < cur.nv;
       const int up = __shfl_up(m.dst, 1);
       const bool head = valid && (l32 == 0 || up != m.dst);
