@@ -194,13 +194,16 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
       auto xread = [&](int s) {
         return *(const bf16x8 *)(xb + (s >> 4) * R::XPART + ((s >> 3) & 1) * 256 + xrow + (((s & 7) ^ xk_t) << 5));
       };
-      bf16x8 xf = xread(0);
+      constexpr int RA = KIND == KIND_NODE ? 3 : 2;             // operands read ahead of their MFMA
+      bf16x8 xq[RA + 1];
+#pragma unroll
+      for (int i = 0; i < RA; ++i) xq[i] = xread(i);
 #pragma unroll
       for (int s = 0; s < 2 * HS; ++s) {
-        bf16x8 xn = xf;
-        if (s + 1 < 2 * HS) xn = xread(s + 1);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(W1r[s], xf, acc, 0, 0, 0);
-        xf = xn;
+        if (s + RA < 2 * HS) xq[(s + RA) % (RA + 1)] = xread(s + RA);
+        __builtin_amdgcn_sched_barrier(0);                      // keep the read ahead of the MFMA it follows
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(W1r[s], xq[s % (RA + 1)], acc, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       if constexpr (KIND == KIND_EDGE) {
         const float *xe = (const float *)(xb + 2 * R::XPART + l32 * 32);
@@ -219,14 +222,18 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
     acc = *(const f32x16 *)&b2l[w][g][0];
     {
       const bf16x8 *zr = (const bf16x8 *)zbuf + lane;
-      bf16x8 zf = zr[0];
+      // z fragments are read two chunks ahead, the W2 fragments parked in LDS one chunk ahead
+      bf16x8 zq[3], wl = W2r[0];
+      zq[0] = zr[0];
+      zq[1] = zr[64];
 #pragma unroll
       for (int c = 0; c < NC2; ++c) {
-        bf16x8 zn = zf;
-        if (c + 1 < NC2) zn = zr[(c + 1) * 64];
-        const bf16x8 wf = c < NC2R ? W2r[c < NC2R ? c : 0] : W2l[(c < NC2R ? 0 : c - NC2R) * 64];
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, zf, acc, 0, 0, 0);
-        zf = zn;
+        if (c + 2 < NC2) zq[(c + 2) % 3] = zr[(c + 2) * 64];
+        const bf16x8 wf = c < NC2R ? W2r[c < NC2R ? c : 0] : wl;
+        if (c + 1 >= NC2R && c + 1 < NC2) wl = W2l[(c + 1 - NC2R) * 64];
+        __builtin_amdgcn_sched_barrier(0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, zq[c % 3], acc, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     // ---------------- epilogue on this wave's 32 features
@@ -239,14 +246,17 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
       const bool head = valid && (l32 == 0 || up != m.dst);
       const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << cur.nv);
       const int rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
-      for (int d = 1; __any(rem >= d); d <<= 1) {
-        const bool take = rem >= d;
-        const int from = ((lane + d) & 63) << 2;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float v = acc[r];
-          const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
-          acc[r] = v + (take ? t : 0.f);
+      for (int d = 1; d < 32; d <<= 1) {                        // see edge_tile_sum
+        if (__any(rem >= d)) {
+          const bool take = rem >= d;
+          const int from = ((lane + d) & 63) << 2;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = acc[r];
+            const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
+            acc[r] = v + (take ? t : 0.f);
+          }
         }
       }
       const bool ends_tile = l32 + rem == cur.nv - 1;
