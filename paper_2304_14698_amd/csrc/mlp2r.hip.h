@@ -1,15 +1,18 @@
-// Register-stationary variant of the fused two-layer MLP for H = 256 in bf16 (edge and node
-// kinds), where the fragment-ordered weights (about 400 KB) fit neither LDS nor one wave's
-// registers: one persistent block of 8 waves per CU, wave w owning output features
-// [32w, 32w + 32) of both layers. Its slices of W1 (33 fragments) and W2 (16 fragments) stay in
-// registers for the whole kernel, so the steady state moves no weights at all; what the waves
-// share instead is the input: a tile of 32 rows is gathered once per block into LDS and read by
-// all 8 waves as MFMA operands, and layer 1's output is exchanged through LDS in operand
-// fragment order.
+// Register-stationary variant of the fused two-layer MLP in bf16 (edge and node kinds):
+// persistent blocks of H / 32 waves, wave w owning output features [32w, 32w + 32) of both
+// layers. Its slices of W1 (2H/16 + 1 fragments) and W2 (H/16 fragments) stay in registers for
+// the whole kernel, so the steady state moves no weights at all; what the waves of a block share
+// instead is the input: a tile of 32 rows is gathered once per block into LDS and read by all
+// its waves as MFMA operands, and layer 1's output is exchanged through LDS in operand fragment
+// order. Used for H = 256, where the fragment-ordered weights (about 400 KB) fit neither LDS nor
+// one wave's registers: one block of 8 waves per CU (a few W2 fragments are parked in LDS, the
+// registers do not hold them all). The template also covers H = 128 (blocks of 4 waves, three
+// per CU) and H = 64, but there the LDS-resident-weights kernel, whose waves run their tiles
+// without block barriers, measured faster.
 //
 // The gather uses the loads that write LDS directly (16 bytes per lane, no registers in between;
 // lane i of an instruction fills bytes [16 i, 16 i + 16) of a 1 KB destination): one instruction
-// fetches two 512-byte row parts, each lane one 16-byte piece, so global reads are whole rows.
+// fetches 1024 / (2H) whole row parts, each lane one 16-byte piece, so global reads are whole rows.
 // Which piece a lane fetches is permuted per row -- slot j of row r holds piece j ^ (r % 16) --
 // which makes the operand reads (32 rows x the same piece) bank-conflict free without padding.
 // The loads of tile t+2 are issued at the end of tile t into the buffer tile t just vacated and
@@ -17,9 +20,9 @@
 // are requested one tile earlier still.
 //
 // Per tile (two block barriers):
-//   layer 1: z1[32w.., rows] = W1[:, 32w..]^T x^T            33 MFMAs per wave, x from LDS
+//   layer 1: z1[32w.., rows] = W1[:, 32w..]^T x^T            2H/16 (+1) MFMAs per wave, x from LDS
 //   ReLU, bf16, own two fragments -> zbuf; barrier
-//   layer 2: y[32w.., rows] = W2[:, 32w..]^T relu(z1)^T       16 MFMAs per wave, z from LDS
+//   layer 2: y[32w.., rows] = W2[:, 32w..]^T relu(z1)^T       H/16 MFMAs per wave, z from LDS
 //   epilogue on the wave's 32 features: NODE ReLU; EDGE ReLU + per-receiver sum across lanes;
 //   rows -> staging buffer; wait for tile t+1's rows; barrier
 //   whole rows stored, 16 bytes per lane; loads of tile t+2 issued
@@ -42,16 +45,23 @@ __device__ __forceinline__ unsigned lds_address(const void *p) {
   return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }
 
-template <int KIND>
+template <int H, int KIND>
 struct RTile {
-  static constexpr int H = 256;
-  static constexpr int XPART = 32 * 512;                                   // one H-wide part of 32 rows
+  static constexpr int MB = H / 32, NT = 64 * MB;                          // waves, threads per block
+  static constexpr int ROWB = H * 2;                                       // bytes of one H-wide row part
+  static constexpr int LPR = ROWB / 16;                                    // 16-byte pieces per row part
+  static constexpr int RPI = 64 / LPR;                                     // row parts per load instruction
+  static constexpr int SWM = LPR < 16 ? LPR - 1 : 15;                      // slot = piece ^ (row & SWM)
+  static constexpr int XPART = 32 * ROWB;                                  // one H-wide part of 32 rows
   static constexpr int XBUF = 2 * XPART + (KIND == KIND_EDGE ? 1024 : 0);  // + raw fp32 edge attributes
-  static constexpr int ZBUF = 16 * 1024;                                   // 16 chunks x 64 lanes x 16 bytes
-  static constexpr int SROW = H * 2 + 16, SBUF = 32 * SROW;                // output staging, padded rows
-  static constexpr int NC2L = KIND == KIND_EDGE ? 7 : 6;                   // W2 fragments per wave kept in LDS
-  static constexpr int W2L = 8 * NC2L * 1024;
-  static constexpr int BYTES = 2 * XBUF + ZBUF + SBUF + 256 + 2 * 1024 + W2L;   // + receiver rows, biases, W2 part
+  static constexpr int NC2 = H / 16;                                       // chunks of layer 2
+  static constexpr int ZBUF = NC2 * 1024;                                  // chunks x 64 lanes x 16 bytes
+  static constexpr int SROW = ROWB + 16, SBUF = 32 * SROW;                 // output staging, padded rows
+  static constexpr int NC2L = H < 256 ? 0 : (KIND == KIND_EDGE ? 7 : 6);   // W2 fragments per wave kept in LDS
+  static constexpr int W2L = MB * NC2L * 1024;
+  static constexpr int BIAS = 2 * H * 4;
+  static constexpr int BYTES = 2 * XBUF + ZBUF + SBUF + 256 + BIAS + W2L;  // + receiver rows, biases, W2 part
+  static constexpr int WAVES_PER_SIMD = H == 256 ? 2 : (H == 128 ? 3 : 4); // occupancy the registers allow
 };
 
 // Rows of one tile: EDGE tiles are the packer's edge tiles, NODE tiles are 32 consecutive nodes.
@@ -73,38 +83,40 @@ __device__ __forceinline__ RTileRows rtile_rows(const Mlp2Args &a, int64_t wt) {
   return t;
 }
 
-// What this lane fetches for a tile: wave w issues the four instructions of row parts 4w .. 4w+3
-// (parts 0..15: sender / node-state rows 2k, 2k+1; parts 16..31: receiver / received-sum rows),
-// wave 0 also the edge attributes. src[j] is the global row the lane reads for instruction j
-// (rows past the tile's last repeat it and are never stored). Nothing here branches on a loaded
-// value, so the index loads can stay in flight until the rows are fetched a tile later.
+// What this lane fetches for a tile: a block issues H / 8 load instructions per tile, four per
+// wave; instruction q = 4w + j covers row parts q * RPI .. of the tile (the first H / 16
+// instructions the sender / node-state rows, the others the receiver / received-sum rows), and
+// wave 0 also fetches the edge attributes. src[j] is the global row the lane reads for
+// instruction j (rows past the tile's last repeat it and are never stored). Nothing here branches
+// on a loaded value, so the index loads can stay in flight until the rows are fetched a tile later.
 struct RFetch {
   int src[4];
 };
-template <int KIND>
+template <int H, int KIND>
 __device__ __forceinline__ RFetch rtile_index(const Mlp2Args &a, const RTileRows &t, int w, int lane) {
+  using R = RTile<H, KIND>;
   RFetch f;
-  const int32_t *ip = w < 4 ? a.in_src : a.in_dst;             // EDGE: parts 0..15 senders, 16..31 receivers
+  const int32_t *ip = w < R::MB / 2 ? a.in_src : a.in_dst;     // EDGE: first half senders, second half receivers
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int r = 2 * ((4 * w + j) & 15) + (lane >> 5);
+    const int r = R::RPI * ((4 * w + j) % (H / 16)) + lane / R::LPR;
     const int64_t row = t.r0 + (r < t.nv ? r : t.nv - 1);
     if constexpr (KIND == KIND_EDGE) f.src[j] = ip[row];
     else f.src[j] = (int)row;
   }
   return f;
 }
-template <int KIND>
+template <int H, int KIND>
 __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &t, const RFetch &f, int w, int lane,
                                             char *xbuf) {
-  constexpr int H = 256;
-  const bf16_t *base = (KIND == KIND_NODE && w >= 4) ? (const bf16_t *)a.agg : (const bf16_t *)a.h;
+  using R = RTile<H, KIND>;
+  const bf16_t *base = (KIND == KIND_NODE && w >= R::MB / 2) ? (const bf16_t *)a.agg : (const bf16_t *)a.h;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int rp = 4 * w + j, r = 2 * (rp & 15) + (lane >> 5);
-    const int piece = (lane & 31) ^ (r & 15);
+    const int q = 4 * w + j, r = R::RPI * (q % (H / 16)) + lane / R::LPR;
+    const int piece = (lane % R::LPR) ^ (r & R::SWM);
     lds_direct_load16(base + (size_t)f.src[j] * H + piece * 8,
-                      __builtin_amdgcn_readfirstlane(lds_address(xbuf) + rp * 1024));
+                      __builtin_amdgcn_readfirstlane(lds_address(xbuf) + q * 1024));
   }
   if constexpr (KIND == KIND_EDGE) {
     if (w == 0) {                                               // 32 rows x 32 bytes of raw fp32 attributes
@@ -112,23 +124,24 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
       const int64_t erow = t.r0 + (r < t.nv ? r : t.nv - 1);
       const void *g = 4 * half < a.De ? (const void *)(a.edge_feat + (size_t)erow * a.De + 4 * half)
                                       : (const void *)a.zero_row;
-      lds_direct_load16(g, __builtin_amdgcn_readfirstlane(lds_address(xbuf) + 2 * RTile<KIND>::XPART));
+      lds_direct_load16(g, __builtin_amdgcn_readfirstlane(lds_address(xbuf) + 2 * R::XPART));
     }
   }
 }
 
-template <int KIND>
-__global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
+template <int H, int KIND>
+__global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SIMD)) void mlp2r_kernel(const Mlp2Args a) {
   using T = bf16_t;
-  using R = RTile<KIND>;
-  constexpr int H = 256, MB = 8, HS = H / 16;
-  constexpr int NS1 = 2 * HS + (KIND == KIND_EDGE ? 1 : 0), NC2 = 16;
+  using R = RTile<H, KIND>;
+  constexpr int MB = R::MB, HS = H / 16, NT = R::NT;
+  constexpr int NS1 = 2 * HS + (KIND == KIND_EDGE ? 1 : 0), NC2 = R::NC2;
   static_assert(KIND == KIND_EDGE || KIND == KIND_NODE, "edge and node MLPs only");
+  static_assert(H == 64 || H == 128 || H == 256, "hidden width");
   extern __shared__ __align__(16) char smem[];
   char *zbuf = smem + 2 * R::XBUF;
   char *sbuf = zbuf + R::ZBUF;
   int *drow = (int *)(sbuf + R::SBUF);                         // EDGE: destination row of each staged row
-  float(*b1l)[2][16] = (float(*)[2][16])(sbuf + R::SBUF + 256), (*b2l)[2][16] = b1l + 8;
+  float(*b1l)[2][16] = (float(*)[2][16])(sbuf + R::SBUF + 256), (*b2l)[2][16] = b1l + MB;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
@@ -142,22 +155,22 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
   // first two tiles' rows, third tile's indices
   RTileRows cur = rtile_rows<KIND>(a, wt);
   RTileRows nxt = cur;
-  rtile_fetch<KIND>(a, cur, rtile_index<KIND>(a, cur, w, lane), w, lane, smem);
+  rtile_fetch<H, KIND>(a, cur, rtile_index<H, KIND>(a, cur, w, lane), w, lane, smem);
   if (wt + nbx < t_end) {
     nxt = rtile_rows<KIND>(a, wt + nbx);
-    rtile_fetch<KIND>(a, nxt, rtile_index<KIND>(a, nxt, w, lane), w, lane, smem + R::XBUF);
+    rtile_fetch<H, KIND>(a, nxt, rtile_index<H, KIND>(a, nxt, w, lane), w, lane, smem + R::XBUF);
   }
   RTileRows nn = nxt;
   RFetch fn;
   if (wt + 2 * nbx < t_end) {
     nn = rtile_rows<KIND>(a, wt + 2 * nbx);
-    fn = rtile_index<KIND>(a, nn, w, lane);
+    fn = rtile_index<H, KIND>(a, nn, w, lane);
   }
   // this wave's weight slices, loaded once, and the biases in accumulator order (parked in LDS:
   // the weight slices leave few registers)
   constexpr int NC2R = NC2 - R::NC2L;                         // W2 fragments in registers; the rest in LDS
   bf16x8 W1r[NS1], W2r[NC2R];
-  bf16x8 *W2l = (bf16x8 *)((char *)(b2l + 8) + w * R::NC2L * 1024) + lane;   // [NC2L][64] of this wave
+  [[maybe_unused]] bf16x8 *W2l = (bf16x8 *)((char *)(b2l + MB) + w * R::NC2L * 1024) + lane;   // [NC2L][64] of this wave
   {
     const bf16x8 *s1 = (const bf16x8 *)a.W1s + w * 64 + lane, *s2 = (const bf16x8 *)a.W2s + w * 64 + lane;
 #pragma unroll
@@ -167,12 +180,12 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
 #pragma unroll
     for (int c = NC2R; c < NC2; ++c) W2l[(c - NC2R) * 64] = s2[(size_t)c * MB * 64];
   }
-  // This lane's operand piece 2k + g of row l32 sits in slot (2k + g) ^ (l32 % 16) of its row part,
+  // This lane's operand piece 2k + g of row l32 sits in slot (2k + g) ^ (l32 & SWM) of its row part,
   // i.e. at byte xrow + ((k ^ xk) << 5); pieces 16.. add 256. (Recomputed per read: two VALU
   // instructions are cheaper here than eight more live registers.)
-  const int xk = (l32 & 15) >> 1;
-  const int xrow = l32 * 512 + (((l32 ^ g) & 1) << 4);
-  if (tid < 256) {
+  const int xk = (l32 & R::SWM) >> 1;
+  const int xrow = l32 * R::ROWB + (((l32 ^ g) & 1) << 4);
+  if (tid < MB * 32) {
     b1l[tid / 32][(tid / 16) % 2][tid % 16] = a.b1[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
     b2l[tid / 32][(tid / 16) % 2][tid % 16] = a.b2[32 * (tid / 32) + acc_row(tid % 16, (tid / 16) % 2)];
   }
@@ -186,13 +199,14 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
     [[maybe_unused]] EdgeTileMeta m;
     if constexpr (KIND == KIND_EDGE) m = load_edge_meta(a.in_dst, a.n_rows, cur.r0, cur.nv, l32);
     // ---------------- layer 1: this wave's 32 features x the tile's rows (each operand is read
-    // from LDS one MFMA ahead of its use)
+    // from LDS ahead of the MFMA that uses it)
     f32x16 acc = *(const f32x16 *)&b1l[w][g][0];
     {
       int xk_t = xk;
       asm volatile("" : "+v"(xk_t));                             // keeps the eight offsets out of registers
       auto xread = [&](int s) {
-        return *(const bf16x8 *)(xb + (s >> 4) * R::XPART + ((s >> 3) & 1) * 256 + xrow + (((s & 7) ^ xk_t) << 5));
+        const int k = s % HS;                                     // slab inside its row part
+        return *(const bf16x8 *)(xb + (s / HS) * R::XPART + (k >> 3) * 256 + xrow + (((k & 7) ^ xk_t) << 5));
       };
       constexpr int RA = KIND == KIND_NODE ? 3 : 2;             // operands read ahead of their MFMA
       bf16x8 xq[RA + 1];
@@ -230,7 +244,9 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
       for (int c = 0; c < NC2; ++c) {
         if (c + 2 < NC2) zq[(c + 2) % 3] = zr[(c + 2) * 64];
         const bf16x8 wf = c < NC2R ? W2r[c < NC2R ? c : 0] : wl;
-        if (c + 1 >= NC2R && c + 1 < NC2) wl = W2l[(c + 1 - NC2R) * 64];
+        if constexpr (R::NC2L > 0) {
+          if (c + 1 >= NC2R && c + 1 < NC2) wl = W2l[(c + 1 - NC2R) * 64];
+        }
         __builtin_amdgcn_sched_barrier(0);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, zq[c % 3], acc, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0): the next tile's rows are in LDS
     __syncthreads();
     {
-      const int piece = tid & 31, rr = tid >> 5;
+      const int piece = tid % R::LPR, rr = tid / R::LPR;          // 16 rows per pass
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int r = rr + 16 * j;
@@ -295,12 +311,12 @@ __global__ __launch_bounds__(512) void mlp2r_kernel(const Mlp2Args a) {
       }
     }
     // the buffer this tile used is free now: rows of the tile after next, indices one further
-    if (wt + 2 * nbx < t_end) rtile_fetch<KIND>(a, nn, fn, w, lane, smem + buf * R::XBUF);
+    if (wt + 2 * nbx < t_end) rtile_fetch<H, KIND>(a, nn, fn, w, lane, smem + buf * R::XBUF);
     cur = nxt;
     nxt = nn;
     if (wt + 3 * nbx < t_end) {
       nn = rtile_rows<KIND>(a, wt + 3 * nbx);
-      fn = rtile_index<KIND>(a, nn, w, lane);
+      fn = rtile_index<H, KIND>(a, nn, w, lane);
     }
     buf ^= 1;
   }

@@ -462,37 +462,47 @@ inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   return mlp2p_lds_bytes(H, a.nslab1) <= (size_t)c->max_lds;
 }
 
-// Register-stationary variant (bf16, H = 256, edge and node kinds).
-template <int KIND>
+// Register-stationary variant (bf16, edge and node kinds).
+template <int H, int KIND>
 int launch_mlp2r_k(xrl_ctx *c, Mlp2Args &a) {
-  auto kern = mlp2r_kernel<KIND>;
-  constexpr int lds = RTile<KIND>::BYTES;
+  using R = RTile<H, KIND>;
+  auto kern = mlp2r_kernel<H, KIND>;
   static bool attr_set = false;
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, R::BYTES));
     attr_set = true;
   }
   const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
   a.n_blocks = n_wt;
+  const int by_lds = c->max_lds / R::BYTES, by_waves = 4 * R::WAVES_PER_SIMD / R::MB;
+  const int per_cu = by_lds < by_waves ? by_lds : by_waves;      // blocks that can be resident on a CU
   int64_t grid = (n_wt + 7) / 8 * 8;
-  const int64_t cap = (int64_t)c->n_cu / 8 * 8;
+  const int64_t cap = (int64_t)c->n_cu / 8 * 8 * per_cu;
   if (grid > cap) grid = cap;
-  kern<<<dim3((unsigned)grid), dim3(512), lds, c->stream>>>(a);
+  kern<<<dim3((unsigned)grid), dim3(R::NT), R::BYTES, c->stream>>>(a);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
 
+template <int H>
+int launch_mlp2r(xrl_ctx *c, int kind, Mlp2Args &a) {
+  return kind == KIND_EDGE ? launch_mlp2r_k<H, KIND_EDGE>(c, a) : launch_mlp2r_k<H, KIND_NODE>(c, a);
+}
+
 inline bool mlp2r_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
-  if (c->elem != 2 || c->m.hidden != 256 || kind == KIND_EMBED || a.n_rows <= 0 || !c->use_persistent) return false;
+  // H = 256 only: at H <= 128 the weights fit LDS, a wave then runs its tile without block
+  // barriers, and that kernel (mlp2p) measured faster (the template itself covers 64 and 128)
+  const int H = c->m.hidden;
+  if (c->elem != 2 || H != 256 || kind == KIND_EMBED || a.n_rows <= 0 || !c->use_persistent) return false;
   if (a.n_rows < c->p_min_rows) return false;
-  if (kind == KIND_EDGE && (a.De > 8 || a.nslab1 != 33)) return false;   // edge attrs: half a slab
-  return (size_t)RTile<KIND_EDGE>::BYTES <= (size_t)c->max_lds;
+  if (kind == KIND_EDGE && (a.De > 8 || a.nslab1 != 2 * (H / 16) + 1)) return false;   // edge attrs: half a slab
+  return RTile<256, KIND_EDGE>::BYTES <= c->max_lds;
 }
 
 template <typename T>
 int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
   if (mlp2r_applies(c, kind, a))
-    return kind == KIND_EDGE ? launch_mlp2r_k<KIND_EDGE>(c, a) : launch_mlp2r_k<KIND_NODE>(c, a);
+    return launch_mlp2r<256>(c, kind, a);
   if (mlp2p_applies(c, kind, a)) {
     if (kind == KIND_EMBED) return c->m.hidden == 64 ? launch_embedp<64>(c, a) : launch_embedp<128>(c, a);
     return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
