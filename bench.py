@@ -2,7 +2,9 @@
 
 One step = one forward pass of the whole path (sum of incoming edge attributes, embed MLP,
 R x (edge MLP + per-receiver sum, node MLP), per-graph readout, policy/value heads) over one
-packed synthetic meta-batch that is already resident in HBM. Prints ONE JSON line.
+packed synthetic meta-batch that is already resident in HBM; with --backward (and always for
+configuration 5, the update minibatch) also the backward pass through heads and encoder.
+Prints ONE JSON line.
 """
 import argparse
 import json
@@ -55,6 +57,8 @@ def main():
     ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
     ap.add_argument("--states", type=int, default=None, help="override the number of states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="a step also runs both backward calls (always on for configuration 5)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -81,9 +85,18 @@ def main():
                 entropy=torch.empty(S, device="cuda"), action=torch.empty(S, dtype=torch.int32, device="cuda"),
                 logit=torch.empty(G, device="cuda"))
 
+    backward = args.backward or args.config == 5
+    if backward:
+        grng = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 7))
+        up = [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in synth.upstream_grads(grng, G, S)]
+        dw = torch.zeros(enc.n_weights, dtype=torch.float32, device="cuda")
+
     def step():
-        enc.encode(batch, out=emb)
+        enc.encode(batch, save_for_backward=backward, out=emb)
         enc.policy_value(batch, emb, out=outs)
+        if backward:
+            demb = enc.policy_value_backward(batch, emb, up[0], up[1], up[2], dw)
+            enc.encode_backward(batch, demb, dw)
 
     for _ in range(args.warmup):
         step()
@@ -120,7 +133,7 @@ def main():
         scaling="weak", vs_baseline=None, dtype=model["precision"], data="synthetic",
         config=dict(workload=f"config {args.config} ({synth.CONFIGS[args.config]['name']}): {S} state(s), "
                              f"{G} graphs, {N} nodes, {E} edges, hidden {H}, {R} rounds, forward "
-                             f"(encode + policy/value heads)",
+                             f"(encode + policy/value heads)" + (" + backward (heads, encoder)" if backward else ""),
                     states=S, graphs=G, nodes=N, edges=E, hidden=H, rounds=R),
         edges_per_s=E * R / (ms * 1e-3),
         roofline=dict(bound="mfma", kernel="edge MLP + per-receiver sum (one launch per round)",

@@ -100,8 +100,7 @@ struct xrl_ctx {
   int elem = 4;                 // bytes per stored activation / operand
   int n_cu = 256;               // compute units of the device
   int max_lds = 65536;          // LDS bytes one block may use
-  bool use_persistent = true;   // LDS-resident-weights MLP kernels where they apply
-  int64_t p_min_rows = 0;       // development switch: smallest row count for the persistent kernels
+  int64_t p_min_rows = 8192;    // smallest row count for the persistent kernels (XRL_PERSISTENT_MIN_ROWS)
   float *d_w = nullptr;         // flat fp32 weights
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
   char *d_swz = nullptr;        // fragment-ordered encoder weights
@@ -451,7 +450,7 @@ int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
 
 inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   const int H = c->m.hidden;
-  if (c->elem != 2 || H > 128 || a.n_rows <= 0 || !c->use_persistent) return false;
+  if (c->elem != 2 || H > 128 || a.n_rows <= 0) return false;
   if (a.n_rows < c->p_min_rows) return false;
   if (kind == KIND_EMBED) {
     const int pieces = 4 * 64 * kPersistWaves;               // see embedp_kernel
@@ -493,7 +492,7 @@ inline bool mlp2r_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   // H = 256 only: at H <= 128 the weights fit LDS, a wave then runs its tile without block
   // barriers, and that kernel (mlp2p) measured faster (the template itself covers 64 and 128)
   const int H = c->m.hidden;
-  if (c->elem != 2 || H != 256 || kind == KIND_EMBED || a.n_rows <= 0 || !c->use_persistent) return false;
+  if (c->elem != 2 || H != 256 || kind == KIND_EMBED || a.n_rows <= 0) return false;
   if (a.n_rows < c->p_min_rows) return false;
   if (kind == KIND_EDGE && (a.De > 8 || a.nslab1 != 2 * (H / 16) + 1)) return false;   // edge attrs: half a slab
   return RTile<256, KIND_EDGE>::BYTES <= c->max_lds;
@@ -921,9 +920,10 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   c->L = L;
   c->stream = (hipStream_t)hip_stream;
   c->elem = model->precision == XRL_PREC_BF16 ? 2 : 4;
-  if (const char *e = getenv("XRL_NO_PERSISTENT")) c->use_persistent = !(e[0] == '1');
+  // Row count from which the persistent kernels replace the streaming one (tuning knob; the
+  // default is where they start to win; 0 = always, a huge value = never)
   c->p_min_rows = 8192;
-  if (const char *e = getenv("XRL_P_MIN_ROWS")) c->p_min_rows = atoll(e);
+  if (const char *e = getenv("XRL_PERSISTENT_MIN_ROWS")) c->p_min_rows = atoll(e);
   {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
