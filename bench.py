@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
     ap.add_argument("--states", type=int, default=None, help="override the number of states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
+                         "reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     ap.add_argument("--backward", action="store_true",
                     help="a step also runs both backward calls (always on for configuration 5)")
     args = ap.parse_args()
@@ -98,6 +101,12 @@ def main():
             demb = enc.policy_value_backward(batch, emb, up[0], up[1], up[2], dw)
             enc.encode_backward(batch, demb, dw)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

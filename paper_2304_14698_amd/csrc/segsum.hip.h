@@ -62,6 +62,7 @@ struct SegsumArgs {
   const void *vals;     // [*, D] rows, type TIn
   const int32_t *perm;  // nullable: row r of the reduction reads vals row perm[r]
   const int32_t *ptr;   // [n_seg + 1]
+  const int32_t *row_seg;  // nullable: segment of vals row i (saves the search for a sub-tile's first segment)
   int64_t n_rows, n_seg;
   int D, RT;
   void *out;            // [n_seg, D], type TOut
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void segsum_kernel(const SegsumArgs a) {
       RowVec<TIn, VEC>::load(vals + (size_t)r * a.D + c, v[i]);
     }
   }
-  int seg = seg_of_row(a.ptr, a.n_seg, r0);
+  int seg = a.row_seg ? a.row_seg[a.perm ? (int64_t)a.perm[r0] : r0] : seg_of_row(a.ptr, a.n_seg, r0);
   if (Put::kZeroEmpty && st == 0)                               // empty segments before row 0
     for (int s = 0; s < seg; ++s)
 #pragma unroll

@@ -143,14 +143,35 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
       out[(size_t)acc_row(r, g) * H + 32 * (kbb0 + 2 * i) + l32] = acc[i][r];
 }
 
-// dW[k, f] += sum over chunks (in order) of partial[chunk, k, f] for k < Ka; db[f] += row Ka.
-__global__ void wgrad_reduce_kernel(const float *partial, int n_chunks, int KaP, int Ka, int H,
-                                    float *dW, float *db) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)(Ka + 1) * H) return;
-  const int k = (int)(i / H), f = (int)(i - (int64_t)k * H);
+// dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka. A block handles
+// 32 consecutive entries; its 8 thread groups take every eighth chunk (eight loads in flight
+// each) and their sums are added in group order, so the result has one fixed summation order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, int n_chunks, int KaP, int Ka,
+                                                           int H, float *dW, float *db) {
+  __shared__ float part[8][32];
+  const int e = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + e;
+  const bool live = i < (int64_t)(Ka + 1) * H;
+  const int k = live ? (int)(i / H) : 0, f = live ? (int)(i - (int64_t)k * H) : 0;
+  const float *p = partial + (size_t)k * H + f;
+  const size_t cs = (size_t)KaP * H;
   float s = 0.f;
-  for (int c = 0; c < n_chunks; ++c) s += partial[((size_t)c * KaP + k) * H + f];
-  if (k < Ka) dW[(size_t)k * H + f] += s;
-  else db[f] += s;
+  int c = g;
+  for (; c + 56 < n_chunks; c += 64) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = p[(size_t)(c + 8 * j) * cs];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += v[j];
+  }
+  for (; c < n_chunks; c += 8) s += p[(size_t)c * cs];
+  part[g][e] = s;
+  __syncthreads();
+  if (g == 0 && live) {
+    float t = part[0][e];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) t += part[j][e];
+    if (k < Ka) dW[(size_t)k * H + f] += t;
+    else db[f] += t;
+  }
 }

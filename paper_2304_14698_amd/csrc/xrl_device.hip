@@ -319,7 +319,7 @@ int check_batch(const xrl_ctx *c, const xrl_batch *b, const char *who) {
 template <typename TIn, typename TOut, int VEC, int RT>
 int launch_segsum_rt(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
                      const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, void *out,
-                     float *carry) {
+                     float *carry, const int32_t *vals_seg = nullptr) {
   if (n_seg == 0) return XRL_OK;
   if (n_rows == 0) {
     static_assert(sizeof(TOut) == 4, "zero fill below writes fp32 words");
@@ -330,6 +330,7 @@ int launch_segsum_rt(xrl_ctx *c, const void *vals, const int32_t *perm, const in
   }
   SegsumArgs a;
   a.vals = vals; a.perm = perm; a.ptr = ptr; a.n_rows = n_rows; a.n_seg = n_seg;
+  a.row_seg = vals_seg ? vals_seg : (perm ? nullptr : row_seg);
   a.D = D; a.RT = RT; a.out = out; a.carry = carry;
   const int64_t nsub = (n_rows + RT - 1) / RT;
   const int64_t threads = nsub * (D / VEC);
@@ -358,11 +359,13 @@ int launch_segsum(xrl_ctx *c, const void *vals, const int32_t *perm, const int32
 // out[s, :] += segment sums (fp32 out, RT = 16); perm as in SegsumArgs
 template <typename TIn, int VEC>
 int launch_segsum_add(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
-                      const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, float *out, float *carry) {
+                      const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, float *out, float *carry,
+                      const int32_t *vals_seg = nullptr) {
   constexpr int RT = 16;
   if (n_seg == 0 || n_rows == 0) return XRL_OK;
   SegsumArgs a;
   a.vals = vals; a.perm = perm; a.ptr = ptr; a.n_rows = n_rows; a.n_seg = n_seg;
+  a.row_seg = vals_seg ? vals_seg : (perm ? nullptr : row_seg);
   a.D = D; a.RT = RT; a.out = out; a.carry = carry;
   const int64_t nsub = (n_rows + RT - 1) / RT;
   const int64_t threads = nsub * (D / VEC);
@@ -612,7 +615,7 @@ int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
   else if (kind == WG_NODE) wgrad_kernel<T, H, WG_NODE><<<grid, dim3(256), 0, c->stream>>>(a);
   else wgrad_kernel<T, H, WG_EMBED><<<grid, dim3(256), 0, c->stream>>>(a);
   const int64_t n = (int64_t)(a.Ka + 1) * H;
-  wgrad_reduce_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream>>>(
+  wgrad_reduce_kernel<<<dim3((unsigned)((n + 31) / 32)), dim3(256), 0, c->stream>>>(
       a.partial, a.n_chunks, kt * 64, a.Ka, H, dW, db);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
@@ -776,7 +779,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
     if (E > 0) {
       if ((rc = launch_segsum_add<T, PV>(c, ddst, nullptr, d.in_ptr, d.in_dst, E, N, H, dhB, carry))) return rc;
-      if ((rc = launch_segsum_add<T, PV>(c, dsrc, d.out_pos, d.out_ptr, nullptr, E, N, H, dhB, carry))) return rc;
+      if ((rc = launch_segsum_add<T, PV>(c, dsrc, d.out_pos, d.out_ptr, nullptr, E, N, H, dhB, carry, d.in_src))) return rc;
     }
     std::swap(dhA, dhB);
   }
