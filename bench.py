@@ -20,6 +20,25 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the edge kernel on the default workload (config 2, bf16), from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; see profiles/), each scaled by the same counter's
+# reading for a 1 GiB device copy (factors 2.000 and 1.000). Valid only for the kernel sources it
+# was taken with: the hash covers the files the kernel is built from.
+EDGE_TRAFFIC = dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="939620329701442e",
+                    config=2, precision="bf16", bytes_per_launch=(11129.6 * 2.000 + 11599.5 * 1.000) * 1024)
+
+
+def edge_traffic(config, precision):
+    import hashlib
+    h = hashlib.sha256()
+    for f in EDGE_TRAFFIC["sources"]:
+        with open(os.path.join(ROOT, "paper_2304_14698_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    same = h.hexdigest()[:16] == EDGE_TRAFFIC["sha256_16"]
+    if same and config == EDGE_TRAFFIC["config"] and precision == EDGE_TRAFFIC["precision"]:
+        return EDGE_TRAFFIC["bytes_per_launch"]
+    return None
+
 
 def oracle_baseline(model, state, w, budget_s=20.0):
     """The float64 oracle timed on the host cores over whole graphs of the same workload."""
@@ -60,6 +79,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
                          "reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure the machine's own MFMA and copy rates (reported as measured_peaks)")
     ap.add_argument("--backward", action="store_true",
                     help="a step also runs both backward calls (always on for configuration 5)")
     args = ap.parse_args()
@@ -80,7 +101,10 @@ def main():
     rng = np.random.Generator(np.random.PCG64(synth.BASE_SEED))
     w = synth.init_weights(rng, xrl.weight_layout(model), bias_range=0.1)
     enc = xrl.Encoder(model, w)
+    t_pack = time.perf_counter()
     batch = enc.pack(state)                       # pack + upload happen before the timed region
+    torch.cuda.synchronize()
+    t_pack = time.perf_counter() - t_pack
     S, G, N, E = batch.S, batch.G, batch.N, batch.E
     H, R, De = model["hidden"], model["rounds"], model["d_edge"]
     emb = torch.empty((G, H), dtype=torch.float32, device="cuda")
@@ -133,6 +157,10 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     achieved = edge_flops / edge_s / 1e12 if edge_s > 0 else 0.0
     b = 2 if bf16 else 4
+    # edge stage, ideal fused: h read once, edge attributes, indices; received sums written for
+    # the receivers that have in-edges
+    n_recv = int((np.diff(batch.host_view()["in_ptr"]) > 0).sum())
+    edge_bytes = N * H * b + E * De * 4 + 4 * (2 * E + E // 32) + n_recv * H * b
     pool_bytes = N * H * b + 4 * (G + 1) + G * H * 4
     pool_s = kern["pool"]["avg_us"] * 1e-6
 
@@ -145,14 +173,22 @@ def main():
                              f"(encode + policy/value heads)" + (" + backward (heads, encoder)" if backward else ""),
                     states=S, graphs=G, nodes=N, edges=E, hidden=H, rounds=R),
         edges_per_s=E * R / (ms * 1e-3),
+        pack_upload_ms=t_pack * 1e3,              # host packing + H2D copies, outside the timed region
         roofline=dict(bound="mfma", kernel="edge MLP + per-receiver sum (one launch per round)",
-                      achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak, traffic=None,
-                      flops_per_launch=edge_flops, avg_launch_us=kern["edge"]["avg_us"]),
+                      achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
+                      traffic=edge_traffic(args.config, model["precision"]),
+                      flops_per_launch=edge_flops, avg_launch_us=kern["edge"]["avg_us"],
+                      algorithmic_bytes_per_launch=edge_bytes,
+                      hbm_frac=(edge_bytes / edge_s / 1e9 / PEAK_HBM_GBS if edge_s > 0 else 0.0)),
         hbm_kernel=dict(kernel="per-graph readout sum (fused with the readout MLP)", bytes_per_launch=pool_bytes,
                         achieved=(pool_bytes / pool_s / 1e9 if pool_s > 0 else 0.0), peak=PEAK_HBM_GBS,
                         unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
         kernels_us=kern,
     )
+    if args.peaks:
+        tf, gb = enc.measure_peaks()
+        res["measured_peaks"] = dict(mfma_bf16_tflops=tf, copy_gbs=gb,
+                                     note="register-resident 32x32x16 bf16 MFMA loop; 1 GiB device copy, read + write")
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = oracle_baseline(model, state, w)
     print(json.dumps(res))

@@ -192,6 +192,14 @@ int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32
 int xrl_set_timing(xrl_ctx *ctx, int enabled);
 int xrl_read_timing(xrl_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 
+/* The machine's own ceilings, measured, to set beside the vendor figures the rooflines use:
+ * *mfma_tflops = bf16 32x32x16 MFMA rate of a loop whose operands and accumulators stay in
+ * registers (four independent accumulator tiles per wave, four waves per SIMD); *copy_gbs =
+ * read + write rate of a plain 16-byte-per-lane device-to-device copy of copy_bytes (rounded down
+ * to a multiple of 16; the library allocates and frees the two buffers). Synchronous.
+ * Errors: NULL, SHAPE (copy_bytes < 16), OOM, HIP. */
+int xrl_measure_peaks(xrl_ctx *ctx, int64_t copy_bytes, double *mfma_tflops, double *copy_gbs);
+
 const char *xrl_last_error(void);
 const char *xrl_version(void);
 

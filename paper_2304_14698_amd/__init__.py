@@ -53,8 +53,8 @@ EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "
            "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_segment_sum",
-           "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_last_error",
-           "xrl_version"]
+           "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
+           "xrl_last_error", "xrl_version"]
 
 
 def load_library():
@@ -88,6 +88,7 @@ def load_library():
     lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
     lib.xrl_set_timing.argtypes = [vp, C.c_int]
     lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.xrl_measure_peaks.argtypes = [vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.xrl_last_error.restype = C.c_char_p
     lib.xrl_version.restype = C.c_char_p
     _lib = lib
@@ -281,6 +282,12 @@ class Encoder:
         ms, n = C.c_double(), C.c_int64()
         _check(self.lib.xrl_read_timing(self.handle, kernel.encode(), C.byref(ms), C.byref(n)))
         return ms.value, int(n.value)
+
+    def measure_peaks(self, copy_bytes=1 << 30):
+        """(bf16 MFMA TFLOP/s of a register-resident loop, GB/s of a device-to-device copy)."""
+        tf, gb = C.c_double(), C.c_double()
+        _check(self.lib.xrl_measure_peaks(self.handle, int(copy_bytes), C.byref(tf), C.byref(gb)))
+        return tf.value, gb.value
 
     def close(self):
         if self.handle:

@@ -1160,6 +1160,79 @@ int xrl_read_timing(xrl_ctx *c, const char *kernel, double *total_ms, int64_t *l
   return XRL_OK;
 }
 
+namespace {
+// 4 independent accumulator tiles per wave, operands never change: nothing but the matrix pipe
+__global__ __launch_bounds__(256) void mfma_peak_kernel(float *out, int iters) {
+  bf16x8 a = Operand<bf16_t>::zero(), b = Operand<bf16_t>::zero();
+  a[threadIdx.x & 7] = (bf16_t)1.0f;
+  b[(threadIdx.x >> 3) & 7] = (bf16_t)0.5f;
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+__global__ __launch_bounds__(256) void copy_peak_kernel(const f32x4 *src, f32x4 *dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+int xrl_measure_peaks(xrl_ctx *c, int64_t copy_bytes, double *mfma_tflops, double *copy_gbs) {
+  if (!c || !mfma_tflops || !copy_gbs) return fail(XRL_ERR_NULL, "xrl_measure_peaks: NULL argument");
+  if (copy_bytes < 16) return fail(XRL_ERR_SHAPE, "xrl_measure_peaks: copy_bytes = %lld", (long long)copy_bytes);
+  const int64_t n16 = copy_bytes / 16;
+  const int blocks = c->n_cu * 4;                              // 16 waves per CU
+  char *buf = nullptr;
+  hipError_t e = hipMalloc((void **)&buf, (size_t)n16 * 32 + (size_t)blocks * 256 * 4);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(XRL_ERR_OOM, "xrl_measure_peaks: %s", hipGetErrorString(e));
+  }
+  f32x4 *src = (f32x4 *)buf, *dst = src + n16;
+  float *out = (float *)(dst + n16);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = XRL_OK;
+  auto run = [&]() -> int {
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    HIP_TRY(hipMemsetAsync(buf, 0, (size_t)n16 * 32, c->stream));
+    const int iters = 20000;
+    mfma_peak_kernel<<<dim3(blocks), dim3(256), 0, c->stream>>>(out, 100);          // warm-up
+    HIP_TRY(hipEventRecord(e0, c->stream));
+    mfma_peak_kernel<<<dim3(blocks), dim3(256), 0, c->stream>>>(out, iters);
+    HIP_TRY(hipEventRecord(e1, c->stream));
+    HIP_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    *mfma_tflops = (double)blocks * 4 * iters * 4 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+    copy_peak_kernel<<<dim3(c->n_cu * 8), dim3(256), 0, c->stream>>>(src, dst, n16);   // warm-up
+    HIP_TRY(hipEventRecord(e0, c->stream));
+    for (int i = 0; i < 5; ++i) copy_peak_kernel<<<dim3(c->n_cu * 8), dim3(256), 0, c->stream>>>(src, dst, n16);
+    HIP_TRY(hipEventRecord(e1, c->stream));
+    HIP_TRY(hipEventSynchronize(e1));
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    *copy_gbs = 5.0 * (double)n16 * 32 / (ms * 1e-3) / 1e9;
+    return XRL_OK;
+  };
+  rc = run();
+  (void)hipStreamSynchronize(c->stream);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(buf);
+  return rc;
+}
+
 int xrl_segment_sum(xrl_ctx *c, const float *d_values, const int32_t *d_ptr, int64_t n_rows,
                     int64_t n_seg, int32_t width, float *d_out) {
   if (!c || !d_ptr || !d_out || (n_rows > 0 && !d_values))
