@@ -21,7 +21,9 @@ What it follows (X-RLflow, arXiv 2304.14698):
     masked out exactly) and a value head; both heads are MLPs with hidden sizes [256, 64]
     (hyper-parameter table in the appendix).
   * Section 3.3.4: everything is trained by one back-propagation; the backward functions here
-    are hand-written reverse-mode code, separate from the forward functions.
+    are hand-written reverse-mode code, separate from the forward functions. ppo_objective is
+    the section's objective J = L_clip + c1 L_vf + c2 L_entropy (its three equations; c1 = 0.5,
+    c2 = 0.01 in the appendix table) with its derivatives w.r.t. the heads' outputs.
 
 Conventions: row vectors, y = x W + b with W stored [in, out]; sigma = ReLU after every encoder
 layer (including each MLP's last), heads end with a linear layer of width 1.
@@ -346,3 +348,36 @@ def loss_and_grad(model, w, state, dlogp, dvalue, dentropy, bound=None):
         + (np.asarray(dentropy, dtype=F) * fw["entropy"]).sum()
     demb, gh = policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound)
     return L, gh + encode_backward(model, w, state, demb, bound=bound), demb
+
+
+# ----------------------------------------------------------------------------- objective
+def ppo_objective(logp, value, entropy, state, action, old_logp, advantage, v_target,
+                  eps=0.2, c1=0.5, c2=0.01):
+    """Clipped-surrogate objective of Section 3.3.4 (to be minimised) over the S states of a
+    minibatch, from the heads' outputs:
+      ratio_s  = exp(logp[slot of the action taken in s] - old_logp_s)
+      L_clip   = -mean_s min(ratio_s A_s, clip(ratio_s, 1-eps, 1+eps) A_s)      (first equation)
+      L_vf     =  mean_s (value_s - v_target_s)^2                               (second equation)
+      L_ent    = -mean_s entropy_s          (the entropy term enters as a bonus)
+      J        = L_clip + c1 L_vf + c2 L_ent                                    (third equation)
+    `action` is the slot index inside each state (0 = No-Op). eps is not printed in the paper
+    (a parameter; 0.2 is the PPO paper's default). Returns J, its three parts and dJ/dlogp [G],
+    dJ/dvalue [S], dJ/dentropy [S] (the inputs of policy_value_backward). Where both arguments of
+    the min are equal the unclipped one is differentiated."""
+    sgp = np.asarray(state["state_graph_ptr"])
+    S, G = len(sgp) - 1, len(np.asarray(logp))
+    logp, value, entropy = (np.asarray(x, dtype=F) for x in (logp, value, entropy))
+    old_logp, A, vt = (np.asarray(x, dtype=F) for x in (old_logp, advantage, v_target))
+    slot = sgp[:-1] + np.asarray(action)
+    ratio = np.exp(logp[slot] - old_logp)
+    s1 = ratio * A
+    s2 = np.clip(ratio, 1.0 - eps, 1.0 + eps) * A
+    l_clip = -np.minimum(s1, s2).mean() if S else 0.0
+    l_vf = ((value - vt) ** 2).mean() if S else 0.0
+    l_ent = -entropy.mean() if S else 0.0
+    dlogp = np.zeros(G)
+    dlogp[slot] = np.where(s1 <= s2, -s1, 0.0) / max(S, 1)       # d(ratio A)/dlogp = ratio A
+    dvalue = 2.0 * c1 * (value - vt) / max(S, 1)
+    dentropy = np.full(S, -c2 / max(S, 1))
+    return dict(J=l_clip + c1 * l_vf + c2 * l_ent, l_clip=l_clip, l_vf=l_vf, l_ent=l_ent,
+                dlogp=dlogp, dvalue=dvalue, dentropy=dentropy)

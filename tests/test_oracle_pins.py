@@ -474,3 +474,77 @@ def test_synthetic_configs_are_valid_states():
         assert np.all(st["slot_mask"][st["state_graph_ptr"][:-1]] == 1)
         m2, st2 = synth.make_config(cfg)
         assert all(np.array_equal(st[k], st2[k]) for k in st if k != "n_states")
+
+
+# ----------------------------------------------------------------------------- PPO objective
+def _ppo_case(rng, S=7, eps=0.2):
+    sizes = rng.integers(1, 6, S)
+    sgp = np.concatenate([[0], np.cumsum(sizes)])
+    G = int(sgp[-1])
+    logit = rng.standard_normal(G)
+    logp = np.concatenate([l - np.log(np.exp(l).sum()) for l in np.split(logit, sgp[1:-1])])
+    action = np.array([rng.integers(0, n) for n in sizes])
+    state = dict(state_graph_ptr=sgp)
+    return state, logp, rng.standard_normal(S), rng.random(S), action, sizes
+
+
+def test_ppo_objective_closed_forms():
+    """Section 3.3.4's objective at points where its value is known in closed form."""
+    rng = np.random.Generator(np.random.PCG64(41))
+    state, logp, value, entropy, action, sizes = _ppo_case(rng)
+    S = len(sizes)
+    slot = state["state_graph_ptr"][:-1] + action
+    A, vt = rng.standard_normal(S), rng.standard_normal(S)
+    # same policy as the one that sampled (ratio = 1): L_clip = -mean A, gradient -A / S
+    r = O.ppo_objective(logp, value, entropy, state, action, logp[slot], A, vt, eps=0.2, c1=0.5, c2=0.01)
+    assert abs(r["l_clip"] + A.mean()) < 1e-14
+    assert np.allclose(r["dlogp"][slot], -A / S) and np.count_nonzero(r["dlogp"]) <= S
+    assert abs(r["l_vf"] - np.mean((value - vt) ** 2)) < 1e-14 and abs(r["l_ent"] + entropy.mean()) < 1e-14
+    assert abs(r["J"] - (r["l_clip"] + 0.5 * r["l_vf"] + 0.01 * r["l_ent"])) < 1e-14
+    # far outside the clip range: positive advantage and ratio > 1 + eps (or negative and ratio < 1 - eps)
+    # gives the clipped constant and no policy gradient; the opposite signs stay unclipped
+    old = logp[slot] - np.log(3.0)                                    # ratio = 3
+    r = O.ppo_objective(logp, value, entropy, state, action, old, np.abs(A), vt, eps=0.2)
+    assert abs(r["l_clip"] + 1.2 * np.abs(A).mean()) < 1e-13 and not r["dlogp"].any()
+    r = O.ppo_objective(logp, value, entropy, state, action, old, -np.abs(A), vt, eps=0.2)
+    assert abs(r["l_clip"] - 3.0 * np.abs(A).mean()) < 1e-13
+    assert np.allclose(r["dlogp"][slot], 3.0 * np.abs(A) / S)
+    old = logp[slot] + np.log(4.0)                                    # ratio = 1/4
+    r = O.ppo_objective(logp, value, entropy, state, action, old, -np.abs(A), vt, eps=0.2)
+    assert abs(r["l_clip"] - 0.8 * np.abs(A).mean()) < 1e-13 and not r["dlogp"].any()
+
+
+def test_ppo_objective_gradients_by_finite_differences():
+    rng = np.random.Generator(np.random.PCG64(43))
+    state, logp, value, entropy, action, sizes = _ppo_case(rng, S=9)
+    S = len(sizes)
+    slot = state["state_graph_ptr"][:-1] + action
+    old = logp[slot] + 0.15 * rng.standard_normal(S)                  # ratios on both sides of the clip range
+    A, vt = rng.standard_normal(S), rng.standard_normal(S)
+    f = lambda lp, v, e: O.ppo_objective(lp, v, e, state, action, old, A, vt, eps=0.1, c1=0.5, c2=0.01)["J"]
+    r = O.ppo_objective(logp, value, entropy, state, action, old, A, vt, eps=0.1, c1=0.5, c2=0.01)
+    ratio = np.exp(logp[slot] - old)
+    assert (np.abs(ratio - 0.9) > 1e-3).all() and (np.abs(ratio - 1.1) > 1e-3).all()   # away from the kinks
+    assert ((ratio > 1.1) | (ratio < 0.9)).any() and ((ratio < 1.1) & (ratio > 0.9)).any()
+    h = 1e-6
+    for name, x, g in (("logp", logp, r["dlogp"]), ("value", value, r["dvalue"]), ("entropy", entropy, r["dentropy"])):
+        for i in range(len(x)):
+            xp, xm = x.copy(), x.copy()
+            xp[i] += h
+            xm[i] -= h
+            args = dict(lp=logp, v=value, e=entropy)
+            key = {"logp": "lp", "value": "v", "entropy": "e"}[name]
+            fd = (f(**{**args, key: xp}) - f(**{**args, key: xm})) / (2 * h)
+            assert abs(fd - g[i]) < 1e-8, (name, i, fd, g[i])
+
+
+def test_ppo_objective_hand_example():
+    """tests/golden/ppo_hand_example.txt: two states worked by hand from the three equations."""
+    rows = [l.split("#")[0].split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "ppo_hand_example.txt"))]
+    vals = {r[0]: [float(x) for x in r[1:]] for r in rows if r}
+    state = dict(state_graph_ptr=np.array([0, 2, 5]))
+    r = O.ppo_objective(vals["logp"], vals["value"], vals["entropy"], state, [1, 0], vals["old_logp"],
+                        vals["advantage"], vals["v_target"], eps=0.2, c1=0.5, c2=0.01)
+    assert abs(r["l_clip"] - vals["l_clip"][0]) < 1e-12 and abs(r["l_vf"] - vals["l_vf"][0]) < 1e-12
+    assert abs(r["l_ent"] - vals["l_ent"][0]) < 1e-12 and abs(r["J"] - vals["J"][0]) < 1e-12
+    assert np.allclose(r["dlogp"], vals["dlogp"], atol=1e-12) and np.allclose(r["dvalue"], vals["dvalue"], atol=1e-12)
