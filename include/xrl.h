@@ -167,6 +167,23 @@ int xrl_policy_value_backward(xrl_ctx *ctx, const xrl_batch *b, const float *d_e
                               const float *d_dentropy, float *d_demb, float *d_dweights);
 int xrl_encode_backward(xrl_ctx *ctx, const xrl_batch *b, const float *d_demb, float *d_dweights);
 
+/* ---- objective (Section 3.3.4: J = L_clip + c1 L_vf + c2 L_entropy, to be minimised) ----------
+ * From the outputs of xrl_policy_value on a minibatch of S states and the rollout's records:
+ * d_action [S] int32 = slot taken inside each state (0 = No-Op; must be a valid slot), d_old_logp
+ * [S] = its log-probability when sampled, d_advantage [S], d_v_target [S]; eps = clip range, c1,
+ * c2 = weights of the value and entropy terms (0.5 and 0.01 in the paper's table; eps is not
+ * printed there).  ratio_s = exp(logp[slot_s] - old_logp_s);
+ *   L_clip = -mean_s min(ratio_s A_s, clip(ratio_s, 1-eps, 1+eps) A_s), L_vf = mean_s (value_s -
+ *   v_target_s)^2, L_entropy = -mean_s entropy_s.
+ * Writes d_J [4] = {J, L_clip, L_vf, L_entropy} and the derivatives d_dlogp [G] (zero except at
+ * the taken slots; where both arguments of the min are equal the unclipped one is
+ * differentiated), d_dvalue [S], d_dentropy [S]: the inputs of xrl_policy_value_backward. All
+ * device pointers, fp32. Sums over states are taken in a fixed order. Errors: NULL, STATE, HIP. */
+int xrl_ppo_objective(xrl_ctx *ctx, const xrl_batch *b, const float *d_logp, const float *d_value,
+                      const float *d_entropy, const int32_t *d_action, const float *d_old_logp,
+                      const float *d_advantage, const float *d_v_target, float eps, float c1,
+                      float c2, float *d_J, float *d_dlogp, float *d_dvalue, float *d_dentropy);
+
 /* ---- building blocks exposed for measurement and per-step checks ----------------------------
  * xrl_segment_sum: out[i, :] = sum of values[r, :] over rows r in [d_ptr[i], d_ptr[i+1]) -- the
  * receiver-side aggregation of Section 3.4's first two equations on receiver-ordered rows, and

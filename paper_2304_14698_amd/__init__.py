@@ -52,7 +52,7 @@ class PackedView(C.Structure):
 EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
            "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
-           "xrl_policy_value_backward", "xrl_encode_backward", "xrl_segment_sum",
+           "xrl_policy_value_backward", "xrl_encode_backward", "xrl_ppo_objective", "xrl_segment_sum",
            "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
            "xrl_last_error", "xrl_version"]
 
@@ -89,6 +89,7 @@ def load_library():
     lib.xrl_set_timing.argtypes = [vp, C.c_int]
     lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.xrl_measure_peaks.argtypes = [vp, i64, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.xrl_ppo_objective.argtypes = [vp] * 9 + [C.c_float] * 3 + [vp] * 4
     lib.xrl_last_error.restype = C.c_char_p
     lib.xrl_version.restype = C.c_char_p
     _lib = lib
@@ -255,6 +256,17 @@ class Encoder:
                                                   dentropy.data_ptr(), demb.data_ptr(),
                                                   dweights.data_ptr()))
         return demb
+
+    def ppo_objective(self, batch, pv, action, old_logp, advantage, v_target, eps=0.2, c1=0.5, c2=0.01):
+        """(J [4] = J, L_clip, L_vf, L_entropy; dlogp [G]; dvalue [S]; dentropy [S]) from the outputs
+        `pv` of policy_value and the rollout's records (device tensors)."""
+        J, dlogp = self._empty((4,)), self._empty((batch.G,))
+        dvalue, dentropy = self._empty((batch.S,)), self._empty((batch.S,))
+        _check(self.lib.xrl_ppo_objective(self.handle, batch.handle, pv["logp"].data_ptr(), pv["value"].data_ptr(),
+                                          pv["entropy"].data_ptr(), action.data_ptr(), old_logp.data_ptr(),
+                                          advantage.data_ptr(), v_target.data_ptr(), eps, c1, c2, J.data_ptr(),
+                                          dlogp.data_ptr(), dvalue.data_ptr(), dentropy.data_ptr()))
+        return J, dlogp, dvalue, dentropy
 
     def encode_backward(self, batch, demb, dweights):
         _check(self.lib.xrl_encode_backward(self.handle, batch.handle, demb.data_ptr(), dweights.data_ptr()))

@@ -413,3 +413,39 @@ __global__ void small_wgrad_kernel(const float *x1, int w1, const float *x2, int
     dW[(size_t)k * dout + f] += acc;
   }
 }
+
+// Clipped-surrogate objective of Section 3.3.4 and its derivatives w.r.t. the heads' outputs, one
+// block for the whole minibatch (S is a few hundred at most; the means are block reductions in a
+// fixed order). dlogp must be zero on entry: only the taken slots are written.
+__global__ __launch_bounds__(256) void ppo_objective_kernel(
+    const float *logp, const float *value, const float *entropy, const int32_t *state_graph_ptr,
+    const int32_t *action, const float *old_logp, const float *advantage, const float *v_target,
+    int S, float eps, float c1, float c2, float *J, float *dlogp, float *dvalue, float *dentropy) {
+  __shared__ float red[256];
+  const int t = threadIdx.x;
+  const float inv = 1.f / (float)(S > 0 ? S : 1);
+  float clip = 0.f, vf = 0.f, ent = 0.f;
+  for (int s = t; s < S; s += 256) {
+    const int j = state_graph_ptr[s] + action[s];
+    const float A = advantage[s];
+    const float ratio = expf(logp[j] - old_logp[s]);
+    const float s1 = ratio * A;
+    const float s2 = fminf(fmaxf(ratio, 1.f - eps), 1.f + eps) * A;
+    clip -= fminf(s1, s2);
+    dlogp[j] = s1 <= s2 ? -s1 * inv : 0.f;
+    const float dv = value[s] - v_target[s];
+    vf += dv * dv;
+    dvalue[s] = 2.f * c1 * dv * inv;
+    ent -= entropy[s];
+    dentropy[s] = -c2 * inv;
+  }
+  clip = block_sum(clip, red) * inv;
+  vf = block_sum(vf, red) * inv;
+  ent = block_sum(ent, red) * inv;
+  if (t == 0) {
+    J[0] = clip + c1 * vf + c2 * ent;
+    J[1] = clip;
+    J[2] = vf;
+    J[3] = ent;
+  }
+}

@@ -1067,6 +1067,25 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   return XRL_OK;
 }
 
+int xrl_ppo_objective(xrl_ctx *c, const xrl_batch *b, const float *d_logp, const float *d_value,
+                      const float *d_entropy, const int32_t *d_action, const float *d_old_logp,
+                      const float *d_advantage, const float *d_v_target, float eps, float c1,
+                      float c2, float *d_J, float *d_dlogp, float *d_dvalue, float *d_dentropy) {
+  int rc = check_batch(c, b, "xrl_ppo_objective");
+  if (rc) return rc;
+  if (!d_J) return fail(XRL_ERR_NULL, "xrl_ppo_objective: d_J is NULL");
+  if (b->S > 0 && (!d_logp || !d_value || !d_entropy || !d_action || !d_old_logp || !d_advantage ||
+                   !d_v_target || !d_dlogp || !d_dvalue || !d_dentropy))
+    return fail(XRL_ERR_NULL, "xrl_ppo_objective: NULL device pointer");
+  if (b->G > 0)
+    fill_zero_kernel<<<dim3((unsigned)((b->G + 255) / 256)), dim3(256), 0, c->stream>>>(d_dlogp, b->G);
+  ppo_objective_kernel<<<dim3(1), dim3(256), 0, c->stream>>>(
+      d_logp, d_value, d_entropy, b->dev.state_graph_ptr, d_action, d_old_logp, d_advantage, d_v_target,
+      (int)b->S, eps, c1, c2, d_J, d_dlogp, d_dvalue, d_dentropy);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
 int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb,
                               const float *d_dlogp, const float *d_dvalue,
                               const float *d_dentropy, float *d_demb, float *d_dweights) {
