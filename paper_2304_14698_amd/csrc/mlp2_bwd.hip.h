@@ -63,6 +63,11 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   int64_t row = row0 + l32;
   const bool valid = row < a.n_rows;
   if (!valid) row = a.n_rows - 1;
+  // every [rows, H] result leaves through a per-wave staging buffer, one 32-feature block at a time
+  __shared__ __align__(16) char stage_all[4][BlockStage<float>::BYTES];
+  char *stage = stage_all[wave];
+  const int64_t left = a.n_rows - row0;
+  const int n_valid = left < 32 ? (left > 0 ? (int)left : 0) : 32;
 
   // ---------------- z1^T = relu(W1^T x^T + b1), exactly as in the forward kernel
   f32x16 acc1[MB];
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc1[mb][r] = fmaxf(acc1[mb][r], 0.f);
-    store_tile_rows<T, H>((T *)a.z1, row, valid, mb, g, acc1[mb]);
+    store_block_via_lds<T, H>((T *)a.z1, row0, n_valid, mb, lane, acc1[mb], stage);
   }
 
   // ---------------- dz2^T = dy^T * [y^T > 0], stored and kept as operand slabs
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) d[4 * q + j] = yv[4 * q + j] > 0.f ? v[j] : 0.f;
       }
-      store_tile_rows<T, H>((T *)a.dz2, row, valid, nb, g, d);
+      store_block_via_lds<T, H>((T *)a.dz2, row0, n_valid, nb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz2s[nb][q] = acc_slab<T>(d, q);
     }
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
         }
 #pragma unroll
       for (int r = 0; r < 16; ++r) d[r] = acc1[mb][r] > 0.f ? d[r] : 0.f;
-      store_tile_rows<T, H>((T *)a.dz1, row, valid, mb, g, d);
+      store_block_via_lds<T, H>((T *)a.dz1, row0, n_valid, mb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz1s[mb][q] = acc_slab<T>(d, q);
     }
@@ -225,10 +230,10 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
         }
       if constexpr (KIND == KIND_EDGE) {
         T *o = (T *)(kb < MB ? a.dx_a : a.dx_b);
-        store_tile_rows<T, H>(o, row, valid, kb % MB, g, d);
+        store_block_via_lds<T, H>(o, row0, n_valid, kb % MB, lane, d, stage);
       } else {
         float *o = (float *)(kb < MB ? a.dx_a : a.dx_b);
-        store_tile_rows<float, H>(o, row, valid, kb % MB, g, d);
+        store_block_via_lds<float, H>(o, row0, n_valid, kb % MB, lane, d, stage);
       }
     }
   }

@@ -208,3 +208,37 @@ __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[H / 32], 
     wave_lds_fence();
   }
 }
+
+// One 32-feature block of a features x rows accumulator tile (lane = row) to a row-major
+// [rows, H] array, through a wave-private LDS buffer: the block's 32 rows x 32 elements are
+// written as register quads and read back 16 bytes per lane, so a store instruction covers
+// 64 / (32 * sizeof(TO) / 16) rows with one contiguous 32-element piece each, instead of 32 rows
+// with 4 elements each. Rows row0 .. row0 + n_valid - 1 are stored. stage: BlockStage<TO>::BYTES.
+template <typename TO>
+struct BlockStage {
+  static constexpr int RB = 32 * (int)sizeof(TO);        // bytes of a row's piece
+  static constexpr int RS = RB + 16;                     // padded
+  static constexpr int BYTES = 32 * RS;
+  static constexpr int LPR = RB / 16, RPI = 64 / LPR;    // lanes per row, rows per instruction
+};
+template <typename TO, int H>
+__device__ __forceinline__ void store_block_via_lds(TO *base, int64_t row0, int n_valid, int fb, int lane,
+                                                    const f32x16 &d, char *stage) {
+  using S = BlockStage<TO>;
+  const int l32 = lane & 31, g = lane >> 5;
+  char *wp = stage + l32 * S::RS + 4 * g * (int)sizeof(TO);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float v[4] = {d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]};
+    store4<TO>((TO *)(wp + 8 * q * (int)sizeof(TO)), v);
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int k = 0; k < 32 / S::RPI; ++k) {
+    const int r = k * S::RPI + lane / S::LPR;
+    const f32x4 v = *(const f32x4 *)(stage + r * S::RS + (lane % S::LPR) * 16);
+    if (r < n_valid)
+      *(f32x4 *)((char *)(base + (size_t)(row0 + r) * H + 32 * fb) + (lane % S::LPR) * 16) = v;
+  }
+  wave_lds_fence();
+}
