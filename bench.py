@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="synthetic configuration (2 = headline)")
     ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
     ap.add_argument("--states", type=int, default=None, help="override the number of states")
+    ap.add_argument("--round-kind", default="mlp", choices=["mlp", "gat"],
+                    help="message-passing layers: edge/node MLPs (measured path) or graph attention (forward only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
@@ -98,6 +100,7 @@ def main():
     model, state = synth.make_config(args.config, n_states=args.states)
     if args.precision:
         model["precision"] = args.precision
+    model["round_kind"] = args.round_kind
     rng = np.random.Generator(np.random.PCG64(synth.BASE_SEED))
     w = synth.init_weights(rng, xrl.weight_layout(model), bias_range=0.1)
     enc = xrl.Encoder(model, w)
@@ -147,7 +150,7 @@ def main():
     for _ in range(args.steps):
         step()
     kern = {}
-    for k in ("embed", "edge", "edge_fixup", "node", "pool", "readout", "heads"):
+    for k in ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads"):
         tot, n = enc.read_timing(k)
         kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)
     enc.set_timing(False)
@@ -155,7 +158,7 @@ def main():
     edge_s = kern["edge"]["avg_us"] * 1e-6
     bf16 = model["precision"] == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
-    achieved = edge_flops / edge_s / 1e12 if edge_s > 0 else 0.0
+    achieved = edge_flops / edge_s / 1e12 if edge_s > 0 else 0.0   # (0 with attention rounds: replaced below)
     b = 2 if bf16 else 4
     # edge stage, ideal fused: h read once, edge attributes, indices; received sums written for
     # the receivers that have in-edges
@@ -185,6 +188,19 @@ def main():
                         unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
         kernels_us=kern,
     )
+    if args.round_kind == "gat":
+        # attention rounds: the dense part z = h W on the matrix cores, then a gather-bound pass
+        # (per edge one z row read, per node its own row read and one row written, scores, indices)
+        agg_bytes = (E + 2 * N) * H * b + 4 * (2 * N + 2 * E)
+        agg_s, lin_s = kern["gat_aggregate"]["avg_us"] * 1e-6, kern["gat_linear"]["avg_us"] * 1e-6
+        res["config"]["workload"] += ", graph-attention rounds"
+        res["roofline"] = dict(bound="hbm", kernel="attention-weighted sum over in-edges (one launch per round)",
+                               achieved=agg_bytes / agg_s / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
+                               frac=agg_bytes / agg_s / 1e9 / PEAK_HBM_GBS, traffic=None,
+                               algorithmic_bytes_per_launch=agg_bytes, avg_launch_us=kern["gat_aggregate"]["avg_us"])
+        res["mfma_kernel"] = dict(kernel="z = h W (one launch per round)", flops_per_launch=2.0 * N * H * H,
+                                  achieved=2.0 * N * H * H / lin_s / 1e12, peak=peak, unit="TFLOP/s",
+                                  frac=2.0 * N * H * H / lin_s / 1e12 / peak, avg_launch_us=kern["gat_linear"]["avg_us"])
     if args.peaks:
         tf, gb = enc.measure_peaks()
         res["measured_peaks"] = dict(mfma_bf16_tflops=tf, copy_gbs=gb,

@@ -43,6 +43,7 @@ typedef enum {
 } xrl_status;
 
 enum { XRL_READOUT_SUM = 0, XRL_READOUT_MEAN = 1 };
+enum { XRL_ROUND_MLP = 0, XRL_ROUND_GAT = 1 };
 enum { XRL_PREC_FP32 = 0,      /* fp32 operands, fp32 accumulate                              */
        XRL_PREC_BF16 = 1 };    /* bf16 MFMA operands (weights, stored activations), fp32
                                   accumulate, bias, ReLU, segment sums, readout and heads     */
@@ -62,6 +63,11 @@ typedef struct xrl_model_desc {
   int32_t head_hidden[2];
   int32_t readout;        /* XRL_READOUT_SUM (the paper's sum) or XRL_READOUT_MEAN            */
   int32_t precision;      /* XRL_PREC_FP32 or XRL_PREC_BF16                                   */
+  int32_t round_kind;     /* XRL_ROUND_MLP, or XRL_ROUND_GAT: the graph-attention reading of
+                             the message-passing layers (Section 3.4, second equation): z = h W,
+                             s = LeakyReLU_0.2(a_src.z_sender + a_dst.z_receiver), softmax over a
+                             receiver's in-edges plus a self edge, h' = ReLU(sum alpha z).
+                             Forward only: xrl_encode_backward returns UNSUPPORTED for it       */
 } xrl_model_desc;
 
 /* One or many states, all host memory. Graphs are listed state by state; the first graph of a
@@ -111,7 +117,8 @@ typedef struct xrl_batch xrl_batch; /* one packed meta-batch (host copy + device
  * h_receiver | edge attrs]) then node MLP (input [h | received sum]) (message-passing layers of
  * Section 3.4); readout MLP (input [sum or mean of node states | global attrs], the global-update
  * layer); policy head; value head (Section 3.3.2). Each MLP lists, per layer, W [in, out] then
- * b [out]. */
+ * b [out]. With XRL_ROUND_GAT a round instead lists W [hidden, hidden], a_src [hidden], a_dst
+ * [hidden] ("gat3.W", "gat3.a_src", "gat3.a_dst"). */
 int64_t xrl_weight_count(const xrl_model_desc *model);        /* total floats, <0 on error     */
 int32_t xrl_weight_tensor_count(const xrl_model_desc *model); /* number of tensors, <0 on error */
 /* Tensor `index`: name (e.g. "edge3.W0") copied into name[name_cap]; vectors report cols = 0. */

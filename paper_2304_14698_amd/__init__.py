@@ -14,6 +14,7 @@ _lib = None
 
 PRECISION = {"fp32": 0, "bf16": 1}
 READOUT = {"sum": 0, "mean": 1}
+ROUND_KIND = {"mlp": 0, "gat": 1}
 
 
 class XrlError(RuntimeError):
@@ -29,7 +30,7 @@ class ModelDesc(C.Structure):
     _fields_ = [("n_op_types", C.c_int32), ("n_node_dense", C.c_int32), ("d_edge", C.c_int32),
                 ("d_global", C.c_int32), ("hidden", C.c_int32), ("rounds", C.c_int32),
                 ("mlp_layers", C.c_int32), ("head_hidden", C.c_int32 * 2),
-                ("readout", C.c_int32), ("precision", C.c_int32)]
+                ("readout", C.c_int32), ("precision", C.c_int32), ("round_kind", C.c_int32)]
 
 
 class StateDesc(C.Structure):
@@ -109,7 +110,8 @@ def model_desc(model):
                      model["hidden"], model["rounds"], model.get("mlp_layers", 2),
                      (C.c_int32 * 2)(int(hh[0]), int(hh[1])),
                      READOUT[ro] if isinstance(ro, str) else int(ro),
-                     PRECISION[prec] if isinstance(prec, str) else int(prec))
+                     PRECISION[prec] if isinstance(prec, str) else int(prec),
+                     ROUND_KIND[model.get("round_kind", "mlp")])
 
 
 def weight_count(model):

@@ -12,6 +12,7 @@
 #include "mlp2_bwd.hip.h"
 #include "mlp2p.hip.h"
 #include "mlp2r.hip.h"
+#include "gat.hip.h"
 #include "wgrad.hip.h"
 #include "segsum.hip.h"
 #include "xrl_internal.h"
@@ -89,9 +90,10 @@ struct EncMlp {           // device pointers of one encoder MLP
 }  // namespace
 
 // kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
-enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_COUNT };
-static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup",
-                                                  "node", "pool", "readout", "heads"};
+enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_GAT_LINEAR,
+       TK_GAT_AGGREGATE, TK_COUNT };
+static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
+                                                  "heads", "gat_linear", "gat_aggregate"};
 
 struct xrl_ctx {
   xrl_model_desc m;
@@ -107,6 +109,7 @@ struct xrl_ctx {
   size_t swz_bytes = 0;
   EncMlp embed;
   std::vector<EncMlp> edge, node;
+  std::vector<const void *> gatW;   // XRL_ROUND_GAT: fragment-ordered W of each round
   // workspaces (grow-only): encoder activations, and a separate small one for the heads
   char *ws = nullptr;
   size_t ws_bytes = 0;
@@ -222,7 +225,27 @@ int upload_weights(xrl_ctx *c, const float *w) {
     refs.push_back(ref);
   };
   add(c->L.embed, true);   // the embed MLP's first layer keeps fp32 operands in both modes
-  for (int r = 0; r < m.rounds; ++r) { add(c->L.edge[r], false); add(c->L.node[r], false); }
+  const bool gat = m.round_kind == XRL_ROUND_GAT;
+  std::vector<size_t> gat_off;
+  if (gat) {
+    for (int r = 0; r < m.rounds; ++r) {               // one fragment-ordered [H, H] matrix per round
+      size_t o = align_up(blob.size());
+      if (c->elem == 2) {
+        std::vector<uint16_t> t;
+        swizzle_l1<uint16_t>(w + c->L.gat[r].W, H, H, V, t);
+        blob.resize(o + t.size() * 2);
+        memcpy(blob.data() + o, t.data(), t.size() * 2);
+      } else {
+        std::vector<float> t;
+        swizzle_l1<float>(w + c->L.gat[r].W, H, H, V, t);
+        blob.resize(o + t.size() * 4);
+        memcpy(blob.data() + o, t.data(), t.size() * 4);
+      }
+      gat_off.push_back(o);
+    }
+  } else {
+    for (int r = 0; r < m.rounds; ++r) { add(c->L.edge[r], false); add(c->L.node[r], false); }
+  }
   if (blob.size() > c->swz_bytes) {
     if (c->d_swz) HIP_TRY(hipFree(c->d_swz));
     c->d_swz = nullptr;
@@ -247,6 +270,11 @@ int upload_weights(xrl_ctx *c, const float *w) {
   };
   size_t i = 0;
   bind(c->embed, refs[i++], c->L.embed);
+  c->gatW.clear();
+  if (gat) {
+    for (int r = 0; r < m.rounds; ++r) c->gatW.push_back(c->d_swz + gat_off[r]);
+    return XRL_OK;
+  }
   c->edge.resize(m.rounds);
   c->node.resize(m.rounds);
   for (int r = 0; r < m.rounds; ++r) {
@@ -802,7 +830,10 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   const int nh = save ? R + 1 : (R > 0 ? 2 : 1), nagg = save ? R : (R > 0 ? 1 : 0);
   size_t need = 0;
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
-  for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));
+  constexpr int PV = 16 / sizeof(T);
+  const bool gat = m.round_kind == XRL_ROUND_GAT;
+  for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));   // (GAT: the agg slot holds z)
+  if (gat) { acc((size_t)N * 4); acc((size_t)N * 4); }
   const size_t carry_floats = std::max(std::max(segsum_carry_floats(E, De), segsum_carry_floats(N, H)),
                                        (size_t)n_tiles * 2 * H);
   acc(carry_floats * 4);
@@ -817,6 +848,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   std::vector<T *> hb(nh), ab(std::max(nagg, 1), nullptr);
   for (int i = 0; i < nh; ++i) hb[i] = bump.take<T>((size_t)N * H);
   for (int i = 0; i < nagg; ++i) ab[i] = bump.take<T>((size_t)N * H);
+  float *gs_src = gat ? bump.take<float>((size_t)N) : nullptr, *gs_dst = gat ? bump.take<float>((size_t)N) : nullptr;
   c->carry = bump.take<float>(carry_floats);
   c->pool = bump.take<float>((size_t)G * H);
   c->ro_act[0] = bump.take<float>((size_t)G * H);
@@ -838,7 +870,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   };
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
-  a.agg0 = ab[0]; a.n_agg = nagg; a.agg_stride = nagg > 1 ? (size_t)((char *)ab[1] - (char *)ab[0]) : 0;
+  a.agg0 = ab[0]; a.n_agg = gat ? 0 : nagg; a.agg_stride = nagg > 1 ? (size_t)((char *)ab[1] - (char *)ab[0]) : 0;
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
   c->h[0] = hb[0];
@@ -847,6 +879,31 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   for (int r = 0; r < R; ++r) {
     T *aggb = save ? ab[r] : ab[0];
     T *hnext = save ? hb[r + 1] : hb[(r + 1) & 1];
+    if (gat) {                         // graph-attention reading of the round (forward only)
+      if (N > 0) {
+        GatArgs ga;
+        ga.n_rows = N; ga.n_blocks = (N + 127) / 128;
+        ga.h = hcur; ga.Ws = c->gatW[r];
+        ga.a_src = c->d_w + c->L.gat[r].a_src; ga.a_dst = c->d_w + c->L.gat[r].a_dst;
+        ga.z = aggb; ga.s_src = gs_src; ga.s_dst = gs_dst;
+        ga.in_ptr = d.in_ptr; ga.in_src = d.in_src; ga.out = hnext;
+        { Timed t(c, TK_GAT_LINEAR);
+          const unsigned grid = (unsigned)((ga.n_blocks + 7) / 8 * 8);
+          switch (H) {
+            case 64: gat_linear_kernel<T, 64><<<dim3(grid), dim3(256), 0, c->stream>>>(ga); break;
+            case 128: gat_linear_kernel<T, 128><<<dim3(grid), dim3(256), 0, c->stream>>>(ga); break;
+            default: gat_linear_kernel<T, 256><<<dim3(grid), dim3(256), 0, c->stream>>>(ga); break;
+          } }
+        { Timed t(c, TK_GAT_AGGREGATE);
+          const int64_t threads = N * (H / PV);
+          gat_aggregate_kernel<T, PV><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(ga, H); }
+        HIP_TRY(hipGetLastError());
+      }
+      c->h[r + 1] = hnext;
+      c->agg[r + 1] = nullptr;
+      hcur = hnext;
+      continue;
+    }
     set_w(c->edge[r]);
     a.n_rows = E; a.h = hcur; a.out = aggb;
     { Timed t(c, TK_EDGE); rc = launch_mlp2<T>(c, KIND_EDGE, a); }
@@ -866,7 +923,6 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     hcur = hnext;
   }
   // ---- global-update layer: per-graph sum (or mean), then the readout MLP
-  constexpr int PV = 16 / sizeof(T);
   if (N <= 4096 * G) {
     // many graphs of moderate size: one block per graph sums its nodes and runs the readout MLP
     Timed t(c, TK_POOL);
@@ -1142,6 +1198,8 @@ int xrl_encode_backward(xrl_ctx *c, const xrl_batch *b, const float *d_demb, flo
   if (rc) return rc;
   if (b->G == 0) return XRL_OK;
   if (!d_demb || !d_dweights) return fail(XRL_ERR_NULL, "xrl_encode_backward: NULL device pointer");
+  if (c->m.round_kind == XRL_ROUND_GAT)
+    return fail(XRL_ERR_UNSUPPORTED, "xrl_encode_backward: the graph-attention rounds are forward only");
   if (!c->enc_saved || c->enc_batch != b->id)
     return fail(XRL_ERR_STATE, "xrl_encode_backward: the batch's last xrl_encode did not save for backward");
   return c->elem == 2 ? encode_backward_impl<bf16_t>(c, b, d_demb, d_dweights)
@@ -1288,6 +1346,8 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
     src = c->h[round];
   } else if (!strcmp(what, "agg")) {
     if (round < 1 || round > R) return fail(XRL_ERR_INDEX, "agg: round %d outside [1, %d]", round, R);
+    if (c->m.round_kind == XRL_ROUND_GAT)
+      return fail(XRL_ERR_UNSUPPORTED, "agg: the graph-attention rounds keep no received sums");
     src = c->agg[round];
     mask_rows = true;
   } else return fail(XRL_ERR_INDEX, "xrl_get_activation: unknown tensor '%s'", what);

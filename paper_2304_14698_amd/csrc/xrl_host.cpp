@@ -56,15 +56,33 @@ int build_layout(const xrl_model_desc &m, Layout &L) {
     return fail(XRL_ERR_SHAPE, "model: readout must be XRL_READOUT_SUM or XRL_READOUT_MEAN");
   if (m.precision != XRL_PREC_FP32 && m.precision != XRL_PREC_BF16)
     return fail(XRL_ERR_SHAPE, "model: precision must be XRL_PREC_FP32 or XRL_PREC_BF16");
+  if (m.round_kind != XRL_ROUND_MLP && m.round_kind != XRL_ROUND_GAT)
+    return fail(XRL_ERR_SHAPE, "model: round_kind must be XRL_ROUND_MLP or XRL_ROUND_GAT");
   L = Layout();
   const int H = m.hidden;
   std::vector<int> enc(m.mlp_layers, H);
   add_mlp(L, L.embed, "embed", m.d_edge + m.n_op_types + m.n_node_dense, enc);
-  L.edge.resize(m.rounds);
-  L.node.resize(m.rounds);
-  for (int r = 0; r < m.rounds; ++r) {
-    add_mlp(L, L.edge[r], "edge" + std::to_string(r), 2 * H + m.d_edge, enc);
-    add_mlp(L, L.node[r], "node" + std::to_string(r), 2 * H, enc);
+  if (m.round_kind == XRL_ROUND_GAT) {
+    L.gat.resize(m.rounds);
+    for (int r = 0; r < m.rounds; ++r) {
+      const std::string p = "gat" + std::to_string(r);
+      L.gat[r].W = L.total;
+      L.tensors.push_back({p + ".W", L.total, H, H});
+      L.total += (int64_t)H * H;
+      L.gat[r].a_src = L.total;
+      L.tensors.push_back({p + ".a_src", L.total, H, 0});
+      L.total += H;
+      L.gat[r].a_dst = L.total;
+      L.tensors.push_back({p + ".a_dst", L.total, H, 0});
+      L.total += H;
+    }
+  } else {
+    L.edge.resize(m.rounds);
+    L.node.resize(m.rounds);
+    for (int r = 0; r < m.rounds; ++r) {
+      add_mlp(L, L.edge[r], "edge" + std::to_string(r), 2 * H + m.d_edge, enc);
+      add_mlp(L, L.node[r], "node" + std::to_string(r), 2 * H, enc);
+    }
   }
   add_mlp(L, L.readout, "readout", H + m.d_global, enc);
   std::vector<int> head = {m.head_hidden[0], m.head_hidden[1], 1};

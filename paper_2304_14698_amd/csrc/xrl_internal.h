@@ -30,7 +30,9 @@ struct Layout {
   std::vector<WeightTensor> tensors;
   int64_t total = 0;
   MlpRef embed, readout, policy, value;
-  std::vector<MlpRef> edge, node;  // per round
+  std::vector<MlpRef> edge, node;  // per round (XRL_ROUND_MLP)
+  struct GatRef { int64_t W = 0, a_src = 0, a_dst = 0; };
+  std::vector<GatRef> gat;         // per round (XRL_ROUND_GAT)
 };
 
 // Validates the dimensions that every part of the library relies on (positive widths, ...)

@@ -55,7 +55,7 @@ def assert_close(got, ref, precision, what, scale=None):
 def oracle_model(model):
     return O.default_model(**{k: model[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
                                                     "hidden", "rounds", "mlp_layers", "head_hidden",
-                                                    "readout")})
+                                                    "readout")}, round_kind=model.get("round_kind", "mlp"))
 
 
 def weights_for(model, seed=11):
@@ -79,7 +79,7 @@ def run_case(xrl, model, state, w, check_inter=True):
         assert_close(enc.get_activation(batch, "a0").cpu().numpy(), cat(lambda i: i["a0"]), "fp32", "a0")
         for r in range(model["rounds"] + 1):
             assert_close(enc.get_activation(batch, "h", r).cpu().numpy(), cat(lambda i: i["h"][r]), pi, f"h[{r}]")
-            if r >= 1:
+            if r >= 1 and model.get("round_kind", "mlp") == "mlp":
                 assert_close(enc.get_activation(batch, "agg", r).cpu().numpy(),
                              cat(lambda i: i["agg"][r - 1]), pi, f"agg[{r}]")
         assert_close(enc.get_activation(batch, "pool").cpu().numpy(),
@@ -159,6 +159,27 @@ def test_persistent_kernels_on_small_ragged_batches(xrl, hidden, monkeypatch):
     model, state = synth.make_config(1)
     model.update(hidden=hidden, precision="bf16")
     run_case(xrl, model, state, weights_for(model))
+
+
+@pytest.mark.parametrize("hidden,precision", [(64, "fp32"), (128, "bf16"), (256, "bf16"), (128, "fp32")])
+def test_graph_attention_rounds(xrl, hidden, precision):
+    """The graph-attention reading of the message-passing layers (forward only) against the
+    oracle's: a ragged batch of Inception-shaped graphs (in-degrees 0..6), then graphs with a
+    receiver of in-degree 300, zero-edge, single-node and empty graphs."""
+    model, state = synth.make_config(4, n_cand=4)
+    model.update(hidden=hidden, precision=precision, rounds=3, round_kind="gat")
+    run_case(xrl, model, state, weights_for(model))
+    rng = np.random.Generator(np.random.PCG64(5))
+    run_case(xrl, model, hub_state(rng, model, 300), weights_for(model, seed=12))
+    enc = xrl.Encoder(model, weights_for(model))
+    batch = enc.pack(state)
+    enc.encode(batch, save_for_backward=True)
+    import torch
+    dw = torch.zeros(enc.n_weights, device="cuda")
+    with pytest.raises(xrl.XrlError) as ei:
+        enc.encode_backward(batch, torch.zeros((batch.G, hidden), device="cuda"), dw)
+    assert ei.value.code == xrl.ERR["UNSUPPORTED"]
+    enc.close()
 
 
 @pytest.mark.parametrize("cfg", [3, 4, 5])

@@ -34,11 +34,13 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(hidden=256, rounds=5), dict(hidden=128, rounds=0),
-                                dict(n_op_types=40, n_node_dense=0, d_edge=4, mlp_layers=1, hidden=64)])
+                                dict(n_op_types=40, n_node_dense=0, d_edge=4, mlp_layers=1, hidden=64),
+                                dict(hidden=128, rounds=3, round_kind="gat")])
 def test_weight_layout_matches_oracle(kw):
     m = base_model(**kw)
     om = O.default_model(**{k: m[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
-                                              "hidden", "rounds", "mlp_layers", "head_hidden")})
+                                              "hidden", "rounds", "mlp_layers", "head_hidden")},
+                         round_kind=m.get("round_kind", "mlp"))
     assert xrl.weight_layout(m) == [(n, tuple(s)) for n, s in O.weight_layout(om)]
     assert xrl.weight_count(m) == O.weight_count(om)
 
