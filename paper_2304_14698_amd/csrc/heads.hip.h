@@ -24,67 +24,121 @@ struct RowMlpArgs {
   float *act[3];           // nullable each
 };
 
-// One row through the layers of `a`, all 256 threads of the block cooperating. The contraction of
-// a layer narrower than the block is split over 256 / d_out thread groups (each thread then has
-// d_in * d_out / 256 weights to fetch, all requested before the first is used -- these kernels
-// are bound by memory latency, not bandwidth); the groups' partial sums are added in group order.
-// cur holds the input row (d_in[0] floats) on entry; cur/nxt: >= widest layer; part: 256 floats.
-// `row` indexes the stores to a.act[l] and a.out.
+// One row through the layers of `a`, all 256 threads of the block cooperating. These kernels are
+// bound by memory latency, not bandwidth, so a layer's weights are requested in as few dependent
+// rounds as possible: with d_out a multiple of 4 (and the matrix 16-byte aligned) a thread owns
+// four adjacent outputs and one of 256 / (d_out / 4) slices of the contraction, loads its weights
+// 16 bytes at a time, sixteen loads in flight, and the slices' partial sums are added in slice
+// order; other layers (a single output, say) split the contraction the same way with scalar loads.
+// cur holds the input row (d_in[0] floats) on entry; cur/nxt: >= widest layer; part: 1024 floats,
+// 16-byte aligned. `row` indexes the stores to a.act[l] and a.out. COHERENT_OUT stores a.out with
+// device scope, for a consumer in another block of the same launch.
+template <bool COHERENT_OUT = false>
+__device__ __forceinline__ void store_row_out(float *p, float y) {
+  if constexpr (COHERENT_OUT) __hip_atomic_store(p, y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = y;
+}
+
+template <bool COHERENT_OUT = false>
 __device__ __forceinline__ void block_row_mlp(const RowMlpArgs &a, float *cur, float *nxt, float *part,
                                               int64_t row) {
   const int t = threadIdx.x;
   for (int l = 0; l < a.n_layers; ++l) {
     const int din = a.d_in[l], dout = a.d_out[l];
     const bool relu = a.relu_last || (l + 1 < a.n_layers);
-    int fw = 256;                                         // outputs handled per pass
-    while (fw / 2 >= dout && 256 / (fw / 2) <= din) fw /= 2;
-    const int KQ = 256 / fw;                              // thread groups splitting the contraction
-    const int kc = (din + KQ - 1) / KQ;
-    const int fl = t % fw, kq = t / fw;
-    const int k0 = kq * kc, k1 = (k0 + kc) < din ? (k0 + kc) : din;
     const float *W = a.W[l];
-    for (int f0 = 0; f0 < dout; f0 += fw) {
-      const int f = f0 + fl;
-      float acc = 0.f;
-      if (f < dout) {
+    if ((dout & 3) == 0 && dout <= 1024 && ((uintptr_t)W & 15) == 0) {
+      const int fq = dout >> 2;                           // 16-byte columns
+      int KQ = 256 / fq;                                  // slices of the contraction
+      if (KQ > din) KQ = din;
+      const int kc = (din + KQ - 1) / KQ;
+      const int fl = t % fq, kq = t / fq;
+      if (kq < KQ) {
+        const int k0 = kq * kc, k1 = (k0 + kc) < din ? (k0 + kc) : din;
+        const float4 *Wp = (const float4 *)W + fl;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         int k = k0;
         for (; k + 16 <= k1; k += 16) {
-          float w[16];
+          float4 w[16];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) w[i] = W[(size_t)(k + i) * dout + f];
+          for (int i = 0; i < 16; ++i) w[i] = Wp[(size_t)(k + i) * fq];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc = fmaf(cur[k + i], w[i], acc);
+          for (int i = 0; i < 16; ++i) {
+            const float x = cur[k + i];
+            acc.x = fmaf(x, w[i].x, acc.x); acc.y = fmaf(x, w[i].y, acc.y);
+            acc.z = fmaf(x, w[i].z, acc.z); acc.w = fmaf(x, w[i].w, acc.w);
+          }
         }
-        for (; k < k1; ++k) acc = fmaf(cur[k], W[(size_t)k * dout + f], acc);
-      }
-      if (KQ > 1) {
-        part[t] = acc;
-        __syncthreads();
-        if (kq == 0) {
-          acc = part[fl];
-          for (int q = 1; q < KQ; ++q) acc += part[q * fw + fl];
+        for (; k < k1; ++k) {
+          const float4 w = Wp[(size_t)k * fq];
+          const float x = cur[k];
+          acc.x = fmaf(x, w.x, acc.x); acc.y = fmaf(x, w.y, acc.y);
+          acc.z = fmaf(x, w.z, acc.z); acc.w = fmaf(x, w.w, acc.w);
         }
+        ((float4 *)part)[kq * fq + fl] = acc;
       }
-      if (kq == 0 && f < dout) {
-        acc += a.b[l][f];
-        const float y = relu ? fmaxf(acc, 0.f) : acc;
+      __syncthreads();
+      for (int f = t; f < dout; f += 256) {
+        float v = part[f];
+        for (int q = 1; q < KQ; ++q) v += part[q * dout + f];
+        v += a.b[l][f];
+        const float y = relu ? fmaxf(v, 0.f) : v;
         nxt[f] = y;
         if (a.act[l]) a.act[l][row * dout + f] = y;
-        if (l + 1 == a.n_layers) a.out[row * dout + f] = y;
+        if (l + 1 == a.n_layers) store_row_out<COHERENT_OUT>(a.out + row * dout + f, y);
       }
-      if (KQ > 1) __syncthreads();
+      __syncthreads();
+    } else {
+      int fw = 256;                                       // outputs handled per pass
+      while (fw / 2 >= dout && 256 / (fw / 2) <= din) fw /= 2;
+      const int KQ = 256 / fw;                            // thread groups splitting the contraction
+      const int kc = (din + KQ - 1) / KQ;
+      const int fl = t % fw, kq = t / fw;
+      const int k0 = kq * kc, k1 = (k0 + kc) < din ? (k0 + kc) : din;
+      for (int f0 = 0; f0 < dout; f0 += fw) {
+        const int f = f0 + fl;
+        float acc = 0.f;
+        if (f < dout) {
+          int k = k0;
+          for (; k + 16 <= k1; k += 16) {
+            float w[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) w[i] = W[(size_t)(k + i) * dout + f];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc = fmaf(cur[k + i], w[i], acc);
+          }
+          for (; k < k1; ++k) acc = fmaf(cur[k], W[(size_t)k * dout + f], acc);
+        }
+        if (KQ > 1) {
+          part[t] = acc;
+          __syncthreads();
+          if (kq == 0) {
+            acc = part[fl];
+            for (int q = 1; q < KQ; ++q) acc += part[q * fw + fl];
+          }
+        }
+        if (kq == 0 && f < dout) {
+          acc += a.b[l][f];
+          const float y = relu ? fmaxf(acc, 0.f) : acc;
+          nxt[f] = y;
+          if (a.act[l]) a.act[l][row * dout + f] = y;
+          if (l + 1 == a.n_layers) store_row_out<COHERENT_OUT>(a.out + row * dout + f, y);
+        }
+        if (KQ > 1) __syncthreads();
+      }
+      __syncthreads();
     }
-    __syncthreads();
     float *tmp = cur; cur = nxt; nxt = tmp;
   }
 }
 
 template <int ROWMLP_ROWS>
 __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
-  extern __shared__ float sm[];          // two buffers of ROWMLP_ROWS * dmax floats (+ 256 for one row)
+  // two buffers of ROWMLP_ROWS * dmax floats; with one row per block, 1024 floats of partial sums first
+  extern __shared__ __align__(16) float sm[];
   int dmax = a.d_in[0];
   for (int l = 0; l < a.n_layers; ++l) dmax = a.d_out[l] > dmax ? a.d_out[l] : dmax;
-  float *cur = sm, *nxt = sm + ROWMLP_ROWS * dmax;
+  float *cur = sm + (ROWMLP_ROWS == 1 ? 1024 : 0), *nxt = cur + ROWMLP_ROWS * dmax;
   const int64_t row0 = (int64_t)blockIdx.x * ROWMLP_ROWS;
   for (int i = threadIdx.x; i < ROWMLP_ROWS * a.d_in[0]; i += blockDim.x) {
     const int r = i / a.d_in[0], k = i - r * a.d_in[0];
@@ -95,7 +149,7 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
   }
   __syncthreads();
   if constexpr (ROWMLP_ROWS == 1) {
-    block_row_mlp(a, cur, nxt, sm + 2 * dmax, row0);
+    block_row_mlp(a, cur, nxt, sm, row0);
     return;
   }
   for (int l = 0; l < a.n_layers; ++l) {
@@ -166,7 +220,7 @@ __global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const in
   __syncthreads();
   int dmax = mlp.d_in[0];
   for (int l = 0; l < mlp.n_layers; ++l) dmax = mlp.d_out[l] > dmax ? mlp.d_out[l] : dmax;
-  float *cur = sm + 256 * VEC, *nxt = cur + dmax, *part = nxt + dmax;
+  float *cur = sm + 256 * VEC, *nxt = cur + dmax, *part = sm;   // (the partial sums are dead by then)
   const float scale = mean ? 1.f / (float)(n1 - n0 > 1 ? n1 - n0 : 1) : 1.f;
   for (int f = t; f < H; f += 256) {
     float a = sm[f];
@@ -288,7 +342,126 @@ __global__ __launch_bounds__(256) void state_policy_kernel(
   }
   __syncthreads();
   // value head on the mean embedding (Section 3.3.2), in the same block
-  if (value.n_layers > 0) block_row_mlp(value, vcur, vnxt, red, s);
+  if (value.n_layers > 0) block_row_mlp(value, vcur, vnxt, zbuf, s);
+}
+
+// Both heads in one launch for batches of at most a few thousand slots. Blocks [0, G): the policy
+// MLP of one slot, and the block that finishes a state's last slot (a per-state counter, which it
+// also resets) does that state's masked log-softmax, entropy and first-max action. Blocks
+// [G, G + S): the mean embedding of a state's valid slots and the value head on it, independent of
+// the policy blocks. Results are the same as rowmlp_kernel<1> followed by state_policy_kernel.
+// Logits cross blocks through device-scope stores and loads (each completed before the block's
+// counter increment is issued), so no cache write-back or invalidation is needed.
+__global__ __launch_bounds__(256) void policy_value_kernel(
+    const RowMlpArgs policy, const uint8_t *mask, const int32_t *state_graph_ptr, int G, int S, int H,
+    int32_t *counter, float *logp, float *entropy, int32_t *action, float *zmean, const RowMlpArgs value) {
+  __shared__ __align__(16) float part[1024];
+  __shared__ __align__(16) float bufa[512], bufb[512];
+  __shared__ float red[256];
+  __shared__ int redi[256];
+  __shared__ int sh_state, sh_last;
+  const int t = threadIdx.x;
+  if ((int)blockIdx.x >= G) {
+    // ---- value head of state s
+    const int s = blockIdx.x - G;
+    const int j0 = state_graph_ptr[s], j1 = state_graph_ptr[s + 1];
+    const float *emb = policy.in1;
+    const int tpr = H / 4, ng = 256 / tpr, c4 = (t % tpr) * 4, q = t / tpr;   // H is 64, 128 or 256
+    float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
+    int cnt = 0;
+    int j = j0 + q;
+    for (; j + 7 * ng < j1; j += 8 * ng) {
+      float4 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = *(const float4 *)(emb + (size_t)(j + i * ng) * H + c4);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (mask[j + i * ng]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; ++cnt; }
+    }
+    for (; j < j1; j += ng)
+      if (mask[j]) {
+        const float4 v = *(const float4 *)(emb + (size_t)j * H + c4);
+        p.x += v.x; p.y += v.y; p.z += v.z; p.w += v.w; ++cnt;
+      }
+    ((float4 *)part)[t] = p;                                       // [ng][H / 4]
+    redi[t] = cnt;
+    __syncthreads();
+    if (t < tpr) {
+      float4 acc = ((float4 *)part)[t];
+      int n = redi[0];
+      for (int k = 1; k < ng; ++k) {
+        const float4 o = ((float4 *)part)[k * tpr + t];
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+        n += redi[k * tpr];
+      }
+      const float nvalid = (float)n;
+      acc.x /= nvalid; acc.y /= nvalid; acc.z /= nvalid; acc.w /= nvalid;
+      *(float4 *)(zmean + (size_t)s * H + c4) = acc;
+      *(float4 *)(bufa + c4) = acc;
+    }
+    __syncthreads();
+    if (value.n_layers > 0) block_row_mlp(value, bufa, bufb, part, s);
+    return;
+  }
+  // ---- policy MLP of slot j; meanwhile find the slot's state
+  const int j = blockIdx.x;
+  if (t == 0) sh_state = -1;
+  for (int k = t; k < H; k += 256) bufa[k] = policy.in1[(size_t)j * H + k];
+  __syncthreads();
+  for (int s = t; s < S; s += 256)
+    if (state_graph_ptr[s] <= j && j < state_graph_ptr[s + 1]) sh_state = s;
+  block_row_mlp<true>(policy, bufa, bufb, part, j);
+  __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0): this wave's logit store has completed
+  __syncthreads();
+  const int s = sh_state;
+  if (s < 0) return;                                               // (a slot outside every state: not packed by this library)
+  const int j0 = state_graph_ptr[s], j1 = state_graph_ptr[s + 1];
+  if (t == 0) {
+    const int done = atomicAdd(&counter[s], 1);
+    sh_last = done == j1 - j0 - 1;
+    if (sh_last) counter[s] = 0;                                   // ready for the next launch
+  }
+  __syncthreads();
+  if (!sh_last) return;
+  const float *logit = policy.out;
+  auto ld = [&](int i) { return __hip_atomic_load(logit + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  // max valid logit and the lowest slot index attaining it
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  for (int i = j0 + t; i < j1; i += 256)
+    if (mask[i]) {
+      const float l = ld(i);
+      if (l > best || (l == best && i < besti)) { best = l; besti = i; }
+    }
+  red[t] = best; redi[t] = besti;
+  __syncthreads();
+  for (int k = 128; k > 0; k >>= 1) {
+    if (t < k) {
+      const float o = red[t + k];
+      const int oi = redi[t + k];
+      if (o > red[t] || (o == red[t] && oi < redi[t])) { red[t] = o; redi[t] = oi; }
+    }
+    __syncthreads();
+  }
+  const float M = red[0];
+  const int arg = redi[0];
+  __syncthreads();
+  float se = 0.f;
+  for (int i = j0 + t; i < j1; i += 256)
+    if (mask[i]) se += expf(ld(i) - M);
+  const float lse = M + logf(block_sum(se, red));
+  float ent = 0.f;
+  for (int i = j0 + t; i < j1; i += 256) {
+    if (mask[i]) {
+      const float lp = ld(i) - lse;
+      logp[i] = lp;
+      ent -= expf(lp) * lp;
+    } else {
+      logp[i] = -INFINITY;
+    }
+  }
+  ent = block_sum(ent, red);
+  if (t == 0) { entropy[s] = ent; action[s] = arg - j0; }
 }
 
 // dJ/dlogit per slot from (dlogp, dentropy) and the forward's logp/entropy; one block per state.

@@ -5,6 +5,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "heads.hip.h"
@@ -95,6 +96,8 @@ enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HE
 static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
                                                   "heads", "gat_linear", "gat_aggregate"};
 
+constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
+
 struct xrl_ctx {
   xrl_model_desc m;
   Layout L;
@@ -104,12 +107,14 @@ struct xrl_ctx {
   int max_lds = 65536;          // LDS bytes one block may use
   int64_t p_min_rows = 8192;    // smallest row count for the persistent kernels (XRL_PERSISTENT_MIN_ROWS)
   float *d_w = nullptr;         // flat fp32 weights
+  int32_t *d_counter = nullptr; // kMaxFusedSlots per-state counters of policy_value_kernel, zero between launches
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
   char *d_swz = nullptr;        // fragment-ordered encoder weights
   size_t swz_bytes = 0;
   EncMlp embed;
   std::vector<EncMlp> edge, node;
   std::vector<const void *> gatW;   // XRL_ROUND_GAT: fragment-ordered W of each round
+  std::unordered_map<int64_t, const float *> row_w;   // readout / head matrices, 16-byte aligned copies
   // workspaces (grow-only): encoder activations, and a separate small one for the heads
   char *ws = nullptr;
   size_t ws_bytes = 0;
@@ -246,6 +251,15 @@ int upload_weights(xrl_ctx *c, const float *w) {
   } else {
     for (int r = 0; r < m.rounds; ++r) { add(c->L.edge[r], false); add(c->L.node[r], false); }
   }
+  // the row-MLPs read their matrices with 16-byte loads: aligned copies, keyed by flat offset
+  std::vector<std::pair<int64_t, size_t>> row_off;
+  for (const MlpRef *r : {&c->L.readout, &c->L.policy, &c->L.value})
+    for (int l = 0; l < r->n_layers; ++l) {
+      const size_t o = align_up(blob.size()), n = sizeof(float) * (size_t)r->d_in[l] * r->d_out[l];
+      blob.resize(o + n);
+      memcpy(blob.data() + o, w + r->w[l], n);
+      row_off.push_back({r->w[l], o});
+    }
   if (blob.size() > c->swz_bytes) {
     if (c->d_swz) HIP_TRY(hipFree(c->d_swz));
     c->d_swz = nullptr;
@@ -268,6 +282,8 @@ int upload_weights(xrl_ctx *c, const float *w) {
     e.nslabx = ref.nsx;
     e.table = c->d_w + r.w[0] + (size_t)m.d_edge * H;    // meaningful for the embed MLP only
   };
+  c->row_w.clear();
+  for (const auto &ro : row_off) c->row_w[ro.first] = (const float *)(c->d_swz + ro.second);
   size_t i = 0;
   bind(c->embed, refs[i++], c->L.embed);
   c->gatW.clear();
@@ -554,7 +570,8 @@ RowMlpArgs rowmlp_args(xrl_ctx *c, const MlpRef &r, bool relu_last, const float 
   a.relu_last = relu_last ? 1 : 0;
   int dmax = r.d_in[0];
   for (int l = 0; l < r.n_layers; ++l) {
-    a.W[l] = c->d_w + r.w[l];
+    const auto it = c->row_w.find(r.w[l]);
+    a.W[l] = it != c->row_w.end() ? it->second : c->d_w + r.w[l];
     a.b[l] = c->d_w + r.b[l];
     a.d_in[l] = r.d_in[l];
     a.d_out[l] = r.d_out[l];
@@ -572,11 +589,34 @@ int launch_rowmlp(xrl_ctx *c, const MlpRef &r, bool relu_last, const float *in1,
   int dmax = 0;
   const RowMlpArgs a = rowmlp_args(c, r, relu_last, in1, w1, in2, w2, n_rows, out, act, &dmax);
   if (n_rows <= 4096) {
-    rowmlp_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)(2 * dmax + 256) * sizeof(float), c->stream>>>(a);
+    rowmlp_kernel<1><<<dim3((unsigned)n_rows), dim3(256), (size_t)(1024 + 2 * dmax) * sizeof(float), c->stream>>>(a);
   } else {
     const unsigned blocks = (unsigned)((n_rows + 7) / 8);
     rowmlp_kernel<8><<<dim3(blocks), dim3(256), (size_t)2 * 8 * dmax * sizeof(float), c->stream>>>(a);
   }
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+// Policy MLP, per-state softmax statistics and value head (Section 3.3.2): one launch for batches
+// of up to kMaxFusedSlots slots, otherwise the row-MLP kernel followed by the per-state kernel.
+// pact / vact (nullable) receive every layer's output for the backward pass.
+int launch_heads(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *logit, float *logp, float *entropy,
+                 int32_t *action, float *zmean, float *value, float *const *pact, float *const *vact) {
+  const int H = c->m.hidden;
+  const xrl_batch_device &d = b->dev;
+  const RowMlpArgs va = rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, b->S, value, vact);
+  if (b->G <= kMaxFusedSlots) {
+    const RowMlpArgs pa = rowmlp_args(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, pact);
+    policy_value_kernel<<<dim3((unsigned)(b->G + b->S)), dim3(256), 0, c->stream>>>(
+        pa, d.mask, d.state_graph_ptr, (int)b->G, (int)b->S, H, c->d_counter, logp, entropy, action, zmean, va);
+    HIP_TRY(hipGetLastError());
+    return XRL_OK;
+  }
+  int rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, pact);
+  if (rc) return rc;
+  state_policy_kernel<<<dim3((unsigned)b->S), dim3(256), 0, c->stream>>>(
+      logit, d.mask, d.state_graph_ptr, d_emb, H, logp, entropy, action, zmean, va);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
@@ -929,7 +969,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     int dmax = 0;
     const RowMlpArgs ra = rowmlp_args(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb,
                                       c->ro_act, &dmax);
-    const size_t lds = (size_t)(256 * PV + 2 * dmax + 256) * sizeof(float);
+    const size_t lds = (size_t)(256 * PV + 2 * dmax) * sizeof(float);
     graph_readout_kernel<T, PV><<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(
         hcur, d.graph_node_ptr, H, m.readout == XRL_READOUT_MEAN ? 1 : 0, c->pool, ra);
     HIP_TRY(hipGetLastError());
@@ -992,13 +1032,15 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   }
   // the weights, followed by 1 KB of zeros (16-byte aligned) that kernels read in place of absent rows
   const size_t w_bytes = align_up(sizeof(float) * L.total);
-  e = hipMalloc((void **)&c->d_w, w_bytes + 1024);
+  const size_t tail_bytes = 1024 + sizeof(int32_t) * kMaxFusedSlots;   // zero row, heads' counters
+  e = hipMalloc((void **)&c->d_w, w_bytes + tail_bytes);
   if (e != hipSuccess) {
     delete c;
     return fail(XRL_ERR_OOM, "device weights: %s", hipGetErrorString(e));
   }
   c->zero_row = (char *)c->d_w + w_bytes;
-  e = hipMemset(c->zero_row, 0, 1024);
+  c->d_counter = (int32_t *)((char *)c->zero_row + 1024);
+  e = hipMemset(c->zero_row, 0, tail_bytes);
   if (e != hipSuccess) {
     xrl_destroy(c);
     return fail(XRL_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
@@ -1114,13 +1156,7 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   float *logit = d_logit ? d_logit : (float *)c->hws;
   float *zmean = (float *)(c->hws + align_up((size_t)b->G * 4));
   Timed t(c, TK_HEADS);
-  rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, nullptr);
-  if (rc) return rc;
-  state_policy_kernel<<<dim3((unsigned)b->S), dim3(256), 0, c->stream>>>(
-      logit, b->dev.mask, b->dev.state_graph_ptr, d_emb, H, d_logp, d_entropy, d_action, zmean,
-      rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, b->S, d_value, nullptr));
-  HIP_TRY(hipGetLastError());
-  return XRL_OK;
+  return launch_heads(c, b, d_emb, logit, d_logp, d_entropy, d_action, zmean, d_value, nullptr, nullptr);
 }
 
 int xrl_ppo_objective(xrl_ctx *c, const xrl_batch *b, const float *d_logp, const float *d_value,
@@ -1176,10 +1212,7 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   float *dzs = bump.take<float>(S * H);
   const xrl_batch_device &d = b->dev;
   // forward of the heads, keeping every layer's output
-  if ((rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, G, logit, pact))) return rc;
-  state_policy_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(
-      logit, d.mask, d.state_graph_ptr, d_emb, H, logp, ent, action, zmean,
-      rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, S, value, vact));
+  if ((rc = launch_heads(c, b, d_emb, logit, logp, ent, action, zmean, value, pact, vact))) return rc;
   // backward
   state_policy_bwd_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(logp, ent, d.mask, d.state_graph_ptr,
                                                                         d_dlogp, d_dentropy, dlogit, inv_n);
