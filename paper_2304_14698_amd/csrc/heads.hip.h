@@ -313,20 +313,19 @@ __global__ __launch_bounds__(256) void state_policy_kernel(
   // sums are combined in group order
   const int tpr = H / 4, ng = 256 / tpr, c4 = (t % tpr) * 4, q = t / tpr;     // H is 64, 128 or 256
   float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
-  int j = j0 + q;
-  for (; j + 7 * ng < j1; j += 8 * ng) {
+  for (int j = j0 + q; j < j1; j += 8 * ng) {
     float4 v[8];
+    bool on[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = *(const float4 *)(emb + (size_t)(j + i * ng) * H + c4);
+    for (int i = 0; i < 8; ++i) {
+      const int ji = j + i * ng < j1 ? j + i * ng : j;
+      v[i] = *(const float4 *)(emb + (size_t)ji * H + c4);
+      on[i] = j + i * ng < j1 && mask[ji];
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      if (mask[j + i * ng]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; }
+      if (on[i]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; }
   }
-  for (; j < j1; j += ng)
-    if (mask[j]) {
-      const float4 v = *(const float4 *)(emb + (size_t)j * H + c4);
-      p.x += v.x; p.y += v.y; p.z += v.z; p.w += v.w;
-    }
   float4 *zp = (float4 *)zbuf;                                   // [ng][H / 4]
   zp[t] = p;
   __syncthreads();
@@ -369,20 +368,19 @@ __global__ __launch_bounds__(256) void policy_value_kernel(
     const int tpr = H / 4, ng = 256 / tpr, c4 = (t % tpr) * 4, q = t / tpr;   // H is 64, 128 or 256
     float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
     int cnt = 0;
-    int j = j0 + q;
-    for (; j + 7 * ng < j1; j += 8 * ng) {
+    for (int j = j0 + q; j < j1; j += 8 * ng) {
       float4 v[8];
+      bool on[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = *(const float4 *)(emb + (size_t)(j + i * ng) * H + c4);
+      for (int i = 0; i < 8; ++i) {
+        const int ji = j + i * ng < j1 ? j + i * ng : j;
+        v[i] = *(const float4 *)(emb + (size_t)ji * H + c4);
+        on[i] = j + i * ng < j1 && mask[ji];
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        if (mask[j + i * ng]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; ++cnt; }
+        if (on[i]) { p.x += v[i].x; p.y += v[i].y; p.z += v[i].z; p.w += v[i].w; ++cnt; }
     }
-    for (; j < j1; j += ng)
-      if (mask[j]) {
-        const float4 v = *(const float4 *)(emb + (size_t)j * H + c4);
-        p.x += v.x; p.y += v.y; p.z += v.z; p.w += v.w; ++cnt;
-      }
     ((float4 *)part)[t] = p;                                       // [ng][H / 4]
     redi[t] = cnt;
     __syncthreads();

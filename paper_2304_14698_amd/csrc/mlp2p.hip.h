@@ -219,6 +219,9 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
 // little LDS -- the fp32 fragments for the [edge-attr sum | dense attrs] columns and the [Tn, H]
 // table of W1's one-hot rows -- so two blocks fit a CU. At most 4 * 64 * NW 16-byte pieces each
 // for the first-layer fragments and for the table (the launcher checks).
+// At H = 256 the second layer's weights alone take 128 KB: the table then stays in global memory
+// (32 KB, read through the caches), the block has four waves, and the rows leave through a
+// staging buffer of one 32-feature block per wave.
 template <typename T, int H, int NW>
 __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   using Opd = Operand<T>;
@@ -227,10 +230,12 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   extern __shared__ __align__(16) char smem[];
   vec *W2l = (vec *)smem;                                              // [NC2][MB][64]
   f32x4 *W1l = (f32x4 *)(W2l + (size_t)NC2 * MB * 64);                 // [nslabx][MB][64]
-  f32x4 *tab = W1l + (size_t)a.nslabx * MB * 64;                       // [Tn][H / 4]
-  float(*b1l)[2][16] = (float(*)[2][16])(tab + (size_t)a.Tn * (H / 4));
+  constexpr bool BIG = H > 128;                                        // table in global memory, block staging
+  f32x4 *tabl = W1l + (size_t)a.nslabx * MB * 64;                      // [Tn][H / 4] (not BIG)
+  const f32x4 *tab = BIG ? (const f32x4 *)a.table : tabl;
+  float(*b1l)[2][16] = (float(*)[2][16])(tabl + (BIG ? 0 : (size_t)a.Tn * (H / 4)));
   float(*b2l)[2][16] = b1l + MB;
-  char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * RowStage<T, H>::BYTES;
+  char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * (BIG ? BlockStage<T>::BYTES : RowStage<T, H>::BYTES);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
@@ -242,7 +247,7 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   int64_t wt = t_begin + (int64_t)wave * nbx + lid;
   {
     constexpr int N2 = NC2 * MB * 64, C2 = (N2 + NT - 1) / NT;
-    const int n1 = a.nslabx * MB * 64, nt = a.Tn * (H / 4);
+    const int n1 = a.nslabx * MB * 64, nt = BIG ? 0 : a.Tn * (H / 4);
     const vec *s2 = (const vec *)a.W2s;
     const f32x4 *s1 = (const f32x4 *)a.W1x, *st = (const f32x4 *)a.table;
     vec t2[C2];
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
       if (tid + c * NT < n1) W1l[tid + c * NT] = t1[c];
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      if (tid + c * NT < nt) tab[tid + c * NT] = tt[c];
+      if (tid + c * NT < nt) tabl[tid + c * NT] = tt[c];
     if (tid < MB * 32) {
       b1l[tid / 32][(tid / 16) % 2][tid % 16] = bb1;
       b2l[tid / 32][(tid / 16) % 2][tid % 16] = bb2;
@@ -300,9 +305,20 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
     T *out = (T *)a.out;
-    store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
-      return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
-    });
+    if constexpr (BIG) {
+      const int64_t left = a.n_rows - row0;
+      const int n_valid = left < 32 ? (int)left : 32;
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc2[nb][r] = relu_f32(acc2[nb][r]);
+        store_block_via_lds<T, H>(out, row0, n_valid, nb, lane, acc2[nb], stage);
+      }
+    } else {
+      store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
+        return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
+      });
+    }
     zero_source_rows<T, H>(a, row0, er.e0 == er.e1, lane);
   }
 }

@@ -468,15 +468,17 @@ int launch_mlp2p(xrl_ctx *c, int kind, Mlp2Args &a) {
   return launch_mlp2p_k<H, KIND_NODE>(c, a, lds);
 }
 
+constexpr int embedp_waves(int H) { return H > 128 ? 4 : kPersistWaves; }
 inline size_t embedp_lds_bytes(int H, int nslabx, int Tn) {
   const int MB = H / 32, HS = H / 16;
-  return ((size_t)nslabx * MB + (size_t)HS * MB) * 1024 + (size_t)Tn * H * 4 + (size_t)MB * 256 +
-         (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;
+  const size_t w = ((size_t)nslabx * MB + (size_t)HS * MB) * 1024 + (size_t)MB * 256;
+  if (H > 128) return w + (size_t)embedp_waves(H) * BlockStage<bf16_t>::BYTES;     // table stays in global memory
+  return w + (size_t)Tn * H * 4 + (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;
 }
 
 template <int H>
 int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
-  constexpr int NW = kPersistWaves;
+  constexpr int NW = embedp_waves(H);
   const size_t lds = embedp_lds_bytes(H, a.nslabx, a.Tn);
   auto kern = embedp_kernel<bf16_t, H, NW>;
   static size_t attr_lds = 0;
@@ -497,13 +499,14 @@ int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
 
 inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   const int H = c->m.hidden;
-  if (c->elem != 2 || H > 128 || a.n_rows <= 0) return false;
+  if (c->elem != 2 || a.n_rows <= 0) return false;
   if (a.n_rows < c->p_min_rows) return false;
   if (kind == KIND_EMBED) {
-    const int pieces = 4 * 64 * kPersistWaves;               // see embedp_kernel
-    return a.nslabx * (H / 32) * 64 <= pieces && a.Tn * (H / 4) <= pieces &&
+    const int pieces = 4 * 64 * embedp_waves(H);             // see embedp_kernel
+    return a.nslabx * (H / 32) * 64 <= pieces && (H > 128 || a.Tn * (H / 4) <= pieces) &&
            embedp_lds_bytes(H, a.nslabx, a.Tn) <= (size_t)c->max_lds;
   }
+  if (H > 128) return false;
   if (kind == KIND_EDGE && a.nslab1 != 2 * (H / 16) + 1) return false;   // edge attrs must fit one slab
   return mlp2p_lds_bytes(H, a.nslab1) <= (size_t)c->max_lds;
 }
@@ -550,7 +553,8 @@ int launch_mlp2(xrl_ctx *c, int kind, Mlp2Args &a) {
   if (mlp2r_applies(c, kind, a))
     return launch_mlp2r<256>(c, kind, a);
   if (mlp2p_applies(c, kind, a)) {
-    if (kind == KIND_EMBED) return c->m.hidden == 64 ? launch_embedp<64>(c, a) : launch_embedp<128>(c, a);
+    if (kind == KIND_EMBED)
+      return c->m.hidden == 64 ? launch_embedp<64>(c, a) : c->m.hidden == 128 ? launch_embedp<128>(c, a) : launch_embedp<256>(c, a);
     return c->m.hidden == 64 ? launch_mlp2p<64>(c, kind, a) : launch_mlp2p<128>(c, kind, a);
   }
   a.n_blocks = kind == KIND_EDGE ? (a.n_tiles + 3) / 4 : (a.n_rows + 127) / 128;
