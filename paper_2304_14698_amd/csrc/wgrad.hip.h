@@ -143,6 +143,219 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
       out[(size_t)acc_row(r, g) * H + 32 * (kbb0 + 2 * i) + l32] = acc[i][r];
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 variant built on the LDS transpose read (ds_read_b64_tr_b16): tiles go into LDS row-major,
+// 16 bytes per lane, and an operand "lane = column, elements = 8 consecutive rows" is two reads.
+// In a group of 16 lanes, lane L passes the address of 4 consecutive 16-bit elements -- lanes
+// 4j .. 4j+3 together one 16-element piece of row j -- and receives element L of each of the four
+// rows; so lane L points at tile[k0 + L / 4][c0 + 4 * (L % 4)] and gets tile[k0 .. k0+3][c0 + L].
+//
+// A block owns 128 columns of X and all H columns of dZ over one contiguous slice of the rows
+// (wave (wa, wb): X columns 64 wa .., dZ columns H/2 wb ..), stages 32 rows at a time, and keeps
+// the next stage's global loads in flight while the matrix cores work on the current one (one
+// barrier per stage); the row indices of gathered X columns are fetched two stages ahead. The
+// 128-column tiles of one row slice run on the same XCD, so dZ is fetched into that L2 once.
+// Rows of an LDS tile are 64 bytes longer than their data: with a row stride of 16 (mod 64)
+// dwords the four rows a transpose read touches fall on different banks.
+struct Wgrad2Plan {
+  int kt, ny, rows_per_slot;     // 128-column tiles of X, row slices, rows per slice (multiple of 32)
+};
+inline Wgrad2Plan wgrad2_plan(int64_t n_rows, int Ka, int n_cu) {
+  Wgrad2Plan p;
+  p.kt = (Ka + 1 + 127) / 128;
+  int per = (2 * n_cu / 8) / p.kt;                        // row slices per XCD: two blocks per CU
+  if (per < 1) per = 1;
+  int64_t want = (n_rows + 63) / 64;                      // at least 64 rows per slice
+  want = (want + 7) / 8;
+  if (want < 1) want = 1;
+  if (per > want) per = (int)want;
+  p.ny = 8 * per;
+  int64_t rps = (n_rows + p.ny - 1) / p.ny;
+  p.rows_per_slot = (int)((rps + 31) / 32 * 32);
+  return p;
+}
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// 8 rows (k0 .. k0+7) of one column as an MFMA operand; p = this lane's address for rows k0 .. k0+3
+__device__ __forceinline__ bf16x8 lds_tr_operand(const char *p, int row_stride) {
+  typedef s16x4 __attribute__((address_space(3))) * lp;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)(p + 4 * row_stride));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// The stage loop of one block. Every global load is unconditional, from a clamped (always valid)
+// address, and masked afterwards: divergent or conditional loads would put waits for memory in
+// the middle of the loop. TAIL = the tile holds columns past the gathered / direct ones (edge
+// attributes, the all-ones bias column, padding); such tiles are whole for the EDGE and NODE
+// kinds (2H is a multiple of 128), PLAIN uses the one formulation for all its tiles.
+template <int H, int KIND, bool TAIL>
+__device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t r_begin, int64_t r_end,
+                                           char (*Xs)[32 * (128 * 2 + 64)], char (*Zs)[32 * (H * 2 + 64)],
+                                           f32x16 (&acc)[2][H / 64 > 0 ? H / 64 : 1]) {
+  using T = bf16_t;
+  using vec = bf16x8;
+  constexpr int TA = 128, RS = 32;
+  constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;         // LDS row strides, bytes
+  constexpr int NB = H / 64 > 0 ? H / 64 : 1;              // 32-column blocks of dZ per wave
+  constexpr int ZV = RS * (H / 8) / 256;                   // dZ vectors per thread per stage
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int wa = wave & 1, wb = wave >> 1;
+  const int n_stage = (int)((r_end - r_begin + RS - 1) / RS);
+
+  // ---- this thread's two X vectors per stage: rows xr, xr + 16 of the stage, columns xc .. xc+7
+  const int xr = tid / 16, xc = ka0 + 8 * (tid % 16);
+  const bool second = xc >= H;                             // EDGE: receiver's state; NODE: aggregate
+  [[maybe_unused]] const int32_t *idx_arr = second ? a.in_dst : a.in_src;
+  [[maybe_unused]] const T *gbase = (const T *)a.h + (second ? xc - H : xc);
+  [[maybe_unused]] const T *nbase = second ? (const T *)a.agg + (xc - H) : (const T *)a.h + xc;
+  vec ones = Operand<T>::zero();                           // the bias column, when this thread holds it
+  if (xc == a.Ka) ones[0] = (T)1.0f;
+
+  auto row_of = [&](int st, int c) {
+    int64_t row = r_begin + (int64_t)st * RS + xr + 16 * c;
+    return row < r_end ? row : r_end - 1;
+  };
+  auto live = [&](int st, int c) { return r_begin + (int64_t)st * RS + xr + 16 * c < r_end; };
+  // row indices (EDGE) or in-degrees (NODE) of stage st, which may be past the end
+  auto load_idx = [&](int st, int (&ix)[2]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      ix[c] = 0;
+      if constexpr (!TAIL && KIND == WG_EDGE) ix[c] = idx_arr[row_of(st, c)];
+      if constexpr (!TAIL && KIND == WG_NODE) ix[c] = a.in_ptr[row_of(st, c) + 1] - a.in_ptr[row_of(st, c)];
+    }
+  };
+  auto load_x = [&](int st, const int (&ix)[2], vec (&x)[2]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int64_t row = row_of(st, c);
+      const bool on = live(st, c);
+      if constexpr (KIND == WG_PLAIN) {
+        const int cc = xc + 8 <= a.Ka ? xc : a.Ka - 8;
+        const vec v = *(const vec *)((const T *)a.A + (size_t)row * a.Ka + cc);
+        x[c] = !on ? Operand<T>::zero() : (xc + 8 <= a.Ka ? v : ones);
+      } else if constexpr (!TAIL && KIND == WG_EDGE) {
+        const vec v = *(const vec *)(gbase + (size_t)ix[c] * H);
+        x[c] = on ? v : Operand<T>::zero();
+      } else if constexpr (!TAIL && KIND == WG_NODE) {
+        const vec v = *(const vec *)(nbase + (size_t)row * H);
+        x[c] = on && (!second || ix[c] > 0) ? v : Operand<T>::zero();
+      } else if constexpr (KIND == WG_EDGE) {              // [edge attributes | 1 | 0 ...]
+        // every lane loads and uses an attribute (times 0 or 1, plus the bias column's 1): a
+        // select would let the compiler move the loads into branches with waits behind them
+        vec v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int k = xc - 2 * H + j;
+          const float f = a.De > 0 ? a.edge_feat[(size_t)row * a.De + (k < a.De ? k : a.De - 1)] : 0.f;
+          v[j] = (T)fmaf(f, k < a.De ? 1.f : 0.f, k == a.De ? 1.f : 0.f);
+        }
+        x[c] = on ? v : Operand<T>::zero();
+      } else {                                             // NODE: [1 | 0 ...]
+        x[c] = on ? ones : Operand<T>::zero();
+      }
+    }
+  };
+  auto load_z = [&](int st, vec (&z)[ZV]) {
+#pragma unroll
+    for (int c = 0; c < ZV; ++c) {
+      const int vi = tid + 256 * c, rl = vi / (H / 8), cc = vi % (H / 8);
+      int64_t row = r_begin + (int64_t)st * RS + rl;
+      const bool on = row < r_end;
+      if (!on) row = r_end - 1;
+      const vec v = *(const vec *)((const T *)a.dZ + (size_t)row * H + cc * 8);
+      z[c] = on ? v : Operand<T>::zero();
+    }
+  };
+  auto commit = [&](int buf, const vec (&x)[2], const vec (&z)[ZV]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) *(vec *)(Xs[buf] + (xr + 16 * c) * XS + (tid % 16) * 16) = x[c];
+#pragma unroll
+    for (int c = 0; c < ZV; ++c) {
+      const int vi = tid + 256 * c, rl = vi / (H / 8), cc = vi % (H / 8);
+      *(vec *)(Zs[buf] + rl * ZS + cc * 16) = z[c];
+    }
+  };
+
+  int ix0[2], ix1[2];
+  vec xn[2], zn[ZV];
+  load_idx(0, ix0);
+  load_idx(1, ix1);
+  load_x(0, ix0, xn);
+  load_z(0, zn);
+  commit(0, xn, zn);
+  __syncthreads();
+  // per-lane offsets of the transpose reads: row 8 g + L / 4, 8 bytes at 16-bit column 16 half + 4 (L % 4)
+  const int L = lane & 15, half = (lane >> 4) & 1;
+  const int xoff = (8 * g + L / 4) * XS + (32 * (2 * wa) + 16 * half + 4 * (L % 4)) * 2;
+  const int zoff = (8 * g + L / 4) * ZS + (32 * (wb * NB) + 16 * half + 4 * (L % 4)) * 2;
+  for (int st = 0; st < n_stage; ++st) {
+    int ix2[2];
+    load_idx(st + 2 < n_stage ? st + 2 : st, ix2);
+    const int sn = st + 1 < n_stage ? st + 1 : st;         // (the last iteration re-reads its own stage)
+    load_x(sn, ix1, xn);
+    load_z(sn, zn);
+    const char *xs = Xs[st & 1] + xoff, *zs = Zs[st & 1] + zoff;
+#pragma unroll
+    for (int k = 0; k < RS / 16; ++k) {
+      vec xa[2], xb[NB];
+#pragma unroll
+      for (int m = 0; m < 2; ++m) xa[m] = lds_tr_operand(xs + 16 * k * XS + 64 * m, XS);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) xb[i] = lds_tr_operand(zs + 16 * k * ZS + 64 * i, ZS);
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) Operand<T>::mma(xa[m], xb[i], acc[m][i]);
+    }
+    commit((st + 1) & 1, xn, zn);
+    __syncthreads();
+    ix1[0] = ix2[0]; ix1[1] = ix2[1];
+  }
+}
+
+template <int H, int KIND>
+__global__ __launch_bounds__(256) void wgrad2_kernel(const WgradArgs a, int kt, int ny) {
+  constexpr int TA = 128, RS = 32;
+  constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;
+  constexpr int NB = H / 64 > 0 ? H / 64 : 1;
+  static_assert(KIND != WG_EMBED, "the embed layer's columns are synthesised: see wgrad_kernel");
+  __shared__ __align__(16) char Xs[2][RS * XS];
+  __shared__ __align__(16) char Zs[2][RS * ZS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
+  const int wa = wave & 1, wb = wave >> 1;
+  // blocks are dealt round-robin to the 8 XCDs: the kt tiles of a row slice stay on one XCD
+  const int xcd = blockIdx.x % 8, q = blockIdx.x / 8;
+  const int ka0 = (q % kt) * TA, y = xcd + 8 * (q / kt);
+  const int64_t r_begin = (int64_t)y * a.rows_per_chunk;
+  int64_t r_end = r_begin + a.rows_per_chunk;
+  if (r_end > a.n_rows) r_end = a.n_rows;
+
+  f32x16 acc[2][NB];
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][i][r] = 0.f;
+  if (r_end > r_begin) {
+    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true>(a, ka0, r_begin, r_end, Xs, Zs, acc);
+    else wgrad2_run<H, KIND, false>(a, ka0, r_begin, r_end, Xs, Zs, acc);
+  }
+  const int KaP = TA * kt;
+  float *out = a.partial + ((size_t)y * KaP + ka0 + 32 * (2 * wa)) * H + 32 * (wb * NB) + l32;
+#pragma unroll
+  for (int m = 0; m < 2; ++m)
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        out[(size_t)(32 * m + acc_row(r, g)) * H + 32 * i] = acc[m][i][r];
+}
+
 // dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka. A block handles
 // 32 consecutive entries; its 8 thread groups take every eighth chunk (eight loads in flight
 // each) and their sums are added in group order, so the result has one fixed summation order.

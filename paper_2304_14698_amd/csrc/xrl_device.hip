@@ -670,15 +670,32 @@ inline void wgrad_chunks(int64_t n_rows, int *rows_per_chunk, int *n_chunks) {
   *n_chunks = (int)((n_rows + rpc - 1) / rpc);
   if (*n_chunks < 1) *n_chunks = 1;
 }
-inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H) {
+inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H, int n_cu) {
   int rpc, nc;
   wgrad_chunks(n_rows, &rpc, &nc);
-  return (size_t)nc * ((Ka + 1 + 63) / 64 * 64) * H;
+  const Wgrad2Plan p = wgrad2_plan(n_rows, Ka, n_cu);
+  return std::max((size_t)nc * ((Ka + 1 + 63) / 64 * 64) * H, (size_t)p.ny * p.kt * 128 * H);
 }
 
 template <typename T, int H>
 int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
   if (a.n_rows <= 0) return XRL_OK;
+  const int64_t n = (int64_t)(a.Ka + 1) * H;
+  if constexpr (sizeof(T) == 2) {
+    if (kind != WG_EMBED) {                                // transpose-read kernel
+      const Wgrad2Plan p = wgrad2_plan(a.n_rows, a.Ka, c->n_cu);
+      a.rows_per_chunk = p.rows_per_slot;
+      a.n_chunks = p.ny;
+      const dim3 grid2((unsigned)(p.ny * p.kt));
+      if (kind == WG_PLAIN) wgrad2_kernel<H, WG_PLAIN><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
+      else if (kind == WG_EDGE) wgrad2_kernel<H, WG_EDGE><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
+      else wgrad2_kernel<H, WG_NODE><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
+      wgrad_reduce_kernel<<<dim3((unsigned)((n + 31) / 32)), dim3(256), 0, c->stream>>>(
+          a.partial, a.n_chunks, p.kt * 128, a.Ka, H, dW, db);
+      HIP_TRY(hipGetLastError());
+      return XRL_OK;
+    }
+  }
   wgrad_chunks(a.n_rows, &a.rows_per_chunk, &a.n_chunks);
   const int kt = (a.Ka + 1 + 63) / 64;
   dim3 grid((unsigned)kt, (unsigned)a.n_chunks);
@@ -686,7 +703,6 @@ int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
   else if (kind == WG_EDGE) wgrad_kernel<T, H, WG_EDGE><<<grid, dim3(256), 0, c->stream>>>(a);
   else if (kind == WG_NODE) wgrad_kernel<T, H, WG_NODE><<<grid, dim3(256), 0, c->stream>>>(a);
   else wgrad_kernel<T, H, WG_EMBED><<<grid, dim3(256), 0, c->stream>>>(a);
-  const int64_t n = (int64_t)(a.Ka + 1) * H;
   wgrad_reduce_kernel<<<dim3((unsigned)((n + 31) / 32)), dim3(256), 0, c->stream>>>(
       a.partial, a.n_chunks, kt * 64, a.Ka, H, dW, db);
   HIP_TRY(hipGetLastError());
@@ -787,7 +803,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   for (int i = 0; i < 3; ++i) acc((size_t)M * H * sizeof(T));      // z1, dz1, dz2
   for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
   for (int i = 0; i < 3; ++i) acc((size_t)N * H * 4);              // dh (two buffers), dagg
-  const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H), wgrad_partial_floats(M, H, H));
+  const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
   const size_t carry_floats = segsum_carry_floats(E, H);
   acc(carry_floats * 4);
