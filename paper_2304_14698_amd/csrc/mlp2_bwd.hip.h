@@ -8,12 +8,14 @@
 //     y^T   = W2^T z1^T           (EDGE only: its per-edge output is not stored by the forward)
 //     dz1^T = W2 dz2^T            (W2 pre-arranged with the contraction over its columns)
 //     dx^T  = W1 dz1^T            (W1 pre-arranged with the contraction over its columns)
-// Weights: a block of 4 waves (128 rows) walks through the four weight matrices in groups of
-// H / 16 fragments (1 KB each); in the bf16 instantiations a group is fetched from L2 once per
-// block -- each wave a quarter of it -- into a double-buffered LDS area and read from there by
-// all four waves, one block barrier per group (fetching every fragment per wave made the kernel
-// L2-bound: 780 KB of weights per 32 rows at H = 256). The fp32 instantiations read their
-// fragments straight from L2.
+// Weights: a block of 4 waves (128 rows) walks through the four weight matrices in units of
+// H / 16 fragments (1 KB each; the fragments one 32-feature output block needs), four units to a
+// group; in the bf16 instantiations a group is fetched from L2 once per block -- each wave a
+// quarter of it, requested a whole group (about 2000 MFMA cycles at H = 256) before it is needed
+// -- into a double-buffered LDS area and read from there by all four waves, one block barrier per
+// group (fetching every fragment per wave made the kernel L2-bound: 780 KB of weights per 32
+// rows at H = 256; groups of one unit left the fetch latency exposed). The fp32 instantiations
+// read their fragments straight from L2.
 // The kernel writes z1, dz1, dz2 as [rows, H] for the weight-gradient kernel, and dx:
 //   EDGE: per-edge gradients w.r.t. h_sender and h_receiver ([E, H] each; summed per node later),
 //   NODE: d/dh [N, H] and d/dagg [N, H] (fp32),   EMBED: nothing (its inputs are data).
@@ -52,39 +54,39 @@ __device__ __forceinline__ bf16x8 acc_slab<bf16_t>(const f32x16 &acc, int q) {
                      acc[8 * q + 5], acc[8 * q + 6], acc[8 * q + 7]);
 }
 
-// Weight fragments of one group for all four waves. SHARED: through LDS (see the file header);
-// otherwise each wave reads its own from global memory. `idx(j)` is the fragment index of the
-// group's j-th fragment inside W (already offset by the lane), `n_valid` how many exist.
-template <typename vecT, int GF, bool SHARED>
+// Weight fragments for all four waves, UG units of UF fragments per group. SHARED: through LDS
+// (see the file header); otherwise each wave reads its own from global memory. `idx(u, j)` is
+// the index inside W (already offset by the lane) of fragment j of the group's u-th unit, or
+// negative if there is no such fragment.
+template <typename vecT, int UF, int UG, bool SHARED>
 struct WeightGroups {
-  static constexpr int PW = GF / 4 > 0 ? GF / 4 : 1;      // fragments a wave fetches per group
+  static constexpr int GF = UF * UG, PW = GF / 4;         // fragments per group / fetched per wave
+  static_assert(GF % 4 == 0, "a group is fetched by four waves");
   f32x4 (*buf)[GF][64];                                   // [2][GF][64] in LDS (SHARED)
   int p = 0, wave, lane;
   f32x4 r[PW];
   template <typename Idx>
-  __device__ __forceinline__ void fetch(const vecT *W, Idx idx, int n_valid) {
+  __device__ __forceinline__ void fetch(const vecT *W, Idx idx) {
     if constexpr (SHARED) {
 #pragma unroll
       for (int i = 0; i < PW; ++i) {
-        const int j = wave * PW + i;
-        if (j < GF && j < n_valid) r[i] = __builtin_bit_cast(f32x4, W[(size_t)idx(j) * 64]);
+        const int jg = wave * PW + i;
+        const int fi = idx(jg / UF, jg % UF);
+        if (fi >= 0) r[i] = __builtin_bit_cast(f32x4, W[(size_t)fi * 64]);
       }
     }
   }
   __device__ __forceinline__ void commit(int q) {
     if constexpr (SHARED) {
 #pragma unroll
-      for (int i = 0; i < PW; ++i) {
-        const int j = wave * PW + i;
-        if (j < GF) buf[q][j][lane] = r[i];
-      }
+      for (int i = 0; i < PW; ++i) buf[q][wave * PW + i][lane] = r[i];
     }
   }
   // first group of a phase: fetch, store, barrier
   template <typename Idx>
-  __device__ __forceinline__ void begin(const vecT *W, Idx idx, int n_valid) {
+  __device__ __forceinline__ void begin(const vecT *W, Idx idx) {
     if constexpr (SHARED) {
-      fetch(W, idx, n_valid);
+      fetch(W, idx);
       commit(p);
       __syncthreads();
     }
@@ -97,10 +99,32 @@ struct WeightGroups {
       p ^= 1;
     }
   }
+  // fragment j of unit u of the current group
   template <typename Idx>
-  __device__ __forceinline__ vecT get(const vecT *W, Idx idx, int j) const {
-    if constexpr (SHARED) return __builtin_bit_cast(vecT, buf[p][j][lane]);
-    else return W[(size_t)idx(j) * 64];
+  __device__ __forceinline__ vecT get(const vecT *W, Idx idx, int u, int j) const {
+    if constexpr (SHARED) return __builtin_bit_cast(vecT, buf[p][u * UF + j][lane]);
+    else return W[(size_t)idx(u, j) * 64];
+  }
+};
+
+// One unit's fragments as registers (SHARED: all LDS reads in flight together, the MFMAs behind
+// them wait for one fragment each) or, for the direct path, read where they are used.
+template <typename vecT, int UF, int UG, bool SHARED>
+struct UnitFrags {
+  vecT w[SHARED ? UF : 1];
+  template <typename Idx>
+  __device__ __forceinline__ void load(const WeightGroups<vecT, UF, UG, SHARED> &wg, const vecT *W, Idx idx, int u) {
+    if constexpr (SHARED) {
+#pragma unroll
+      for (int j = 0; j < UF; ++j) w[j] = wg.get(W, idx, u, j);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  template <typename Idx>
+  __device__ __forceinline__ vecT operator()(const WeightGroups<vecT, UF, UG, SHARED> &wg, const vecT *W, Idx idx,
+                                             int u, int j) const {
+    if constexpr (SHARED) return w[j];
+    else return wg.get(W, idx, u, j);
   }
 };
 
@@ -113,8 +137,11 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   using vec1 = typename Opd1::vec;
   constexpr int V1 = Opd1::V, SL1 = 2 * V1;
   constexpr bool SHARED = sizeof(T) == 2;
-  constexpr int GF = MB * QB;                               // fragments per group (H / 16 in bf16)
-  constexpr int SPG = GF / MB;                              // layer-1 slabs per group
+  constexpr int UF = MB * QB;                               // fragments per unit (H / 16 in bf16)
+  constexpr int SPU = UF / MB;                              // layer-1 slabs per unit
+  constexpr int UG = MB < 4 ? MB : 4;                       // units per group
+  using WG = WeightGroups<vec, UF, UG, SHARED>;
+  using UFr = UnitFrags<vec, UF, UG, SHARED>;
 
   const int64_t per_xcd = (a.n_blocks + 7) / 8;
   const int64_t tile = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -125,13 +152,13 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   const bool valid = row < a.n_rows;
   if (!valid) row = a.n_rows - 1;
   // every [rows, H] result leaves through a per-wave staging buffer, one 32-feature block at a time
-  __shared__ __align__(16) char stage_all[4][BlockStage<float>::BYTES];
-  __shared__ __align__(16) f32x4 wshared[SHARED ? 2 : 1][SHARED ? GF : 1][64];
-  char *stage = stage_all[wave];
+  extern __shared__ __align__(16) char smem[];
+  char *stage = smem + wave * BlockStage<float>::BYTES;
   const int64_t left = a.n_rows - row0;
   const int n_valid = left < 32 ? (left > 0 ? (int)left : 0) : 32;
-  WeightGroups<vec, GF, SHARED> wg;
-  wg.buf = reinterpret_cast<f32x4 (*)[GF][64]>(&wshared[0][0][0]); wg.wave = wave; wg.lane = lane;
+  WG wg;
+  wg.buf = reinterpret_cast<f32x4 (*)[WG::GF][64]>(smem + 4 * BlockStage<float>::BYTES);
+  wg.wave = wave; wg.lane = lane;
 
   // ---------------- z1^T = relu(W1^T x^T + b1), exactly as in the forward kernel
   f32x16 acc1[MB];
@@ -141,9 +168,9 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     for (int r = 0; r < 16; ++r) acc1[mb][r] = a.b1[32 * mb + acc_row(r, g)];
   int64_t src = 0, dst = 0;
   {
-    // layer 1's fragments are contiguous: group gi = fragments [gi * GF, gi * GF + GF) = SPG slabs
+    // layer 1's fragments are contiguous: unit u = fragments [u * UF, u * UF + UF) = SPU slabs
     const vec *W1 = (const vec *)a.W1s + lane;              // (vec and vec1 are both 16 bytes)
-    const int n_frag = a.nslab1 * MB, n_groups = (a.nslab1 + SPG - 1) / SPG;
+    const int n_frag = a.nslab1 * MB, n_units = (a.nslab1 + SPU - 1) / SPU;
     [[maybe_unused]] const T *pa = nullptr, *pb = nullptr;
     [[maybe_unused]] bool has_in = true;
     [[maybe_unused]] EmbedRow er;
@@ -159,44 +186,79 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     } else {
       er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
     }
-    wg.begin(W1, [&](int j) { return j; }, n_frag);
-    for (int gi = 0; gi < n_groups; ++gi) {
-      const int f0 = gi * GF;
-      if (gi + 1 < n_groups) wg.fetch(W1, [&](int j) { return f0 + GF + j; }, n_frag - f0 - GF);
+    // fragment j of unit u of the group that starts at unit u0
+    auto idx_from = [&](int u0) {
+      return [=](int u, int j) { const int f = (u0 + u) * UF + j; return f < n_frag ? f : -1; };
+    };
+    wg.begin(W1, idx_from(0));
+    int u0 = 0;
+    if constexpr (KIND != KIND_EMBED) {
+      // the 2 HS slabs of the two H-wide input parts: gathered rows, requested XQ slabs ahead
+      constexpr int NSH = 2 * HS, XQ = 8 < NSH ? 8 : NSH, NSU = NSH / SPU;
+      static_assert(NSU % UG == 0, "the H-wide parts fill whole groups");
+      auto load_slab = [&](int s) -> vec {
+        if (s < HS) return *(const vec *)(pa + s * SL);
+        return has_in ? *(const vec *)(pb + (s - HS) * SL) : Opd::zero();
+      };
+      vec xq[XQ];
 #pragma unroll
-      for (int j2 = 0; j2 < SPG; ++j2) {
-        const int s = gi * SPG + j2;
-        if (s < a.nslab1) {
-          if constexpr (KIND == KIND_EMBED) {
-            vec1 x;
+      for (int s = 0; s < XQ; ++s) xq[s] = load_slab(s);
 #pragma unroll
-            for (int j = 0; j < V1; ++j) {
-              const int k = s * SL1 + g * V1 + j;           // column of [edge-attr sum | one-hot | dense]
-              float v = 0.f;
-              if (k >= a.De && k < a.De + a.Tn) v = (k - a.De == er.op) ? 1.f : 0.f;
-              else if (k >= a.De + a.Tn && k < a.De + a.Tn + a.Dd) v = er.dense[k - a.De - a.Tn];
-              x[j] = Opd1::from_float(v);
-            }
-            if (s * SL1 + g * V1 < a.De) {                  // (De and V1 are multiples of 4)
-              const f32x4 e4 = embed_columns(er, a.edge_feat, a.De, 0, s * SL1 + g * V1);
+      for (int g0 = 0; g0 < NSU; g0 += UG) {
+        const auto idx = idx_from(g0);
+        if (g0 + UG < n_units) wg.fetch(W1, idx_from(g0 + UG));
 #pragma unroll
-              for (int j = 0; j < 4; ++j) x[j] = Opd1::from_float(e4[j]);
-            }
+        for (int u = 0; u < UG; ++u) {
+          UFr w;
+          w.load(wg, W1, idx, u);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-              Opd1::mma(__builtin_bit_cast(vec1, wg.get(W1, [&](int j) { return f0 + j; }, j2 * MB + mb)), x, acc1[mb]);
-          } else {
-            vec x;
-            if (s < HS) x = *(const vec *)(pa + s * SL);
-            else if (s < 2 * HS) x = has_in ? *(const vec *)(pb + (s - HS) * SL) : Opd::zero();
-            else x = tail_to_operand<T>(load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, s - 2 * HS, g));
+          for (int j2 = 0; j2 < SPU; ++j2) {
+            const int sl = (g0 + u) * SPU + j2;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-              Opd::mma(wg.get(W1, [&](int j) { return f0 + j; }, j2 * MB + mb), x, acc1[mb]);
+            for (int mb = 0; mb < MB; ++mb) Opd::mma(w(wg, W1, idx, u, j2 * MB + mb), xq[sl % XQ], acc1[mb]);
+            if (sl + XQ < NSH) xq[sl % XQ] = load_slab(sl + XQ);
           }
         }
+        wg.next(g0 + UG < n_units);
       }
-      wg.next(gi + 1 < n_groups);
+      u0 = NSU;
+    }
+    // the remaining slabs (EDGE: edge attributes; EMBED: all of them)
+    for (; u0 < n_units; u0 += UG) {
+      const auto idx = idx_from(u0);
+      if (u0 + UG < n_units) wg.fetch(W1, idx_from(u0 + UG));
+#pragma unroll
+      for (int u = 0; u < UG; ++u)
+#pragma unroll
+        for (int j2 = 0; j2 < SPU; ++j2) {
+          const int sl = (u0 + u) * SPU + j2;
+          if (sl < a.nslab1) {
+            if constexpr (KIND == KIND_EMBED) {
+              vec1 x;
+#pragma unroll
+              for (int j = 0; j < V1; ++j) {
+                const int k = sl * SL1 + g * V1 + j;        // column of [edge-attr sum | one-hot | dense]
+                float v = 0.f;
+                if (k >= a.De && k < a.De + a.Tn) v = (k - a.De == er.op) ? 1.f : 0.f;
+                else if (k >= a.De + a.Tn && k < a.De + a.Tn + a.Dd) v = er.dense[k - a.De - a.Tn];
+                x[j] = Opd1::from_float(v);
+              }
+              if (sl * SL1 + g * V1 < a.De) {               // (De and V1 are multiples of 4)
+                const f32x4 e4 = embed_columns(er, a.edge_feat, a.De, 0, sl * SL1 + g * V1);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x[j] = Opd1::from_float(e4[j]);
+              }
+#pragma unroll
+              for (int mb = 0; mb < MB; ++mb)
+                Opd1::mma(__builtin_bit_cast(vec1, wg.get(W1, idx, u, j2 * MB + mb)), x, acc1[mb]);
+            } else {
+              const vec x = tail_to_operand<T>(load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, sl - 2 * HS, g));
+#pragma unroll
+              for (int mb = 0; mb < MB; ++mb) Opd::mma(wg.get(W1, idx, u, j2 * MB + mb), x, acc1[mb]);
+            }
+          }
+        }
+      wg.next(u0 + UG < n_units);
     }
   }
 #pragma unroll
@@ -211,61 +273,74 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   {
     const float *dyrow = a.dy + (size_t)(KIND == KIND_EDGE ? dst : row) * H;
     [[maybe_unused]] const vec *W2 = (const vec *)a.W2s + lane;
-    // EDGE: y^T block nb needs W2's fragments ((mb, q), nb) for all (mb, q): one group per nb
-    if constexpr (KIND == KIND_EDGE) wg.begin(W2, [&](int j) { return j * MB; }, GF);
-#pragma unroll
-    for (int nb = 0; nb < MB; ++nb) {
-      f32x16 yv;
-      if constexpr (KIND == KIND_EDGE) {
-        if (nb + 1 < MB) wg.fetch(W2, [&](int j) { return j * MB + nb + 1; }, GF);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) yv[r] = a.b2[32 * nb + acc_row(r, g)];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int q = 0; q < QB; ++q)
-            Opd::mma(wg.get(W2, [&](int j) { return j * MB + nb; }, mb * QB + q), acc_slab<T>(acc1[mb], q), yv);
-        wg.next(nb + 1 < MB);
-      } else {
-        const T *yrow = (const T *)a.y + (size_t)row * H + 32 * nb + 4 * g;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float v[4];
-          load4<T>(yrow + 8 * q, v);
-          yv[4 * q] = v[0]; yv[4 * q + 1] = v[1]; yv[4 * q + 2] = v[2]; yv[4 * q + 3] = v[3];
-        }
-      }
-      f32x16 d;
+    [[maybe_unused]] const T *yrow = KIND == KIND_EDGE ? nullptr : (const T *)a.y + (size_t)row * H + 4 * g;
+    // dy (and, where the forward stored it, y) of block nb + 1 is requested while block nb is
+    // worked on: the fences of the staged stores keep the compiler from doing that itself
+    auto load_dy = [&](int nb, f32x16 &d, f32x16 &yv) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float v[4];
         load4<float>(dyrow + 32 * nb + 8 * q + 4 * g, v);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) d[4 * q + j] = yv[4 * q + j] > 0.f ? v[j] : 0.f;
+        d[4 * q] = v[0]; d[4 * q + 1] = v[1]; d[4 * q + 2] = v[2]; d[4 * q + 3] = v[3];
+        if constexpr (KIND != KIND_EDGE) {
+          load4<T>(yrow + 32 * nb + 8 * q, v);
+          yv[4 * q] = v[0]; yv[4 * q + 1] = v[1]; yv[4 * q + 2] = v[2]; yv[4 * q + 3] = v[3];
+        }
       }
+    };
+    f32x16 dyc, yc, dyn, yn;
+    load_dy(0, dyc, yc);
+    // EDGE: y^T block nb needs W2's fragments ((mb, q), nb) for all (mb, q): unit nb
+    auto idx_from = [&](int u0) { return [=](int u, int j) { return j * MB + u0 + u; }; };
+    if constexpr (KIND == KIND_EDGE) wg.begin(W2, idx_from(0));
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) {
+      if (nb + 1 < MB) load_dy(nb + 1, dyn, yn);
+      if constexpr (KIND == KIND_EDGE) {
+        const int g0 = nb / UG * UG, u = nb % UG;
+        const auto idx = idx_from(g0);
+        if (u == 0 && g0 + UG < MB) wg.fetch(W2, idx_from(g0 + UG));
+        UFr w;
+        w.load(wg, W2, idx, u);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) yc[r] = a.b2[32 * nb + acc_row(r, g)];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int q = 0; q < QB; ++q) Opd::mma(w(wg, W2, idx, u, mb * QB + q), acc_slab<T>(acc1[mb], q), yc);
+        if (u == UG - 1) wg.next(g0 + UG < MB);
+      }
+      f32x16 d;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) d[r] = yc[r] > 0.f ? dyc[r] : 0.f;
       store_block_via_lds<T, H>((T *)a.dz2, row0, n_valid, nb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz2s[nb][q] = acc_slab<T>(d, q);
+      if (nb + 1 < MB) { dyc = dyn; yc = yn; }
     }
   }
 
-  // ---------------- dz1^T = (W2 dz2^T) * [z1^T > 0]: one group of W2^T fragments per block mb
+  // ---------------- dz1^T = (W2 dz2^T) * [z1^T > 0]: unit mb = the W2^T fragments of block mb
   vec dz1s[MB][QB];
   {
     const vec *W2b = (const vec *)a.W2bt + lane;
-    wg.begin(W2b, [&](int j) { return j * MB; }, GF);
+    auto idx_from = [&](int u0) { return [=](int u, int j) { return j * MB + u0 + u; }; };
+    wg.begin(W2b, idx_from(0));
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      if (mb + 1 < MB) wg.fetch(W2b, [&](int j) { return j * MB + mb + 1; }, GF);
+      const int g0 = mb / UG * UG, u = mb % UG;
+      const auto idx = idx_from(g0);
+      if (u == 0 && g0 + UG < MB) wg.fetch(W2b, idx_from(g0 + UG));
+      UFr w;
+      w.load(wg, W2b, idx, u);
       f32x16 d;
 #pragma unroll
       for (int r = 0; r < 16; ++r) d[r] = 0.f;
 #pragma unroll
       for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
-        for (int q = 0; q < QB; ++q)
-          Opd::mma(wg.get(W2b, [&](int j) { return j * MB + mb; }, nb * QB + q), dz2s[nb][q], d);
-      wg.next(mb + 1 < MB);
+        for (int q = 0; q < QB; ++q) Opd::mma(w(wg, W2b, idx, u, nb * QB + q), dz2s[nb][q], d);
+      if (u == UG - 1) wg.next(g0 + UG < MB);
 #pragma unroll
       for (int r = 0; r < 16; ++r) d[r] = acc1[mb][r] > 0.f ? d[r] : 0.f;
       store_block_via_lds<T, H>((T *)a.dz1, row0, n_valid, mb, lane, d, stage);
@@ -274,24 +349,28 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     }
   }
 
-  // ---------------- dx^T = W1 dz1^T over the first 2H input columns (h parts only): one group
-  // of W1^T fragments per 32-column block kb of [part a | part b]
+  // ---------------- dx^T = W1 dz1^T over the first 2H input columns (h parts only): unit kb =
+  // the W1^T fragments of the 32-column block kb of [part a | part b]
   if constexpr (KIND != KIND_EMBED) {
     const vec *W1b = (const vec *)a.W1bt + lane;
     constexpr int KB = 2 * MB;
-    wg.begin(W1b, [&](int j) { return j * KB; }, GF);
+    auto idx_from = [&](int u0) { return [=](int u, int j) { return j * KB + u0 + u; }; };
+    wg.begin(W1b, idx_from(0));
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
-      if (kb + 1 < KB) wg.fetch(W1b, [&](int j) { return j * KB + kb + 1; }, GF);
+      const int g0 = kb / UG * UG, u = kb % UG;
+      const auto idx = idx_from(g0);
+      if (u == 0 && g0 + UG < KB) wg.fetch(W1b, idx_from(g0 + UG));
+      UFr w;
+      w.load(wg, W1b, idx, u);
       f32x16 d;
 #pragma unroll
       for (int r = 0; r < 16; ++r) d[r] = 0.f;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int q = 0; q < QB; ++q)
-          Opd::mma(wg.get(W1b, [&](int j) { return j * KB + kb; }, mb * QB + q), dz1s[mb][q], d);
-      wg.next(kb + 1 < KB);
+        for (int q = 0; q < QB; ++q) Opd::mma(w(wg, W1b, idx, u, mb * QB + q), dz1s[mb][q], d);
+      if (u == UG - 1) wg.next(g0 + UG < KB);
       if constexpr (KIND == KIND_EDGE) {
         T *o = (T *)(kb < MB ? a.dx_a : a.dx_b);
         store_block_via_lds<T, H>(o, row0, n_valid, kb % MB, lane, d, stage);
@@ -301,4 +380,11 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
       }
     }
   }
+}
+
+// dynamic LDS of mlp2_bwd_kernel: four staging buffers, then (bf16) two groups of fragments
+template <typename T, int H>
+constexpr size_t mlp2_bwd_lds_bytes() {
+  constexpr int MB = H / 32, QB = 32 / (2 * Operand<T>::V), UG = MB < 4 ? MB : 4;
+  return 4 * (size_t)BlockStage<float>::BYTES + (sizeof(T) == 2 ? 2 * (size_t)(MB * QB * UG) * 1024 : 0);
 }

@@ -637,15 +637,27 @@ __global__ void export_rows_kernel(const T *src, const int32_t *in_ptr, int64_t 
 }
 
 
+template <typename T1, typename T, int H, int KIND>
+int launch_mlp2_bwd_k(xrl_ctx *c, const Mlp2BwdArgs &a) {
+  constexpr size_t lds = mlp2_bwd_lds_bytes<T, H>();
+  auto kern = mlp2_bwd_kernel<T1, T, H, KIND>;
+  static bool attr_set = false;          // one attribute per kernel instantiation
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) / 8) * 8);
+  kern<<<dim3(grid), dim3(256), lds, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
 template <typename T, int H>
 int launch_mlp2_bwd_h(xrl_ctx *c, int kind, const Mlp2BwdArgs &a) {
   if (a.n_rows <= 0) return XRL_OK;
-  const unsigned grid = (unsigned)(((a.n_blocks + 7) / 8) * 8);
-  if (kind == KIND_EMBED) mlp2_bwd_kernel<float, T, H, KIND_EMBED><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
-  else if (kind == KIND_EDGE) mlp2_bwd_kernel<T, T, H, KIND_EDGE><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
-  else mlp2_bwd_kernel<T, T, H, KIND_NODE><<<dim3(grid), dim3(256), 0, c->stream>>>(a);
-  HIP_TRY(hipGetLastError());
-  return XRL_OK;
+  if (kind == KIND_EMBED) return launch_mlp2_bwd_k<float, T, H, KIND_EMBED>(c, a);
+  if (kind == KIND_EDGE) return launch_mlp2_bwd_k<T, T, H, KIND_EDGE>(c, a);
+  return launch_mlp2_bwd_k<T, T, H, KIND_NODE>(c, a);
 }
 
 template <typename T>
