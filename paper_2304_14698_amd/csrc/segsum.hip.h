@@ -1,7 +1,7 @@
 // Deterministic segment sum over consecutive rows: out[s, :] = sum of rows [ptr[s], ptr[s+1]).
 // Used for the receiver-side sum of incoming edge attributes (node-update layer, Section 3.4),
-// the per-graph sum of node states (global-update layer) and, in the backward pass, the sums over
-// a receiver's in-edges and over a sender's out-edges (through a row permutation).
+// the per-graph sum of node states (global-update layer); the backward pass gathers per node
+// instead (node_grad_gather_kernel at the end of this file).
 //
 // Rows are cut into fixed sub-tiles of RT rows; D / VEC lanes own one sub-tile, each lane a
 // 16-byte column slice. A lane walks its sub-tile in row order, so every sum has a fixed order
@@ -36,16 +36,11 @@ __device__ __forceinline__ void store_out<float>(float *p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_out<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)v; }
 
-// Output policy of the segment-sum kernels: plain store (empty segments get zeros) or
-// accumulate (out[s] += sum; each segment has exactly one writer, so the order stays fixed).
+// Output policy of the segment-sum kernels: plain store (empty segments get zeros).
 struct PutStore {
   template <typename TO>
   static __device__ __forceinline__ void put(TO *p, float v) { store_out<TO>(p, v); }
   static constexpr bool kZeroEmpty = true;
-};
-struct PutAdd {
-  static __device__ __forceinline__ void put(float *p, float v) { *p += v; }
-  static constexpr bool kZeroEmpty = false;
 };
 
 // largest s in [0, n_seg) with ptr[s] <= row < ptr[s+1]; requires 0 <= row < ptr[n_seg]
@@ -199,4 +194,42 @@ __global__ __launch_bounds__(256) void edge_tile_fixup(const int32_t *tile_ptr, 
     sum += *(const f32x4 *)(carry + ((size_t)t * 2) * D + c);
 #pragma unroll
   for (int j = 0; j < 4; ++j) store_out<TOut>(out + (size_t)seg * D + c + j, sum[j]);
+}
+
+// Backward of the message gathers, per node: dh[n] += sum over n's in-edges e of d_recv[e] + sum
+// over n's out-edges (edge ids out_pos[k], k in [out_ptr[n], out_ptr[n+1])) of d_send[e]. One
+// group of D / VEC lanes per node, each lane a 16-byte column slice of the edge rows; the edges
+// are taken in index order, so the result is run-to-run identical. One pass over dh instead of
+// one per direction.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, const T *d_send,
+                                                               const int32_t *in_ptr, const int32_t *out_ptr,
+                                                               const int32_t *out_pos, int64_t n_nodes, int D,
+                                                               float *dh) {
+  const int lpr = D / VEC;
+  const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t n = gt / lpr;
+  if (n >= n_nodes) return;
+  const int c = (int)(gt - n * lpr) * VEC;
+  const int e0 = in_ptr[n], e1 = in_ptr[n + 1], k0 = out_ptr[n], k1 = out_ptr[n + 1];
+  float *o = dh + (size_t)n * D + c;
+  float acc[VEC], v[VEC];
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q) {
+    const f32x4 x = *(const f32x4 *)(o + 4 * q);
+    acc[4 * q] = x[0]; acc[4 * q + 1] = x[1]; acc[4 * q + 2] = x[2]; acc[4 * q + 3] = x[3];
+  }
+  for (int e = e0; e < e1; ++e) {
+    RowVec<T, VEC>::load(d_recv + (size_t)e * D + c, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+  }
+  for (int k = k0; k < k1; ++k) {
+    RowVec<T, VEC>::load(d_send + (size_t)out_pos[k] * D + c, v);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+  }
+#pragma unroll
+  for (int q = 0; q < VEC / 4; ++q)
+    *(f32x4 *)(o + 4 * q) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
 }

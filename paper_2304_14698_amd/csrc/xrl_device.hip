@@ -400,27 +400,6 @@ int launch_segsum(xrl_ctx *c, const void *vals, const int32_t *perm, const int32
   return launch_segsum_rt<TIn, TOut, VEC, 16>(c, vals, perm, ptr, row_seg, n_rows, n_seg, D, out, carry);
 }
 
-// out[s, :] += segment sums (fp32 out, RT = 16); perm as in SegsumArgs
-template <typename TIn, int VEC>
-int launch_segsum_add(xrl_ctx *c, const void *vals, const int32_t *perm, const int32_t *ptr,
-                      const int32_t *row_seg, int64_t n_rows, int64_t n_seg, int D, float *out, float *carry,
-                      const int32_t *vals_seg = nullptr) {
-  constexpr int RT = 16;
-  if (n_seg == 0 || n_rows == 0) return XRL_OK;
-  SegsumArgs a;
-  a.vals = vals; a.perm = perm; a.ptr = ptr; a.n_rows = n_rows; a.n_seg = n_seg;
-  a.row_seg = vals_seg ? vals_seg : (perm ? nullptr : row_seg);
-  a.D = D; a.RT = RT; a.out = out; a.carry = carry;
-  const int64_t nsub = (n_rows + RT - 1) / RT;
-  const int64_t threads = nsub * (D / VEC);
-  segsum_kernel<TIn, float, VEC, RT, PutAdd><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(a);
-  const int64_t fthreads = nsub * (D / 4);
-  segsum_fixup<float, PutAdd><<<dim3((unsigned)((fthreads + 255) / 256)), dim3(256), 0, c->stream>>>(
-      ptr, row_seg, n_rows, n_seg, D, RT, carry, out);
-  HIP_TRY(hipGetLastError());
-  return XRL_OK;
-}
-
 size_t segsum_carry_floats(int64_t n_rows, int D) { return (size_t)((n_rows + 3) / 4) * 2 * D; }
 
 template <typename T, int H>
@@ -814,11 +793,10 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
   for (int i = 0; i < 3; ++i) acc((size_t)M * H * sizeof(T));      // z1, dz1, dz2
   for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
-  for (int i = 0; i < 3; ++i) acc((size_t)N * H * 4);              // dh (two buffers), dagg
+  for (int i = 0; i < 2; ++i) acc((size_t)N * H * 4);              // dh (two buffers)
+  acc((size_t)N * H * sizeof(T));                                  // dagg
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
-  const size_t carry_floats = segsum_carry_floats(E, H);
-  acc(carry_floats * 4);
   acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
   int rc = ensure_bws(c, need);
   if (rc) return rc;
@@ -826,9 +804,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   T *z1 = bump.take<T>((size_t)M * H), *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
   T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)E * H);
   float *dhA = bump.take<float>((size_t)N * H), *dhB = bump.take<float>((size_t)N * H);
-  float *dagg = bump.take<float>((size_t)N * H);
+  T *dagg = bump.take<T>((size_t)N * H);
   float *partial = bump.take<float>(part);
-  float *carry = bump.take<float>(carry_floats);
   float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
   float *rdx = bump.take<float>((size_t)G * (H + Dg));
 
@@ -878,8 +855,9 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r]))) return rc;
     // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
     if (E > 0) {
-      if ((rc = launch_segsum_add<T, PV>(c, ddst, nullptr, d.in_ptr, d.in_dst, E, N, H, dhB, carry))) return rc;
-      if ((rc = launch_segsum_add<T, PV>(c, dsrc, d.out_pos, d.out_ptr, nullptr, E, N, H, dhB, carry, d.in_src))) return rc;
+      const int64_t threads = N * (H / PV);
+      node_grad_gather_kernel<T, PV><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(
+          ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB);
     }
     std::swap(dhA, dhB);
   }
