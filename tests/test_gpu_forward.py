@@ -291,6 +291,56 @@ def test_all_candidates_masked_and_single_slot(xrl):
     assert_close(pv["value"].cpu().numpy(), rp["value"], "fp32", "value")
 
 
+@pytest.mark.parametrize("hidden,n_states,n_cand", [(64, 1, 3), (128, 7, 40), (256, 3, 130)])
+def test_heads_on_given_embeddings_repeated(xrl, hidden, n_states, n_cand):
+    """Policy and value heads alone, on random embeddings (the oracle gets the same ones), called
+    three times on one batch: the single-launch kernel keeps per-state counters between calls, so
+    every call must give bit-identical results; states of 1 to n_cand + 1 slots, random masks."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(17))
+    model, _ = synth.make_config(1)
+    model.update(hidden=hidden, rounds=1)
+    slots = np.concatenate([[1], rng.integers(2, n_cand + 2, n_states - 1)]).astype(np.int64)[:n_states]
+    G = int(slots.sum())
+    sgp = np.concatenate([[0], np.cumsum(slots)]).astype(np.int32)
+    mask = (rng.random(G) > 0.3).astype(np.uint8)
+    mask[sgp[:-1]] = 1                                        # at least one valid slot per state
+    Dd, De = model["n_node_dense"], model["d_edge"]
+    state = dict(n_states=n_states, state_graph_ptr=sgp,
+                 graph_node_ptr=np.arange(G + 1, dtype=np.int32),        # one node per graph, no edges
+                 graph_edge_ptr=np.zeros(G + 1, np.int32),
+                 node_op=rng.integers(0, model["n_op_types"], G).astype(np.int32),
+                 node_dense=rng.integers(0, 13, (G, Dd)).astype(np.float32),
+                 edge_src=np.zeros(0, np.int32), edge_dst=np.zeros(0, np.int32),
+                 edge_feat=np.zeros((0, De), np.float32),
+                 graph_global=rng.standard_normal((G, model["d_global"])).astype(np.float32),
+                 slot_mask=mask)
+    w = weights_for(model)
+    emb = rng.standard_normal((G, hidden)).astype(np.float32)
+    rp = O.policy_value(oracle_model(model), w, emb.astype(np.float64), state)
+    enc = xrl.Encoder(model, w)
+    batch = enc.pack(state)
+    d_emb = torch.from_numpy(emb).cuda()
+    runs = []
+    for _ in range(3):
+        pv = enc.policy_value(batch, d_emb)
+        torch.cuda.synchronize()
+        runs.append({k: v.clone() for k, v in pv.items()})
+    for k in runs[0]:
+        assert torch.equal(runs[0][k], runs[1][k]) and torch.equal(runs[0][k], runs[2][k]), f"{k}: calls differ"
+    pv = runs[0]
+    m = mask.astype(bool)
+    scale = float(np.abs(rp["logit"]).max())
+    assert_close(pv["logit"].cpu().numpy(), rp["logit"], "fp32", "logit")
+    assert_close(pv["logp"].cpu().numpy()[m], rp["logp"][m], "fp32", "logp", scale=scale)
+    assert np.all(np.isneginf(pv["logp"].cpu().numpy()[~m]))
+    assert_close(pv["value"].cpu().numpy(), rp["value"], "fp32", "value", scale=scale)
+    assert_close(pv["entropy"].cpu().numpy(), rp["entropy"], "fp32", "entropy")
+    np.testing.assert_array_equal(pv["action"].cpu().numpy(), rp["action"])
+    batch.free()
+    enc.close()
+
+
 def test_segment_sum_entry_point(xrl):
     import torch
     model, _ = synth.make_config(1)
