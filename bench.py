@@ -150,7 +150,10 @@ def main():
     for _ in range(args.steps):
         step()
     kern = {}
-    for k in ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads"):
+    names = ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads")
+    if backward:
+        names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad", "grad_gather")
+    for k in names:
         tot, n = enc.read_timing(k)
         kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)
     enc.set_timing(False)

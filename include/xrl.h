@@ -209,10 +209,14 @@ int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32
                        float *d_out);
 
 /* Per-kernel timing for roofline measurement. While enabled, every launch group of the forward
- * path is bracketed by HIP events on the ctx stream. xrl_read_timing synchronises the stream,
- * returns the summed duration and launch count recorded since the last read for `kernel` in
- * {"embed", "edge", "edge_fixup", "node", "pool", "readout", "heads"} (the steps of
- * Section 3.4 / 3.3.2 in execution order) and forgets them. Errors: NULL, INDEX, HIP. */
+ * path and of the encoder's backward is bracketed by HIP events on the ctx stream.
+ * xrl_read_timing synchronises the stream, returns the summed duration and launch count
+ * recorded since the last read for `kernel` and forgets them. Forward: {"embed", "edge",
+ * "edge_fixup", "node", "pool", "readout", "heads"} (the steps of Section 3.4 / 3.3.2 in
+ * execution order; "gat_linear", "gat_aggregate" with XRL_ROUND_GAT). Backward (Section 3.3.4):
+ * {"bwd_edge", "bwd_node", "bwd_embed"} = gradients through the fused MLPs, "wgrad" = both
+ * layers' weight gradients of one MLP with their reductions, "grad_gather" = per-node sum of the
+ * per-edge gradients. Errors: NULL, INDEX, HIP. */
 int xrl_set_timing(xrl_ctx *ctx, int enabled);
 int xrl_read_timing(xrl_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 

@@ -92,9 +92,10 @@ struct EncMlp {           // device pointers of one encoder MLP
 
 // kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
 enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_GAT_LINEAR,
-       TK_GAT_AGGREGATE, TK_COUNT };
+       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_COUNT };
 static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
-                                                  "heads", "gat_linear", "gat_aggregate"};
+                                                  "heads", "gat_linear", "gat_aggregate", "bwd_edge", "bwd_node",
+                                                  "bwd_embed", "wgrad", "grad_gather"};
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
 
@@ -833,6 +834,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   };
   auto wgrads = [&](int kind, int64_t rows, int Ka, const MlpRef &r) -> int {
     wa.n_rows = rows; wa.Ka = Ka; wa.dZ = dz1; wa.A = nullptr;
+    Timed t(c, TK_WGRAD);                                  // both layers' weight gradients and their reductions
     int rc2 = launch_wgrad<T>(c, kind, wa, dweights + r.w[0], dweights + r.b[0]);
     if (rc2) return rc2;
     wa.Ka = H; wa.dZ = dz2; wa.A = z1;
@@ -844,17 +846,20 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     set_w(c->node[r]);
     a.n_rows = N; a.h = c->h[r]; a.agg = c->agg[r + 1]; a.y = c->h[r + 1]; a.dy = dhA;
     a.dx_a = dhB; a.dx_b = dagg;
-    if ((rc = launch_mlp2_bwd<T>(c, KIND_NODE, a))) return rc;
+    { Timed t(c, TK_BWD_NODE); rc = launch_mlp2_bwd<T>(c, KIND_NODE, a); }
+    if (rc) return rc;
     wa.h = c->h[r]; wa.agg = c->agg[r + 1];
     if ((rc = wgrads(WG_NODE, N, 2 * H, c->L.node[r]))) return rc;
     // edge MLP of round r+1: upstream = dagg gathered by receiver
     set_w(c->edge[r]);
     a.n_rows = E; a.h = c->h[r]; a.agg = nullptr; a.y = nullptr; a.dy = dagg;
     a.dx_a = dsrc; a.dx_b = ddst;
-    if ((rc = launch_mlp2_bwd<T>(c, KIND_EDGE, a))) return rc;
+    { Timed t(c, TK_BWD_EDGE); rc = launch_mlp2_bwd<T>(c, KIND_EDGE, a); }
+    if (rc) return rc;
     if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r]))) return rc;
     // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
     if (E > 0) {
+      Timed t(c, TK_GRAD_GATHER);
       const int64_t threads = N * (H / PV);
       node_grad_gather_kernel<T, PV><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(
           ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB);
@@ -864,7 +869,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   // ---- node-update layer backward (weights only: its inputs are data)
   set_w(c->embed);
   a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
-  if ((rc = launch_mlp2_bwd<T>(c, KIND_EMBED, a))) return rc;
+  { Timed t(c, TK_BWD_EMBED); rc = launch_mlp2_bwd<T>(c, KIND_EMBED, a); }
+  if (rc) return rc;
   if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed))) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
