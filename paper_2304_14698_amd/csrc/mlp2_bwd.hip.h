@@ -18,8 +18,10 @@
 // read their fragments straight from L2.
 // The kernel writes z1, dz1, dz2 as [rows, H] for the weight-gradient kernel, and dx:
 //   EDGE: per-edge gradients w.r.t. h_sender and h_receiver ([E, H] each; summed per node later),
-//   NODE: d/dh [N, H] fp32 and d/dagg [N, H] in the operand type (its only reader, the EDGE
-//   instantiation, turns it into an operand of that type anyway),   EMBED: nothing (its inputs are data).
+//   NODE: d/dh and d/dagg [N, H],   EMBED: nothing (its inputs are data).
+// Gradients w.r.t. node states travel between kernels in the operand type: their only readers
+// are this kernel's instantiations, which turn them into operands of that type anyway, and the
+// per-node gather, which sums in fp32.
 #pragma once
 #include <type_traits>
 #include "mlp2.hip.h"
@@ -32,7 +34,7 @@ struct Mlp2BwdArgs {
   int nslab1;
   const void *h, *agg;       // forward inputs, operand type
   const void *y;             // saved forward output [N, H] operand type      (NODE, EMBED)
-  const void *dy;            // upstream gradient [N, H]: fp32; EDGE: operand type, indexed by receiver
+  const void *dy;            // upstream gradient [N, H], operand type (EDGE: indexed by receiver)
   const int32_t *in_ptr, *in_src, *in_dst;
   const float *edge_feat;
   const int32_t *node_op;
@@ -40,7 +42,7 @@ struct Mlp2BwdArgs {
   int De, Tn, Dd;
   void *z1, *dz1, *dz2;      // [rows, H] operand type
   void *dx_a, *dx_b;         // EDGE: d h_sender, d h_receiver [E, H] operand type;
-                             // NODE: d h [N, H] fp32, d agg [N, H] operand type
+                             // NODE: d h, d agg [N, H] operand type
 };
 
 // Accumulator tile (features x rows) -> the 32 / (2V) operand slabs of its 32 features.
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   // ---------------- dz2^T = dy^T * [y^T > 0], stored and kept as operand slabs
   vec dz2s[MB][QB];
   {
-    using DY = std::conditional_t<KIND == KIND_EDGE, T, float>;
+    using DY = T;
     const DY *dyrow = (const DY *)a.dy + (size_t)(KIND == KIND_EDGE ? dst : row) * H;
     [[maybe_unused]] const vec *W2 = (const vec *)a.W2s + lane;
     [[maybe_unused]] const T *yrow = KIND == KIND_EDGE ? nullptr : (const T *)a.y + (size_t)row * H + 4 * g;
@@ -378,8 +380,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
         T *o = (T *)(kb < MB ? a.dx_a : a.dx_b);
         store_block_via_lds<T, H>(o, row0, n_valid, kb % MB, lane, d, stage);
       } else {
-        if (kb < MB) store_block_via_lds<float, H>((float *)a.dx_a, row0, n_valid, kb, lane, d, stage);
-        else store_block_via_lds<T, H>((T *)a.dx_b, row0, n_valid, kb - MB, lane, d, stage);
+        store_block_via_lds<T, H>((T *)(kb < MB ? a.dx_a : a.dx_b), row0, n_valid, kb % MB, lane, d, stage);
       }
     }
   }

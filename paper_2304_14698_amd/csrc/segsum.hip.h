@@ -198,27 +198,23 @@ __global__ __launch_bounds__(256) void edge_tile_fixup(const int32_t *tile_ptr, 
 
 // Backward of the message gathers, per node: dh[n] += sum over n's in-edges e of d_recv[e] + sum
 // over n's out-edges (edge ids out_pos[k], k in [out_ptr[n], out_ptr[n+1])) of d_send[e]. One
-// group of D / VEC lanes per node, each lane a 16-byte column slice of the edge rows; the edges
-// are taken in index order, so the result is run-to-run identical. One pass over dh instead of
+// group of D / VEC lanes per node, each lane a 16-byte column slice; the edges are taken in index
+// order and summed in fp32, so the result is run-to-run identical. One pass over dh instead of
 // one per direction.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, const T *d_send,
                                                                const int32_t *in_ptr, const int32_t *out_ptr,
                                                                const int32_t *out_pos, int64_t n_nodes, int D,
-                                                               float *dh) {
+                                                               T *dh) {
   const int lpr = D / VEC;
   const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n = gt / lpr;
   if (n >= n_nodes) return;
   const int c = (int)(gt - n * lpr) * VEC;
   const int e0 = in_ptr[n], e1 = in_ptr[n + 1], k0 = out_ptr[n], k1 = out_ptr[n + 1];
-  float *o = dh + (size_t)n * D + c;
+  T *o = dh + (size_t)n * D + c;
   float acc[VEC], v[VEC];
-#pragma unroll
-  for (int q = 0; q < VEC / 4; ++q) {
-    const f32x4 x = *(const f32x4 *)(o + 4 * q);
-    acc[4 * q] = x[0]; acc[4 * q + 1] = x[1]; acc[4 * q + 2] = x[2]; acc[4 * q + 3] = x[3];
-  }
+  RowVec<T, VEC>::load(o, acc);
   for (int e = e0; e < e1; ++e) {
     RowVec<T, VEC>::load(d_recv + (size_t)e * D + c, v);
 #pragma unroll
@@ -230,6 +226,5 @@ __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, 
     for (int j = 0; j < VEC; ++j) acc[j] += v[j];
   }
 #pragma unroll
-  for (int q = 0; q < VEC / 4; ++q)
-    *(f32x4 *)(o + 4 * q) = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+  for (int q = 0; q < VEC / 4; ++q) store4<T>(o + 4 * q, acc + 4 * q);
 }

@@ -767,9 +767,11 @@ __global__ void demb_combine_kernel(float *demb, const float *dzs, const float *
   }
 }
 
-// dh[i, :] = dx[graph(i), :H] (divided by the graph's node count for the mean readout)
+// dh[i, :] = dx[graph(i), :H] (divided by the graph's node count for the mean readout), stored in
+// the operand type like every later dh
+template <typename T>
 __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *node_graph,
-                                       const int32_t *graph_node_ptr, int mean, int64_t N, int H, float *dh) {
+                                       const int32_t *graph_node_ptr, int mean, int64_t N, int H, T *dh) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N * H) return;
   const int64_t n = i / H;
@@ -779,7 +781,7 @@ __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *
     const int cnt = graph_node_ptr[gph + 1] - graph_node_ptr[gph];
     v /= (float)(cnt > 1 ? cnt : 1);
   }
-  dh[i] = v;
+  dh[i] = (T)v;
 }
 
 template <typename T>
@@ -794,8 +796,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
   for (int i = 0; i < 3; ++i) acc((size_t)M * H * sizeof(T));      // z1, dz1, dz2
   for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
-  for (int i = 0; i < 2; ++i) acc((size_t)N * H * 4);              // dh (two buffers)
-  acc((size_t)N * H * sizeof(T));                                  // dagg
+  for (int i = 0; i < 3; ++i) acc((size_t)N * H * sizeof(T));      // dh (two buffers), dagg
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
   acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
@@ -804,7 +805,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   Bump bump{c->bws};
   T *z1 = bump.take<T>((size_t)M * H), *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
   T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)E * H);
-  float *dhA = bump.take<float>((size_t)N * H), *dhB = bump.take<float>((size_t)N * H);
+  T *dhA = bump.take<T>((size_t)N * H), *dhB = bump.take<T>((size_t)N * H);
   T *dagg = bump.take<T>((size_t)N * H);
   float *partial = bump.take<float>(part);
   float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
@@ -815,7 +816,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   if ((rc = launch_rowmlp_bwd(c, c->L.readout, true, ract, d_demb, G, rdz, rdx))) return rc;
   if ((rc = launch_small_wgrads(c, c->L.readout, c->pool, H, d.graph_global, Dg, ract, rdz, G, dweights))) return rc;
   if (N > 0)
-    broadcast_dpool_kernel<<<dim3((unsigned)((N * H + 255) / 256)), dim3(256), 0, c->stream>>>(
+    broadcast_dpool_kernel<T><<<dim3((unsigned)((N * H + 255) / 256)), dim3(256), 0, c->stream>>>(
         rdx, H + Dg, d.node_graph, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, N, H, dhA);
 
   Mlp2BwdArgs a;
