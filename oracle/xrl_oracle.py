@@ -294,6 +294,42 @@ def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound=N
     return demb, flatten(model, grads)
 
 
+def _gat_round_backward(W, r, h, c, dh_out, src, dst, grads, bound=None):
+    """Reverse of one graph-attention round (see encode_graph): h' = relu(pre),
+    pre_i = sum_k alpha_k z[src_k] + alpha_i z_i with alpha the softmax over i's in-edges and its
+    self edge of leaky(a_src . z_sender + a_dst . z_i), z = h W. Returns d/dh and accumulates the
+    gradients of W, a_src, a_dst (and, into `bound`, their sums of absolute terms)."""
+    Wg, a_s, a_d = W[f"gat{r}.W"], W[f"gat{r}.a_src"], W[f"gat{r}.a_dst"]
+    z, alpha_e, alpha_s, pre = c["z"], c["alpha_e"], c["alpha_s"], c["pre"]
+    n = h.shape[0]
+    dpre = dh_out * (pre > 0.0)
+    # through the weighted sum: to the summed rows, and to the weights
+    dz = alpha_s[:, None] * dpre
+    np.add.at(dz, src, alpha_e[:, None] * dpre[dst])
+    dal_e = (dpre[dst] * z[src]).sum(axis=1)
+    dal_s = (dpre * z).sum(axis=1)
+    # softmax over each receiver's in-edges plus its self edge: ds = alpha (dalpha - sum alpha dalpha)
+    tot = alpha_s * dal_s + segment_sum(alpha_e * dal_e, dst, n)
+    ds_e = alpha_e * (dal_e - tot[dst])
+    ds_s = alpha_s * (dal_s - tot)
+    # leaky ReLU (slope 0.2) of u = a_src . z_sender + a_dst . z_receiver
+    u_e = z[src] @ a_s + z[dst] @ a_d
+    u_s = z @ a_s + z @ a_d
+    du_e = ds_e * np.where(u_e > 0.0, 1.0, 0.2)
+    du_s = ds_s * np.where(u_s > 0.0, 1.0, 0.2)
+    d_ss = du_s + segment_sum(du_e, src, n)          # d / d (a_src . z_n): self edge + out-edges
+    d_sd = du_s + segment_sum(du_e, dst, n)          # d / d (a_dst . z_n): self edge + in-edges
+    grads[f"gat{r}.a_src"] += d_ss @ z
+    grads[f"gat{r}.a_dst"] += d_sd @ z
+    dz += d_ss[:, None] * a_s[None, :] + d_sd[:, None] * a_d[None, :]
+    grads[f"gat{r}.W"] += h.T @ dz
+    if bound is not None:
+        bound[f"gat{r}.a_src"] += np.abs(d_ss) @ np.abs(z)
+        bound[f"gat{r}.a_dst"] += np.abs(d_sd) @ np.abs(z)
+        bound[f"gat{r}.W"] += np.abs(h).T @ np.abs(dz)
+    return dz @ Wg.T
+
+
 def encode_graph_backward(model, W, inter, demb_g, src, dst, grads, bound=None):
     """Accumulates into `grads` the gradient through one graph's encoder given d/d emb (and into
     `bound`, a dict like grads, the sums of absolute terms; see mlp_backward)."""
@@ -304,8 +340,6 @@ def encode_graph_backward(model, W, inter, demb_g, src, dst, grads, bound=None):
         if bound is not None:
             _put(bound, model, prefix, bl)
         return dx
-    if model.get("round_kind", "mlp") != "mlp":
-        raise NotImplementedError("backward is written for round_kind='mlp'")
     n, H = inter["h"][0].shape[0], model["hidden"]
     dgin = back(np.asarray(demb_g, dtype=F)[None, :], "readout", inter["c_readout"])
     dpool = dgin[0, :H]
@@ -313,6 +347,9 @@ def encode_graph_backward(model, W, inter, demb_g, src, dst, grads, bound=None):
         dpool = dpool / max(n, 1)
     dh = np.tile(dpool, (n, 1))
     for r in reversed(range(model["rounds"])):
+        if model.get("round_kind", "mlp") == "gat":
+            dh = _gat_round_backward(W, r, inter["h"][r], inter["gat"][r], dh, src, dst, grads, bound)
+            continue
         dxin = back(dh, f"node{r}", inter["c_node"][r])
         dh, dagg = dxin[:, :H].copy(), dxin[:, H:]
         dm = dagg[dst]                                   # reverse of the sum at the receiver

@@ -316,9 +316,9 @@ def test_gather_and_segment_sum_are_adjoint():
 
 
 # ------------------------------------------------------------------ P8, P9: gradients
-def fd_case(seed, readout="sum"):
+def fd_case(seed, readout="sum", round_kind="mlp"):
     rng = np.random.default_rng(seed)
-    model = tiny_model(readout=readout)
+    model = tiny_model(readout=readout, round_kind=round_kind)
     w = rand_weights(rng, model)
     graphs = [rand_graph(rng, model, int(rng.integers(2, 12)), int(rng.integers(1, 22))) for _ in range(7)]
     mask = np.array([1, 1, 0, 1, 1, 0, 1], np.uint8)
@@ -334,9 +334,10 @@ def loss_only(model, w, st, c, d, f):
     return (c[v] * pv["logp"][v]).sum() + (d * pv["value"]).sum() + (f * pv["entropy"]).sum()
 
 
-@pytest.mark.parametrize("seed,readout", [(20, "sum"), (21, "mean"), (22, "sum")])
-def test_backward_matches_central_differences(seed, readout):
-    model, w, st, c, d, f = fd_case(seed, readout)
+@pytest.mark.parametrize("seed,readout,round_kind", [(20, "sum", "mlp"), (21, "mean", "mlp"), (22, "sum", "mlp"),
+                                                     (26, "sum", "gat"), (27, "mean", "gat")])
+def test_backward_matches_central_differences(seed, readout, round_kind):
+    model, w, st, c, d, f = fd_case(seed, readout, round_kind)
     L, grad, _ = O.loss_and_grad(model, w, st, c, d, f)
     assert abs(L - loss_only(model, w, st, c, d, f)) < 1e-12
     rng = np.random.default_rng(seed + 100)
