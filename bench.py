@@ -76,7 +76,7 @@ def main():
     ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
     ap.add_argument("--states", type=int, default=None, help="override the number of states")
     ap.add_argument("--round-kind", default="mlp", choices=["mlp", "gat"],
-                    help="message-passing layers: edge/node MLPs (measured path) or graph attention (forward only)")
+                    help="message-passing layers: edge/node MLPs (measured path) or graph attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
@@ -152,7 +152,7 @@ def main():
     kern = {}
     names = ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads")
     if backward:
-        names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad", "grad_gather")
+        names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad", "grad_gather", "gat_bwd")
     for k in names:
         tot, n = enc.read_timing(k)
         kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)

@@ -66,8 +66,7 @@ typedef struct xrl_model_desc {
   int32_t round_kind;     /* XRL_ROUND_MLP, or XRL_ROUND_GAT: the graph-attention reading of
                              the message-passing layers (Section 3.4, second equation): z = h W,
                              s = LeakyReLU_0.2(a_src.z_sender + a_dst.z_receiver), softmax over a
-                             receiver's in-edges plus a self edge, h' = ReLU(sum alpha z).
-                             Forward only: xrl_encode_backward returns UNSUPPORTED for it       */
+                             receiver's in-edges plus a self edge, h' = ReLU(sum alpha z)        */
 } xrl_model_desc;
 
 /* One or many states, all host memory. Graphs are listed state by state; the first graph of a
@@ -216,7 +215,7 @@ int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32
  * execution order; "gat_linear", "gat_aggregate" with XRL_ROUND_GAT). Backward (Section 3.3.4):
  * {"bwd_edge", "bwd_node", "bwd_embed"} = gradients through the fused MLPs, "wgrad" = both
  * layers' weight gradients of one MLP with their reductions, "grad_gather" = per-node sum of the
- * per-edge gradients. Errors: NULL, INDEX, HIP. */
+ * per-edge gradients; "gat_bwd" = one attention round's backward. Errors: NULL, INDEX, HIP. */
 int xrl_set_timing(xrl_ctx *ctx, int enabled);
 int xrl_read_timing(xrl_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 

@@ -356,7 +356,8 @@ __global__ __launch_bounds__(256) void wgrad2_kernel(const WgradArgs a, int kt, 
         out[(size_t)(32 * m + acc_row(r, g)) * H + 32 * i] = acc[m][i][r];
 }
 
-// dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka. A block handles
+// dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka (db may be null:
+// a product without a bias row). A block handles
 // 32 consecutive entries; its 8 thread groups take every eighth chunk (eight loads in flight
 // each) and their sums are added in group order, so the result has one fixed summation order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial, int n_chunks, int KaP, int Ka,
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *partial,
   __shared__ float part[8][32];
   const int e = threadIdx.x & 31, g = threadIdx.x >> 5;
   const int64_t i = (int64_t)blockIdx.x * 32 + e;
-  const bool live = i < (int64_t)(Ka + 1) * H;
+  const bool live = i < (int64_t)(Ka + (db ? 1 : 0)) * H;   // (db null: no bias row)
   const int k = live ? (int)(i / H) : 0, f = live ? (int)(i - (int64_t)k * H) : 0;
   const float *p = partial + (size_t)k * H + f;
   const size_t cs = (size_t)KaP * H;

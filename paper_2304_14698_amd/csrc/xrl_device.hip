@@ -92,10 +92,10 @@ struct EncMlp {           // device pointers of one encoder MLP
 
 // kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
 enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_GAT_LINEAR,
-       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_COUNT };
+       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_GAT_BWD, TK_COUNT };
 static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
                                                   "heads", "gat_linear", "gat_aggregate", "bwd_edge", "bwd_node",
-                                                  "bwd_embed", "wgrad", "grad_gather"};
+                                                  "bwd_embed", "wgrad", "grad_gather", "gat_bwd"};
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
 
@@ -115,6 +115,8 @@ struct xrl_ctx {
   EncMlp embed;
   std::vector<EncMlp> edge, node;
   std::vector<const void *> gatW;   // XRL_ROUND_GAT: fragment-ordered W of each round
+  std::vector<const void *> gatWt;  //   and of W^T (backward: dh = dz W^T)
+  std::vector<float *> gat_ss, gat_sd;   // saved per-node scores of each round (inside ws)
   std::unordered_map<int64_t, const float *> row_w;   // readout / head matrices, 16-byte aligned copies
   // workspaces (grow-only): encoder activations, and a separate small one for the heads
   char *ws = nullptr;
@@ -232,7 +234,7 @@ int upload_weights(xrl_ctx *c, const float *w) {
   };
   add(c->L.embed, true);   // the embed MLP's first layer keeps fp32 operands in both modes
   const bool gat = m.round_kind == XRL_ROUND_GAT;
-  std::vector<size_t> gat_off;
+  std::vector<size_t> gat_off, gat_off_t;
   if (gat) {
     for (int r = 0; r < m.rounds; ++r) {               // one fragment-ordered [H, H] matrix per round
       size_t o = align_up(blob.size());
@@ -248,6 +250,22 @@ int upload_weights(xrl_ctx *c, const float *w) {
         memcpy(blob.data() + o, t.data(), t.size() * 4);
       }
       gat_off.push_back(o);
+      std::vector<float> wt((size_t)H * H);
+      for (int k = 0; k < H; ++k)
+        for (int f = 0; f < H; ++f) wt[(size_t)f * H + k] = w[c->L.gat[r].W + (size_t)k * H + f];
+      o = align_up(blob.size());
+      if (c->elem == 2) {
+        std::vector<uint16_t> t;
+        swizzle_l1<uint16_t>(wt.data(), H, H, V, t);
+        blob.resize(o + t.size() * 2);
+        memcpy(blob.data() + o, t.data(), t.size() * 2);
+      } else {
+        std::vector<float> t;
+        swizzle_l1<float>(wt.data(), H, H, V, t);
+        blob.resize(o + t.size() * 4);
+        memcpy(blob.data() + o, t.data(), t.size() * 4);
+      }
+      gat_off_t.push_back(o);
     }
   } else {
     for (int r = 0; r < m.rounds; ++r) { add(c->L.edge[r], false); add(c->L.node[r], false); }
@@ -289,7 +307,11 @@ int upload_weights(xrl_ctx *c, const float *w) {
   bind(c->embed, refs[i++], c->L.embed);
   c->gatW.clear();
   if (gat) {
-    for (int r = 0; r < m.rounds; ++r) c->gatW.push_back(c->d_swz + gat_off[r]);
+    c->gatWt.clear();
+    for (int r = 0; r < m.rounds; ++r) {
+      c->gatW.push_back(c->d_swz + gat_off[r]);
+      c->gatWt.push_back(c->d_swz + gat_off_t[r]);
+    }
     return XRL_OK;
   }
   c->edge.resize(m.rounds);
@@ -800,6 +822,11 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
   acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
+  const bool gat = m.round_kind == XRL_ROUND_GAT;
+  if (gat) {                                                       // softmax weights and score gradients
+    for (int i = 0; i < 2; ++i) acc((size_t)E * 4);
+    for (int i = 0; i < 4; ++i) acc((size_t)N * 4);
+  }
   int rc = ensure_bws(c, need);
   if (rc) return rc;
   Bump bump{c->bws};
@@ -810,6 +837,12 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   float *partial = bump.take<float>(part);
   float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
   float *rdx = bump.take<float>((size_t)G * (H + Dg));
+  float *g_ale = nullptr, *g_due = nullptr, *g_als = nullptr, *g_dus = nullptr, *g_dss = nullptr, *g_dsd = nullptr;
+  if (gat) {
+    g_ale = bump.take<float>((size_t)E); g_due = bump.take<float>((size_t)E);
+    g_als = bump.take<float>((size_t)N); g_dus = bump.take<float>((size_t)N);
+    g_dss = bump.take<float>((size_t)N); g_dsd = bump.take<float>((size_t)N);
+  }
 
   // ---- global-update layer backward
   float *ract[3] = {c->ro_act[0], c->ro_act[1], nullptr};
@@ -842,7 +875,50 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     return launch_wgrad<T>(c, WG_PLAIN, wa, dweights + r.w[1], dweights + r.b[1]);
   };
   constexpr int PV = 16 / sizeof(T);
-  for (int r = R - 1; r >= 0; --r) {
+  for (int r = R - 1; r >= 0 && gat; --r) {
+    // attention round r+1: input h[r], saved z (in the agg slot) and scores, output h[r+1]; upstream dhA
+    if (N == 0) break;
+    Timed t(c, TK_GAT_BWD);
+    GatBwdArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.n_rows = N; ga.z = c->agg[r + 1]; ga.hout = c->h[r + 1]; ga.dout = dhA;
+    ga.s_src = c->gat_ss[r]; ga.s_dst = c->gat_sd[r];
+    ga.a_src = c->d_w + c->L.gat[r].a_src; ga.a_dst = c->d_w + c->L.gat[r].a_dst;
+    ga.in_ptr = d.in_ptr; ga.in_src = d.in_src; ga.in_dst = d.in_dst; ga.out_ptr = d.out_ptr; ga.out_pos = d.out_pos;
+    ga.alpha_e = g_ale; ga.du_e = g_due; ga.alpha_s = g_als; ga.du_s = g_dus; ga.d_ss = g_dss; ga.d_sd = g_dsd;
+    ga.dpre = dz2; ga.dz = dz1;
+    const int64_t threads = N * (H / PV);
+    const dim3 grid_n((unsigned)((threads + 255) / 256));
+    gat_bwd_scores_kernel<T, PV><<<grid_n, dim3(256), 0, c->stream>>>(ga, H);
+    gat_bwd_dz_kernel<T, PV><<<grid_n, dim3(256), 0, c->stream>>>(ga, H);
+    // d a_src, d a_dst: chunk partials (at most 512 chunks: they share the weight-gradient buffer)
+    int64_t nc = (N + 1023) / 1024;
+    if (nc > 512) nc = 512;
+    const int rpc = (int)((N + nc - 1) / nc);
+    nc = (N + rpc - 1) / rpc;
+    gat_avec_grad_kernel<T, PV><<<dim3((unsigned)nc), dim3(256), (size_t)(256 / (H / PV)) * 2 * H * sizeof(float), c->stream>>>(
+        (const T *)c->agg[r + 1], g_dss, g_dsd, N, rpc, H, partial);
+    wgrad_reduce_kernel<<<dim3((unsigned)((H + 31) / 32)), dim3(256), 0, c->stream>>>(
+        partial, (int)nc, 2, 1, H, dweights + c->L.gat[r].a_src, nullptr);
+    wgrad_reduce_kernel<<<dim3((unsigned)((H + 31) / 32)), dim3(256), 0, c->stream>>>(
+        partial + H, (int)nc, 2, 1, H, dweights + c->L.gat[r].a_dst, nullptr);
+    // dW = h^T dz (no bias row), dh = dz W^T
+    wa.n_rows = N; wa.Ka = H; wa.dZ = dz1; wa.A = c->h[r];
+    if ((rc = launch_wgrad<T>(c, WG_PLAIN, wa, dweights + c->L.gat[r].W, nullptr))) return rc;
+    GatArgs gl;
+    memset(&gl, 0, sizeof(gl));
+    gl.n_rows = N; gl.n_blocks = (N + 127) / 128;
+    gl.h = dz1; gl.Ws = c->gatWt[r]; gl.a_src = ga.a_src; gl.a_dst = ga.a_dst; gl.z = dhB;
+    const unsigned grid_l = (unsigned)((gl.n_blocks + 7) / 8 * 8);
+    switch (H) {
+      case 64: gat_linear_kernel<T, 64><<<dim3(grid_l), dim3(256), 0, c->stream>>>(gl); break;
+      case 128: gat_linear_kernel<T, 128><<<dim3(grid_l), dim3(256), 0, c->stream>>>(gl); break;
+      default: gat_linear_kernel<T, 256><<<dim3(grid_l), dim3(256), 0, c->stream>>>(gl); break;
+    }
+    HIP_TRY(hipGetLastError());
+    std::swap(dhA, dhB);
+  }
+  for (int r = R - 1; r >= 0 && !gat; --r) {
     // node MLP of round r+1: inputs h[r], agg[r+1]; output h[r+1]; upstream dhA
     set_w(c->node[r]);
     a.n_rows = N; a.h = c->h[r]; a.agg = c->agg[r + 1]; a.y = c->h[r + 1]; a.dy = dhA;
@@ -890,7 +966,8 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   constexpr int PV = 16 / sizeof(T);
   const bool gat = m.round_kind == XRL_ROUND_GAT;
   for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));   // (GAT: the agg slot holds z)
-  if (gat) { acc((size_t)N * 4); acc((size_t)N * 4); }
+  const int n_gs = gat ? (save ? R : 1) : 0;                            // saved per round for the backward
+  for (int i = 0; i < 2 * n_gs; ++i) acc((size_t)N * 4);
   const size_t carry_floats = std::max(std::max(segsum_carry_floats(E, De), segsum_carry_floats(N, H)),
                                        (size_t)n_tiles * 2 * H);
   acc(carry_floats * 4);
@@ -905,7 +982,12 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   std::vector<T *> hb(nh), ab(std::max(nagg, 1), nullptr);
   for (int i = 0; i < nh; ++i) hb[i] = bump.take<T>((size_t)N * H);
   for (int i = 0; i < nagg; ++i) ab[i] = bump.take<T>((size_t)N * H);
-  float *gs_src = gat ? bump.take<float>((size_t)N) : nullptr, *gs_dst = gat ? bump.take<float>((size_t)N) : nullptr;
+  c->gat_ss.assign(R, nullptr);
+  c->gat_sd.assign(R, nullptr);
+  for (int i = 0; i < n_gs; ++i) {
+    c->gat_ss[i] = bump.take<float>((size_t)N);
+    c->gat_sd[i] = bump.take<float>((size_t)N);
+  }
   c->carry = bump.take<float>(carry_floats);
   c->pool = bump.take<float>((size_t)G * H);
   c->ro_act[0] = bump.take<float>((size_t)G * H);
@@ -936,13 +1018,13 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   for (int r = 0; r < R; ++r) {
     T *aggb = save ? ab[r] : ab[0];
     T *hnext = save ? hb[r + 1] : hb[(r + 1) & 1];
-    if (gat) {                         // graph-attention reading of the round (forward only)
+    if (gat) {                         // graph-attention reading of the round
       if (N > 0) {
         GatArgs ga;
         ga.n_rows = N; ga.n_blocks = (N + 127) / 128;
         ga.h = hcur; ga.Ws = c->gatW[r];
         ga.a_src = c->d_w + c->L.gat[r].a_src; ga.a_dst = c->d_w + c->L.gat[r].a_dst;
-        ga.z = aggb; ga.s_src = gs_src; ga.s_dst = gs_dst;
+        ga.z = aggb; ga.s_src = c->gat_ss[save ? r : 0]; ga.s_dst = c->gat_sd[save ? r : 0];
         ga.in_ptr = d.in_ptr; ga.in_src = d.in_src; ga.out = hnext;
         { Timed t(c, TK_GAT_LINEAR);
           const unsigned grid = (unsigned)((ga.n_blocks + 7) / 8 * 8);
@@ -957,7 +1039,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
         HIP_TRY(hipGetLastError());
       }
       c->h[r + 1] = hnext;
-      c->agg[r + 1] = nullptr;
+      c->agg[r + 1] = aggb;            // (z of this round)
       hcur = hnext;
       continue;
     }
@@ -1248,8 +1330,6 @@ int xrl_encode_backward(xrl_ctx *c, const xrl_batch *b, const float *d_demb, flo
   if (rc) return rc;
   if (b->G == 0) return XRL_OK;
   if (!d_demb || !d_dweights) return fail(XRL_ERR_NULL, "xrl_encode_backward: NULL device pointer");
-  if (c->m.round_kind == XRL_ROUND_GAT)
-    return fail(XRL_ERR_UNSUPPORTED, "xrl_encode_backward: the graph-attention rounds are forward only");
   if (!c->enc_saved || c->enc_batch != b->id)
     return fail(XRL_ERR_STATE, "xrl_encode_backward: the batch's last xrl_encode did not save for backward");
   return c->elem == 2 ? encode_backward_impl<bf16_t>(c, b, d_demb, d_dweights)

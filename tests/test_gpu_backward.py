@@ -169,6 +169,21 @@ def test_backward_other_widths(xrl, hidden, precision, readout):
     run_backward_case(xrl, model, state, weights_for(model))
 
 
+@pytest.mark.parametrize("cfg,hidden,precision", [(1, 64, "fp32"), (2, 128, "bf16"), (4, 256, "bf16"),
+                                                  (4, 128, "fp32")])
+def test_backward_graph_attention_rounds(xrl, cfg, hidden, precision):
+    """The graph-attention reading of the rounds: softmax and score gradients per receiver, dz per
+    sender, the two dense products. fp32: the elementwise criterion of the MLP rounds. bf16: the
+    per-tensor criterion with wider thresholds -- an attention round has no bias and puts its
+    ReLU directly on a convex combination of z rows, so more pre-activations lie within the bf16
+    forward's rounding error of zero than in an MLP round; the gradients of the readout MLP,
+    computed in fp32 from that forward, are already 15-16 % (relative L2) away from the float64
+    oracle's, and the attention weights' gradients show the same 16-17 %."""
+    model, state = synth.make_config(cfg, n_cand=12 if cfg != 1 else None)
+    model.update(hidden=hidden, precision=precision, rounds=2, round_kind="gat")
+    run_backward_case(xrl, model, state, weights_for(model), bf16_rel=0.3, bf16_cos=0.95)
+
+
 def test_backward_ppo_minibatch_subset_bf16(xrl):
     """Two states of the PPO-minibatch configuration with a reduced candidate count."""
     model, state = synth.make_config(5, n_states=2, n_cand=12)
