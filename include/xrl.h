@@ -190,6 +190,17 @@ int xrl_ppo_objective(xrl_ctx *ctx, const xrl_batch *b, const float *d_logp, con
                       const float *d_advantage, const float *d_v_target, float eps, float c1,
                       float c2, float *d_J, float *d_dlogp, float *d_dvalue, float *d_dentropy);
 
+/* ---- featurisation of Section 3.3.2 (the paragraph on building the graph input) --------------
+ * Edge attributes from tensor shapes: an edge's attribute is its tensor's shape, zero-padded on
+ * the leading side to rank 4 and divided by the constant M (4096 in the hyper-parameter table of
+ * the appendix). All host memory. shape_ptr: [n_edges + 1], non-decreasing from 0, edge e's
+ * shape is dims[shape_ptr[e] .. shape_ptr[e+1]) (rank 0 to 4, entries >= 0); edge_feat:
+ * [n_edges, 4] fp32, written. With n_op_types ~ 40, n_node_dense = 0, d_edge = 4 and graph_global
+ * NULL (zeros) this gives the state description the paper prints.
+ * Errors: NULL, SHAPE (rank above 4, shape_ptr not monotone), VALUE (negative extent, M <= 0). */
+int xrl_edge_features_from_shapes(const int32_t *shape_ptr, const int64_t *dims, int64_t n_edges,
+                                  double M, float *edge_feat);
+
 /* ---- building blocks exposed for measurement and per-step checks ----------------------------
  * xrl_segment_sum: out[i, :] = sum of values[r, :] over rows r in [d_ptr[i], d_ptr[i+1]) -- the
  * receiver-side aggregation of Section 3.4's first two equations on receiver-ordered rows, and

@@ -144,6 +144,19 @@ def node_features(model, op, dense):
     return x
 
 
+def edge_features_from_shapes(shapes, M=4096.0):
+    """Section 3.3.2, paragraph on the graph input: an edge's attribute is its tensor's shape,
+    zero-padded on the leading side to rank 4, divided by the constant M of the appendix's
+    hyper-parameter table (4096)."""
+    out = np.zeros((len(shapes), 4), dtype=F)
+    for e, sh in enumerate(shapes):
+        sh = list(sh)
+        assert len(sh) <= 4 and all(d >= 0 for d in sh)
+        for k, d in enumerate(sh):
+            out[e, 4 - len(sh) + k] = d / M
+    return out
+
+
 def segment_sum(values, index, n):
     """out[i] = sum of values[e] over e with index[e] == i."""
     out = np.zeros((n,) + values.shape[1:], dtype=F)

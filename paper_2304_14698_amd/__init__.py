@@ -55,7 +55,7 @@ EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_ppo_objective", "xrl_segment_sum",
            "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
-           "xrl_last_error", "xrl_version"]
+           "xrl_edge_features_from_shapes", "xrl_last_error", "xrl_version"]
 
 
 def load_library():
@@ -86,6 +86,7 @@ def load_library():
     lib.xrl_policy_value_backward.argtypes = [vp] * 8
     lib.xrl_encode_backward.argtypes = [vp] * 4
     lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+    lib.xrl_edge_features_from_shapes.argtypes = [vp, vp, i64, C.c_double, vp]
     lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
     lib.xrl_set_timing.argtypes = [vp, C.c_int]
     lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -198,6 +199,18 @@ class Batch:
 
 def pack_state(model, state):
     return Batch(model, state)
+
+
+def edge_features_from_shapes(shapes, M=4096.0):
+    """[E, 4] float32 edge attributes from a list of tensor shapes (rank <= 4 each)."""
+    lib = load_library()
+    ptr = np.zeros(len(shapes) + 1, dtype=np.int32)
+    ptr[1:] = np.cumsum([len(sh) for sh in shapes])
+    dims = np.ascontiguousarray([d for sh in shapes for d in sh], dtype=np.int64)
+    out = np.empty((len(shapes), 4), dtype=np.float32)
+    _check(lib.xrl_edge_features_from_shapes(ptr.ctypes.data, dims.ctypes.data if dims.size else None,
+                                             len(shapes), C.c_double(M), out.ctypes.data))
+    return out
 
 
 class Encoder:

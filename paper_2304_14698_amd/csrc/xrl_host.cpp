@@ -289,6 +289,29 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
   return XRL_OK;
 }
 
+int xrl_edge_features_from_shapes(const int32_t *shape_ptr, const int64_t *dims, int64_t n_edges,
+                                  double M, float *edge_feat) {
+  if (n_edges < 0) return fail(XRL_ERR_SHAPE, "n_edges = %lld is negative", (long long)n_edges);
+  if (!shape_ptr || (n_edges > 0 && !edge_feat))
+    return fail(XRL_ERR_NULL, "xrl_edge_features_from_shapes: NULL argument");
+  if (!(M > 0.0)) return fail(XRL_ERR_VALUE, "the normalisation constant M must be positive");
+  if (shape_ptr[0] != 0) return fail(XRL_ERR_SHAPE, "shape_ptr[0] must be 0");
+  for (int64_t e = 0; e < n_edges; ++e) {
+    const int64_t r = (int64_t)shape_ptr[e + 1] - shape_ptr[e];
+    if (r < 0 || r > 4)
+      return fail(XRL_ERR_SHAPE, "edge %lld: rank %lld outside [0, 4]", (long long)e, (long long)r);
+    if (r > 0 && !dims) return fail(XRL_ERR_NULL, "xrl_edge_features_from_shapes: dims is NULL");
+    float *o = edge_feat + 4 * e;
+    for (int k = 0; k < 4; ++k) o[k] = 0.0f;                  // leading dimensions padded with zeros
+    for (int64_t k = 0; k < r; ++k) {
+      const int64_t d = dims[shape_ptr[e] + k];
+      if (d < 0) return fail(XRL_ERR_VALUE, "edge %lld: negative extent %lld", (long long)e, (long long)d);
+      o[4 - r + k] = (float)((double)d / M);
+    }
+  }
+  return XRL_OK;
+}
+
 int xrl_batch_dims(const xrl_batch *b, int64_t *S, int64_t *G, int64_t *N, int64_t *E) {
   if (!b) return fail(XRL_ERR_NULL, "xrl_batch_dims: batch is NULL");
   if (S) *S = b->S;

@@ -184,6 +184,22 @@ def test_backward_graph_attention_rounds(xrl, cfg, hidden, precision):
     run_backward_case(xrl, model, state, weights_for(model), bf16_rel=0.3, bf16_cos=0.95)
 
 
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_backward_paper_feature_dimensions(xrl, precision):
+    """Backward with the state description the paper prints: 40 operator types, no other node
+    attributes, 4 edge attributes (shape over 4096), zero global attribute."""
+    model, state = synth.make_config(2, n_cand=5)
+    model.update(hidden=128, precision=precision, rounds=2, n_op_types=40, n_node_dense=0, d_edge=4)
+    rng = np.random.Generator(np.random.PCG64(31))
+    E, N = len(state["edge_src"]), len(state["node_op"])
+    extents = np.array([1, 3, 12, 64, 128, 197, 256, 768, 1000, 3072])
+    shapes = [list(rng.choice(extents, size=int(rng.integers(1, 5)))) for _ in range(E)]
+    state = dict(state, node_op=rng.integers(0, 40, N).astype(np.int32), node_dense=np.zeros((N, 0), np.float32),
+                 edge_feat=xrl.edge_features_from_shapes(shapes),
+                 graph_global=np.zeros((len(state["slot_mask"]), model["d_global"]), np.float32))
+    run_backward_case(xrl, model, state, weights_for(model))
+
+
 def test_backward_ppo_minibatch_subset_bf16(xrl):
     """Two states of the PPO-minibatch configuration with a reduced candidate count."""
     model, state = synth.make_config(5, n_states=2, n_cand=12)

@@ -282,6 +282,25 @@ def test_all_candidates_masked_and_single_slot(xrl):
     assert_close(pv["value"].cpu().numpy(), rp["value"], "fp32", "value")
 
 
+@pytest.mark.parametrize("hidden,precision", [(64, "fp32"), (128, "bf16")])
+def test_paper_feature_dimensions(xrl, hidden, precision):
+    """The state description the paper prints (Section 3.3.2): 40 operator types one-hot, no other
+    node attributes, edge attribute = tensor shape padded to rank 4 over M = 4096 (built by the
+    library's featuriser from synthetic shapes), global attribute initialised to zero."""
+    model, state = synth.make_config(2, n_cand=5)
+    model.update(hidden=hidden, precision=precision, rounds=3, n_op_types=40, n_node_dense=0, d_edge=4)
+    rng = np.random.Generator(np.random.PCG64(31))
+    E, N = len(state["edge_src"]), len(state["node_op"])
+    extents = np.array([1, 3, 12, 64, 128, 197, 256, 768, 1000, 3072])
+    shapes = [list(rng.choice(extents, size=int(rng.integers(1, 5)))) for _ in range(E)]
+    state = dict(state, node_op=rng.integers(0, 40, N).astype(np.int32),
+                 node_dense=np.zeros((N, 0), np.float32),
+                 edge_feat=xrl.edge_features_from_shapes(shapes), graph_global=None)
+    state["graph_global"] = np.zeros((len(state["slot_mask"]), model["d_global"]), np.float32)
+    np.testing.assert_array_equal(state["edge_feat"], O.edge_features_from_shapes(shapes).astype(np.float32))
+    run_case(xrl, model, state, weights_for(model))
+
+
 @pytest.mark.parametrize("hidden,n_states,n_cand", [(64, 1, 3), (128, 7, 40), (256, 3, 130)])
 def test_heads_on_given_embeddings_repeated(xrl, hidden, n_states, n_cand):
     """Policy and value heads alone, on random embeddings (the oracle gets the same ones), called

@@ -186,3 +186,25 @@ def test_device_calls_fail_cleanly_without_gpu_or_upload():
             xrl.Encoder(model, w)
     b = xrl.pack_state(model, st)
     assert lib.xrl_encode(None, b.handle, None, 0) == xrl.ERR["NULL"]
+
+
+def test_shape_features_host_call():
+    """xrl_edge_features_from_shapes against the oracle's (random shapes of rank 0..4) and the
+    paper's printed example; error codes for bad input."""
+    import ctypes as C
+    from oracle import xrl_oracle as O
+    rng = np.random.default_rng(9)
+    shapes = [[1, 3, 256, 256]] + [list(rng.integers(0, 5000, size=int(rng.integers(0, 5)))) for _ in range(200)]
+    got = xrl.edge_features_from_shapes(shapes)
+    ref = O.edge_features_from_shapes(shapes)
+    assert got.dtype == np.float32 and got.shape == (201, 4)
+    np.testing.assert_array_equal(got, ref.astype(np.float32))
+    np.testing.assert_array_equal(got[0], np.float32([1 / 4096, 3 / 4096, 0.0625, 0.0625]))
+    assert xrl.edge_features_from_shapes([]).shape == (0, 4)
+    for bad, code in (([[1, 2, 3, 4, 5]], "SHAPE"), ([[3, -1]], "VALUE")):
+        with pytest.raises(xrl.XrlError) as ei:
+            xrl.edge_features_from_shapes(bad)
+        assert ei.value.code == xrl.ERR[code]
+    with pytest.raises(xrl.XrlError) as ei:
+        xrl.edge_features_from_shapes([[1]], M=0.0)
+    assert ei.value.code == xrl.ERR["VALUE"]

@@ -549,3 +549,28 @@ def test_ppo_objective_hand_example():
     assert abs(r["l_clip"] - vals["l_clip"][0]) < 1e-12 and abs(r["l_vf"] - vals["l_vf"][0]) < 1e-12
     assert abs(r["l_ent"] - vals["l_ent"][0]) < 1e-12 and abs(r["J"] - vals["J"][0]) < 1e-12
     assert np.allclose(r["dlogp"], vals["dlogp"], atol=1e-12) and np.allclose(r["dvalue"], vals["dvalue"], atol=1e-12)
+
+
+# ------------------------------------------------------------------ featurisation (Section 3.3.2)
+def _shape_examples():
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "shape_features_example.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            t = line.split()
+            r = int(t[0])
+            rows.append(([int(x) for x in t[1:1 + r]], [float(x) for x in t[1 + r:1 + r + 4]]))
+    return rows
+
+
+def test_shape_features_match_the_printed_example():
+    """The paper's example shape and hand-worked padded cases (tests/golden/shape_features_example.txt);
+    every extent of the values used is a multiple of a power of two, so the quotients are exact."""
+    rows = _shape_examples()
+    got = O.edge_features_from_shapes([r[0] for r in rows])
+    assert got.shape == (len(rows), 4)
+    np.testing.assert_array_equal(got, np.array([r[1] for r in rows]))
+    # padding sits on the leading side: the last rank entries are the shape, in order
+    assert np.array_equal(O.edge_features_from_shapes([[5, 7]], M=1.0), [[0, 0, 5, 7]])
