@@ -1,9 +1,13 @@
 // Host side of the library: weight layout, validation and packing of states into the
 // receiver-sorted meta-batch. Nothing in this file calls the GPU runtime.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
+#include <system_error>
+#include <thread>
 
 #include "xrl_internal.h"
 
@@ -95,6 +99,79 @@ int build_layout(const xrl_model_desc &m, Layout &L) {
 
 using namespace xrl;
 
+namespace {
+// Packing works graph by graph (a graph's nodes, and its edges in receiver order, occupy the same
+// index ranges before and after), so large batches are cut into contiguous graph ranges of about
+// equal nodes + edges, one per thread. XRL_PACK_THREADS overrides the thread count (1 = serial).
+struct PackIssue {
+  int code = 0;
+  char msg[200] = "";
+  void set(int c, const char *fmt, ...) {
+    if (code) return;                                   // keep the first one of this range
+    code = c;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(msg, sizeof(msg), fmt, ap);
+    va_end(ap);
+  }
+};
+
+int pack_thread_count(int64_t work) {
+  if (const char *e = getenv("XRL_PACK_THREADS")) {
+    const int v = atoi(e);
+    if (v >= 1) return v > 64 ? 64 : v;
+  }
+  int hw = (int)std::thread::hardware_concurrency();
+  if (hw < 1) hw = 1;
+  if (hw > 16) hw = 16;
+  int64_t t = work / 65536;
+  return (int)(t < 1 ? 1 : (t > hw ? hw : t));
+}
+
+// graph range boundaries [T + 1], balanced by nodes + edges
+std::vector<int64_t> graph_ranges(const xrl_state_desc *st, int64_t G, int T) {
+  std::vector<int64_t> cut(T + 1, G);
+  cut[0] = 0;
+  const int64_t total = (int64_t)st->graph_node_ptr[G] + st->graph_edge_ptr[G];
+  int64_t g = 0;
+  for (int t = 1; t < T; ++t) {
+    const int64_t want = total * t / T;
+    while (g < G && (int64_t)st->graph_node_ptr[g] + st->graph_edge_ptr[g] < want) ++g;
+    cut[t] = g;
+  }
+  return cut;
+}
+
+// fn(t, g_begin, g_end) for every range; returns false if a range ran out of memory. Ranges whose
+// thread cannot be started run on the calling thread.
+template <typename F>
+bool run_ranges(const std::vector<int64_t> &cut, F fn) {
+  const int T = (int)cut.size() - 1;
+  std::atomic<bool> ok{true};
+  auto guarded = [&](int t) {
+    try {
+      fn(t, cut[t], cut[t + 1]);
+    } catch (const std::bad_alloc &) {
+      ok = false;
+    }
+  };
+  std::vector<std::thread> th;
+  th.reserve(T > 1 ? T - 1 : 0);
+  int started = 1;
+  for (; started < T; ++started) {
+    try {
+      th.emplace_back(guarded, started);
+    } catch (const std::system_error &) {
+      break;
+    }
+  }
+  guarded(0);
+  for (int t = started; t < T; ++t) guarded(t);
+  for (auto &x : th) x.join();
+  return ok;
+}
+}  // namespace
+
 extern "C" {
 
 const char *xrl_last_error(void) { return g_err; }
@@ -178,23 +255,41 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
   for (int64_t s = 0; s < S; ++s)
     if (st->slot_mask[st->state_graph_ptr[s]] == 0)
       return fail(XRL_ERR_MASK, "state %lld masks its No-Op slot (its first graph)", (long long)s);
-  for (int64_t i = 0; i < N; ++i)
-    if (st->node_op[i] < 0 || st->node_op[i] >= model->n_op_types)
-      return fail(XRL_ERR_INDEX, "node %lld: op id %d outside [0, %d)", (long long)i,
-                  st->node_op[i], model->n_op_types);
-  for (int64_t g = 0; g < G; ++g) {
-    const int32_t n = st->graph_node_ptr[g + 1] - st->graph_node_ptr[g];
-    for (int64_t e = st->graph_edge_ptr[g]; e < st->graph_edge_ptr[g + 1]; ++e)
-      if (st->edge_src[e] < 0 || st->edge_src[e] >= n || st->edge_dst[e] < 0 ||
-          st->edge_dst[e] >= n)
-        return fail(XRL_ERR_INDEX, "edge %lld of graph %lld: endpoint (%d -> %d) outside [0, %d)",
-                    (long long)e, (long long)g, st->edge_src[e], st->edge_dst[e], n);
+  // per-range checks, reported in the order a serial pass would find them: operator ids, edge
+  // endpoints, node attributes, edge attributes; within a kind, the lowest range first
+  const int T = pack_thread_count(N + E);
+  const std::vector<int64_t> cut = graph_ranges(st, G, T);
+  {
+    std::vector<PackIssue> issue((size_t)4 * T);
+    const bool ok = run_ranges(cut, [&](int t, int64_t g0, int64_t g1) {
+      const int64_t n0 = st->graph_node_ptr[g0], n1 = st->graph_node_ptr[g1];
+      const int64_t e0 = st->graph_edge_ptr[g0], e1 = st->graph_edge_ptr[g1];
+      for (int64_t i = n0; i < n1; ++i)
+        if (st->node_op[i] < 0 || st->node_op[i] >= model->n_op_types) {
+          issue[0 * T + t].set(XRL_ERR_INDEX, "node %lld: op id %d outside [0, %d)", (long long)i,
+                               st->node_op[i], model->n_op_types);
+          break;
+        }
+      for (int64_t g = g0; g < g1 && !issue[1 * T + t].code; ++g) {
+        const int32_t n = st->graph_node_ptr[g + 1] - st->graph_node_ptr[g];
+        for (int64_t e = st->graph_edge_ptr[g]; e < st->graph_edge_ptr[g + 1]; ++e)
+          if (st->edge_src[e] < 0 || st->edge_src[e] >= n || st->edge_dst[e] < 0 || st->edge_dst[e] >= n) {
+            issue[1 * T + t].set(XRL_ERR_INDEX, "edge %lld of graph %lld: endpoint (%d -> %d) outside [0, %d)",
+                                 (long long)e, (long long)g, st->edge_src[e], st->edge_dst[e], n);
+            break;
+          }
+      }
+      int64_t where = 0;
+      if (Dd > 0 && !all_finite(st->node_dense + n0 * Dd, (n1 - n0) * Dd, &where))
+        issue[2 * T + t].set(XRL_ERR_VALUE, "node_dense[%lld] is not finite", (long long)(n0 * Dd + where));
+      if (!all_finite(st->edge_feat + e0 * De, (e1 - e0) * De, &where))
+        issue[3 * T + t].set(XRL_ERR_VALUE, "edge_feat[%lld] is not finite", (long long)(e0 * De + where));
+    });
+    if (!ok) return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
+    for (const PackIssue &is : issue)
+      if (is.code) return fail(is.code, "%s", is.msg);
   }
   int64_t bad = 0;
-  if (Dd > 0 && !all_finite(st->node_dense, N * Dd, &bad))
-    return fail(XRL_ERR_VALUE, "node_dense[%lld] is not finite", (long long)bad);
-  if (!all_finite(st->edge_feat, E * De, &bad))
-    return fail(XRL_ERR_VALUE, "edge_feat[%lld] is not finite", (long long)bad);
   if (st->graph_global && !all_finite(st->graph_global, G * Dg, &bad))
     return fail(XRL_ERR_VALUE, "graph_global[%lld] is not finite", (long long)bad);
 
@@ -207,8 +302,8 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
     b->S = S; b->G = G; b->N = N; b->E = E;
     b->state_graph_ptr.assign(st->state_graph_ptr, st->state_graph_ptr + S + 1);
     b->graph_node_ptr.assign(st->graph_node_ptr, st->graph_node_ptr + G + 1);
-    b->node_op.assign(st->node_op, st->node_op + N);
-    b->node_dense.assign(st->node_dense, st->node_dense + (Dd > 0 ? N * Dd : 0));
+    b->node_op.resize(N);                            // (copied by the packing threads below)
+    b->node_dense.resize(Dd > 0 ? (size_t)N * Dd : 0);
     b->mask.resize(G);
     for (int64_t g = 0; g < G; ++g) b->mask[g] = st->slot_mask[g] ? 1 : 0;
     if (st->graph_global)
@@ -220,43 +315,46 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
       if (c > b->max_slots) b->max_slots = c;
     }
     b->node_graph.resize(N);
-    for (int64_t g = 0; g < G; ++g)
-      for (int32_t i = st->graph_node_ptr[g]; i < st->graph_node_ptr[g + 1]; ++i)
-        b->node_graph[i] = (int32_t)g;
-
-    // receiver order: stable counting sort of the edges by global receiver id
     b->in_ptr.assign(N + 1, 0);
     b->out_ptr.assign(N + 1, 0);
-    std::vector<int32_t> gsrc(E), gdst(E);
-    for (int64_t g = 0; g < G; ++g) {
-      const int32_t base = st->graph_node_ptr[g];
-      for (int64_t e = st->graph_edge_ptr[g]; e < st->graph_edge_ptr[g + 1]; ++e) {
-        gsrc[e] = base + st->edge_src[e];
-        gdst[e] = base + st->edge_dst[e];
-        b->in_ptr[gdst[e] + 1]++;
-        b->out_ptr[gsrc[e] + 1]++;
-      }
-    }
-    for (int64_t i = 0; i < N; ++i) {
-      b->in_ptr[i + 1] += b->in_ptr[i];
-      b->out_ptr[i + 1] += b->out_ptr[i];
-    }
     b->in_src.resize(E); b->in_dst.resize(E); b->in_eid.resize(E); b->out_pos.resize(E);
     b->edge_feat.resize((size_t)E * De);
-    {
-      std::vector<int32_t> cur(b->in_ptr.begin(), b->in_ptr.end() - 1);
-      for (int64_t e = 0; e < E; ++e) {
-        const int32_t p = cur[gdst[e]]++;
-        b->in_src[p] = gsrc[e];
-        b->in_dst[p] = gdst[e];
-        b->in_eid[p] = (int32_t)e;
-        memcpy(&b->edge_feat[(size_t)p * De], &st->edge_feat[(size_t)e * De], sizeof(float) * De);
+    // Receiver order: stable counting sort of each graph's edges by receiver; then the sender-side
+    // index (receiver-order positions grouped by sender, ascending position). A graph's edges
+    // keep the index range they came with, so the graph ranges are independent.
+    const bool sorted = run_ranges(cut, [&](int, int64_t g0, int64_t g1) {
+      std::vector<int32_t> cur;
+      for (int64_t g = g0; g < g1; ++g) {
+        const int32_t base = st->graph_node_ptr[g], n = st->graph_node_ptr[g + 1] - base;
+        const int64_t e0 = st->graph_edge_ptr[g], e1 = st->graph_edge_ptr[g + 1];
+        for (int32_t i = 0; i < n; ++i) b->node_graph[base + i] = (int32_t)g;
+        if (n > 0) {
+          memcpy(&b->node_op[base], st->node_op + base, sizeof(int32_t) * n);
+          if (Dd > 0) memcpy(&b->node_dense[(size_t)base * Dd], st->node_dense + (size_t)base * Dd, sizeof(float) * n * Dd);
+        }
+        int32_t *inp = b->in_ptr.data() + base + 1, *outp = b->out_ptr.data() + base + 1;   // counts, then ends
+        for (int64_t e = e0; e < e1; ++e) {
+          inp[st->edge_dst[e]]++;
+          outp[st->edge_src[e]]++;
+        }
+        cur.assign((size_t)2 * n, 0);
+        int32_t ri = (int32_t)e0, ro = (int32_t)e0;
+        for (int32_t i = 0; i < n; ++i) {
+          cur[i] = ri; cur[n + i] = ro;                   // first position of node i's in- / out-edges
+          ri += inp[i]; ro += outp[i];
+          inp[i] = ri; outp[i] = ro;
+        }
+        for (int64_t e = e0; e < e1; ++e) {
+          const int32_t p = cur[st->edge_dst[e]]++;
+          b->in_src[p] = base + st->edge_src[e];
+          b->in_dst[p] = base + st->edge_dst[e];
+          b->in_eid[p] = (int32_t)e;
+          memcpy(&b->edge_feat[(size_t)p * De], &st->edge_feat[(size_t)e * De], sizeof(float) * De);
+        }
+        for (int64_t p = e0; p < e1; ++p) b->out_pos[cur[n + (b->in_src[p] - base)]++] = (int32_t)p;
       }
-    }
-    {  // sender-side index: receiver-order positions grouped by sender, ascending position
-      std::vector<int32_t> cur(b->out_ptr.begin(), b->out_ptr.end() - 1);
-      for (int64_t p = 0; p < E; ++p) b->out_pos[cur[b->in_src[p]]++] = (int32_t)p;
-    }
+    });
+    if (!sorted) throw std::bad_alloc();
     {  // Edge tiles of the message kernels: consecutive receiver-order edges, at most 32 per tile,
        // cut at receiver boundaries so that a receiver's in-edges share a tile. Only a receiver
        // with more than 32 in-edges is split (into full tiles plus a remainder that later

@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -41,6 +42,18 @@ int build_layout(const xrl_model_desc &m, Layout &out);
 
 }  // namespace xrl
 
+// Allocator whose resize() leaves new trivially-constructible elements uninitialised: the packed
+// arrays are written in full by the packing threads, which then also take their page faults.
+template <typename T>
+struct RawAlloc : std::allocator<T> {
+  template <typename U> struct rebind { typedef RawAlloc<U> other; };
+  RawAlloc() = default;
+  template <typename U> RawAlloc(const RawAlloc<U> &) {}
+  template <typename U> void construct(U *p) { ::new ((void *)p) U; }              // default-init: no write
+  template <typename U, typename... A> void construct(U *p, A &&...a) { ::new ((void *)p) U(std::forward<A>(a)...); }
+};
+template <typename T> using RawVec = std::vector<T, RawAlloc<T>>;
+
 // Device-side copies of a packed batch (all owned by one hipMalloc block).
 struct xrl_batch_device {
   void *block = nullptr;
@@ -56,11 +69,12 @@ struct xrl_batch {
   xrl_model_desc model;
   int64_t S = 0, G = 0, N = 0, E = 0;
   int32_t max_slots = 0;  // largest number of slots in one state
-  std::vector<int32_t> state_graph_ptr, graph_node_ptr, node_op;
-  std::vector<int32_t> in_ptr, in_src, in_dst, in_eid, out_ptr, out_pos, node_graph;
+  std::vector<int32_t> state_graph_ptr, graph_node_ptr, in_ptr, out_ptr;
+  RawVec<int32_t> node_op, in_src, in_dst, in_eid, out_pos, node_graph;
   std::vector<int32_t> tile_ptr;  // [n_tiles + 1] edge tiles of the message kernels (see the packer)
   int64_t n_split_tiles = 0;      // tiles that end inside a receiver's in-edge range
-  std::vector<float> node_dense, edge_feat, graph_global;
+  RawVec<float> node_dense, edge_feat;
+  std::vector<float> graph_global;
   std::vector<uint8_t> mask;
   xrl_batch_device dev;
   bool uploaded = false;

@@ -208,3 +208,41 @@ def test_shape_features_host_call():
     with pytest.raises(xrl.XrlError) as ei:
         xrl.edge_features_from_shapes([[1]], M=0.0)
     assert ei.value.code == xrl.ERR["VALUE"]
+
+
+def test_threaded_pack_equals_serial(monkeypatch):
+    """The packer cuts large batches into graph ranges, one per thread (XRL_PACK_THREADS forces the
+    count): every packed array must be identical to the serial result, for thread counts below,
+    at and above the number of graphs, and errors must be reported as a serial pass finds them."""
+    model, st = synth.make_config(3, n_states=2)
+    monkeypatch.setenv("XRL_PACK_THREADS", "1")
+    b = xrl.pack_state(model, st)
+    ref = b.host_view()
+    check_tiles(ref)
+    b.free()
+    G = len(st["graph_node_ptr"]) - 1
+    for t in (2, 7, G, G + 5):
+        monkeypatch.setenv("XRL_PACK_THREADS", str(t))
+        b = xrl.pack_state(model, st)
+        v = b.host_view()
+        b.free()
+        for k in ref:
+            np.testing.assert_array_equal(v[k], ref[k], err_msg=f"{k} with {t} threads")
+    # a bad operator id late in the batch and a bad edge early: the operator id is reported
+    # (operator ids are checked before edges), whatever the thread count
+    bad = _mutate(st)
+    bad["node_op"][-3] = 999
+    bad["edge_dst"][2] = 10_000_000
+    for t in ("1", "7"):
+        monkeypatch.setenv("XRL_PACK_THREADS", t)
+        with pytest.raises(xrl.XrlError) as ei:
+            xrl.pack_state(model, bad)
+        assert ei.value.code == xrl.ERR["INDEX"] and "op id 999" in str(ei.value)
+    # two bad edges: the one with the lower index is reported
+    bad = _mutate(st)
+    bad["edge_src"][5] = -7
+    bad["edge_src"][len(bad["edge_src"]) - 1] = -9
+    monkeypatch.setenv("XRL_PACK_THREADS", "7")
+    with pytest.raises(xrl.XrlError) as ei:
+        xrl.pack_state(model, bad)
+    assert "(-7 ->" in str(ei.value)
