@@ -137,7 +137,9 @@ int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is acc
  * weights_host: xrl_weight_count floats. hip_stream: a hipStream_t (NULL = default stream).
  * Errors: NULL, UNSUPPORTED (hidden not in {64,128,256}, mlp_layers != 2, ...), VALUE, HIP, OOM.
  * Environment, read here: XRL_PERSISTENT_MIN_ROWS = row count from which the persistent MLP
- * kernels replace the streaming one (default 8192; 0 = always; results agree within rounding). */
+ * kernels replace the streaming one (default 8192; 0 = always; results agree within rounding);
+ * XRL_WGRAD_WIDE_MIN_ROWS = row count from which the weight-gradient kernel uses 256-column
+ * tiles (default 2^20; same sums in a different, equally fixed order). */
 int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip_stream,
                xrl_ctx **out);
 int xrl_set_weights(xrl_ctx *ctx, const float *weights_host);

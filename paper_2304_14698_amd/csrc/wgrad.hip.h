@@ -158,12 +158,13 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 // Rows of an LDS tile are 64 bytes longer than their data: with a row stride of 16 (mod 64)
 // dwords the four rows a transpose read touches fall on different banks.
 struct Wgrad2Plan {
-  int kt, ny, rows_per_slot;     // 128-column tiles of X, row slices, rows per slice (multiple of 32)
+  int kt, ny, rows_per_slot;     // column tiles of X, row slices, rows per slice (multiple of 32)
 };
-inline Wgrad2Plan wgrad2_plan(int64_t n_rows, int Ka, int n_cu) {
+// kt column tiles; blocks_per_cu = how many blocks of the kernel variant a CU holds
+inline Wgrad2Plan wgrad2_plan(int64_t n_rows, int kt, int n_cu, int blocks_per_cu) {
   Wgrad2Plan p;
-  p.kt = (Ka + 1 + 127) / 128;
-  int per = (2 * n_cu / 8) / p.kt;                        // row slices per XCD: two blocks per CU
+  p.kt = kt;
+  int per = (blocks_per_cu * n_cu / 8) / p.kt;            // row slices per XCD
   if (per < 1) per = 1;
   int64_t want = (n_rows + 63) / 64;                      // at least 64 rows per slice
   want = (want + 7) / 8;
@@ -191,22 +192,23 @@ __device__ __forceinline__ bf16x8 lds_tr_operand(const char *p, int row_stride) 
 // the middle of the loop. TAIL = the tile holds columns past the gathered / direct ones (edge
 // attributes, the all-ones bias column, padding); such tiles are whole for the EDGE and NODE
 // kinds (2H is a multiple of 128), PLAIN uses the one formulation for all its tiles.
-template <int H, int KIND, bool TAIL>
+template <int H, int KIND, bool TAIL, int TA>
 __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t r_begin, int64_t r_end,
-                                           char (*Xs)[32 * (128 * 2 + 64)], char (*Zs)[32 * (H * 2 + 64)],
+                                           char (*Xs)[32 * (TA * 2 + 64)], char (*Zs)[32 * (H * 2 + 64)],
                                            f32x16 (&acc)[2][H / 64 > 0 ? H / 64 : 1]) {
   using T = bf16_t;
   using vec = bf16x8;
-  constexpr int TA = 128, RS = 32;
+  constexpr int RS = 32, NT = 2 * TA;                      // TA / 64 x 2 waves
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;         // LDS row strides, bytes
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;              // 32-column blocks of dZ per wave
-  constexpr int ZV = RS * (H / 8) / 256;                   // dZ vectors per thread per stage
+  constexpr int ZV = RS * (H / 8) / NT;                    // dZ vectors per thread per stage
+  static_assert(ZV >= 1, "a stage of dZ gives every thread at least one vector");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int wa = wave & 1, wb = wave >> 1;
+  const int wa = wave % (TA / 64), wb = wave / (TA / 64);
   const int n_stage = (int)((r_end - r_begin + RS - 1) / RS);
 
   // ---- this thread's two X vectors per stage: rows xr, xr + 16 of the stage, columns xc .. xc+7
-  const int xr = tid / 16, xc = ka0 + 8 * (tid % 16);
+  const int xr = tid / (TA / 8), xcl = tid % (TA / 8), xc = ka0 + 8 * xcl;
   const bool second = xc >= H;                             // EDGE: receiver's state; NODE: aggregate
   [[maybe_unused]] const int32_t *idx_arr = second ? a.in_dst : a.in_src;
   [[maybe_unused]] const T *gbase = (const T *)a.h + (second ? xc - H : xc);
@@ -262,7 +264,7 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   auto load_z = [&](int st, vec (&z)[ZV]) {
 #pragma unroll
     for (int c = 0; c < ZV; ++c) {
-      const int vi = tid + 256 * c, rl = vi / (H / 8), cc = vi % (H / 8);
+      const int vi = tid + NT * c, rl = vi / (H / 8), cc = vi % (H / 8);
       int64_t row = r_begin + (int64_t)st * RS + rl;
       const bool on = row < r_end;
       if (!on) row = r_end - 1;
@@ -272,10 +274,10 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   };
   auto commit = [&](int buf, const vec (&x)[2], const vec (&z)[ZV]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) *(vec *)(Xs[buf] + (xr + 16 * c) * XS + (tid % 16) * 16) = x[c];
+    for (int c = 0; c < 2; ++c) *(vec *)(Xs[buf] + (xr + 16 * c) * XS + xcl * 16) = x[c];
 #pragma unroll
     for (int c = 0; c < ZV; ++c) {
-      const int vi = tid + 256 * c, rl = vi / (H / 8), cc = vi % (H / 8);
+      const int vi = tid + NT * c, rl = vi / (H / 8), cc = vi % (H / 8);
       *(vec *)(Zs[buf] + rl * ZS + cc * 16) = z[c];
     }
   };
@@ -317,19 +319,24 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   }
 }
 
-template <int H, int KIND>
-__global__ __launch_bounds__(256) void wgrad2_kernel(const WgradArgs a, int kt, int ny) {
-  constexpr int TA = 128, RS = 32;
+// TA = X columns per block: 128 (four waves, two blocks per CU) or 256 (eight waves, one block
+// per CU: X enters once, dZ once per 256 instead of once per 128 columns). ka_base = first column
+// of the launch's tiles (a launch may cover only the columns past the H-wide parts).
+template <int H, int KIND, int TA>
+__global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int kt, int ny, int ka_base) {
+  constexpr int RS = 32;
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;
   static_assert(KIND != WG_EMBED, "the embed layer's columns are synthesised: see wgrad_kernel");
-  __shared__ __align__(16) char Xs[2][RS * XS];
-  __shared__ __align__(16) char Zs[2][RS * ZS];
+  extern __shared__ __align__(16) char smem[];              // wgrad2_lds_bytes<H, TA>()
+  char(*Xs)[RS * XS] = reinterpret_cast<char(*)[RS * XS]>(smem);
+  char(*Zs)[RS * ZS] = reinterpret_cast<char(*)[RS * ZS]>(smem + 2 * RS * XS);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
-  const int wa = wave & 1, wb = wave >> 1;
+  const int wa = wave % (TA / 64), wb = wave / (TA / 64);
   // blocks are dealt round-robin to the 8 XCDs: the kt tiles of a row slice stay on one XCD
   const int xcd = blockIdx.x % 8, q = blockIdx.x / 8;
-  const int ka0 = (q % kt) * TA, y = xcd + 8 * (q / kt);
+  const int kq = q % kt, y = xcd + 8 * (q / kt);
+  const int ka0 = ka_base + kq * TA;
   const int64_t r_begin = (int64_t)y * a.rows_per_chunk;
   int64_t r_end = r_begin + a.rows_per_chunk;
   if (r_end > a.n_rows) r_end = a.n_rows;
@@ -342,11 +349,12 @@ __global__ __launch_bounds__(256) void wgrad2_kernel(const WgradArgs a, int kt, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][i][r] = 0.f;
   if (r_end > r_begin) {
-    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true>(a, ka0, r_begin, r_end, Xs, Zs, acc);
-    else wgrad2_run<H, KIND, false>(a, ka0, r_begin, r_end, Xs, Zs, acc);
+    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc);
+    else wgrad2_run<H, KIND, false, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc);
   }
+  // partial[y][column - ka_base][f]
   const int KaP = TA * kt;
-  float *out = a.partial + ((size_t)y * KaP + ka0 + 32 * (2 * wa)) * H + 32 * (wb * NB) + l32;
+  float *out = a.partial + ((size_t)y * KaP + kq * TA + 32 * (2 * wa)) * H + 32 * (wb * NB) + l32;
 #pragma unroll
   for (int m = 0; m < 2; ++m)
 #pragma unroll
@@ -355,6 +363,9 @@ __global__ __launch_bounds__(256) void wgrad2_kernel(const WgradArgs a, int kt, 
       for (int r = 0; r < 16; ++r)
         out[(size_t)(32 * m + acc_row(r, g)) * H + 32 * i] = acc[m][i][r];
 }
+
+template <int H, int TA>
+constexpr size_t wgrad2_lds_bytes() { return 2 * 32 * (size_t)(TA * 2 + 64) + 2 * 32 * (size_t)(H * 2 + 64); }
 
 // dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka (db may be null:
 // a product without a bias row). A block handles

@@ -107,6 +107,7 @@ struct xrl_ctx {
   int n_cu = 256;               // compute units of the device
   int max_lds = 65536;          // LDS bytes one block may use
   int64_t p_min_rows = 8192;    // smallest row count for the persistent kernels (XRL_PERSISTENT_MIN_ROWS)
+  int64_t wide_min_rows = 1 << 20;   // ... for the 256-column weight-gradient tiles (XRL_WGRAD_WIDE_MIN_ROWS)
   float *d_w = nullptr;         // flat fp32 weights
   int32_t *d_counter = nullptr; // kMaxFusedSlots per-state counters of policy_value_kernel, zero between launches
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
@@ -687,25 +688,72 @@ inline void wgrad_chunks(int64_t n_rows, int *rows_per_chunk, int *n_chunks) {
 inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H, int n_cu) {
   int rpc, nc;
   wgrad_chunks(n_rows, &rpc, &nc);
-  const Wgrad2Plan p = wgrad2_plan(n_rows, Ka, n_cu);
-  return std::max((size_t)nc * ((Ka + 1 + 63) / 64 * 64) * H, (size_t)p.ny * p.kt * 128 * H);
+  // transpose-read kernel: at most n_cu wide tiles of 256 columns plus 2 n_cu tiles of 128, or
+  // 2 n_cu tiles of 128 columns alone (see launch_wgrad_h)
+  const size_t wide = (size_t)n_cu * 256 * H + (size_t)2 * n_cu * 128 * H;
+  return std::max((size_t)nc * ((Ka + 1 + 63) / 64 * 64) * H, wide);
+}
+
+template <int H, int KIND, int TA>
+int launch_wgrad2(xrl_ctx *c, const WgradArgs &a, const Wgrad2Plan &p, int ka_base) {
+  constexpr size_t lds = wgrad2_lds_bytes<H, TA>();
+  auto kern = wgrad2_kernel<H, KIND, TA>;
+  static bool attr_set = false;          // one attribute per kernel instantiation
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  WgradArgs b = a;
+  b.rows_per_chunk = p.rows_per_slot;
+  b.n_chunks = p.ny;
+  kern<<<dim3((unsigned)(p.ny * p.kt)), dim3(2 * TA), lds, c->stream>>>(b, p.kt, p.ny, ka_base);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+template <int H, int TA>
+int launch_wgrad2_kind(xrl_ctx *c, int kind, const WgradArgs &a, const Wgrad2Plan &p, int ka_base) {
+  if (kind == WG_PLAIN) return launch_wgrad2<H, WG_PLAIN, TA>(c, a, p, ka_base);
+  if (kind == WG_EDGE) return launch_wgrad2<H, WG_EDGE, TA>(c, a, p, ka_base);
+  return launch_wgrad2<H, WG_NODE, TA>(c, a, p, ka_base);
 }
 
 template <typename T, int H>
 int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
   if (a.n_rows <= 0) return XRL_OK;
   const int64_t n = (int64_t)(a.Ka + 1) * H;
+  auto reduce = [&](const float *partial, int n_chunks, int KaP, int Ka, float *dw, float *dbias) {
+    const int64_t cnt = (int64_t)(Ka + (dbias ? 1 : 0)) * H;
+    if (cnt > 0)
+      wgrad_reduce_kernel<<<dim3((unsigned)((cnt + 31) / 32)), dim3(256), 0, c->stream>>>(partial, n_chunks, KaP, Ka, H,
+                                                                                         dw, dbias);
+  };
   if constexpr (sizeof(T) == 2) {
     if (kind != WG_EMBED) {                                // transpose-read kernel
-      const Wgrad2Plan p = wgrad2_plan(a.n_rows, a.Ka, c->n_cu);
-      a.rows_per_chunk = p.rows_per_slot;
-      a.n_chunks = p.ny;
-      const dim3 grid2((unsigned)(p.ny * p.kt));
-      if (kind == WG_PLAIN) wgrad2_kernel<H, WG_PLAIN><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
-      else if (kind == WG_EDGE) wgrad2_kernel<H, WG_EDGE><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
-      else wgrad2_kernel<H, WG_NODE><<<grid2, dim3(256), 0, c->stream>>>(a, p.kt, p.ny);
-      wgrad_reduce_kernel<<<dim3((unsigned)((n + 31) / 32)), dim3(256), 0, c->stream>>>(
-          a.partial, a.n_chunks, p.kt * 128, a.Ka, H, dW, db);
+      int rc;
+      const int k_main = kind == WG_PLAIN ? a.Ka : 2 * H;  // the H-wide column parts
+      bool wide = false;
+      if constexpr (H >= 128) wide = k_main % 256 == 0 && a.n_rows >= c->wide_min_rows;
+      if (wide) {
+        // wide tiles over the H-wide parts, then one launch of narrow tiles for the columns past them
+        // (edge attributes, the all-ones bias column)
+        if constexpr (H >= 128) {
+          const Wgrad2Plan pa = wgrad2_plan(a.n_rows, k_main / 256, c->n_cu, 1);
+          if ((rc = launch_wgrad2_kind<H, 256>(c, kind, a, pa, 0))) return rc;
+          reduce(a.partial, pa.ny, pa.kt * 256, k_main, dW, nullptr);
+          if (a.Ka > k_main || db) {
+            WgradArgs t = a;
+            t.partial = a.partial + (size_t)pa.ny * pa.kt * 256 * H;
+            const Wgrad2Plan pb = wgrad2_plan(a.n_rows, 1, c->n_cu, 2);
+            if ((rc = launch_wgrad2_kind<H, 128>(c, kind, t, pb, k_main))) return rc;
+            reduce(t.partial, pb.ny, 128, a.Ka - k_main, dW + (size_t)k_main * H, db);
+          }
+        }
+      } else {
+        const Wgrad2Plan p = wgrad2_plan(a.n_rows, (a.Ka + 1 + 127) / 128, c->n_cu, 2);
+        if ((rc = launch_wgrad2_kind<H, 128>(c, kind, a, p, 0))) return rc;
+        reduce(a.partial, p.ny, p.kt * 128, a.Ka, dW, db);
+      }
       HIP_TRY(hipGetLastError());
       return XRL_OK;
     }
@@ -1122,6 +1170,7 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   // default is where they start to win; 0 = always, a huge value = never)
   c->p_min_rows = 8192;
   if (const char *e = getenv("XRL_PERSISTENT_MIN_ROWS")) c->p_min_rows = atoll(e);
+  if (const char *e = getenv("XRL_WGRAD_WIDE_MIN_ROWS")) c->wide_min_rows = atoll(e);
   {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
