@@ -200,6 +200,16 @@ def test_backward_paper_feature_dimensions(xrl, precision):
     run_backward_case(xrl, model, state, weights_for(model))
 
 
+@pytest.mark.parametrize("hidden", [128, 256])
+def test_backward_wide_weight_gradient_tiles(xrl, hidden, monkeypatch):
+    """The 256-column tiles of the weight-gradient kernel (used from 2^20 rows on) forced onto a
+    small batch, where row slices are short and ragged."""
+    monkeypatch.setenv("XRL_WGRAD_WIDE_MIN_ROWS", "0")
+    model, state = synth.make_config(4, n_cand=3)
+    model.update(hidden=hidden, precision="bf16", rounds=2)
+    run_backward_case(xrl, model, state, weights_for(model))
+
+
 def test_backward_ppo_minibatch_subset_bf16(xrl):
     """Two states of the PPO-minibatch configuration with a reduced candidate count."""
     model, state = synth.make_config(5, n_states=2, n_cand=12)
