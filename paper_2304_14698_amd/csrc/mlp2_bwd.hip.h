@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
   constexpr bool SHARED = sizeof(T) == 2;
   constexpr int UF = MB * QB;                               // fragments per unit (H / 16 in bf16)
   constexpr int SPU = UF / MB;                              // layer-1 slabs per unit
-  constexpr int UG = MB < 4 ? MB : 4;                       // units per group
+  constexpr int UG = H >= 256 ? 4 : 2;                      // units per group (H <= 128: two blocks share a CU's LDS)
   using WG = WeightGroups<vec, UF, UG, SHARED>;
   using UFr = UnitFrags<vec, UF, UG, SHARED>;
 
@@ -389,6 +389,6 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
 // dynamic LDS of mlp2_bwd_kernel: four staging buffers, then (bf16) two groups of fragments
 template <typename T, int H>
 constexpr size_t mlp2_bwd_lds_bytes() {
-  constexpr int MB = H / 32, QB = 32 / (2 * Operand<T>::V), UG = MB < 4 ? MB : 4;
+  constexpr int MB = H / 32, QB = 32 / (2 * Operand<T>::V), UG = H >= 256 ? 4 : 2;
   return 4 * (size_t)BlockStage<float>::BYTES + (sizeof(T) == 2 ? 2 * (size_t)(MB * QB * UG) * 1024 : 0);
 }
