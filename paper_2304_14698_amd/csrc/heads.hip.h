@@ -565,24 +565,29 @@ __global__ __launch_bounds__(256) void rowmlp_bwd_kernel(const RowMlpBwdArgs a) 
 
 // Weight gradient of one affine layer over a modest number of rows, deterministic:
 //   dW[k, f] += sum_rows x[row, k] dz[row, f],  db[f] += sum_rows dz[row, f]
-// x = [x1 | x2] (x2 nullable). One thread per (k, f) walks the rows in order.
+// x = [x1 | x2] (x2 nullable). One thread per (k, f) walks a chunk of rows in order (blockIdx.y =
+// chunk). With one chunk the sums are added to dW / db directly; with several, chunk c writes
+// partial[c][k][f] (k = din is the bias row) and the fixed-order reduction of the weight-gradient
+// kernels adds them up.
 __global__ void small_wgrad_kernel(const float *x1, int w1, const float *x2, int w2,
-                                   const float *dz, int64_t n_rows, int din, int dout, float *dW,
-                                   float *db) {
+                                   const float *dz, int64_t n_rows, int rows_per_chunk, int din, int dout,
+                                   float *dW, float *db, float *partial) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)(din + 1) * dout) return;
   const int k = (int)(i / dout), f = (int)(i - (int64_t)k * dout);
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
+  const int64_t r1 = r0 + rows_per_chunk < n_rows ? r0 + rows_per_chunk : n_rows;
   float acc = 0.f;
   if (k == din) {
-    for (int64_t r = 0; r < n_rows; ++r) acc += dz[r * dout + f];
-    db[f] += acc;
+    for (int64_t r = r0; r < r1; ++r) acc += dz[r * dout + f];
+  } else if (k < w1) {
+    for (int64_t r = r0; r < r1; ++r) acc = fmaf(x1[r * w1 + k], dz[r * dout + f], acc);
   } else {
-    if (k < w1)
-      for (int64_t r = 0; r < n_rows; ++r) acc = fmaf(x1[r * w1 + k], dz[r * dout + f], acc);
-    else
-      for (int64_t r = 0; r < n_rows; ++r) acc = fmaf(x2[r * w2 + (k - w1)], dz[r * dout + f], acc);
-    dW[(size_t)k * dout + f] += acc;
+    for (int64_t r = r0; r < r1; ++r) acc = fmaf(x2[r * w2 + (k - w1)], dz[r * dout + f], acc);
   }
+  if (partial) partial[(size_t)blockIdx.y * (din + 1) * dout + i] = acc;
+  else if (k == din) db[f] += acc;
+  else dW[(size_t)k * dout + f] += acc;
 }
 
 // Clipped-surrogate objective of Section 3.3.4 and its derivatives w.r.t. the heads' outputs, one

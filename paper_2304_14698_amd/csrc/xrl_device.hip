@@ -808,17 +808,37 @@ int launch_rowmlp_bwd(xrl_ctx *c, const MlpRef &r, bool relu_last, float *const 
   return XRL_OK;
 }
 
-// dW, db of every layer of a small row-MLP: x of layer 0 is [x1 | x2], of layer l > 0 act[l-1]
+// dW, db of every layer of a small row-MLP: x of layer 0 is [x1 | x2], of layer l > 0 act[l-1].
+// Above kSmallWgradRows rows the rows are cut into chunks of that size (as many as `partial`,
+// partial_floats long, has room for) whose partial sums are reduced in chunk order.
+constexpr int kSmallWgradRows = 512;
+inline size_t small_wgrad_partial_floats(const MlpRef &r, int64_t n_rows) {
+  size_t big = 0;
+  for (int l = 0; l < r.n_layers; ++l) big = std::max(big, (size_t)(r.d_in[l] + 1) * r.d_out[l]);
+  const int64_t nc = (n_rows + kSmallWgradRows - 1) / kSmallWgradRows;
+  return nc > 1 ? big * (size_t)nc : 0;
+}
 int launch_small_wgrads(xrl_ctx *c, const MlpRef &r, const float *x1, int w1, const float *x2, int w2,
-                        float *const *act, float *const *dz, int64_t n_rows, float *dweights) {
+                        float *const *act, float *const *dz, int64_t n_rows, float *dweights,
+                        float *partial, size_t partial_floats) {
   if (n_rows <= 0) return XRL_OK;
   for (int l = 0; l < r.n_layers; ++l) {
     const int64_t n = (int64_t)(r.d_in[l] + 1) * r.d_out[l];
     const float *a1 = l == 0 ? x1 : act[l - 1];
     const int aw1 = l == 0 ? w1 : r.d_in[l];
-    small_wgrad_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream>>>(
-        a1, aw1, l == 0 ? x2 : nullptr, l == 0 ? w2 : 0, dz[l], n_rows, r.d_in[l], r.d_out[l],
-        dweights + r.w[l], dweights + r.b[l]);
+    int64_t nc = (n_rows + kSmallWgradRows - 1) / kSmallWgradRows;
+    if (partial && (size_t)nc * n > partial_floats) nc = (int64_t)(partial_floats / n);
+    if (!partial || nc < 2) nc = 1;
+    if (nc > 65535) nc = 65535;
+    const int64_t rpc = (n_rows + nc - 1) / nc;
+    nc = (n_rows + rpc - 1) / rpc;
+    float *dW = dweights + r.w[l], *db = dweights + r.b[l];
+    small_wgrad_kernel<<<dim3((unsigned)((n + 255) / 256), (unsigned)nc), dim3(256), 0, c->stream>>>(
+        a1, aw1, l == 0 ? x2 : nullptr, l == 0 ? w2 : 0, dz[l], n_rows, (int)rpc, r.d_in[l], r.d_out[l], dW, db,
+        nc > 1 ? partial : nullptr);
+    if (nc > 1)
+      wgrad_reduce_kernel<<<dim3((unsigned)((n + 31) / 32)), dim3(256), 0, c->stream>>>(
+          partial, (int)nc, r.d_in[l] + 1, r.d_in[l], r.d_out[l], dW, db);
   }
   HIP_TRY(hipGetLastError());
   return XRL_OK;
@@ -837,21 +857,26 @@ __global__ void demb_combine_kernel(float *demb, const float *dzs, const float *
   }
 }
 
-// dh[i, :] = dx[graph(i), :H] (divided by the graph's node count for the mean readout), stored in
-// the operand type like every later dh
+// dh[n, :] = dx[graph(n), :H] (divided by the graph's node count for the mean readout), stored in
+// the operand type like every later dh; one thread per four columns
 template <typename T>
 __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *node_graph,
                                        const int32_t *graph_node_ptr, int mean, int64_t N, int H, T *dh) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= N * H) return;
-  const int64_t n = i / H;
-  const int f = (int)(i - n * H), gph = node_graph[n];
-  float v = dx[(size_t)gph * ldx + f];
+  const int q = H / 4;
+  if (i >= N * q) return;
+  const int64_t n = i / q;
+  const int f = (int)(i - n * q) * 4, gph = node_graph[n];
+  float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = dx[(size_t)gph * ldx + f + j];
   if (mean) {
     const int cnt = graph_node_ptr[gph + 1] - graph_node_ptr[gph];
-    v /= (float)(cnt > 1 ? cnt : 1);
+    const float d = (float)(cnt > 1 ? cnt : 1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] /= d;
   }
-  dh[i] = (T)v;
+  store4<T>(dh + (size_t)n * H + f, v);
 }
 
 template <typename T>
@@ -895,9 +920,9 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   // ---- global-update layer backward
   float *ract[3] = {c->ro_act[0], c->ro_act[1], nullptr};
   if ((rc = launch_rowmlp_bwd(c, c->L.readout, true, ract, d_demb, G, rdz, rdx))) return rc;
-  if ((rc = launch_small_wgrads(c, c->L.readout, c->pool, H, d.graph_global, Dg, ract, rdz, G, dweights))) return rc;
+  if ((rc = launch_small_wgrads(c, c->L.readout, c->pool, H, d.graph_global, Dg, ract, rdz, G, dweights, partial, part))) return rc;
   if (N > 0)
-    broadcast_dpool_kernel<T><<<dim3((unsigned)((N * H + 255) / 256)), dim3(256), 0, c->stream>>>(
+    broadcast_dpool_kernel<T><<<dim3((unsigned)((N * (H / 4) + 255) / 256)), dim3(256), 0, c->stream>>>(
         rdx, H + Dg, d.node_graph, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, N, H, dhA);
 
   Mlp2BwdArgs a;
@@ -1346,6 +1371,8 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   acc(G); acc(S);                                                     // dlogit, 1/|valid|
   acc(G * h0); acc(G * h1); acc(G);                                   // policy dz
   acc(S * h0); acc(S * h1); acc(S); acc(S * H);                       // value dz, dz_mean
+  const size_t spart_floats = std::max(small_wgrad_partial_floats(c->L.policy, G), small_wgrad_partial_floats(c->L.value, S));
+  acc(spart_floats);                                                  // chunk partials of the heads' weight gradients
   if ((rc = ensure_hws(c, need))) return rc;
   Bump bump{c->hws};
   float *logit = bump.take<float>(G), *logp = bump.take<float>(G), *ent = bump.take<float>(S);
@@ -1358,6 +1385,7 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   float *pdz[3] = {bump.take<float>(G * h0), bump.take<float>(G * h1), bump.take<float>(G)};
   float *vdz[3] = {bump.take<float>(S * h0), bump.take<float>(S * h1), bump.take<float>(S)};
   float *dzs = bump.take<float>(S * H);
+  float *spart = spart_floats ? bump.take<float>(spart_floats) : nullptr;
   const xrl_batch_device &d = b->dev;
   // forward of the heads, keeping every layer's output
   if ((rc = launch_heads(c, b, d_emb, logit, logp, ent, action, zmean, value, pact, vact))) return rc;
@@ -1368,8 +1396,8 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   if ((rc = launch_rowmlp_bwd(c, c->L.value, false, vact, d_dvalue, S, vdz, dzs))) return rc;
   demb_combine_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(d_demb, dzs, inv_n, d.mask,
                                                                     d.state_graph_ptr, H);
-  if ((rc = launch_small_wgrads(c, c->L.policy, d_emb, H, nullptr, 0, pact, pdz, G, d_dweights))) return rc;
-  if ((rc = launch_small_wgrads(c, c->L.value, zmean, H, nullptr, 0, vact, vdz, S, d_dweights))) return rc;
+  if ((rc = launch_small_wgrads(c, c->L.policy, d_emb, H, nullptr, 0, pact, pdz, G, d_dweights, spart, spart_floats))) return rc;
+  if ((rc = launch_small_wgrads(c, c->L.value, zmean, H, nullptr, 0, vact, vdz, S, d_dweights, spart, spart_floats))) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
