@@ -195,7 +195,8 @@ __device__ __forceinline__ bf16x8 lds_tr_operand(const char *p, int row_stride) 
 template <int H, int KIND, bool TAIL, int TA>
 __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t r_begin, int64_t r_end,
                                            char (*Xs)[32 * (TA * 2 + 64)], char (*Zs)[32 * (H * 2 + 64)],
-                                           f32x16 (&acc)[2][H / 64 > 0 ? H / 64 : 1]) {
+                                           f32x16 (&acc)[2][H / 64 > 0 ? H / 64 : 1], bool do_bias,
+                                           float (&bsum)[8]) {
   using T = bf16_t;
   using vec = bf16x8;
   constexpr int RS = 32, NT = 2 * TA;                      // TA / 64 x 2 waves
@@ -282,6 +283,14 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
     }
   };
 
+  // column sums of dZ (the bias gradient) from the vectors this thread stages: all of them cover
+  // the same eight columns (NT is a multiple of H / 8)
+  auto add_bias = [&](const vec (&z)[ZV]) {
+#pragma unroll
+    for (int c = 0; c < ZV; ++c)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) bsum[j] += (float)z[c][j];
+  };
   int ix0[2], ix1[2];
   vec xn[2], zn[ZV];
   load_idx(0, ix0);
@@ -289,6 +298,7 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   load_x(0, ix0, xn);
   load_z(0, zn);
   commit(0, xn, zn);
+  if (do_bias) add_bias(zn);
   __syncthreads();
   // per-lane offsets of the transpose reads: row 8 g + L / 4, 8 bytes at 16-bit column 16 half + 4 (L % 4)
   const int L = lane & 15, half = (lane >> 4) & 1;
@@ -314,6 +324,7 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
         for (int i = 0; i < NB; ++i) Operand<T>::mma(xa[m], xb[i], acc[m][i]);
     }
     commit((st + 1) & 1, xn, zn);
+    if (do_bias && st + 1 < n_stage) add_bias(zn);
     __syncthreads();
     ix1[0] = ix2[0]; ix1[1] = ix2[1];
   }
@@ -322,8 +333,12 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
 // TA = X columns per block: 128 (four waves, two blocks per CU) or 256 (eight waves, one block
 // per CU: X enters once, dZ once per 256 instead of once per 128 columns). ka_base = first column
 // of the launch's tiles (a launch may cover only the columns past the H-wide parts).
+// bias_row >= 0: the column sums of dZ are taken on the vector ALU by the first tile's block of
+// every row slice and stored as row bias_row of the slice's partial (then no tile has to hold the
+// all-ones column); KaP = rows per slice of the partial array.
 template <int H, int KIND, int TA>
-__global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int kt, int ny, int ka_base) {
+__global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int kt, int ny, int ka_base, int KaP,
+                                                        int bias_row) {
   constexpr int RS = 32;
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;
@@ -348,12 +363,28 @@ __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int k
     for (int i = 0; i < NB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][i][r] = 0.f;
+  const bool do_bias = bias_row >= 0 && kq == 0;
+  float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (r_end > r_begin) {
-    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc);
-    else wgrad2_run<H, KIND, false, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc);
+    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
+    else wgrad2_run<H, KIND, false, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
+  }
+  if (do_bias) {
+    // thread t holds columns 8 (t % (H / 8)) ..; the 2 TA / (H / 8) threads of a column chunk are
+    // added in thread order (the stage loop ended with a barrier: the tile buffers are free)
+    constexpr int NT = 2 * TA, CH = H / 8, NG = NT / CH;
+    float *red = reinterpret_cast<float *>(smem);          // [NG][H]
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[(t / CH) * H + 8 * (t % CH) + j] = bsum[j];
+    __syncthreads();
+    for (int f = t; f < H; f += NT) {
+      float sum = red[f];
+      for (int k = 1; k < NG; ++k) sum += red[k * H + f];
+      a.partial[((size_t)y * KaP + bias_row) * H + f] = sum;
+    }
   }
   // partial[y][column - ka_base][f]
-  const int KaP = TA * kt;
   float *out = a.partial + ((size_t)y * KaP + kq * TA + 32 * (2 * wa)) * H + 32 * (wb * NB) + l32;
 #pragma unroll
   for (int m = 0; m < 2; ++m)

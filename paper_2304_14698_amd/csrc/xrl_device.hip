@@ -695,7 +695,7 @@ inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H, int n_cu) {
 }
 
 template <int H, int KIND, int TA>
-int launch_wgrad2(xrl_ctx *c, const WgradArgs &a, const Wgrad2Plan &p, int ka_base) {
+int launch_wgrad2(xrl_ctx *c, const WgradArgs &a, const Wgrad2Plan &p, int ka_base, int KaP, int bias_row) {
   constexpr size_t lds = wgrad2_lds_bytes<H, TA>();
   auto kern = wgrad2_kernel<H, KIND, TA>;
   static bool attr_set = false;          // one attribute per kernel instantiation
@@ -706,16 +706,17 @@ int launch_wgrad2(xrl_ctx *c, const WgradArgs &a, const Wgrad2Plan &p, int ka_ba
   WgradArgs b = a;
   b.rows_per_chunk = p.rows_per_slot;
   b.n_chunks = p.ny;
-  kern<<<dim3((unsigned)(p.ny * p.kt)), dim3(2 * TA), lds, c->stream>>>(b, p.kt, p.ny, ka_base);
+  kern<<<dim3((unsigned)(p.ny * p.kt)), dim3(2 * TA), lds, c->stream>>>(b, p.kt, p.ny, ka_base, KaP, bias_row);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
 
 template <int H, int TA>
-int launch_wgrad2_kind(xrl_ctx *c, int kind, const WgradArgs &a, const Wgrad2Plan &p, int ka_base) {
-  if (kind == WG_PLAIN) return launch_wgrad2<H, WG_PLAIN, TA>(c, a, p, ka_base);
-  if (kind == WG_EDGE) return launch_wgrad2<H, WG_EDGE, TA>(c, a, p, ka_base);
-  return launch_wgrad2<H, WG_NODE, TA>(c, a, p, ka_base);
+int launch_wgrad2_kind(xrl_ctx *c, int kind, const WgradArgs &a, const Wgrad2Plan &p, int ka_base, int KaP,
+                       int bias_row = -1) {
+  if (kind == WG_PLAIN) return launch_wgrad2<H, WG_PLAIN, TA>(c, a, p, ka_base, KaP, bias_row);
+  if (kind == WG_EDGE) return launch_wgrad2<H, WG_EDGE, TA>(c, a, p, ka_base, KaP, bias_row);
+  return launch_wgrad2<H, WG_NODE, TA>(c, a, p, ka_base, KaP, bias_row);
 }
 
 template <typename T, int H>
@@ -734,24 +735,33 @@ int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
       const int k_main = kind == WG_PLAIN ? a.Ka : 2 * H;  // the H-wide column parts
       bool wide = false;
       if constexpr (H >= 128) wide = k_main % 256 == 0 && a.n_rows >= c->wide_min_rows;
+      // PLAIN and NODE have one column past the H-wide parts, the all-ones bias column: its sums
+      // come from the vector ALU of the first tile's blocks (EDGE also has the edge attributes
+      // there and keeps them on the matrix cores)
+      const bool only_bias = kind != WG_EDGE && a.Ka == k_main && k_main % 128 == 0;
       if (wide) {
-        // wide tiles over the H-wide parts, then one launch of narrow tiles for the columns past them
-        // (edge attributes, the all-ones bias column)
         if constexpr (H >= 128) {
           const Wgrad2Plan pa = wgrad2_plan(a.n_rows, k_main / 256, c->n_cu, 1);
-          if ((rc = launch_wgrad2_kind<H, 256>(c, kind, a, pa, 0))) return rc;
-          reduce(a.partial, pa.ny, pa.kt * 256, k_main, dW, nullptr);
-          if (a.Ka > k_main || db) {
+          const int KaP = k_main + (only_bias && db ? 1 : 0);
+          if ((rc = launch_wgrad2_kind<H, 256>(c, kind, a, pa, 0, KaP, only_bias && db ? k_main : -1))) return rc;
+          reduce(a.partial, pa.ny, KaP, k_main, dW, only_bias ? db : nullptr);
+          if (!only_bias) {
+            // one launch of narrow tiles for the columns past the H-wide parts
             WgradArgs t = a;
-            t.partial = a.partial + (size_t)pa.ny * pa.kt * 256 * H;
+            t.partial = a.partial + (size_t)pa.ny * KaP * H;
             const Wgrad2Plan pb = wgrad2_plan(a.n_rows, 1, c->n_cu, 2);
-            if ((rc = launch_wgrad2_kind<H, 128>(c, kind, t, pb, k_main))) return rc;
+            if ((rc = launch_wgrad2_kind<H, 128>(c, kind, t, pb, k_main, 128))) return rc;
             reduce(t.partial, pb.ny, 128, a.Ka - k_main, dW + (size_t)k_main * H, db);
           }
         }
+      } else if (only_bias) {
+        const Wgrad2Plan p = wgrad2_plan(a.n_rows, k_main / 128, c->n_cu, 2);
+        const int KaP = k_main + (db ? 1 : 0);
+        if ((rc = launch_wgrad2_kind<H, 128>(c, kind, a, p, 0, KaP, db ? k_main : -1))) return rc;
+        reduce(a.partial, p.ny, KaP, a.Ka, dW, db);
       } else {
         const Wgrad2Plan p = wgrad2_plan(a.n_rows, (a.Ka + 1 + 127) / 128, c->n_cu, 2);
-        if ((rc = launch_wgrad2_kind<H, 128>(c, kind, a, p, 0))) return rc;
+        if ((rc = launch_wgrad2_kind<H, 128>(c, kind, a, p, 0, p.kt * 128))) return rc;
         reduce(a.partial, p.ny, p.kt * 128, a.Ka, dW, db);
       }
       HIP_TRY(hipGetLastError());
