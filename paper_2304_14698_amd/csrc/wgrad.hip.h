@@ -25,6 +25,7 @@ struct WgradArgs {
   const float *node_dense;
   int De, Tn, Dd;
   const void *dZ;           // [rows, H] operand type
+  const void *zero_row;     // 1 KB of zeros (stands in for the received sums of nodes without in-edges)
   float *partial;           // [n_chunks, KaP, H], KaP = 64 * gridDim.x
 };
 
@@ -244,8 +245,11 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
         const vec v = *(const vec *)(gbase + (size_t)ix[c] * H);
         x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (!TAIL && KIND == WG_NODE) {
-        const vec v = *(const vec *)(nbase + (size_t)row * H);
-        x[c] = on && (!second || ix[c] > 0) ? v : Operand<T>::zero();
+        // (a node without in-edges reads zeros through the address, not through a select on the
+        // loaded value: the latter made the compiler wait for the load on the spot)
+        const T *p = second && ix[c] <= 0 ? (const T *)a.zero_row + (xc - H) : nbase + (size_t)row * H;
+        const vec v = *(const vec *)p;
+        x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (KIND == WG_EDGE) {              // [edge attributes | 1 | 0 ...]
         // every lane loads and uses an attribute (times 0 or 1, plus the bias column's 1): a
         // select would let the compiler move the loads into branches with waits behind them
