@@ -176,7 +176,6 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     const vec *W1 = (const vec *)a.W1s + lane;              // (vec and vec1 are both 16 bytes)
     const int n_frag = a.nslab1 * MB, n_units = (a.nslab1 + SPU - 1) / SPU;
     [[maybe_unused]] const T *pa = nullptr, *pb = nullptr;
-    [[maybe_unused]] bool has_in = true;
     [[maybe_unused]] EmbedRow er;
     if constexpr (KIND == KIND_EDGE) {
       src = a.in_src[row];
@@ -186,7 +185,6 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
     } else if constexpr (KIND == KIND_NODE) {
       pa = (const T *)a.h + (size_t)row * H + g * V;
       pb = (const T *)a.agg + (size_t)row * H + g * V;
-      has_in = a.in_ptr[row + 1] > a.in_ptr[row];
     } else {
       er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
     }
@@ -202,7 +200,7 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
       static_assert(NSU % UG == 0, "the H-wide parts fill whole groups");
       auto load_slab = [&](int s) -> vec {
         if (s < HS) return *(const vec *)(pa + s * SL);
-        return has_in ? *(const vec *)(pb + (s - HS) * SL) : Opd::zero();
+        return *(const vec *)(pb + (s - HS) * SL);   // (the forward zeroed the received sums of nodes without in-edges)
       };
       vec xq[XQ];
 #pragma unroll

@@ -25,7 +25,6 @@ struct WgradArgs {
   const float *node_dense;
   int De, Tn, Dd;
   const void *dZ;           // [rows, H] operand type
-  const void *zero_row;     // 1 KB of zeros (stands in for the received sums of nodes without in-edges)
   float *partial;           // [n_chunks, KaP, H], KaP = 64 * gridDim.x
 };
 
@@ -223,13 +222,12 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
     return row < r_end ? row : r_end - 1;
   };
   auto live = [&](int st, int c) { return r_begin + (int64_t)st * RS + xr + 16 * c < r_end; };
-  // row indices (EDGE) or in-degrees (NODE) of stage st, which may be past the end
+  // row indices (EDGE) of stage st, which may be past the end
   auto load_idx = [&](int st, int (&ix)[2]) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       ix[c] = 0;
       if constexpr (!TAIL && KIND == WG_EDGE) ix[c] = idx_arr[row_of(st, c)];
-      if constexpr (!TAIL && KIND == WG_NODE) ix[c] = a.in_ptr[row_of(st, c) + 1] - a.in_ptr[row_of(st, c)];
     }
   };
   auto load_x = [&](int st, const int (&ix)[2], vec (&x)[2]) {
@@ -245,10 +243,9 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
         const vec v = *(const vec *)(gbase + (size_t)ix[c] * H);
         x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (!TAIL && KIND == WG_NODE) {
-        // (a node without in-edges reads zeros through the address, not through a select on the
-        // loaded value: the latter made the compiler wait for the load on the spot)
-        const T *p = second && ix[c] <= 0 ? (const T *)a.zero_row + (xc - H) : nbase + (size_t)row * H;
-        const vec v = *(const vec *)p;
+        // (the forward zeroed the received sums of nodes without in-edges: read as they are. A
+        // select on the loaded value here made the compiler wait for the load on the spot.)
+        const vec v = *(const vec *)(nbase + (size_t)row * H);
         x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (KIND == WG_EDGE) {              // [edge attributes | 1 | 0 ...]
         // every lane loads and uses an attribute (times 0 or 1, plus the bias column's 1): a

@@ -945,7 +945,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   memset(&wa, 0, sizeof(wa));
   wa.in_ptr = d.in_ptr; wa.in_src = d.in_src; wa.in_dst = d.in_dst; wa.edge_feat = d.edge_feat;
   wa.node_op = d.node_op; wa.node_dense = d.node_dense; wa.De = De; wa.Tn = m.n_op_types; wa.Dd = m.n_node_dense;
-  wa.partial = partial; wa.zero_row = c->zero_row;
+  wa.partial = partial;
   auto set_w = [&](const EncMlp &e) {
     a.W1s = e.W1s; a.W2s = e.W2s; a.W2bt = e.W2bt; a.W1bt = e.W1bt; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
   };
