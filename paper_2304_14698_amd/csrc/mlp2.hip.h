@@ -131,17 +131,32 @@ __device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeT
   for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nb][r] = relu_f32(acc[nb][r]);
-  for (int d = 1; __any(rem >= d); d <<= 1) {
-    const bool take = rem >= d;
-    const int from = ((lane + d) & 63) << 2;
+  // (the lane's partner value enters through a product with 0 or 1: one fused multiply-add per
+  // register instead of a select and an add; the values are finite sums of ReLU outputs)
+  if (__any(rem >= 1)) {
+    // first step, the only one for in-degrees up to 2: the neighbouring lane's value by a
+    // wave-wide shift (no LDS traffic)
+    const float takef = rem >= 1 ? 1.f : 0.f;
 #pragma unroll
     for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         // (a copy first: bit-casting the vector-element lvalue itself reads element 0)
         const float v = acc[nb][r];
+        const float t = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false));
+        acc[nb][r] = fmaf(t, takef, v);
+      }
+  }
+  for (int d = 2; __any(rem >= d); d <<= 1) {
+    const float takef = rem >= d ? 1.f : 0.f;
+    const int from = ((lane + d) & 63) << 2;
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float v = acc[nb][r];
         const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
-        acc[nb][r] = v + (take ? t : 0.f);
+        acc[nb][r] = fmaf(t, takef, v);
       }
   }
   const bool ends_tile = l32 + rem == nv - 1;
