@@ -265,13 +265,14 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
 #pragma unroll
       for (int d = 1; d < 32; d <<= 1) {                        // see edge_tile_sum
         if (__any(rem >= d)) {
-          const bool take = rem >= d;
+          const float takef = rem >= d ? 1.f : 0.f;
           const int from = ((lane + d) & 63) << 2;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float v = acc[r];
-            const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
-            acc[r] = v + (take ? t : 0.f);
+            const float t = d == 1 ? __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false))
+                                   : __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
+            acc[r] = fmaf(t, takef, v);
           }
         }
       }
