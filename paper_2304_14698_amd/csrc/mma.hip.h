@@ -129,6 +129,22 @@ __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float *v) {
   *(u32x2 *)p = u32x2{cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3])};
 }
 
+// four consecutive features of one row in their stored form
+template <typename T>
+struct Quad;
+template <>
+struct Quad<float> {
+  typedef f32x4 type;
+  static __device__ __forceinline__ type pack(const float *v) { return f32x4{v[0], v[1], v[2], v[3]}; }
+};
+template <>
+struct Quad<bf16_t> {
+  typedef unsigned type __attribute__((ext_vector_type(2)));
+  static __device__ __forceinline__ type pack(const float *v) {
+    return type{cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3])};
+  }
+};
+
 // Writes a features x rows accumulator tile (feature block fb) to a row-major [rows, H] array:
 // lane = row, register quads = four consecutive features.
 template <typename TO, int H>
@@ -182,7 +198,20 @@ template <typename T, int H, bool RELU, typename RowDst>
 __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[H / 32], char *stage, int lane,
                                                    RowDst row_dst) {
   using S = RowStage<T, H>;
+  using Q = typename Quad<T>::type;
   const int l32 = lane & 31, g = lane >> 5;
+  // converted once, before the passes (inside a pass only the lanes of its rows are active, and
+  // every pass would repeat the conversions)
+  Q quad[H / 32][4];
+#pragma unroll
+  for (int nb = 0; nb < H / 32; ++nb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = RELU ? relu_f32(acc[nb][4 * q + j]) : acc[nb][4 * q + j];
+      quad[nb][q] = Quad<T>::pack(v);
+    }
 #pragma unroll
   for (int p = 0; p < 32 / S::RP; ++p) {
     if (l32 / S::RP == p) {
@@ -190,12 +219,7 @@ __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[H / 32], 
 #pragma unroll
       for (int nb = 0; nb < H / 32; ++nb)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float v[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = RELU ? relu_f32(acc[nb][4 * q + j]) : acc[nb][4 * q + j];
-          store4<T>((T *)(wp + (32 * nb + 8 * q) * (int)sizeof(T)), v);
-        }
+        for (int q = 0; q < 4; ++q) *(Q *)(wp + (32 * nb + 8 * q) * (int)sizeof(T)) = quad[nb][q];
     }
     wave_lds_fence();
 #pragma unroll
