@@ -220,6 +220,20 @@ int xrl_segment_sum(xrl_ctx *ctx, const float *d_values, const int32_t *d_ptr, i
 int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32_t round,
                        float *d_out);
 
+/* xrl_weight_gradient: dW[k, f] += sum over rows of X[row, k] dZ[row, f] and db[f] += sum over
+ * rows of dZ[row, f] -- the weight gradient of one affine layer of the encoder's MLPs as
+ * xrl_encode_backward computes it (Section 3.3.4), exposed so that the product can be checked and
+ * timed on its own. kind XRL_WG_PLAIN: X = d_x [n_rows, H]. XRL_WG_EDGE: X = [h[sender] |
+ * h[receiver] | edge attributes] over the batch's E edges in receiver order, d_x = h [N, H].
+ * XRL_WG_NODE: X = [h | received sums], d_x = h, d_x2 = the sums, both [N, H], the sums' rows of
+ * nodes without in-edges zero as xrl_encode leaves them (n_rows is ignored for these two kinds).
+ * d_x, d_x2 and d_dZ [rows, H] are device arrays in the ctx's operand type (fp32, or bf16 bit
+ * patterns); d_dW [K, H] (K = columns of X) and d_db [H] are device fp32 and are accumulated
+ * into. Deterministic. Uses the backward's scratch. Errors: NULL, STATE, INDEX, SHAPE, OOM, HIP. */
+enum { XRL_WG_PLAIN = 0, XRL_WG_EDGE = 1, XRL_WG_NODE = 2 };
+int xrl_weight_gradient(xrl_ctx *ctx, const xrl_batch *b, int32_t kind, const void *d_x, const void *d_x2,
+                        const void *d_dZ, int64_t n_rows, float *d_dW, float *d_db);
+
 /* Per-kernel timing for roofline measurement. While enabled, every launch group of the forward
  * path and of the encoder's backward is bracketed by HIP events on the ctx stream.
  * xrl_read_timing synchronises the stream, returns the summed duration and launch count

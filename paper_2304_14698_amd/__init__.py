@@ -55,7 +55,7 @@ EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_ppo_objective", "xrl_segment_sum",
            "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
-           "xrl_edge_features_from_shapes", "xrl_last_error", "xrl_version"]
+           "xrl_edge_features_from_shapes", "xrl_weight_gradient", "xrl_last_error", "xrl_version"]
 
 
 def load_library():
@@ -87,6 +87,7 @@ def load_library():
     lib.xrl_encode_backward.argtypes = [vp] * 4
     lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.xrl_edge_features_from_shapes.argtypes = [vp, vp, i64, C.c_double, vp]
+    lib.xrl_weight_gradient.argtypes = [vp, vp, i32, vp, vp, vp, i64, vp, vp]
     lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
     lib.xrl_set_timing.argtypes = [vp, C.c_int]
     lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -286,6 +287,14 @@ class Encoder:
     def encode_backward(self, batch, demb, dweights):
         _check(self.lib.xrl_encode_backward(self.handle, batch.handle, demb.data_ptr(), dweights.data_ptr()))
         return dweights
+
+    def weight_gradient(self, batch, kind, x, dz, dW, db, x2=None):
+        """dW += X^T dz, db += column sums of dz (kind: "plain" | "edge" | "node"; see xrl.h)."""
+        k = dict(plain=0, edge=1, node=2)[kind]
+        _check(self.lib.xrl_weight_gradient(self.handle, batch.handle, k, x.data_ptr(),
+                                            x2.data_ptr() if x2 is not None else None, dz.data_ptr(),
+                                            x.shape[0], dW.data_ptr(), db.data_ptr()))
+        return dW, db
 
     def segment_sum(self, values, ptr, out=None):
         n_rows, width = values.shape

@@ -1541,6 +1541,36 @@ int xrl_segment_sum(xrl_ctx *c, const float *d_values, const int32_t *d_ptr, int
                                         (float *)c->ws);
 }
 
+int xrl_weight_gradient(xrl_ctx *c, const xrl_batch *b, int32_t kind, const void *d_x, const void *d_x2,
+                        const void *d_dZ, int64_t n_rows, float *d_dW, float *d_db) {
+  int rc = check_batch(c, b, "xrl_weight_gradient");
+  if (rc) return rc;
+  if (kind != XRL_WG_PLAIN && kind != XRL_WG_EDGE && kind != XRL_WG_NODE)
+    return fail(XRL_ERR_INDEX, "xrl_weight_gradient: unknown kind %d", kind);
+  const int H = c->m.hidden, De = c->m.d_edge;
+  if (kind == XRL_WG_EDGE) n_rows = b->E;
+  if (kind == XRL_WG_NODE) n_rows = b->N;
+  if (n_rows < 0) return fail(XRL_ERR_SHAPE, "xrl_weight_gradient: n_rows is negative");
+  if (n_rows == 0) return XRL_OK;
+  if (!d_x || !d_dZ || !d_dW || !d_db || (kind == XRL_WG_NODE && !d_x2))
+    return fail(XRL_ERR_NULL, "xrl_weight_gradient: NULL device pointer");
+  const int Ka = kind == XRL_WG_PLAIN ? H : (kind == XRL_WG_EDGE ? 2 * H + De : 2 * H);
+  const size_t part = wgrad_partial_floats(n_rows, Ka, H, c->n_cu);
+  if ((rc = ensure_bws(c, align_up(part * 4)))) return rc;
+  WgradArgs wa;
+  memset(&wa, 0, sizeof(wa));
+  const xrl_batch_device &d = b->dev;
+  wa.in_ptr = d.in_ptr; wa.in_src = d.in_src; wa.in_dst = d.in_dst; wa.edge_feat = d.edge_feat;
+  wa.node_op = d.node_op; wa.node_dense = d.node_dense; wa.De = De; wa.Tn = c->m.n_op_types; wa.Dd = c->m.n_node_dense;
+  wa.partial = (float *)c->bws;
+  wa.n_rows = n_rows; wa.Ka = Ka; wa.dZ = d_dZ;
+  if (kind == XRL_WG_PLAIN) wa.A = d_x;
+  else { wa.h = d_x; wa.agg = d_x2; }
+  const int wk = kind == XRL_WG_PLAIN ? WG_PLAIN : (kind == XRL_WG_EDGE ? WG_EDGE : WG_NODE);
+  Timed t(c, TK_WGRAD);
+  return c->elem == 2 ? launch_wgrad<bf16_t>(c, wk, wa, d_dW, d_db) : launch_wgrad<float>(c, wk, wa, d_dW, d_db);
+}
+
 int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t round, float *d_out) {
   int rc = check_batch(c, b, "xrl_get_activation");
   if (rc) return rc;
