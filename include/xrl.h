@@ -234,6 +234,20 @@ enum { XRL_WG_PLAIN = 0, XRL_WG_EDGE = 1, XRL_WG_NODE = 2 };
 int xrl_weight_gradient(xrl_ctx *ctx, const xrl_batch *b, int32_t kind, const void *d_x, const void *d_x2,
                         const void *d_dZ, int64_t n_rows, float *d_dW, float *d_db);
 
+/* xrl_mlp_backward: the gradients through one fused two-layer MLP of a message-passing round as
+ * xrl_encode_backward computes them (Section 3.3.4), on caller-given inputs, for per-step checks.
+ * For y = relu(relu(x W1 + b1) W2 + b2) of MLP (`kind`, `round`) and upstream dy:
+ *   z1 = relu(x W1 + b1), dz2 = dy * [y > 0], dz1 = (dz2 W2^T) * [z1 > 0], dx = dz1 W1^T.
+ * kind XRL_WG_EDGE: rows = the batch's E edges in receiver order, x = [h[sender] | h[receiver] |
+ * edge attrs], d_dy [N, H] is indexed by receiver (y is recomputed), d_dxa / d_dxb [E, H] =
+ * gradients w.r.t. h[sender] / h[receiver] per edge. XRL_WG_NODE: rows = N nodes, x = [d_h |
+ * d_agg], d_y [N, H] = the forward's output, d_dy [N, H], d_dxa / d_dxb [N, H] = gradients w.r.t.
+ * h / the received sums. Outputs d_z1, d_dz1, d_dz2 [rows, H]. All arrays are device memory in the
+ * ctx's operand type. Errors: NULL, STATE, INDEX, UNSUPPORTED (attention rounds), HIP. */
+int xrl_mlp_backward(xrl_ctx *ctx, const xrl_batch *b, int32_t kind, int32_t round, const void *d_h,
+                     const void *d_agg, const void *d_y, const void *d_dy, void *d_z1, void *d_dz1,
+                     void *d_dz2, void *d_dxa, void *d_dxb);
+
 /* Per-kernel timing for roofline measurement. While enabled, every launch group of the forward
  * path and of the encoder's backward is bracketed by HIP events on the ctx stream.
  * xrl_read_timing synchronises the stream, returns the summed duration and launch count

@@ -55,7 +55,7 @@ EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_ppo_objective", "xrl_segment_sum",
            "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
-           "xrl_edge_features_from_shapes", "xrl_weight_gradient", "xrl_last_error", "xrl_version"]
+           "xrl_edge_features_from_shapes", "xrl_weight_gradient", "xrl_mlp_backward", "xrl_last_error", "xrl_version"]
 
 
 def load_library():
@@ -88,6 +88,7 @@ def load_library():
     lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.xrl_edge_features_from_shapes.argtypes = [vp, vp, i64, C.c_double, vp]
     lib.xrl_weight_gradient.argtypes = [vp, vp, i32, vp, vp, vp, i64, vp, vp]
+    lib.xrl_mlp_backward.argtypes = [vp, vp, i32, i32] + [vp] * 9
     lib.xrl_get_activation.argtypes = [vp, vp, C.c_char_p, i32, vp]
     lib.xrl_set_timing.argtypes = [vp, C.c_int]
     lib.xrl_read_timing.argtypes = [vp, C.c_char_p, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -287,6 +288,17 @@ class Encoder:
     def encode_backward(self, batch, demb, dweights):
         _check(self.lib.xrl_encode_backward(self.handle, batch.handle, demb.data_ptr(), dweights.data_ptr()))
         return dweights
+
+    def mlp_backward(self, batch, kind, rnd, h, dy, agg=None, y=None):
+        """Gradients through the edge / node MLP of round `rnd` on given inputs (see xrl.h):
+        returns dict(z1, dz1, dz2, dxa, dxb), tensors of the operand type."""
+        t = self.torch
+        rows = batch.E if kind == "edge" else batch.N
+        o = {k: t.empty((rows, self.H), dtype=h.dtype, device="cuda") for k in ("z1", "dz1", "dz2", "dxa", "dxb")}
+        p = lambda x: None if x is None else x.data_ptr()
+        _check(self.lib.xrl_mlp_backward(self.handle, batch.handle, dict(edge=1, node=2)[kind], rnd, p(h), p(agg),
+                                         p(y), p(dy), p(o["z1"]), p(o["dz1"]), p(o["dz2"]), p(o["dxa"]), p(o["dxb"])))
+        return o
 
     def weight_gradient(self, batch, kind, x, dz, dW, db, x2=None):
         """dW += X^T dz, db += column sums of dz (kind: "plain" | "edge" | "node"; see xrl.h)."""

@@ -1571,6 +1571,32 @@ int xrl_weight_gradient(xrl_ctx *c, const xrl_batch *b, int32_t kind, const void
   return c->elem == 2 ? launch_wgrad<bf16_t>(c, wk, wa, d_dW, d_db) : launch_wgrad<float>(c, wk, wa, d_dW, d_db);
 }
 
+int xrl_mlp_backward(xrl_ctx *c, const xrl_batch *b, int32_t kind, int32_t round, const void *d_h,
+                     const void *d_agg, const void *d_y, const void *d_dy, void *d_z1, void *d_dz1,
+                     void *d_dz2, void *d_dxa, void *d_dxb) {
+  int rc = check_batch(c, b, "xrl_mlp_backward");
+  if (rc) return rc;
+  if (c->m.round_kind != XRL_ROUND_MLP) return fail(XRL_ERR_UNSUPPORTED, "xrl_mlp_backward: MLP rounds only");
+  if (kind != XRL_WG_EDGE && kind != XRL_WG_NODE) return fail(XRL_ERR_INDEX, "xrl_mlp_backward: unknown kind %d", kind);
+  if (round < 0 || round >= c->m.rounds) return fail(XRL_ERR_INDEX, "xrl_mlp_backward: round %d outside [0, %d)", round, c->m.rounds);
+  const int64_t rows = kind == XRL_WG_EDGE ? b->E : b->N;
+  if (rows == 0) return XRL_OK;
+  if (!d_h || !d_dy || !d_z1 || !d_dz1 || !d_dz2 || !d_dxa || !d_dxb || (kind == XRL_WG_NODE && (!d_agg || !d_y)))
+    return fail(XRL_ERR_NULL, "xrl_mlp_backward: NULL device pointer");
+  const xrl_batch_device &d = b->dev;
+  Mlp2BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.De = c->m.d_edge; a.Tn = c->m.n_op_types; a.Dd = c->m.n_node_dense;
+  a.in_ptr = d.in_ptr; a.in_src = d.in_src; a.in_dst = d.in_dst;
+  a.edge_feat = d.edge_feat; a.node_op = d.node_op; a.node_dense = d.node_dense;
+  const EncMlp &e = kind == XRL_WG_EDGE ? c->edge[round] : c->node[round];
+  a.W1s = e.W1s; a.W2s = e.W2s; a.W2bt = e.W2bt; a.W1bt = e.W1bt; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
+  a.n_rows = rows; a.h = d_h; a.agg = d_agg; a.y = d_y; a.dy = d_dy;
+  a.z1 = d_z1; a.dz1 = d_dz1; a.dz2 = d_dz2; a.dx_a = d_dxa; a.dx_b = d_dxb;
+  const int k = kind == XRL_WG_EDGE ? KIND_EDGE : KIND_NODE;
+  return c->elem == 2 ? launch_mlp2_bwd<bf16_t>(c, k, a) : launch_mlp2_bwd<float>(c, k, a);
+}
+
 int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t round, float *d_out) {
   int rc = check_batch(c, b, "xrl_get_activation");
   if (rc) return rc;
