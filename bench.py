@@ -150,7 +150,7 @@ def main():
     for _ in range(args.steps):
         step()
     kern = {}
-    names = ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads")
+    names = ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads", "resident")
     if backward:
         names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad", "grad_gather", "gat_bwd")
     for k in names:
@@ -191,6 +191,18 @@ def main():
                         unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
         kernels_us=kern,
     )
+    if kern["resident"]["launches_per_step"] > 0:
+        # small batch: the encoder ran as one launch (a block per graph), rated as a whole
+        enc_flops = 2.0 * N * H * (De + model["n_op_types"] + model["n_node_dense"] + H) \
+            + R * (edge_flops + 2.0 * N * H * 3 * H)
+        enc_s = kern["resident"]["avg_us"] * 1e-6
+        enc_bytes = (R + 1) * N * H * b + R * n_recv * H * b + E * De * 4 + 4 * (3 * E + 3 * N) + G * H * 4
+        res["roofline"] = dict(bound="mfma", kernel="one-launch encoder (node-update layer, all rounds, readout)",
+                               achieved=enc_flops / enc_s / 1e12, peak=peak, unit="TFLOP/s",
+                               frac=enc_flops / enc_s / 1e12 / peak, traffic=None, flops_per_launch=enc_flops,
+                               avg_launch_us=kern["resident"]["avg_us"], algorithmic_bytes_per_launch=enc_bytes,
+                               hbm_frac=enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS)
+        res.pop("hbm_kernel")
     if args.round_kind == "gat":
         # attention rounds: the dense part z = h W on the matrix cores, then a gather-bound pass
         # (per edge one z row read, per node its own row read and one row written, scores, indices)

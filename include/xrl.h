@@ -105,6 +105,12 @@ typedef struct xrl_packed_view {
   const int32_t *tile_ptr;        /* [n_tiles+1] first receiver-order edge of each tile: 1..32
                                      edges per tile, cut at receiver boundaries except inside a
                                      receiver with more than 32 in-edges                      */
+  int64_t n_graph_tiles;          /* per-graph tiles for the one-launch encoder of small
+                                     batches, 0 when the batch has none (more than 4096 graphs,
+                                     or a node with more than 32 in-edges)                     */
+  const int32_t *graph_tile_ptr;  /* [G+1] graph g owns tiles [graph_tile_ptr[g], [g+1])      */
+  const int32_t *gtile_ptr;       /* [n_graph_tiles+1] first edge of each: the same cutting
+                                     rule, and no tile spans two graphs                        */
 } xrl_packed_view;
 
 typedef struct xrl_ctx xrl_ctx;     /* device weights + workspaces, bound to one HIP stream    */
@@ -139,7 +145,11 @@ int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is acc
  * Environment, read here: XRL_PERSISTENT_MIN_ROWS = row count from which the persistent MLP
  * kernels replace the streaming one (default 8192; 0 = always; results agree within rounding);
  * XRL_WGRAD_WIDE_MIN_ROWS = row count from which the weight-gradient kernel uses 256-column
- * tiles (default 2^20; same sums in a different, equally fixed order). */
+ * tiles (default 2^20; same sums in a different, equally fixed order);
+ * XRL_RESIDENT_MAX_GRAPHS (default 256; 0 = never) and XRL_RESIDENT_MAX_TILES (default 4) =
+ * largest batch, in graphs and in 32-row tiles of nodes or edges per graph, that xrl_encode runs
+ * as one launch with a block per graph (message-passing rounds of the MLP kind, rows of at most
+ * 256 bytes, no receiver of more than 32 in-edges; results identical to the other path's). */
 int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip_stream,
                xrl_ctx **out);
 int xrl_set_weights(xrl_ctx *ctx, const float *weights_host);
@@ -253,7 +263,8 @@ int xrl_mlp_backward(xrl_ctx *ctx, const xrl_batch *b, int32_t kind, int32_t rou
  * xrl_read_timing synchronises the stream, returns the summed duration and launch count
  * recorded since the last read for `kernel` and forgets them. Forward: {"embed", "edge",
  * "edge_fixup", "node", "pool", "readout", "heads"} (the steps of Section 3.4 / 3.3.2 in
- * execution order; "gat_linear", "gat_aggregate" with XRL_ROUND_GAT). Backward (Section 3.3.4):
+ * execution order; "gat_linear", "gat_aggregate" with XRL_ROUND_GAT; "resident" = the whole
+ * encoder of a small batch in one launch). Backward (Section 3.3.4):
  * {"bwd_edge", "bwd_node", "bwd_embed"} = gradients through the fused MLPs, "wgrad" = both
  * layers' weight gradients of one MLP with their reductions, "grad_gather" = per-node sum of the
  * per-edge gradients; "gat_bwd" = one attention round's backward. Errors: NULL, INDEX, HIP. */

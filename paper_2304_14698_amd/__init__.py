@@ -47,7 +47,8 @@ class PackedView(C.Structure):
                 ("in_ptr", C.c_void_p), ("in_src", C.c_void_p), ("in_dst", C.c_void_p),
                 ("in_eid", C.c_void_p), ("out_ptr", C.c_void_p), ("out_pos", C.c_void_p),
                 ("node_graph", C.c_void_p), ("edge_feat", C.c_void_p),
-                ("n_tiles", C.c_int64), ("tile_ptr", C.c_void_p)]
+                ("n_tiles", C.c_int64), ("tile_ptr", C.c_void_p),
+                ("n_graph_tiles", C.c_int64), ("graph_tile_ptr", C.c_void_p), ("gtile_ptr", C.c_void_p)]
 
 
 EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
@@ -185,6 +186,8 @@ class Batch:
                     out_ptr=grab(v.out_ptr, self.N + 1), out_pos=grab(v.out_pos, self.E),
                     node_graph=grab(v.node_graph, self.N),
                     tile_ptr=grab(v.tile_ptr, int(v.n_tiles) + 1),
+                    graph_tile_ptr=grab(v.graph_tile_ptr, self.G + 1 if v.graph_tile_ptr else 0),
+                    gtile_ptr=grab(v.gtile_ptr, int(v.n_graph_tiles) + 1 if v.gtile_ptr else 0),
                     edge_feat=grab(v.edge_feat, self.E * De, C.c_float, np.float32).reshape(self.E, De))
 
     def free(self):

@@ -189,13 +189,12 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
 // sums are added in group order, so the result does not depend on timing. pool [G, H] is also
 // stored (it is an input of the backward pass). Meant for batches of many graphs of moderate
 // size; a few huge graphs go through the generic segment-sum kernels instead.
+// (sm: (256 * VEC + 2 * widest layer) floats of LDS; all 256 threads of the block call it together)
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const int32_t *graph_node_ptr, int H,
-                                                            int mean, float *pool, const RowMlpArgs mlp) {
-  extern __shared__ __align__(16) float sm[];   // [256 * VEC] partial sums, then the MLP's buffers
-  const int g = blockIdx.x, t = threadIdx.x;
+__device__ __forceinline__ void graph_readout_block(const T *h, const int n0, const int n1, const int g, int H,
+                                                    int mean, float *pool, const RowMlpArgs &mlp, float *sm) {
+  const int t = threadIdx.x;
   const int tpr = H / VEC, ng = 256 / tpr, c0 = (t % tpr) * VEC, q = t / tpr;
-  const int n0 = graph_node_ptr[g], n1 = graph_node_ptr[g + 1];
   float acc[VEC];
 #pragma unroll
   for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
@@ -232,6 +231,14 @@ __global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const in
   for (int k = t; k < mlp.w2; k += 256) cur[H + k] = mlp.in2[(size_t)g * mlp.w2 + k];
   __syncthreads();
   block_row_mlp(mlp, cur, nxt, part, g);
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const int32_t *graph_node_ptr, int H,
+                                                            int mean, float *pool, const RowMlpArgs mlp) {
+  extern __shared__ __align__(16) float sm[];   // [256 * VEC] partial sums, then the MLP's buffers
+  const int g = blockIdx.x;
+  graph_readout_block<T, VEC>(h, graph_node_ptr[g], graph_node_ptr[g + 1], g, H, mean, pool, mlp, sm);
 }
 
 // pool[g, :] /= max(n_g, 1)  (mean readout)

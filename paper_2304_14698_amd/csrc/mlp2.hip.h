@@ -7,11 +7,11 @@
 //          -> ReLU MLP -> summed per receiver (the message-passing sum)                 -> agg
 //   NODE   rows = nodes,  x = [h | agg]                                                 -> h'
 //
-// Each wave owns 32 rows. Layer 1 is computed transposed (features x rows: the weights are the
-// A operand, the gathered input rows the B operand, loaded straight from global memory into
-// registers), so its accumulator layout (lane = row, registers = features) is exactly the
-// A-operand layout layer 2 needs; layer 2 then yields rows x features with lane = feature,
-// registers = rows, which makes the per-receiver sum a walk down each lane's column.
+// Each wave owns 32 rows. Both layers are computed transposed (features x rows: the weights are
+// the A operand, the gathered input rows the B operand, loaded straight from global memory into
+// registers), so layer 1's accumulator layout (lane = row, registers = features) is, after ReLU
+// and conversion, the B-operand layout of layer 2; layer 2's accumulators have lane = row as
+// well, so a row leaves as register quads and the per-receiver sum runs across adjacent lanes.
 // Weights are pre-arranged on the host in the per-lane fragment order (see swizzle_* in the
 // runtime), so every weight fragment is one coalesced 1 KB load per wave.
 #pragma once
@@ -56,17 +56,28 @@ template <int V>
 struct TailRaw {
   f32x4 q[V / 4];
 };
+// (the two halves -- request, then zeroing at the point of use -- are separate so that a caller
+// can request a tile ahead without the zeroing's wait landing next to the request)
 template <int V>
-__device__ __forceinline__ TailRaw<V> load_tail(const float *rowp, int width, int ts, int g) {
+__device__ __forceinline__ TailRaw<V> request_tail(const float *rowp, int width, int ts, int g) {
   TailRaw<V> r;
 #pragma unroll
   for (int i = 0; i < V / 4; ++i) {
     const int k = ts * 2 * V + g * V + 4 * i;
-    const bool ok = k + 4 <= width;
-    const f32x4 v = *(const f32x4 *)(rowp + (ok ? k : 0));
-    r.q[i] = ok ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+    r.q[i] = *(const f32x4 *)(rowp + (k + 4 <= width ? k : 0));
   }
   return r;
+}
+template <int V>
+__device__ __forceinline__ TailRaw<V> zero_tail_beyond(TailRaw<V> r, int width, int ts, int g) {
+#pragma unroll
+  for (int i = 0; i < V / 4; ++i)
+    if (ts * 2 * V + g * V + 4 * i + 4 > width) r.q[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  return r;
+}
+template <int V>
+__device__ __forceinline__ TailRaw<V> load_tail(const float *rowp, int width, int ts, int g) {
+  return zero_tail_beyond<V>(request_tail<V>(rowp, width, ts, g), width, ts, g);
 }
 template <typename T>
 __device__ __forceinline__ typename Operand<T>::vec tail_to_operand(const TailRaw<Operand<T>::V> &r);
@@ -151,13 +162,17 @@ __device__ __forceinline__ void edge_tile_sum(f32x16 (&acc)[H / 32], const EdgeT
     const float takef = rem >= d ? 1.f : 0.f;
     const int from = ((lane + d) & 63) << 2;
 #pragma unroll
-    for (int nb = 0; nb < MB; ++nb)
+    for (int nb = 0; nb < MB; ++nb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float v = acc[nb][r];
         const float t = __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
         acc[nb][r] = fmaf(t, takef, v);
       }
+      // one block's exchanges at a time: all of them in flight at once would hold 16 * MB more
+      // registers than the callers that keep a next tile's rows in flight can spare
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   const bool ends_tile = l32 + rem == nv - 1;
   const bool to_c0 = head && l32 == 0 && m.prev_d == m.dst;
@@ -214,14 +229,14 @@ __device__ __forceinline__ f32x4 embed_columns(const EmbedRow &r, const float *e
 // EMBED: zero rows of the received-sum buffers for the tile's nodes without in-edges (`no_in`:
 // this lane's node, lane = row l % 32), whole rows, 16 bytes per lane.
 template <typename T, int H>
-__device__ __forceinline__ void zero_source_rows(const Mlp2Args &a, int64_t row0, bool no_in, int lane) {
+__device__ __forceinline__ void zero_source_rows(const Mlp2Args &a, int64_t row0, int nv, bool no_in, int lane) {
   constexpr int LPR = H * (int)sizeof(T) / 16, RPI = 64 / LPR;
   if (a.n_agg == 0 || !__any(no_in)) return;
   const int flag = no_in ? 1 : 0;
 #pragma unroll
   for (int k = 0; k < 32 / RPI; ++k) {
     const int r = k * RPI + lane / LPR;
-    const bool z = __shfl(flag, r) != 0 && row0 + r < a.n_rows;
+    const bool z = __shfl(flag, r) != 0 && r < nv;
     if (z)
       for (int i = 0; i < a.n_agg; ++i)
         *(f32x4 *)((char *)a.agg0 + i * a.agg_stride + ((size_t)(row0 + r) * H) * sizeof(T) + (lane % LPR) * 16) =
@@ -229,12 +244,15 @@ __device__ __forceinline__ void zero_source_rows(const Mlp2Args &a, int64_t row0
   }
 }
 
+// One wave tile: rows [row0, row0 + nv) (nv in 1..32; for EDGE the edges of tile `wt` of the
+// tile table in use), staged out through `stage` (RowStage<T, H>::BYTES, private to the wave).
 // T1 = operand type of layer 1 (its input rows and W1), T = operand type of layer 2 and of the
 // stored activations. They differ only for EMBED in bf16 mode, whose first layer stays in fp32:
 // its inputs (log2 shape attributes up to 12, sums of edge attributes) are large enough for bf16
 // weight rounding to dominate the error of the whole encoder.
 template <typename T1, typename T, int H, int KIND>
-__global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
+__device__ __forceinline__ void mlp2_wave_tile(const Mlp2Args &a, const int64_t row0, const int nv, const int64_t wt,
+                                               char *stage, const int lane) {
   using Opd = Operand<T>;
   using vec = typename Opd::vec;
   constexpr int V = Opd::V, SL = 2 * V, MB = H / 32, HS = H / SL;
@@ -242,25 +260,8 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   using vec1 = typename Opd1::vec;
   constexpr int V1 = Opd1::V, SL1 = 2 * V1;
   static_assert(KIND == KIND_EMBED || sizeof(T1) == sizeof(T), "only EMBED mixes operand types");
-  __shared__ __align__(16) char stage[4][RowStage<T, H>::BYTES];  // per-wave staging of output rows
-
-  // consecutive tiles stay on one XCD (blocks are dealt round-robin to the 8 XCDs), so the rows
-  // a tile gathers are mostly in that XCD's L2 already
-  const int64_t per_xcd = (a.n_blocks + 7) / 8;
-  const int64_t tile = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (tile >= a.n_blocks) return;
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
-  const int64_t wt = tile * 4 + wave;                           // wave tile: 32 rows, or an edge tile
-  int64_t row0 = wt * 32;
-  [[maybe_unused]] int nv = 32;
-  if constexpr (KIND == KIND_EDGE) {
-    if (wt >= a.n_tiles) return;
-    row0 = a.tile_ptr[wt];
-    nv = a.tile_ptr[wt + 1] - (int)row0;
-  }
-  int64_t row = row0 + (l32 < nv ? l32 : nv - 1);
-  if (row >= a.n_rows) row = a.n_rows - 1;                      // clamp loads; stores are guarded
+  const int l32 = lane & 31, g = lane >> 5;
+  const int64_t row = row0 + (l32 < nv ? l32 : nv - 1);          // clamp loads; stores are guarded
 
   // ---------------- layer 1: acc1[mb] = (W1^T x^T) tile, features x rows, bias pre-loaded
   f32x16 acc1[MB];
@@ -371,12 +372,37 @@ __global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
   // ---------------- epilogue
   T *out = (T *)a.out;
   if constexpr (KIND != KIND_EDGE) {
-    store_rows_via_lds<T, H, true>(acc2, stage[wave], lane, [&](int r) -> T * {
-      return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
+    store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
+      return r < nv ? out + (size_t)(row0 + r) * H : nullptr;
     });
-    if constexpr (KIND == KIND_EMBED) zero_source_rows<T, H>(a, row0, a.in_ptr[row + 1] == a.in_ptr[row], lane);
+    if constexpr (KIND == KIND_EMBED) zero_source_rows<T, H>(a, row0, nv, a.in_ptr[row + 1] == a.in_ptr[row], lane);
   } else {
     const EdgeTileMeta m = load_edge_meta(a.in_dst, a.n_rows, row0, nv, l32);
-    edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry, stage[wave]);
+    edge_tile_sum<T, H>(acc2, m, wt, nv, lane, out, a.carry, stage);
   }
+}
+
+// Streaming form: one block of four waves per 128 rows (four edge tiles), weights read from
+// memory (L2) as they are needed.
+template <typename T1, typename T, int H, int KIND>
+__global__ __launch_bounds__(256) void mlp2_kernel(const Mlp2Args a) {
+  __shared__ __align__(16) char stage[4][RowStage<T, H>::BYTES];  // per-wave staging of output rows
+  // consecutive tiles stay on one XCD (blocks are dealt round-robin to the 8 XCDs), so the rows
+  // a tile gathers are mostly in that XCD's L2 already
+  const int64_t per_xcd = (a.n_blocks + 7) / 8;
+  const int64_t tile = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= a.n_blocks) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t wt = tile * 4 + wave;                           // wave tile: 32 rows, or an edge tile
+  int64_t row0 = wt * 32;
+  int nv;
+  if constexpr (KIND == KIND_EDGE) {
+    if (wt >= a.n_tiles) return;
+    row0 = a.tile_ptr[wt];
+    nv = a.tile_ptr[wt + 1] - (int)row0;
+  } else {
+    if (row0 >= a.n_rows) return;
+    nv = a.n_rows - row0 < 32 ? (int)(a.n_rows - row0) : 32;
+  }
+  mlp2_wave_tile<T1, T, H, KIND>(a, row0, nv, wt, stage[wave], lane);
 }

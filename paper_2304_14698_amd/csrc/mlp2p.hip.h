@@ -20,7 +20,7 @@ struct TileRows {
   using vec = typename Operand<T>::vec;
   static constexpr int NX = 2 * (H / (2 * Operand<T>::V));   // slabs of the two H-wide parts
   vec x[NX];
-  TailRaw<Operand<T>::V> xe;   // EDGE: the single zero-padded slab of edge attributes, raw
+  TailRaw<Operand<T>::V> xe;   // EDGE: the single slab of edge attributes as requested (not yet zero-padded)
 };
 
 struct TileIndex {
@@ -29,44 +29,65 @@ struct TileIndex {
   EdgeTileMeta m;   // EDGE: receivers
 };
 
+struct TileBounds {
+  int e0, e1;       // EDGE: the tile's edges are [e0, e1)
+};
 template <int KIND>
-__device__ __forceinline__ TileIndex load_index(const Mlp2Args &a, int64_t wt, int l32) {
+__device__ __forceinline__ TileBounds load_bounds(const Mlp2Args &a, int64_t wt) {
+  TileBounds b{0, 0};
+  if constexpr (KIND == KIND_EDGE) {
+    b.e0 = a.tile_ptr[wt];
+    b.e1 = a.tile_ptr[wt + 1];
+  }
+  return b;
+}
+template <int KIND>
+__device__ __forceinline__ TileIndex load_index(const Mlp2Args &a, const TileBounds &b, int l32) {
   TileIndex ix;
   if constexpr (KIND == KIND_EDGE) {
-    ix.e0 = a.tile_ptr[wt];
-    ix.nv = a.tile_ptr[wt + 1] - ix.e0;
+    ix.e0 = b.e0;
+    ix.nv = b.e1 - b.e0;
     ix.src = a.in_src[ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1)];
     ix.m = load_edge_meta(a.in_dst, a.n_rows, ix.e0, ix.nv, l32);
   }
   return ix;
 }
 
-// Issues every row load of a wave tile; all loads are unconditional (clamped) so none waits on
-// another.
-template <typename T, int H, int KIND>
+// Issues the row loads of a wave tile: PARTS & 1 the first H-wide part (EDGE: the sender's row,
+// NODE: the node's own), PARTS & 2 the second (EDGE: the receiver's row and the edge attributes,
+// NODE: the received sum). All loads are unconditional (clamped) so none waits on another.
+template <typename T, int H, int KIND, int PARTS>
 __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32, int g, const TileIndex &ix,
                                           TileRows<T, H> &in) {
   using Opd = Operand<T>;
   using vec = typename Opd::vec;
   constexpr int V = Opd::V, SL = 2 * V, HS = H / SL;
   if constexpr (KIND == KIND_EDGE) {
-    const int64_t row = ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1);
-    const T *hs = (const T *)a.h + (size_t)ix.src * H + g * V;
-    const T *hd = (const T *)a.h + (size_t)ix.m.dst * H + g * V;
+    if constexpr ((PARTS & 1) != 0) {
+      const T *hs = (const T *)a.h + (size_t)ix.src * H + g * V;
 #pragma unroll
-    for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hs + k * SL);
+      for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hs + k * SL);
+    }
+    if constexpr ((PARTS & 2) != 0) {
+      const int64_t row = ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1);
+      const T *hd = (const T *)a.h + (size_t)ix.m.dst * H + g * V;
 #pragma unroll
-    for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(hd + k * SL);
-    in.xe = load_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, 0, g);
+      for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(hd + k * SL);
+      in.xe = request_tail<V>(a.edge_feat + (size_t)row * a.De, a.De, 0, g);
+    }
   } else {
     int64_t row = wt * 32 + l32;
     if (row >= a.n_rows) row = a.n_rows - 1;
-    const T *hp = (const T *)a.h + (size_t)row * H + g * V;
-    const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
+    if constexpr ((PARTS & 1) != 0) {
+      const T *hp = (const T *)a.h + (size_t)row * H + g * V;
 #pragma unroll
-    for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hp + k * SL);
+      for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hp + k * SL);
+    }
+    if constexpr ((PARTS & 2) != 0) {
+      const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
 #pragma unroll
-    for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(ap + k * SL);
+      for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(ap + k * SL);
+    }
   }
 }
 
@@ -117,7 +138,8 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   float(*b2l)[2][16] = b1l + MB;                                         // same for layer 2
   char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * RowStage<T, H>::BYTES;   // this wave's output staging
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // tile counters stay in scalar registers
   // the wave tiles of one XCD are contiguous (blocks are dealt round-robin to the 8 XCDs); inside
   // the XCD, tile j of a pass goes to wave j / nbx of block j % nbx
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
@@ -132,7 +154,11 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   // in one batch of loads (a load-store loop would pay one memory round trip per 8 KB), and only
   // then move the weights into LDS.
   TileIndex ix;
-  if (wt < t_end) ix = load_index<KIND>(a, wt, l32);
+  TileBounds bnext;   // of the wave's next tile (of its last one again when there is no next)
+  if (wt < t_end) {
+    ix = load_index<KIND>(a, load_bounds<KIND>(a, wt), l32);
+    bnext = load_bounds<KIND>(a, wt + stride < t_end ? wt + stride : wt);
+  }
   {
     constexpr int NT = 64 * NW, N1 = NS1 * MB * 64, N2 = NC2 * MB * 64;
     constexpr int C1 = (N1 + NT - 1) / NT, C2 = (N2 + NT - 1) / NT;
@@ -160,21 +186,28 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   }
   __syncthreads();
 
+  // The rows of a wave's next tile are requested once layer 2 has consumed layer 1's accumulators
+  // (the registers of the current rows and of those accumulators are free from there on), so the
+  // gather's round trip runs under the epilogue; the next tile's indices are requested a tile
+  // earlier and its edge range a tile before that, so no request waits on another's answer.
+  TileRows<T, H> in;
+  if (wt < t_end) load_rows<T, H, KIND, 3>(a, wt, l32, g, ix, in);
   for (; wt < t_end; wt += stride) {
     // the weights in LDS never change, but keeping all their fragments in registers across
     // tiles would not fit: make the compiler re-read them from LDS in every tile
     asm volatile("" ::: "memory");
-    TileRows<T, H> in;
-    load_rows<T, H, KIND>(a, wt, l32, g, ix, in);
     [[maybe_unused]] const EdgeTileMeta meta = ix.m;
     [[maybe_unused]] const int nv = ix.nv;
-    ix = load_index<KIND>(a, wt + stride < t_end ? wt + stride : wt, l32);
+    const bool more = wt + stride < t_end;
+    const int64_t wnext = more ? wt + stride : wt;
+    ix = load_index<KIND>(a, bnext, l32);
+    bnext = load_bounds<KIND>(a, wnext + stride < t_end ? wnext + stride : wnext);
     // ---------------- layer 1 (features x rows)
     f32x16 acc1[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
     [[maybe_unused]] vec xe;
-    if constexpr (KIND == KIND_EDGE) xe = tail_to_operand<T>(in.xe);
+    if constexpr (KIND == KIND_EDGE) xe = tail_to_operand<T>(zero_tail_beyond<V>(in.xe, a.De, 0, g));
     {
       vec wc[MB];
 #pragma unroll
@@ -202,6 +235,9 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     // ---------------- layer 2 (features x rows)
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+    if (more) load_rows<T, H, KIND, 3>(a, wnext, l32, g, ix, in);
+    else in = TileRows<T, H>{};   // (so that the consumed rows need not stay live up to here)
+    __builtin_amdgcn_sched_barrier(0);
     // ---------------- epilogue
     T *out = (T *)a.out;
     if constexpr (KIND == KIND_NODE) {
@@ -305,9 +341,9 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
     T *out = (T *)a.out;
+    const int64_t left = a.n_rows - row0;
+    const int n_valid = left < 32 ? (int)left : 32;
     if constexpr (BIG) {
-      const int64_t left = a.n_rows - row0;
-      const int n_valid = left < 32 ? (int)left : 32;
 #pragma unroll
       for (int nb = 0; nb < MB; ++nb) {
 #pragma unroll
@@ -319,6 +355,6 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
         return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
       });
     }
-    zero_source_rows<T, H>(a, row0, er.e0 == er.e1, lane);
+    zero_source_rows<T, H>(a, row0, n_valid, er.e0 == er.e1, lane);
   }
 }

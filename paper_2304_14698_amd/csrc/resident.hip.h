@@ -1,0 +1,113 @@
+// One-launch encoder for small batches (the agent's own inference loop encodes one state of a few
+// dozen candidate graphs per step, Section 4.2): one block per graph runs the node-update layer,
+// every message-passing round and the global-update layer (Section 3.4) on its graph, with block
+// barriers where the streaming path has kernel boundaries. A graph's node states and received
+// sums live in the same global buffers as on the streaming path (a few hundred KB per graph: they
+// stay in the CU's L1 and the XCD's L2), so both paths save the same activations for the
+// backward pass; what the launch removes is a dozen launch latencies and pipeline drains.
+//
+// Tiles, arithmetic and the order of every sum are those of mlp2_wave_tile and
+// graph_readout_block, so the embeddings equal the streaming path's bit for bit. Edge tiles
+// come from the packer's per-graph table (no tile spans two graphs, no receiver spans two
+// tiles), which is why no carry fix-up is needed here.
+#pragma once
+#include "heads.hip.h"
+#include "mlp2.hip.h"
+
+constexpr int kResidentMaxRounds = 8;
+
+struct ResidentMlp {
+  const void *W1s, *W2s;
+  const float *b1, *b2;
+  int nslab1;
+};
+
+struct ResidentArgs {
+  Mlp2Args base;                         // batch arrays, embed weights, agg0 / n_agg / agg_stride, out = h[0]
+  ResidentMlp edge[kResidentMaxRounds], node[kResidentMaxRounds];
+  void *h[kResidentMaxRounds + 1];       // node states after the embed layer and after each round
+  void *agg[kResidentMaxRounds];         // received sums of each round
+  int rounds;
+  int w1_bytes_max;                      // LDS reserved for a phase's first-layer weights
+  int64_t E;
+  const int32_t *graph_node_ptr, *graph_tile_ptr, *gtile_ptr;
+  int mean;
+  float *pool;
+  RowMlpArgs readout;
+};
+
+// Copies `bytes` (a multiple of 16) from global memory into LDS with all 256 threads, eight
+// 16-byte loads in flight per thread (a plain copy loop would pay one memory round trip per 4 KB).
+__device__ __forceinline__ void fill_lds(char *dst, const void *src, int bytes) {
+  const f32x4 *s = (const f32x4 *)src;
+  f32x4 *d = (f32x4 *)dst;
+  const int n = bytes / 16, tid = threadIdx.x;
+  for (int base = 0; base < n; base += 256 * 8) {
+    f32x4 t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = base + i * 256 + tid;
+      t[i] = s[k < n ? k : 0];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = base + i * 256 + tid;
+      if (k < n) d[k] = t[i];
+    }
+  }
+}
+
+// LDS: [four waves' row staging | W1 of the running phase | its W2 | the embed layer's table];
+// the readout reuses it from the start. With a handful of tiles per graph a weight fragment
+// requested from L2 one slab ahead of its MFMAs (as the streaming kernel does, where other waves
+// hide the wait) would cost a memory round trip per slab, so every phase first copies its two
+// matrices into LDS in one batch of loads.
+template <typename T, int H>
+__global__ __launch_bounds__(256) void encode_resident_kernel(const ResidentArgs ra) {
+  extern __shared__ __align__(16) char smem[];
+  constexpr int VEC = 16 / (int)sizeof(T), MB = H / 32;
+  constexpr int W2_BYTES = MB * (32 / (2 * VEC)) * MB * 1024;   // fragment-ordered [H, H]
+  const int gi = blockIdx.x, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char *stage = smem + wave * RowStage<T, H>::BYTES;
+  char *w1l = smem + 4 * RowStage<T, H>::BYTES, *w2l = w1l + ra.w1_bytes_max, *tabl = w2l + W2_BYTES;
+  const int n0 = ra.graph_node_ptr[gi], n1 = ra.graph_node_ptr[gi + 1];
+  const int t0 = ra.graph_tile_ptr[gi], t1 = ra.graph_tile_ptr[gi + 1];
+  const int n_node_tiles = (n1 - n0 + 31) / 32;
+
+  Mlp2Args a = ra.base;
+  fill_lds(w1l, a.W1x, a.nslabx * MB * 1024);
+  fill_lds(w2l, a.W2s, W2_BYTES);
+  fill_lds(tabl, a.table, a.Tn * H * 4);
+  a.W1x = w1l; a.W2s = w2l; a.table = (const float *)tabl;
+  __syncthreads();
+  for (int k = wave; k < n_node_tiles; k += 4) {
+    const int left = n1 - n0 - 32 * k;
+    mlp2_wave_tile<float, T, H, KIND_EMBED>(a, n0 + 32 * k, left < 32 ? left : 32, 0, stage, lane);
+  }
+  __syncthreads();   // (a block's global stores are visible to its own waves after the barrier)
+  a.W1s = w1l;
+  for (int r = 0; r < ra.rounds; ++r) {
+    fill_lds(w1l, ra.edge[r].W1s, ra.edge[r].nslab1 * MB * 1024);
+    fill_lds(w2l, ra.edge[r].W2s, W2_BYTES);
+    a.b1 = ra.edge[r].b1; a.b2 = ra.edge[r].b2; a.nslab1 = ra.edge[r].nslab1;
+    a.n_rows = ra.E; a.h = ra.h[r]; a.out = ra.agg[r];
+    __syncthreads();
+    for (int wt = t0 + wave; wt < t1; wt += 4) {
+      const int e0 = ra.gtile_ptr[wt];
+      mlp2_wave_tile<T, T, H, KIND_EDGE>(a, e0, ra.gtile_ptr[wt + 1] - e0, wt, stage, lane);
+    }
+    __syncthreads();
+    fill_lds(w1l, ra.node[r].W1s, ra.node[r].nslab1 * MB * 1024);
+    fill_lds(w2l, ra.node[r].W2s, W2_BYTES);
+    a.b1 = ra.node[r].b1; a.b2 = ra.node[r].b2; a.nslab1 = ra.node[r].nslab1;
+    a.agg = ra.agg[r]; a.out = ra.h[r + 1];
+    __syncthreads();
+    for (int k = wave; k < n_node_tiles; k += 4) {
+      const int left = n1 - n0 - 32 * k;
+      mlp2_wave_tile<T, T, H, KIND_NODE>(a, n0 + 32 * k, left < 32 ? left : 32, 0, stage, lane);
+    }
+    __syncthreads();
+  }
+  graph_readout_block<T, VEC>((const T *)ra.h[ra.rounds], n0, n1, gi, H, ra.mean, ra.pool, ra.readout, (float *)smem);
+}

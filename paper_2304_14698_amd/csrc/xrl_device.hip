@@ -12,6 +12,7 @@
 #include "mlp2.hip.h"
 #include "mlp2_bwd.hip.h"
 #include "mlp2p.hip.h"
+#include "resident.hip.h"
 #include "mlp2r.hip.h"
 #include "gat.hip.h"
 #include "wgrad.hip.h"
@@ -92,10 +93,10 @@ struct EncMlp {           // device pointers of one encoder MLP
 
 // kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
 enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_GAT_LINEAR,
-       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_GAT_BWD, TK_COUNT };
+       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_GAT_BWD, TK_RESIDENT, TK_COUNT };
 static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
                                                   "heads", "gat_linear", "gat_aggregate", "bwd_edge", "bwd_node",
-                                                  "bwd_embed", "wgrad", "grad_gather", "gat_bwd"};
+                                                  "bwd_embed", "wgrad", "grad_gather", "gat_bwd", "resident"};
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
 
@@ -108,6 +109,8 @@ struct xrl_ctx {
   int max_lds = 65536;          // LDS bytes one block may use
   int64_t p_min_rows = 8192;    // smallest row count for the persistent kernels (XRL_PERSISTENT_MIN_ROWS)
   int64_t wide_min_rows = 1 << 20;   // ... for the 256-column weight-gradient tiles (XRL_WGRAD_WIDE_MIN_ROWS)
+  int64_t resident_max_graphs = 0;   // largest batch (graphs) for the one-launch encoder (XRL_RESIDENT_MAX_GRAPHS)
+  int64_t resident_max_tiles = 0;    // ... and the most 32-row tiles (nodes, or edges) of one graph (XRL_RESIDENT_MAX_TILES)
   float *d_w = nullptr;         // flat fp32 weights
   int32_t *d_counter = nullptr; // kMaxFusedSlots per-state counters of policy_value_kernel, zero between launches
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
@@ -1093,6 +1096,48 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
   a.agg0 = ab[0]; a.n_agg = gat ? 0 : nagg; a.agg_stride = nagg > 1 ? (size_t)((char *)ab[1] - (char *)ab[0]) : 0;
+  if (!gat && H * sizeof(T) <= 256 && d.graph_tile_ptr && R <= kResidentMaxRounds && G <= c->resident_max_graphs &&
+      (b->max_graph_nodes + 31) / 32 <= c->resident_max_tiles && b->max_graph_tiles <= c->resident_max_tiles) {
+    // small batch: the whole encoder in one launch, one block per graph (rows of at most 256
+    // bytes: the three inlined tile routines of wider ones do not fit the register file)
+    ResidentArgs ra;
+    memset(&ra, 0, sizeof(ra));
+    ra.base = a;
+    ra.rounds = R; ra.E = E;
+    ra.graph_node_ptr = d.graph_node_ptr; ra.graph_tile_ptr = d.graph_tile_ptr; ra.gtile_ptr = d.gtile_ptr;
+    ra.h[0] = hb[0];
+    c->h[0] = hb[0];
+    for (int r = 0; r < R; ++r) {
+      ra.edge[r] = ResidentMlp{c->edge[r].W1s, c->edge[r].W2s, c->edge[r].b1, c->edge[r].b2, c->edge[r].nslab1};
+      ra.node[r] = ResidentMlp{c->node[r].W1s, c->node[r].W2s, c->node[r].b1, c->node[r].b2, c->node[r].nslab1};
+      ra.agg[r] = save ? ab[r] : ab[0];
+      ra.h[r + 1] = save ? hb[r + 1] : hb[(r + 1) & 1];
+      c->h[r + 1] = ra.h[r + 1];
+      c->agg[r + 1] = ra.agg[r];
+    }
+    ra.mean = m.readout == XRL_READOUT_MEAN ? 1 : 0;
+    ra.pool = c->pool;
+    int dmax = 0;
+    ra.readout = rowmlp_args(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb, c->ro_act, &dmax);
+    const int MB = H / 32;
+    int w1 = c->embed.nslabx;
+    for (int r = 0; r < R; ++r) w1 = std::max(w1, std::max(c->edge[r].nslab1, c->node[r].nslab1));
+    ra.w1_bytes_max = w1 * MB * 1024;
+    const size_t w2_bytes = (size_t)MB * (32 / (2 * PV)) * MB * 1024;
+    const size_t lds = std::max((size_t)4 * RowStage<T, 128>::BYTES + ra.w1_bytes_max + w2_bytes + (size_t)m.n_op_types * H * 4,
+                                (size_t)(256 * PV + 2 * dmax) * sizeof(float));
+    if (lds <= (size_t)c->max_lds) {
+      Timed t(c, TK_RESIDENT);
+      auto launch = [&](auto kern) -> int {
+        if (lds > 65536) HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        kern<<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(ra);
+        HIP_TRY(hipGetLastError());
+        return XRL_OK;
+      };
+      if (H == 64) return launch(encode_resident_kernel<T, 64>);
+      if constexpr (sizeof(T) == 2) return launch(encode_resident_kernel<T, 128>);
+    }
+  }
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
   c->h[0] = hb[0];
@@ -1206,6 +1251,13 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   c->p_min_rows = 8192;
   if (const char *e = getenv("XRL_PERSISTENT_MIN_ROWS")) c->p_min_rows = atoll(e);
   if (const char *e = getenv("XRL_WGRAD_WIDE_MIN_ROWS")) c->wide_min_rows = atoll(e);
+  // Batches the one-launch encoder takes: one block of four waves per graph wins while every
+  // phase of a graph is a single pass of its waves (measured: 51-node graphs, 9 to 144 of them,
+  // 49 us against 66 us; 340-node graphs 190 us against 122 us). 0 graphs = never.
+  c->resident_max_graphs = 256;
+  c->resident_max_tiles = 4;
+  if (const char *e = getenv("XRL_RESIDENT_MAX_GRAPHS")) c->resident_max_graphs = atoll(e);
+  if (const char *e = getenv("XRL_RESIDENT_MAX_TILES")) c->resident_max_tiles = atoll(e);
   {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
@@ -1268,7 +1320,8 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
                o_outp = plan((N + 1) * 4), o_outpos = plan(E * 4), o_ng = plan(N * 4),
                o_nd = plan((size_t)N * Dd * 4), o_ef = plan((size_t)E * De * 4),
                o_gg = plan((size_t)G * Dg * 4), o_mask = plan(G),
-               o_tile = plan(b->tile_ptr.size() * 4);
+               o_tile = plan(b->tile_ptr.size() * 4), o_gtile = plan(b->gtile_ptr.size() * 4),
+               o_gtp = plan(b->graph_tile_ptr.size() * 4);
   char *blk = nullptr;
   hipError_t e = hipMalloc((void **)&blk, off);
   if (e != hipSuccess) {
@@ -1297,6 +1350,8 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   HIP_TRY(cp(o_gg, b->graph_global.data(), (size_t)G * Dg * 4));
   HIP_TRY(cp(o_mask, b->mask.data(), G));
   HIP_TRY(cp(o_tile, b->tile_ptr.data(), b->tile_ptr.size() * 4));
+  HIP_TRY(cp(o_gtile, b->gtile_ptr.data(), b->gtile_ptr.size() * 4));
+  HIP_TRY(cp(o_gtp, b->graph_tile_ptr.data(), b->graph_tile_ptr.size() * 4));
   HIP_TRY(hipStreamSynchronize(c->stream));
   d.state_graph_ptr = (int32_t *)(blk + o_sgp);
   d.graph_node_ptr = (int32_t *)(blk + o_gnp);
@@ -1312,6 +1367,8 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   d.graph_global = (float *)(blk + o_gg);
   d.mask = (uint8_t *)(blk + o_mask);
   d.tile_ptr = (int32_t *)(blk + o_tile);
+  d.gtile_ptr = b->graph_tile_ptr.empty() ? nullptr : (int32_t *)(blk + o_gtile);
+  d.graph_tile_ptr = b->graph_tile_ptr.empty() ? nullptr : (int32_t *)(blk + o_gtp);
   b->uploaded = true;
   return XRL_OK;
 }

@@ -379,6 +379,38 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
       }
       if (fill > 0) b->tile_ptr.push_back((int32_t)E);
     }
+    b->max_graph_nodes = 0;
+    for (int64_t g = 0; g < G; ++g)
+      b->max_graph_nodes = std::max(b->max_graph_nodes, b->graph_node_ptr[g + 1] - b->graph_node_ptr[g]);
+    b->gtile_ptr.clear();
+    b->graph_tile_ptr.clear();
+    b->max_graph_tiles = 0;
+    if (G <= kGraphTileMaxGraphs) {   // the same rule graph by graph (see xrl_batch)
+      bool ok = true;
+      b->graph_tile_ptr.push_back(0);
+      for (int64_t g = 0; g < G && ok; ++g) {
+        int32_t fill = 0;
+        const int32_t n1 = b->graph_node_ptr[g + 1];
+        for (int32_t n = b->graph_node_ptr[g]; n < n1; ++n) {
+          const int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
+          if (d == 0) continue;
+          if (d > 32) { ok = false; break; }
+          if (fill + d > 32 || fill == 0) {
+            b->gtile_ptr.push_back(b->in_ptr[n]);
+            fill = 0;
+          }
+          fill += d;
+        }
+        b->max_graph_tiles = std::max(b->max_graph_tiles, (int32_t)b->gtile_ptr.size() - b->graph_tile_ptr.back());
+        b->graph_tile_ptr.push_back((int32_t)b->gtile_ptr.size());
+      }
+      if (ok) {
+        b->gtile_ptr.push_back((int32_t)E);
+      } else {
+        b->gtile_ptr.clear();
+        b->graph_tile_ptr.clear();
+      }
+    }
   } catch (const std::bad_alloc &) {
     delete b;
     return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
@@ -434,6 +466,9 @@ int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *v) {
   v->edge_feat = b->edge_feat.data();
   v->n_tiles = (int64_t)b->tile_ptr.size() - 1;
   v->tile_ptr = b->tile_ptr.data();
+  v->n_graph_tiles = b->gtile_ptr.empty() ? 0 : (int64_t)b->gtile_ptr.size() - 1;
+  v->graph_tile_ptr = b->graph_tile_ptr.empty() ? nullptr : b->graph_tile_ptr.data();
+  v->gtile_ptr = b->gtile_ptr.empty() ? nullptr : b->gtile_ptr.data();
   return XRL_OK;
 }
 

@@ -61,6 +61,7 @@ struct xrl_batch_device {
   int32_t *state_graph_ptr = nullptr, *graph_node_ptr = nullptr, *node_op = nullptr;
   int32_t *in_ptr = nullptr, *in_src = nullptr, *in_dst = nullptr;
   int32_t *out_ptr = nullptr, *out_pos = nullptr, *node_graph = nullptr, *tile_ptr = nullptr;
+  int32_t *gtile_ptr = nullptr, *graph_tile_ptr = nullptr;   // null unless the batch has per-graph tiles
   float *node_dense = nullptr, *edge_feat = nullptr, *graph_global = nullptr;
   uint8_t *mask = nullptr;
 };
@@ -73,6 +74,13 @@ struct xrl_batch {
   RawVec<int32_t> node_op, in_src, in_dst, in_eid, out_pos, node_graph;
   std::vector<int32_t> tile_ptr;  // [n_tiles + 1] edge tiles of the message kernels (see the packer)
   int64_t n_split_tiles = 0;      // tiles that end inside a receiver's in-edge range
+  // Per-graph edge tiles for the one-launch encoder of small batches: the same cutting rule, but
+  // a tile never spans two graphs; graph g owns tiles [graph_tile_ptr[g], graph_tile_ptr[g + 1])
+  // of gtile_ptr. Both empty when the batch has more than kGraphTileMaxGraphs graphs or a node
+  // with more than 32 in-edges.
+  std::vector<int32_t> gtile_ptr, graph_tile_ptr;
+  int32_t max_graph_nodes = 0;    // nodes of the largest graph
+  int32_t max_graph_tiles = 0;    // most per-graph edge tiles of one graph
   RawVec<float> node_dense, edge_feat;
   std::vector<float> graph_global;
   std::vector<uint8_t> mask;
@@ -80,6 +88,8 @@ struct xrl_batch {
   bool uploaded = false;
   uint64_t id = 0;  // unique per packed batch; ties saved activations to their batch
 };
+
+constexpr int64_t kGraphTileMaxGraphs = 4096;
 
 // Implemented in the device translation unit; frees dev.block if any.
 extern "C" void xrl_batch_release_device(xrl_batch *b);

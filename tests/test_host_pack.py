@@ -124,6 +124,50 @@ def test_edge_tiles():
         assert len(v["tile_ptr"]) - 1 >= -(-len(src) // 32)
 
 
+def check_graph_tiles(v):
+    """Per-graph edge tiles: every graph's in-edges partitioned into runs of 1..32 edges whose
+    boundaries fall between receivers; no tile spans two graphs; greedy inside a graph."""
+    gtp, tp, in_ptr, in_dst, gnp = v["graph_tile_ptr"], v["gtile_ptr"], v["in_ptr"], v["in_dst"], v["graph_node_ptr"]
+    G, E = len(gnp) - 1, len(in_dst)
+    assert len(gtp) == G + 1 and gtp[0] == 0 and gtp[-1] == len(tp) - 1 and tp[-1] == E
+    for g in range(G):
+        e0, e1 = in_ptr[gnp[g]], in_ptr[gnp[g + 1]]
+        mine = tp[gtp[g]:gtp[g + 1] + 1]
+        if e0 == e1:
+            assert gtp[g] == gtp[g + 1]
+            continue
+        assert mine[0] == e0 and mine[-1] == e1
+        sizes = np.diff(mine)
+        assert np.all(sizes >= 1) and np.all(sizes <= 32)
+        for i, t in enumerate(mine[1:-1]):
+            assert in_dst[t - 1] != in_dst[t]
+            deg = in_ptr[in_dst[t] + 1] - in_ptr[in_dst[t]]
+            assert sizes[i] + deg > 32
+
+
+def test_graph_edge_tiles():
+    model, st = synth.make_config(1)
+    check_graph_tiles(xrl.pack_state(model, st).host_view())
+    model, st = synth.make_config(4, n_cand=5)
+    check_graph_tiles(xrl.pack_state(model, st).host_view())
+    # graphs without edges between graphs with edges, and at both ends
+    n = 6
+    st = dict(n_states=1, state_graph_ptr=[0, 5], graph_node_ptr=[0, n, 2 * n, 3 * n, 4 * n, 5 * n],
+              graph_edge_ptr=[0, 0, 4, 4, 7, 7], node_op=np.zeros(5 * n, np.int32), node_dense=np.zeros((5 * n, 4)),
+              edge_src=np.array([0, 1, 2, 3, 0, 1, 2], np.int32), edge_dst=np.array([1, 2, 3, 4, 5, 5, 3], np.int32),
+              edge_feat=np.zeros((7, 8)), graph_global=None, slot_mask=[1] * 5)
+    v = xrl.pack_state(base_model(), st).host_view()
+    check_graph_tiles(v)
+    assert list(v["graph_tile_ptr"]) == [0, 0, 1, 1, 2, 2]
+    # a receiver of more than 32 in-edges: the batch has no per-graph tiles
+    src = np.arange(1, 41).astype(np.int32)
+    st = dict(n_states=1, state_graph_ptr=[0, 1], graph_node_ptr=[0, 50], graph_edge_ptr=[0, 40],
+              node_op=np.zeros(50, np.int32), node_dense=np.zeros((50, 4)), edge_src=src,
+              edge_dst=np.full(40, 7, np.int32), edge_feat=np.zeros((40, 8)), graph_global=None, slot_mask=[1])
+    v = xrl.pack_state(base_model(), st).host_view()
+    assert len(v["graph_tile_ptr"]) == 0 and len(v["gtile_ptr"]) == 0
+
+
 def _mutate(st, **kw):
     out = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in st.items()}
     out.update(kw)
