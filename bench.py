@@ -24,8 +24,8 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; see profiles/), each scaled by the same counter's
 # reading for a 1 GiB device copy (factors 2.000 and 1.000). Valid only for the kernel sources it
 # was taken with: the hash covers the files the kernel is built from.
-EDGE_TRAFFIC = dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="15b264d3fb48592d",
-                    config=2, precision="bf16", bytes_per_launch=(11129.6 * 2.000 + 11599.5 * 1.000) * 1024)
+EDGE_TRAFFIC = dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="c85ecde8f675e87b",
+                    config=2, precision="bf16", bytes_per_launch=(11193.8 * 2.000 + 11599.5 * 1.000) * 1024)
 
 
 def edge_traffic(config, precision):
