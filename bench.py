@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--round-kind", default="mlp", choices=["mlp", "gat"],
                     help="message-passing layers: edge/node MLPs (measured path) or graph attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-seconds", type=float, default=20.0,
+                    help="CPU time given to the oracle for the cpu_baseline figure")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
                          "reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
@@ -221,7 +223,7 @@ def main():
         res["measured_peaks"] = dict(mfma_bf16_tflops=tf, copy_gbs=gb,
                                      note="register-resident 32x32x16 bf16 MFMA loop; 1 GiB device copy, read + write")
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = oracle_baseline(model, state, w)
+        res["cpu_baseline"] = oracle_baseline(model, state, w, budget_s=args.cpu_baseline_seconds)
     print(json.dumps(res))
 
 

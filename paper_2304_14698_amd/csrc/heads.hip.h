@@ -189,8 +189,9 @@ __global__ __launch_bounds__(256) void rowmlp_kernel(const RowMlpArgs a) {
 // sums are added in group order, so the result does not depend on timing. pool [G, H] is also
 // stored (it is an input of the backward pass). Meant for batches of many graphs of moderate
 // size; a few huge graphs go through the generic segment-sum kernels instead.
-// (sm: (256 * VEC + 2 * widest layer) floats of LDS; all 256 threads of the block call it together)
-template <typename T, int VEC>
+// (sm: (256 * VEC + 2 * widest layer) floats of LDS; all 256 threads of the block call it together.
+// UF = loads a thread keeps in flight: a thread adds its rows in the same order whatever UF is.)
+template <typename T, int VEC, int UF = 8>
 __device__ __forceinline__ void graph_readout_block(const T *h, const int n0, const int n1, const int g, int H,
                                                     int mean, float *pool, const RowMlpArgs &mlp, float *sm) {
   const int t = threadIdx.x;
@@ -199,20 +200,28 @@ __device__ __forceinline__ void graph_readout_block(const T *h, const int n0, co
 #pragma unroll
   for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
   int n = n0 + q;
-  for (; n + 7 * ng < n1; n += 8 * ng) {
-    float v[8][VEC];
+  for (; n + (UF - 1) * ng < n1; n += UF * ng) {
+    float v[UF][VEC];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) RowVec<T, VEC>::load(h + (size_t)(n + i * ng) * H + c0, v[i]);
+    for (int i = 0; i < UF; ++i) RowVec<T, VEC>::load(h + (size_t)(n + i * ng) * H + c0, v[i]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < UF; ++i)
 #pragma unroll
       for (int j = 0; j < VEC; ++j) acc[j] += v[i][j];
   }
-  for (; n < n1; n += ng) {
-    float v[VEC];
-    RowVec<T, VEC>::load(h + (size_t)n * H + c0, v);
+  if (n < n1) {
+    // the last, partial round: the same loads in flight (rows past the end re-read the graph's
+    // last row and are left out of the sum), not one dependent load after another
+    float v[UF][VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+    for (int i = 0; i < UF; ++i) {
+      const int r = n + i * ng;
+      RowVec<T, VEC>::load(h + (size_t)(r < n1 ? r : n1 - 1) * H + c0, v[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < UF; ++i)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc[j] += n + i * ng < n1 ? v[i][j] : 0.f;
   }
 #pragma unroll
   for (int j = 0; j < VEC; ++j) sm[(q * tpr + t % tpr) * VEC + j] = acc[j];
@@ -233,12 +242,12 @@ __device__ __forceinline__ void graph_readout_block(const T *h, const int n0, co
   block_row_mlp(mlp, cur, nxt, part, g);
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, int UF>
 __global__ __launch_bounds__(256) void graph_readout_kernel(const T *h, const int32_t *graph_node_ptr, int H,
                                                             int mean, float *pool, const RowMlpArgs mlp) {
   extern __shared__ __align__(16) float sm[];   // [256 * VEC] partial sums, then the MLP's buffers
   const int g = blockIdx.x;
-  graph_readout_block<T, VEC>(h, graph_node_ptr[g], graph_node_ptr[g + 1], g, H, mean, pool, mlp, sm);
+  graph_readout_block<T, VEC, UF>(h, graph_node_ptr[g], graph_node_ptr[g + 1], g, H, mean, pool, mlp, sm);
 }
 
 // pool[g, :] /= max(n_g, 1)  (mean readout)

@@ -1197,7 +1197,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     const RowMlpArgs ra = rowmlp_args(c, c->L.readout, true, c->pool, H, d.graph_global, m.d_global, G, d_emb,
                                       c->ro_act, &dmax);
     const size_t lds = (size_t)(256 * PV + 2 * dmax) * sizeof(float);
-    graph_readout_kernel<T, PV><<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(
+    graph_readout_kernel<T, PV, 8><<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(
         hcur, d.graph_node_ptr, H, m.readout == XRL_READOUT_MEAN ? 1 : 0, c->pool, ra);
     HIP_TRY(hipGetLastError());
     return XRL_OK;
