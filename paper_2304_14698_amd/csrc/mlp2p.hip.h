@@ -6,10 +6,10 @@
 // few tiles per CU still spreads evenly.
 //
 // Each wave loads the rows of its tile, computes and stores; the two waves that share a SIMD
-// overlap one's loads and epilogue with the other's MFMAs, and the row indices of a wave's next
-// tile are requested a tile ahead. (Requesting the next tile's rows ahead as well costs about 50
-// registers and measured slower; more than 8 waves per CU do not fit the register file at H = 128
-// without spilling and measured slower too.)
+// overlap one's loads and epilogue with the other's MFMAs. A wave's requests run ahead of its
+// arithmetic: the edge range of the tile after next, the row indices of the next tile, and, once
+// layer 2 has freed the registers, the next tile's rows. (More than 8 waves per CU do not fit the
+// register file at H = 128 without spilling and measured slower.)
 // Inside a layer the weight fragments of the next contraction slab are read from LDS while the
 // MFMAs of the current slab run. Math, operand layouts and epilogues are those of mlp2_kernel.
 #pragma once
