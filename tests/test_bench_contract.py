@@ -1,5 +1,5 @@
 """The benchmark's command-line contract: one JSON line with the agreed fields; more than one GPU
-is refused with a message (this build has no multi-GPU path)."""
+is refused with a message (this library has no multi-GPU path)."""
 import json
 import os
 import subprocess
