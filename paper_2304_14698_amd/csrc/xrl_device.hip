@@ -857,16 +857,21 @@ int launch_small_wgrads(xrl_ctx *c, const MlpRef &r, const float *x1, int w1, co
   return XRL_OK;
 }
 
-// demb[j, :] = mask[j] ? demb[j, :] + dz[s, :] * inv_n[s] : 0 for the slots j of state s
+// demb[j, :] = mask[j] ? demb[j, :] + dz[s, :] * inv_n[s] : 0 for the slots j of state s; one block
+// per slot (a batch may be a single state of hundreds of slots), which finds its state by bisection
 __global__ void demb_combine_kernel(float *demb, const float *dzs, const float *inv_n, const uint8_t *mask,
-                                    const int32_t *state_graph_ptr, int H) {
-  const int s = blockIdx.x;
-  const int j0 = state_graph_ptr[s], j1 = state_graph_ptr[s + 1];
-  const float w = inv_n[s];
-  for (int64_t i = threadIdx.x; i < (int64_t)(j1 - j0) * H; i += blockDim.x) {
-    const int j = j0 + (int)(i / H), f = (int)(i % H);
+                                    const int32_t *state_graph_ptr, int S, int H) {
+  const int j = blockIdx.x;
+  int lo = 0, hi = S;                       // state_graph_ptr[lo] <= j < state_graph_ptr[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (state_graph_ptr[mid] <= j) lo = mid; else hi = mid;
+  }
+  const float w = inv_n[lo];
+  const bool on = mask[j] != 0;
+  for (int f = threadIdx.x; f < H; f += blockDim.x) {
     const size_t o = (size_t)j * H + f;
-    demb[o] = mask[j] ? demb[o] + dzs[(size_t)s * H + f] * w : 0.f;
+    demb[o] = on ? demb[o] + dzs[(size_t)lo * H + f] * w : 0.f;
   }
 }
 
@@ -1461,8 +1466,8 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
                                                                         d_dlogp, d_dentropy, dlogit, inv_n);
   if ((rc = launch_rowmlp_bwd(c, c->L.policy, false, pact, dlogit, G, pdz, d_demb))) return rc;
   if ((rc = launch_rowmlp_bwd(c, c->L.value, false, vact, d_dvalue, S, vdz, dzs))) return rc;
-  demb_combine_kernel<<<dim3((unsigned)S), dim3(256), 0, c->stream>>>(d_demb, dzs, inv_n, d.mask,
-                                                                    d.state_graph_ptr, H);
+  demb_combine_kernel<<<dim3((unsigned)G), dim3(H < 256 ? H : 256), 0, c->stream>>>(d_demb, dzs, inv_n, d.mask,
+                                                                                 d.state_graph_ptr, (int)S, H);
   if ((rc = launch_small_wgrads(c, c->L.policy, d_emb, H, nullptr, 0, pact, pdz, G, d_dweights, spart, spart_floats))) return rc;
   if ((rc = launch_small_wgrads(c, c->L.value, zmean, H, nullptr, 0, vact, vdz, S, d_dweights, spart, spart_floats))) return rc;
   HIP_TRY(hipGetLastError());
