@@ -593,13 +593,21 @@ __global__ void small_wgrad_kernel(const float *x1, int w1, const float *x2, int
   const int k = (int)(i / dout), f = (int)(i - (int64_t)k * dout);
   const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
   const int64_t r1 = r0 + rows_per_chunk < n_rows ? r0 + rows_per_chunk : n_rows;
+  // rows are added in order, eight requested at a time (a plain loop waits for every row's loads)
+  const float *xp = k < w1 ? x1 + k : (k < din ? x2 + (k - w1) : nullptr);
+  const int xs = k < w1 ? w1 : w2;
   float acc = 0.f;
-  if (k == din) {
-    for (int64_t r = r0; r < r1; ++r) acc += dz[r * dout + f];
-  } else if (k < w1) {
-    for (int64_t r = r0; r < r1; ++r) acc = fmaf(x1[r * w1 + k], dz[r * dout + f], acc);
-  } else {
-    for (int64_t r = r0; r < r1; ++r) acc = fmaf(x2[r * w2 + (k - w1)], dz[r * dout + f], acc);
+  for (int64_t r = r0; r < r1; r += 8) {
+    float xv[8], dv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int64_t ri = r + i < r1 ? r + i : r1 - 1;
+      dv[i] = dz[ri * dout + f];
+      xv[i] = xp ? xp[ri * xs] : 1.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (r + i < r1) acc = xp ? fmaf(xv[i], dv[i], acc) : acc + dv[i];
   }
   if (partial) partial[(size_t)blockIdx.y * (din + 1) * dout + i] = acc;
   else if (k == din) db[f] += acc;
