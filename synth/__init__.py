@@ -7,8 +7,8 @@ the oracle nor the GPU package.
 from .graphs import (Graph, layered_dag, transformer_dag, resnet_dag, inception_dag,
                      local_rewrite, shuffle_edges)
 from .states import (CONFIGS, BASE_SEED, make_state, make_config, concat_states,
-                     init_weights, upstream_grads, state_subset)
+                     init_weights, upstream_grads, state_subset, random_states)
 
 __all__ = ["Graph", "layered_dag", "transformer_dag", "resnet_dag", "inception_dag",
            "local_rewrite", "shuffle_edges", "CONFIGS", "BASE_SEED", "make_state",
-           "make_config", "concat_states", "init_weights", "upstream_grads", "state_subset"]
+           "make_config", "concat_states", "init_weights", "upstream_grads", "state_subset", "random_states"]

@@ -136,3 +136,32 @@ def upstream_grads(rng, n_graphs, n_states):
     return ((rng.standard_normal(n_graphs) * s).astype(np.float32),
             (rng.standard_normal(n_states) * s).astype(np.float32),
             (rng.standard_normal(n_states) * s).astype(np.float32))
+
+
+def random_states(rng, model, n_states, max_graphs=6, max_nodes=120, edge_factor=(0.0, 2.5), mask_p=0.25):
+    """Unstructured random states for robustness sweeps: every state has 1..max_graphs graphs of
+    0..max_nodes nodes and a random number of arbitrary edges (self loops and repeated edges
+    included, any direction), random attributes, random slot masks (slot 0 always valid)."""
+    De, Dd, Dg, T = model["d_edge"], model["n_node_dense"], model["d_global"], model["n_op_types"]
+    ns, es, srcs, dsts, sgp, mask = [], [], [], [], [0], []
+    for _ in range(n_states):
+        g_s = int(rng.integers(1, max_graphs + 1))
+        for j in range(g_s):
+            n = int(rng.integers(0, max_nodes + 1))
+            e = int(rng.uniform(*edge_factor) * n) if n > 0 else 0
+            ns.append(n); es.append(e)
+            srcs.append(rng.integers(0, max(n, 1), e).astype(np.int32))
+            dsts.append(rng.integers(0, max(n, 1), e).astype(np.int32))
+            mask.append(1 if j == 0 else int(rng.random() >= mask_p))
+        sgp.append(sgp[-1] + g_s)
+    N, E, G = sum(ns), sum(es), len(ns)
+    return dict(n_states=n_states, state_graph_ptr=np.array(sgp, np.int32),
+                graph_node_ptr=np.concatenate([[0], np.cumsum(ns)]).astype(np.int32),
+                graph_edge_ptr=np.concatenate([[0], np.cumsum(es)]).astype(np.int32),
+                node_op=rng.integers(0, T, N).astype(np.int32),
+                node_dense=rng.integers(0, 13, (N, Dd)).astype(np.float32),
+                edge_src=np.concatenate(srcs + [np.zeros(0, np.int32)]).astype(np.int32),
+                edge_dst=np.concatenate(dsts + [np.zeros(0, np.int32)]).astype(np.int32),
+                edge_feat=(rng.standard_normal((E, De)) * 0.3).astype(np.float32),
+                graph_global=rng.standard_normal((G, Dg)).astype(np.float32),
+                slot_mask=np.array(mask, np.uint8))
