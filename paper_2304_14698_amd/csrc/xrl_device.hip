@@ -679,7 +679,7 @@ int launch_mlp2_bwd(xrl_ctx *c, int kind, Mlp2BwdArgs &a) {
 
 // rows per chunk / number of chunks of the weight-gradient kernels
 inline void wgrad_chunks(int64_t n_rows, int *rows_per_chunk, int *n_chunks) {
-  int64_t nc = (n_rows + 511) / 512;
+  int64_t nc = (n_rows + 127) / 128;        // (small batches: enough chunks to occupy the machine)
   if (nc > 512) nc = 512;
   if (nc < 1) nc = 1;
   int64_t rpc = (n_rows + nc - 1) / nc;
