@@ -290,3 +290,18 @@ def test_threaded_pack_equals_serial(monkeypatch):
     with pytest.raises(xrl.XrlError) as ei:
         xrl.pack_state(model, bad)
     assert "(-7 ->" in str(ei.value)
+
+
+def test_public_header_is_plain_c(tmp_path):
+    """include/xrl.h is the boundary: it must compile as C99 on its own (no C++, no HIP or torch types)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "h.c"
+    src.write_text('#include "xrl.h"\nint main(void) { return XRL_OK; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
