@@ -172,6 +172,17 @@ int xrl_encode(xrl_ctx *ctx, const xrl_batch *b, float *d_emb, int save_for_back
 int xrl_policy_value(xrl_ctx *ctx, const xrl_batch *b, const float *d_emb, float *d_logp,
                      float *d_value, float *d_entropy, int32_t *d_action, float *d_logit);
 
+/* xrl_policy_value_static: xrl_policy_value for callers that cannot allocate (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc). Same arguments, same kernel and
+ * bit-identical outputs, but it calls no allocation routine at all: its scratch (per-state
+ * counters, the logits when d_logit is NULL, the per-state mean embeddings) is a fixed array in
+ * device memory, 288 KiB per GPU, held until the process ends. Limits: at most 4096 slots (G) and
+ * n_states * hidden <= 65536; beyond them XRL_ERR_UNSUPPORTED and nothing is launched. Every call
+ * on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two contexts)
+ * race; calls on one stream are safe. Other errors: NULL, SHAPE (alignment), STATE, HIP. */
+int xrl_policy_value_static(xrl_ctx *ctx, const xrl_batch *b, const float *d_emb, float *d_logp,
+                            float *d_value, float *d_entropy, int32_t *d_action, float *d_logit);
+
 /* ---- backward (Section 3.3.4: one back-propagation through heads and GNN) -------------------
  * For a scalar J with dJ/dlogp = d_dlogp [G] (entries at masked slots are ignored), dJ/dvalue =
  * d_dvalue [S], dJ/dentropy = d_dentropy [S]:

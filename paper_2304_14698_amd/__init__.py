@@ -54,6 +54,7 @@ class PackedView(C.Structure):
 EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
            "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
+           "xrl_policy_value_static",
            "xrl_policy_value_backward", "xrl_encode_backward", "xrl_ppo_objective", "xrl_segment_sum",
            "xrl_get_activation", "xrl_set_timing", "xrl_read_timing", "xrl_measure_peaks",
            "xrl_edge_features_from_shapes", "xrl_weight_gradient", "xrl_mlp_backward", "xrl_last_error", "xrl_version"]
@@ -84,6 +85,7 @@ def load_library():
     lib.xrl_batch_upload.argtypes = [vp, vp]
     lib.xrl_encode.argtypes = [vp, vp, vp, C.c_int]
     lib.xrl_policy_value.argtypes = [vp] * 8
+    lib.xrl_policy_value_static.argtypes = [vp] * 8
     lib.xrl_policy_value_backward.argtypes = [vp] * 8
     lib.xrl_encode_backward.argtypes = [vp] * 4
     lib.xrl_segment_sum.argtypes = [vp, vp, vp, i64, i64, i32, vp]
@@ -259,14 +261,17 @@ class Encoder:
         _check(self.lib.xrl_encode(self.handle, batch.handle, emb.data_ptr(), int(save_for_backward)))
         return emb
 
-    def policy_value(self, batch, emb, out=None):
+    def policy_value(self, batch, emb, out=None, static=False):
+        """static=True: the entry point that allocates nothing (`out` must then be given)."""
         t = self.torch
         o = out or dict(logp=self._empty((batch.G,)), value=self._empty((batch.S,)),
                         entropy=self._empty((batch.S,)), action=self._empty((batch.S,), t.int32),
                         logit=self._empty((batch.G,)))
-        _check(self.lib.xrl_policy_value(self.handle, batch.handle, emb.data_ptr(), o["logp"].data_ptr(),
-                                         o["value"].data_ptr(), o["entropy"].data_ptr(),
-                                         o["action"].data_ptr(), o["logit"].data_ptr()))
+        fn = self.lib.xrl_policy_value_static if static else self.lib.xrl_policy_value
+        logit = o.get("logit")
+        _check(fn(self.handle, batch.handle, emb.data_ptr(), o["logp"].data_ptr(),
+                  o["value"].data_ptr(), o["entropy"].data_ptr(),
+                  o["action"].data_ptr(), None if logit is None else logit.data_ptr()))
         return o
 
     def policy_value_backward(self, batch, emb, dlogp, dvalue, dentropy, dweights):

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <unordered_map>
 #include <vector>
@@ -100,6 +101,18 @@ static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup",
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
 
+// Scratch of xrl_policy_value_static, the entry point that allocates nothing: per-state counters,
+// the logits when the caller does not ask for them, and the per-state mean embeddings. One copy
+// per GPU, held until the process ends; host code never passes the array's name to a kernel, only
+// the address hipGetSymbolAddress reports for the current device (static_scratch below).
+constexpr int64_t kStaticMaxSlots = kMaxFusedSlots;          // G
+constexpr int64_t kStaticMaxStateFloats = 65536;             // S * hidden
+constexpr size_t kStaticCounterOff = 0;
+constexpr size_t kStaticLogitOff = kStaticCounterOff + sizeof(int32_t) * kStaticMaxSlots;
+constexpr size_t kStaticZmeanOff = kStaticLogitOff + sizeof(float) * kStaticMaxSlots;
+constexpr size_t kStaticBytes = kStaticZmeanOff + sizeof(float) * kStaticMaxStateFloats;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
 struct xrl_ctx {
   xrl_model_desc m;
   Layout L;
@@ -113,6 +126,8 @@ struct xrl_ctx {
   int64_t resident_max_tiles = 0;    // ... and the most 32-row tiles (nodes, or edges) of one graph (XRL_RESIDENT_MAX_TILES)
   float *d_w = nullptr;         // flat fp32 weights
   int32_t *d_counter = nullptr; // kMaxFusedSlots per-state counters of policy_value_kernel, zero between launches
+  int device = 0;               // the device that was current at xrl_create
+  char *static_ws = nullptr;    // this device's copy of `scratch` (its device address)
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
   char *d_swz = nullptr;        // fragment-ordered encoder weights
   size_t swz_bytes = 0;
@@ -159,6 +174,25 @@ struct Timed {
   }
   ~Timed() { if (idx >= 0) (void)hipEventRecord(c->spans[idx].b, c->stream); }
 };
+}  // namespace
+
+namespace {
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char *g_scratch_ptr[kMaxDevices] = {};
+int static_scratch(int dev, char **out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(XRL_ERR_UNSUPPORTED, "device ordinal %d", dev);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(XRL_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = (char *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return XRL_OK;
+}
 }  // namespace
 
 extern "C" void xrl_batch_release_device(xrl_batch *b) {
@@ -1266,6 +1300,7 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
+      c->device = dev;
       if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) c->n_cu = v;
       if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0) c->max_lds = v;
     }
@@ -1286,6 +1321,7 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
     return fail(XRL_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
   }
   rc = upload_weights(c, weights_host);
+  if (!rc) rc = static_scratch(c->device, &c->static_ws);
   if (rc) {
     xrl_destroy(c);
     return rc;
@@ -1402,6 +1438,33 @@ int xrl_policy_value(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *
   float *zmean = (float *)(c->hws + align_up((size_t)b->G * 4));
   Timed t(c, TK_HEADS);
   return launch_heads(c, b, d_emb, logit, d_logp, d_entropy, d_action, zmean, d_value, nullptr, nullptr);
+}
+
+int xrl_policy_value_static(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *d_logp,
+                            float *d_value, float *d_entropy, int32_t *d_action, float *d_logit) {
+  int rc = check_batch(c, b, "xrl_policy_value_static");
+  if (rc) return rc;
+  if (b->S == 0) return XRL_OK;
+  if (!d_emb || !d_logp || !d_value || !d_entropy || !d_action)
+    return fail(XRL_ERR_NULL, "xrl_policy_value_static: NULL device pointer");
+  if ((uintptr_t)d_emb & 15) return fail(XRL_ERR_SHAPE, "xrl_policy_value_static: d_emb must be 16-byte aligned");
+  const int H = c->m.hidden;
+  if (b->G > kStaticMaxSlots || b->S * H > kStaticMaxStateFloats)
+    return fail(XRL_ERR_UNSUPPORTED,
+                "xrl_policy_value_static: %lld slots, %lld states x hidden %d exceed the fixed scratch "
+                "(at most %lld slots and %lld state floats)",
+                (long long)b->G, (long long)b->S, H, (long long)kStaticMaxSlots, (long long)kStaticMaxStateFloats);
+  int32_t *counter = (int32_t *)(c->static_ws + kStaticCounterOff);
+  float *logit = d_logit ? d_logit : (float *)(c->static_ws + kStaticLogitOff);
+  float *zmean = (float *)(c->static_ws + kStaticZmeanOff);
+  // the array keeps the last call's contents: the counters must start at zero
+  fill_zero_kernel<<<dim3((unsigned)((b->S + 255) / 256)), dim3(256), 0, c->stream>>>((float *)counter, b->S);
+  const RowMlpArgs va = rowmlp_args(c, c->L.value, false, zmean, H, nullptr, 0, b->S, d_value, nullptr);
+  const RowMlpArgs pa = rowmlp_args(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, nullptr);
+  policy_value_kernel<<<dim3((unsigned)(b->G + b->S)), dim3(256), 0, c->stream>>>(
+      pa, b->dev.mask, b->dev.state_graph_ptr, (int)b->G, (int)b->S, H, counter, d_logp, d_entropy, d_action, zmean, va);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
 }
 
 int xrl_ppo_objective(xrl_ctx *c, const xrl_batch *b, const float *d_logp, const float *d_value,
