@@ -1,10 +1,13 @@
 """Throughput of the state encoder + heads on one MI355X, with roofline and CPU-oracle baseline.
 
-One step = one forward pass of the whole path (sum of incoming edge attributes, embed MLP,
-R x (edge MLP + per-receiver sum, node MLP), per-graph readout, policy/value heads) over one
-packed synthetic meta-batch that is already resident in HBM; with --backward (and always for
-configuration 5, the update minibatch) also the backward pass through heads and encoder.
-Prints ONE JSON line.
+One step = one pass of the whole path over one packed synthetic meta-batch that is already
+resident in HBM: sum of incoming edge attributes, embed MLP, R x (edge MLP + per-receiver sum,
+node MLP), per-graph readout, policy/value heads (xrl_encode + xrl_policy_value) and, for the
+update minibatch (configuration 5, the default) or with --backward, the backward pass through
+heads and encoder (xrl_policy_value_backward + xrl_encode_backward). Prints ONE JSON line.
+
+Every step is bracketed by HIP events on the library's stream (which is torch's current stream);
+`value` uses the median step, `ms_per_step_mean` is the host clock over all K steps.
 """
 import argparse
 import json
@@ -20,44 +23,57 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the edge kernel on the default workload (config 2, bf16), from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; see profiles/), each scaled by the same counter's
-# reading for a 1 GiB device copy (factors 2.000 and 1.000). Valid only for the kernel sources it
-# was taken with: the hash covers the files the kernel is built from (comments and blank space apart).
-EDGE_TRAFFIC = dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="b660f3c7d5a8681c",
-                    config=2, precision="bf16", bytes_per_launch=(11193.8 * 2.000 + 11599.5 * 1.000) * 1024)
+# HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch;
+# summaries under profiles/), each scaled by the same counter's reading for a 1 GiB device copy
+# (factors 2.000 and 1.000). An entry is valid only for the kernel sources it was taken with: the
+# hash covers the files the kernel is built from (comments and blank space apart); otherwise null.
+TRAFFIC = {
+    (2, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="b660f3c7d5a8681c",
+                              bytes_per_launch=(11193.8 * 2.000 + 11599.5 * 1.000) * 1024),
+}
 
 
-def edge_traffic(config, precision):
+def source_hash(files):
     import hashlib
     h = hashlib.sha256()
-    for f in EDGE_TRAFFIC["sources"]:          # the code without its comments and blank space
+    for f in files:                               # the code without its comments and blank space
         with open(os.path.join(ROOT, "paper_2304_14698_amd", "csrc", f), "r") as fh:
             for ln in fh:
                 ln = ln.split("//")[0].strip()
                 if ln:
                     h.update(ln.encode() + b"\n")
-    same = h.hexdigest()[:16] == EDGE_TRAFFIC["sha256_16"]
-    if same and config == EDGE_TRAFFIC["config"] and precision == EDGE_TRAFFIC["precision"]:
-        return EDGE_TRAFFIC["bytes_per_launch"]
-    return None
+    return h.hexdigest()[:16]
 
 
-def oracle_baseline(model, state, w, budget_s=20.0):
-    """The float64 oracle timed on the host cores over whole graphs of the same workload."""
-    import numpy as np
+def measured_traffic(config, precision, kernel):
+    t = TRAFFIC.get((config, precision, kernel))
+    if t is None or source_hash(t["sources"]) != t["sha256_16"]:
+        return None
+    return t["bytes_per_launch"]
+
+
+def oracle_model(model):
     from oracle import xrl_oracle as O
+    return O.default_model(**{k: model[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
+                                                    "hidden", "rounds", "mlp_layers", "head_hidden", "readout")})
+
+
+def host_threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
     except Exception:
-        cores = os.cpu_count()
-    om = O.default_model(**{k: model[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
-                                                  "hidden", "rounds", "mlp_layers", "head_hidden", "readout")})
+        return int(os.cpu_count() or 1)
+
+
+def oracle_baseline_forward(model, state, w, budget_s):
+    """The float64 oracle's forward over whole graphs of the same meta-batch, for budget_s seconds."""
+    import numpy as np
+    from oracle import xrl_oracle as O
+    om = oracle_model(model)
     G = len(state["graph_node_ptr"]) - 1
     t0 = time.perf_counter()
-    done = 0
-    embs = []
+    done, embs = 0, []
     for g in range(G):
         embs.append(O.encode(om, w, state, graphs=[g])[0])
         done += 1
@@ -66,23 +82,55 @@ def oracle_baseline(model, state, w, budget_s=20.0):
     if done == G:
         O.policy_value(om, w, np.stack(embs), state)
     dt = time.perf_counter() - t0
-    return dict(value=done / dt, unit="graphs/s", cores=int(cores), kind="oracle",
-                sample=f"{done} of {G} graphs of the same meta-batch, float64 numpy, {dt:.1f} s")
+    return dict(value=done / dt, unit="graphs/s", cores=host_threads(), kind="oracle",
+                sample=f"forward of {done} of {G} graphs of the same meta-batch, float64 numpy, {dt:.1f} s")
+
+
+def oracle_baseline_update(model, state, w, up, n_states):
+    """Forward + backward of the float64 oracle on the n_states whole states of the meta-batch with
+    the fewest slots (all their graphs). The encoder's reverse mode evaluates the forward itself,
+    so the timed work is one forward and one backward per graph: heads forward, heads backward,
+    then forward + backward of the encoder (the embeddings the heads need come from an untimed
+    first encode)."""
+    import numpy as np
+    import synth
+    from oracle import xrl_oracle as O
+    om = oracle_model(model)
+    sgp = np.asarray(state["state_graph_ptr"])
+    order = np.argsort(np.diff(sgp), kind="stable")[:n_states]
+    order = np.sort(order)
+    sub = synth.state_subset(state, order)
+    gsel = np.concatenate([np.arange(sgp[s], sgp[s + 1]) for s in order])
+    emb = O.encode(om, w, sub)                                  # untimed (see above)
+    t0 = time.perf_counter()
+    O.policy_value(om, w, emb, sub)
+    demb, _ = O.policy_value_backward(om, w, emb, sub, up[0][gsel], up[1][order], up[2][order])
+    O.encode_backward(om, w, sub, demb)
+    dt = time.perf_counter() - t0
+    Gs = len(gsel)
+    return dict(value=Gs / dt, unit="graphs/s", cores=host_threads(), kind="oracle",
+                sample=f"forward + backward of states {order.tolist()} ({Gs} graphs, "
+                       f"{int(sub['node_op'].shape[0])} nodes: the {n_states} whole states of the same "
+                       f"meta-batch with the fewest slots), float64 numpy, {dt:.1f} s")
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="synthetic configuration (2 = headline)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 20 for configuration 5, else 200)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps first (default 5, or 20 below configuration 5)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="synthetic configuration; 5 = the update minibatch, the largest that fits one GPU (default)")
     ap.add_argument("--precision", default=None, help="fp32 | bf16 (default: the configuration's)")
     ap.add_argument("--states", type=int, default=None, help="override the number of states")
     ap.add_argument("--round-kind", default="mlp", choices=["mlp", "gat"],
                     help="message-passing layers: edge/node MLPs (measured path) or graph attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=20.0,
-                    help="CPU time given to the oracle for the cpu_baseline figure")
+                    help="CPU time given to the oracle's forward for the cpu_baseline figure (forward-only steps)")
+    ap.add_argument("--cpu-baseline-states", type=int, default=4,
+                    help="whole states the oracle runs forward + backward on (steps with the backward pass)")
+    ap.add_argument("--no-segment-sum", action="store_true", help="skip the standalone [E, H] segment-sum timing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one 1 GiB device-to-device copy (a kernel of known HBM traffic, the "
                          "reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
@@ -94,6 +142,10 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU: this library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.steps is None:
+        args.steps = 20 if args.config == 5 else 200
+    if args.warmup is None:
+        args.warmup = 5 if args.config == 5 else 20
 
     import numpy as np
     import torch
@@ -115,15 +167,18 @@ def main():
     t_pack = time.perf_counter() - t_pack
     S, G, N, E = batch.S, batch.G, batch.N, batch.E
     H, R, De = model["hidden"], model["rounds"], model["d_edge"]
+    Dd = model["n_node_dense"]
     emb = torch.empty((G, H), dtype=torch.float32, device="cuda")
     outs = dict(logp=torch.empty(G, device="cuda"), value=torch.empty(S, device="cuda"),
                 entropy=torch.empty(S, device="cuda"), action=torch.empty(S, dtype=torch.int32, device="cuda"),
                 logit=torch.empty(G, device="cuda"))
 
     backward = args.backward or args.config == 5
+    up_host = None
     if backward:
         grng = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 7))
-        up = [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in synth.upstream_grads(grng, G, S)]
+        up_host = synth.upstream_grads(grng, G, S)
+        up = [torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in up_host]
         dw = torch.zeros(enc.n_weights, dtype=torch.float32, device="cuda")
 
     def step():
@@ -141,16 +196,20 @@ def main():
         del src, dst
     for _ in range(args.warmup):
         step()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for a, b_ in ev:
+        a.record()
         step()
+        b_.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms = dt / args.steps * 1e3
+    per_step = sorted(a.elapsed_time(b_) for a, b_ in ev)
+    ms = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
+    ms_mean = dt / args.steps * 1e3
 
-    # the dominant kernel (edge MLP + per-receiver sum), timed with HIP events on the library's
-    # stream over the same number of steps
+    # every launch group timed with HIP events on the library's stream over the same number of steps
     enc.set_timing(True)
     for _ in range(args.steps):
         step()
@@ -162,44 +221,79 @@ def main():
         tot, n = enc.read_timing(k)
         kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)
     enc.set_timing(False)
-    edge_flops = 2.0 * E * H * (3 * H + De)       # edge L1 (2H+De -> H) + edge L2 (H -> H), per launch
-    edge_s = kern["edge"]["avg_us"] * 1e-6
+
     bf16 = model["precision"] == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
-    achieved = edge_flops / edge_s / 1e12 if edge_s > 0 else 0.0   # (0 with attention rounds: replaced below)
     b = 2 if bf16 else 4
-    # edge stage, ideal fused: h read once, edge attributes, indices; received sums written for
-    # the receivers that have in-edges
-    n_recv = int((np.diff(batch.host_view()["in_ptr"]) > 0).sum())
-    edge_bytes = N * H * b + E * De * 4 + 4 * (2 * E + E // 32) + n_recv * H * b
-    pool_bytes = N * H * b + 4 * (G + 1) + G * H * 4
-    pool_s = kern["pool"]["avg_us"] * 1e-6
+    hv = batch.host_view()
+    n_recv = int((np.diff(hv["in_ptr"]) > 0).sum())
+    # Algorithmic work per launch of each kernel (multiply-add = 2 flop; b = bytes per stored
+    # activation). The backward kernels recompute the first layer (and, for the edge kind, the
+    # second) of the forward: that recomputation is counted, it runs on the matrix cores.
+    work = {
+        "embed": dict(kernel="node-update layer: sum of incoming edge attributes + embed MLP", bound="mfma",
+                      flops=2.0 * N * H * (De + Dd + H),
+                      bytes=E * De * 4 + N * (4 + 4 * Dd) + 4 * (N + 1) + N * H * b),
+        "edge": dict(kernel="edge MLP + per-receiver sum (one launch per round)", bound="mfma",
+                     flops=2.0 * E * H * (3 * H + De),
+                     bytes=N * H * b + E * De * 4 + 4 * (2 * E + E // 32) + n_recv * H * b),
+        "node": dict(kernel="node MLP (one launch per round)", bound="mfma",
+                     flops=2.0 * N * H * 3 * H, bytes=3 * N * H * b),
+        "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", bound="hbm",
+                     flops=0.0, bytes=N * H * b + 4 * (G + 1) + G * H * 4),
+        "bwd_edge": dict(kernel="backward through the edge MLP (one launch per round)", bound="mfma",
+                         flops=2.0 * E * H * (6 * H + De), bytes=None),
+        "bwd_node": dict(kernel="backward through the node MLP (one launch per round)", bound="mfma",
+                         flops=2.0 * N * H * 5 * H, bytes=None),
+        "bwd_embed": dict(kernel="backward through the embed MLP", bound="mfma",
+                          flops=2.0 * N * H * (De + Dd + 2 * H), bytes=None),
+        # both layers' weight gradients of one MLP and their reductions; the launches of a step
+        # differ (R edge MLPs, R node MLPs, the embed MLP): flops = the step's total / its launches
+        "wgrad": dict(kernel="weight gradients dW = X^T dZ of one MLP, both layers (edge, node and embed MLPs averaged)",
+                      bound="mfma", bytes=None,
+                      flops=(R * (2.0 * E * H * (3 * H + De) + 2.0 * N * H * 3 * H)
+                             + 2.0 * N * H * (De + model["n_op_types"] + Dd + H)) / max(2 * R + 1, 1)),
+        "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", bound="hbm",
+                            flops=0.0, bytes=2 * E * H * b + 2 * N * H * b + 4 * (2 * N + E)),
+    }
+    report = {}
+    for k, wk in work.items():
+        if k not in kern or kern[k]["launches_per_step"] == 0 or kern[k]["avg_us"] <= 0:
+            continue
+        s = kern[k]["avg_us"] * 1e-6
+        e = dict(kernel=wk["kernel"], bound=wk["bound"], avg_launch_us=kern[k]["avg_us"],
+                 launches_per_step=kern[k]["launches_per_step"],
+                 share_of_step=kern[k]["avg_us"] * kern[k]["launches_per_step"] * 1e-3 / ms)
+        if wk["bound"] == "mfma":
+            e.update(achieved=wk["flops"] / s / 1e12, peak=peak, unit="TFLOP/s", flops_per_launch=wk["flops"])
+            if wk["bytes"] is not None:
+                e.update(algorithmic_bytes_per_launch=wk["bytes"], hbm_frac=wk["bytes"] / s / 1e9 / PEAK_HBM_GBS)
+        else:
+            e.update(achieved=wk["bytes"] / s / 1e9, peak=PEAK_HBM_GBS, unit="GB/s", algorithmic_bytes_per_launch=wk["bytes"])
+        e["frac"] = e["achieved"] / e["peak"]
+        e["traffic"] = measured_traffic(args.config, model["precision"], k)
+        report[k] = e
 
     res = dict(
         metric="candidate graphs encoded/sec on 1 MI355X", value=G / (ms * 1e-3), unit="graphs/s",
-        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms, higher_is_better=True,
-        scaling="weak", vs_baseline=None, dtype=model["precision"], data="synthetic",
+        n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms, ms_per_step_mean=ms_mean,
+        higher_is_better=True, scaling="weak", vs_baseline=None, dtype=model["precision"], data="synthetic",
         config=dict(workload=f"config {args.config} ({synth.CONFIGS[args.config]['name']}): {S} state(s), "
                              f"{G} graphs, {N} nodes, {E} edges, hidden {H}, {R} rounds, forward "
                              f"(encode + policy/value heads)" + (" + backward (heads, encoder)" if backward else ""),
                     states=S, graphs=G, nodes=N, edges=E, hidden=H, rounds=R),
         edges_per_s=E * R / (ms * 1e-3),
         pack_upload_ms=t_pack * 1e3,              # host packing + H2D copies, outside the timed region
-        roofline=dict(bound="mfma", kernel="edge MLP + per-receiver sum (one launch per round)",
-                      achieved=achieved, peak=peak, unit="TFLOP/s", frac=achieved / peak,
-                      traffic=edge_traffic(args.config, model["precision"]),
-                      flops_per_launch=edge_flops, avg_launch_us=kern["edge"]["avg_us"],
-                      algorithmic_bytes_per_launch=edge_bytes,
-                      hbm_frac=(edge_bytes / edge_s / 1e9 / PEAK_HBM_GBS if edge_s > 0 else 0.0)),
-        hbm_kernel=dict(kernel="per-graph readout sum (fused with the readout MLP)", bytes_per_launch=pool_bytes,
-                        achieved=(pool_bytes / pool_s / 1e9 if pool_s > 0 else 0.0), peak=PEAK_HBM_GBS,
-                        unit="GB/s", avg_launch_us=kern["pool"]["avg_us"]),
         kernels_us=kern,
     )
+    if report:
+        # the roofline entry rates the kernel that takes the largest share of the step
+        top = max(report, key=lambda k: report[k]["share_of_step"])
+        res["roofline"] = report[top]
+        res["kernels"] = {k: v for k, v in report.items() if k != top}
     if kern["resident"]["launches_per_step"] > 0:
         # small batch: the encoder ran as one launch (a block per graph), rated as a whole
-        enc_flops = 2.0 * N * H * (De + model["n_op_types"] + model["n_node_dense"] + H) \
-            + R * (edge_flops + 2.0 * N * H * 3 * H)
+        enc_flops = 2.0 * N * H * (De + model["n_op_types"] + Dd + H) + R * (work["edge"]["flops"] + 2.0 * N * H * 3 * H)
         enc_s = kern["resident"]["avg_us"] * 1e-6
         enc_bytes = (R + 1) * N * H * b + R * n_recv * H * b + E * De * 4 + 4 * (3 * E + 3 * N) + G * H * 4
         res["roofline"] = dict(bound="mfma", kernel="one-launch encoder (node-update layer, all rounds, readout)",
@@ -207,7 +301,6 @@ def main():
                                frac=enc_flops / enc_s / 1e12 / peak, traffic=None, flops_per_launch=enc_flops,
                                avg_launch_us=kern["resident"]["avg_us"], algorithmic_bytes_per_launch=enc_bytes,
                                hbm_frac=enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS)
-        res.pop("hbm_kernel")
     if args.round_kind == "gat":
         # attention rounds: the dense part z = h W on the matrix cores, then a gather-bound pass
         # (per edge one z row read, per node its own row read and one row written, scores, indices)
@@ -221,12 +314,35 @@ def main():
         res["mfma_kernel"] = dict(kernel="z = h W (one launch per round)", flops_per_launch=2.0 * N * H * H,
                                   achieved=2.0 * N * H * H / lin_s / 1e12, peak=peak, unit="TFLOP/s",
                                   frac=2.0 * N * H * H / lin_s / 1e12 / peak, avg_launch_us=kern["gat_linear"]["avg_us"])
+    if not args.no_segment_sum and E > 0:
+        # the receiver-side sum on its own: an [E, H] fp32 message tensor in receiver order summed
+        # into [N, H] (xrl_segment_sum), 5 launches after one warm-up
+        vals = torch.empty((E, H), dtype=torch.float32, device="cuda").normal_()
+        ptr = torch.from_numpy(hv["in_ptr"]).cuda()
+        out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        enc.segment_sum(vals, ptr, out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            enc.segment_sum(vals, ptr, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        seg_s = e0.elapsed_time(e1) * 1e-3 / 5
+        seg_bytes = E * H * 4 + 4 * (N + 1) + N * H * 4
+        res["segment_sum"] = dict(kernel="standalone receiver-side sum of an [E, H] fp32 tensor (segment-sum + carry fix-up)",
+                                  bound="hbm", algorithmic_bytes_per_launch=seg_bytes, avg_launch_us=seg_s * 1e6,
+                                  achieved=seg_bytes / seg_s / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
+                                  frac=seg_bytes / seg_s / 1e9 / PEAK_HBM_GBS)
+        del vals, out
     if args.peaks:
         tf, gb = enc.measure_peaks()
         res["measured_peaks"] = dict(mfma_bf16_tflops=tf, copy_gbs=gb,
                                      note="register-resident 32x32x16 bf16 MFMA loop; 1 GiB device copy, read + write")
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = oracle_baseline(model, state, w, budget_s=args.cpu_baseline_seconds)
+        if backward and args.round_kind == "mlp":
+            res["cpu_baseline"] = oracle_baseline_update(model, state, w, up_host, min(args.cpu_baseline_states, S))
+        else:
+            res["cpu_baseline"] = oracle_baseline_forward(model, state, w, args.cpu_baseline_seconds)
     print(json.dumps(res))
 
 

@@ -18,17 +18,24 @@ def test_more_than_one_gpu_is_refused():
 
 
 @pytest.mark.gpu
-def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
-    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "5", "--warmup", "2",
-                        "--cpu-baseline-seconds", "2"], capture_output=True, text=True, cwd=ROOT, timeout=600)
+@pytest.mark.parametrize("extra,workload", [
+    # the default run: the update minibatch (the largest single-GPU configuration), forward + backward
+    (["--steps", "3", "--warmup", "1", "--cpu-baseline-states", "1"], "config 5"),
+    (["--config", "2", "--steps", "5", "--warmup", "2", "--cpu-baseline-seconds", "2"], "config 2")])
+def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline(extra, workload):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")] + extra, capture_output=True, text=True,
+                       cwd=ROOT, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1
     d = json.loads(lines[0])
+    assert d["config"]["workload"].startswith(workload)
+    assert ("backward" in d["config"]["workload"]) == (workload == "config 5")
+    assert "segment_sum" in d and d["segment_sum"]["bound"] == "hbm" and 0 < d["segment_sum"]["frac"] < 1
     for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
               "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
         assert k in d, k
-    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2 and d["vs_baseline"] is None
+    assert d["n_gpus"] == 1 and d["steps"] == int(extra[extra.index("--steps") + 1]) and d["vs_baseline"] is None
     assert d["unit"] == "graphs/s" and d["value"] > 0 and d["data"] == "synthetic" and "workload" in d["config"]
     assert abs(d["value"] - d["config"]["graphs"] / (d["ms_per_step"] * 1e-3)) <= 1e-6 * d["value"]
     rf = d["roofline"]
