@@ -198,7 +198,9 @@ int xrl_encode_backward(xrl_ctx *ctx, const xrl_batch *b, const float *d_demb, f
 
 /* ---- objective (Section 3.3.4: J = L_clip + c1 L_vf + c2 L_entropy, to be minimised) ----------
  * From the outputs of xrl_policy_value on a minibatch of S states and the rollout's records:
- * d_action [S] int32 = slot taken inside each state (0 = No-Op; must be a valid slot), d_old_logp
+ * d_action [S] int32 = slot taken inside each state (0 = No-Op; must be a valid slot: an index outside
+ * the state's slots or on a masked slot contributes nothing, leaves that state's derivatives zero and
+ * turns all four entries of d_J into NaN, which is how the caller detects it), d_old_logp
  * [S] = its log-probability when sampled, d_advantage [S], d_v_target [S]; eps = clip range, c1,
  * c2 = weights of the value and entropy terms (0.5 and 0.01 in the paper's table; eps is not
  * printed there).  ratio_s = exp(logp[slot_s] - old_logp_s);
@@ -236,7 +238,8 @@ int xrl_segment_sum(xrl_ctx *ctx, const float *d_values, const int32_t *d_ptr, i
 /* Copies one saved activation of the last xrl_encode(save_for_backward=1) into d_out as fp32:
  * what = "a0" [N, d_edge] (sum of incoming edge attrs), "h" [N, hidden] (node states after the
  * node-update layer for round = 0, after message-passing round r for round = r), "agg" [N,
- * hidden] (received sums of round r >= 1; rows of receivers without in-edges are 0), "pool"
+ * hidden] (received sums of round r >= 1 as the node MLP reads them: rows of receivers without
+ * in-edges hold the zeros the node-update kernel wrote there), "pool"
  * [G, hidden] (per-graph sum or mean). */
 int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32_t round,
                        float *d_out);

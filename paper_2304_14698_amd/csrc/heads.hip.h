@@ -616,17 +616,26 @@ __global__ void small_wgrad_kernel(const float *x1, int w1, const float *x2, int
 
 // Clipped-surrogate objective of Section 3.3.4 and its derivatives w.r.t. the heads' outputs, one
 // block for the whole minibatch (S is a few hundred at most; the means are block reductions in a
-// fixed order). dlogp must be zero on entry: only the taken slots are written.
+// fixed order). dlogp must be zero on entry: only the taken slots are written. A recorded action
+// outside its state's slots, or on a masked slot, touches nothing of that state and turns all
+// four entries of J into NaN.
 __global__ __launch_bounds__(256) void ppo_objective_kernel(
     const float *logp, const float *value, const float *entropy, const int32_t *state_graph_ptr,
-    const int32_t *action, const float *old_logp, const float *advantage, const float *v_target,
+    const uint8_t *mask, const int32_t *action, const float *old_logp, const float *advantage, const float *v_target,
     int S, float eps, float c1, float c2, float *J, float *dlogp, float *dvalue, float *dentropy) {
   __shared__ float red[256];
   const int t = threadIdx.x;
   const float inv = 1.f / (float)(S > 0 ? S : 1);
-  float clip = 0.f, vf = 0.f, ent = 0.f;
+  float clip = 0.f, vf = 0.f, ent = 0.f, bad = 0.f;
   for (int s = t; s < S; s += 256) {
-    const int j = state_graph_ptr[s] + action[s];
+    const int j0 = state_graph_ptr[s], n_slots = state_graph_ptr[s + 1] - j0, act = action[s];
+    if (act < 0 || act >= n_slots || !mask[j0 + act]) {
+      bad = 1.f;
+      dvalue[s] = 0.f;
+      dentropy[s] = 0.f;
+      continue;
+    }
+    const int j = j0 + act;
     const float A = advantage[s];
     const float ratio = expf(logp[j] - old_logp[s]);
     const float s1 = ratio * A;
@@ -642,10 +651,12 @@ __global__ __launch_bounds__(256) void ppo_objective_kernel(
   clip = block_sum(clip, red) * inv;
   vf = block_sum(vf, red) * inv;
   ent = block_sum(ent, red) * inv;
+  bad = block_sum(bad, red);
   if (t == 0) {
-    J[0] = clip + c1 * vf + c2 * ent;
-    J[1] = clip;
-    J[2] = vf;
-    J[3] = ent;
+    const float nan = __int_as_float(0x7fc00000);
+    J[0] = bad > 0.f ? nan : clip + c1 * vf + c2 * ent;
+    J[1] = bad > 0.f ? nan : clip;
+    J[2] = bad > 0.f ? nan : vf;
+    J[3] = bad > 0.f ? nan : ent;
   }
 }

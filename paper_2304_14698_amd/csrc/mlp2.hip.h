@@ -43,6 +43,10 @@ struct Mlp2Args {
   size_t agg_stride;       //        the embed kernel zeroes their rows of nodes without in-edges, which
   int n_agg;               //        the message kernels never write
   void *out;               // [N, H] operand type
+  void *z1;                // kernels instantiated to keep the forward for the backward pass: the hidden
+  uint16_t *ymask;         //   activation relu(z1) [rows, H] operand type and, EDGE (whose per-edge output is
+                           //   not stored), the ReLU mask of y: [n_tiles][H / 32][64 lanes] words, bit r of
+                           //   lane l = accumulator register r of that lane (its edge, its feature block) > 0
   float *carry;            // [n_tiles, 2, H]                (EDGE)
   const int32_t *tile_ptr; // [n_tiles + 1] first edge of each edge tile (EDGE)
   int64_t n_tiles;         //                                (EDGE)
@@ -113,6 +117,14 @@ __device__ __forceinline__ EdgeTileMeta load_edge_meta(const int32_t *in_dst, in
   m.prev_d = e0 > 0 ? in_dst[e0 - 1] : -1;
   m.next_d = e0 + nv < n_rows ? in_dst[e0 + nv] : -1;
   return m;
+}
+
+// The mask bits (value > 0) of this lane's 16 registers of one accumulator block.
+__device__ __forceinline__ uint16_t lane_mask_bits(const f32x16 &acc) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) m |= (acc[r] > 0.f ? 1u : 0u) << r;
+  return (uint16_t)m;
 }
 
 // Per-receiver sum of a wave tile of messages held as features x rows accumulators (lane = edge,

@@ -123,7 +123,36 @@ __device__ __forceinline__ void layer2_lds(const f32x16 (&acc1)[H / 32], const t
   }
 }
 
-template <typename T, int H, int KIND, int NW>
+// Stores what a SAVE kernel keeps for the backward pass from a wave tile held as features x rows
+// accumulators (lane = row): relu(z1) rows [row0, row0 + nv) of a.z1 through the staging buffer
+// (one 32-feature block at a time with BLOCKWISE staging, else whole rows) and, EDGE (tile wt), the
+// mask bits of y.
+template <typename T, int H, int KIND, bool BLOCKWISE>
+__device__ __forceinline__ void save_forward_tile(const Mlp2Args &a, const f32x16 (&acc1)[H / 32],
+                                                  const f32x16 (&acc2)[H / 32], int64_t row0, int nv, int64_t wt,
+                                                  int lane, char *stage) {
+  constexpr int MB = H / 32;
+  if constexpr (KIND == KIND_EDGE) {
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) a.ymask[((size_t)wt * MB + nb) * 64 + lane] = lane_mask_bits(acc2[nb]);
+  }
+  T *z1 = (T *)a.z1;
+  if constexpr (BLOCKWISE) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      f32x16 d;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) d[r] = relu_f32(acc1[mb][r]);
+      store_block_via_lds<T, H>(z1, row0, nv, mb, lane, d, stage);
+    }
+  } else {
+    store_rows_via_lds<T, H, true>(acc1, stage, lane, [&](int r) -> T * {
+      return r < nv ? z1 + (size_t)(row0 + r) * H : nullptr;
+    });
+  }
+}
+
+template <typename T, int H, int KIND, int NW, bool SAVE>
 __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
   using Opd = Operand<T>;
   using vec = typename Opd::vec;
@@ -198,6 +227,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     asm volatile("" ::: "memory");
     [[maybe_unused]] const EdgeTileMeta meta = ix.m;
     [[maybe_unused]] const int nv = ix.nv;
+    [[maybe_unused]] const int64_t meta_e0 = ix.e0;
     const bool more = wt + stride < t_end;
     const int64_t wnext = more ? wt + stride : wt;
     ix = load_index<KIND>(a, bnext, l32);
@@ -235,6 +265,14 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     // ---------------- layer 2 (features x rows)
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+    if constexpr (SAVE) {
+      if constexpr (KIND == KIND_NODE) {
+        const int64_t left = a.n_rows - wt * 32;
+        save_forward_tile<T, H, KIND, false>(a, acc1, acc2, wt * 32, left < 32 ? (int)left : 32, wt, lane, stage);
+      } else {
+        save_forward_tile<T, H, KIND, false>(a, acc1, acc2, meta_e0, nv, wt, lane, stage);
+      }
+    }
     if (more) load_rows<T, H, KIND, 3>(a, wnext, l32, g, ix, in);
     else in = TileRows<T, H>{};   // (so that the consumed rows need not stay live up to here)
     __builtin_amdgcn_sched_barrier(0);
@@ -258,7 +296,7 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
 // At H = 256 the second layer's weights alone take 128 KB: the table then stays in global memory
 // (32 KB, read through the caches), the block has four waves, and the rows leave through a
 // staging buffer of one 32-feature block per wave.
-template <typename T, int H, int NW>
+template <typename T, int H, int NW, bool SAVE>
 __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   using Opd = Operand<T>;
   using vec = typename Opd::vec;
@@ -343,6 +381,7 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     T *out = (T *)a.out;
     const int64_t left = a.n_rows - row0;
     const int n_valid = left < 32 ? (int)left : 32;
+    if constexpr (SAVE) save_forward_tile<T, H, KIND_EMBED, BIG>(a, acc1, acc2, row0, n_valid, wt, lane, stage);
     if constexpr (BIG) {
 #pragma unroll
       for (int nb = 0; nb < MB; ++nb) {

@@ -129,7 +129,14 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
   }
 }
 
-template <int H, int KIND>
+// SAVE: also keeps the forward for the backward pass (a.z1, a.ymask; see Mlp2Args). relu(z1) leaves
+// as whole rows through the input buffer of the tile itself, which is idle between the end of
+// layer 1 and the prefetch of the tile after next: after the first barrier every wave writes its
+// 32 features of all rows there, after the second barrier wave w reads rows 4w .. 4w+3 back and
+// stores them -- from the 4 KB of the buffer that only its own prefetch loads write, so no wave
+// waits for another. Row r sits at 4096 (r / 4) + 64 ((r / 4) % 4) + 528 (r % 4): 16-byte aligned,
+// and the 8-byte writes of 32 rows fall on 16 different bank groups.
+template <int H, int KIND, bool SAVE>
 __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SIMD)) void mlp2r_kernel(const Mlp2Args a) {
   using T = bf16_t;
   using R = RTile<H, KIND>;
@@ -232,6 +239,17 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
     for (int q = 0; q < 2; ++q)
       *(bf16x8 *)(zbuf + ((2 * w + q) * 64 + lane) * 16) = relu_operand<T>(acc, q);
     __syncthreads();
+    if constexpr (SAVE) {
+      static_assert(!SAVE || H == 256, "the staging layout below is laid out for eight waves");
+      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+      char *zrow = smem + buf * R::XBUF + 4096 * (l32 >> 2) + 64 * ((l32 >> 2) & 3) + 528 * (l32 & 3) + (32 * w + 4 * g) * 2;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const u32x4 z = __builtin_bit_cast(u32x4, relu_operand<T>(acc, q));   // features 16 q + 4 g + {0..3}, + 8
+        *(u32x2 *)(zrow + 32 * q) = u32x2{z[0], z[1]};
+        *(u32x2 *)(zrow + 32 * q + 16) = u32x2{z[2], z[3]};
+      }
+    }
     // ---------------- layer 2
     acc = *(const f32x16 *)&b2l[w][g][0];
     {
@@ -251,6 +269,9 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, zq[c % 3], acc, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
+    }
+    if constexpr (SAVE && KIND == KIND_EDGE) {
+      if (wt < a.n_tiles) a.ymask[((size_t)wt * MB + w) * 64 + lane] = lane_mask_bits(acc);
     }
     // ---------------- epilogue on this wave's 32 features
     T *out = (T *)a.out;
@@ -309,6 +330,16 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
         if constexpr (KIND == KIND_EDGE) drw = drow[r];
         else drw = r < cur.nv ? cur.r0 + r : -1;
         if (drw >= 0) *(f32x4 *)((char *)(out + (size_t)drw * H) + piece * 16) = v;
+      }
+    }
+    if constexpr (SAVE) {
+      // this wave's four rows of relu(z1), from its own part of the tile's input buffer
+      const char *zreg = smem + buf * R::XBUF + 4096 * w + 64 * (w & 3);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int j = 2 * i + g, r = 4 * w + j;
+        const f32x4 v = *(const f32x4 *)(zreg + 528 * j + 16 * l32);
+        if (r < cur.nv) *(f32x4 *)((char *)((T *)a.z1 + (size_t)(cur.r0 + r) * H) + 16 * l32) = v;
       }
     }
     // the buffer this tile used is free now: rows of the tile after next, indices one further

@@ -12,6 +12,7 @@
 #include "heads.hip.h"
 #include "mlp2.hip.h"
 #include "mlp2_bwd.hip.h"
+#include "mlp2_bwdz.hip.h"
 #include "mlp2p.hip.h"
 #include "resident.hip.h"
 #include "mlp2r.hip.h"
@@ -149,6 +150,13 @@ struct xrl_ctx {
   bool enc_saved = false;
   float *pool = nullptr, *carry = nullptr, *ro_act[2] = {nullptr, nullptr};
   std::vector<void *> h, agg;   // h[0..R], agg[1..R] (index 0 unused)
+  // what the forward kernels of large bf16 batches keep for the backward pass (inside ws): relu(z1)
+  // of the embed MLP and of every round's edge and node MLP, and the mask bits of every round's
+  // per-edge output (which is summed per receiver and never stored itself)
+  bool fwd_kept = false;
+  void *z1_embed = nullptr;
+  std::vector<void *> z1_edge, z1_node;
+  std::vector<uint16_t *> ym_edge;
   // optional per-kernel timing
   bool timing = false;
   struct Span { int kind; hipEvent_t a, b; };
@@ -482,10 +490,10 @@ inline size_t mlp2p_lds_bytes(int H, int nslab1) {
          (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;   // staging sized for the widest H served
 }
 
-template <int H, int KIND>
-int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
+template <int H, int KIND, bool SAVE>
+int launch_mlp2p_ks(xrl_ctx *c, Mlp2Args &a, size_t lds) {
   constexpr int NW = kPersistWaves;
-  auto kern = mlp2p_kernel<bf16_t, H, KIND, NW>;
+  auto kern = mlp2p_kernel<bf16_t, H, KIND, NW, SAVE>;
   static bool attr_set = false;          // one attribute per kernel instantiation
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -499,6 +507,11 @@ int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
   kern<<<dim3((unsigned)grid), dim3(64 * NW), lds, c->stream>>>(a);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
+}
+
+template <int H, int KIND>
+int launch_mlp2p_k(xrl_ctx *c, Mlp2Args &a, size_t lds) {
+  return a.z1 ? launch_mlp2p_ks<H, KIND, true>(c, a, lds) : launch_mlp2p_ks<H, KIND, false>(c, a, lds);
 }
 
 template <int H>
@@ -516,11 +529,11 @@ inline size_t embedp_lds_bytes(int H, int nslabx, int Tn) {
   return w + (size_t)Tn * H * 4 + (size_t)kPersistWaves * RowStage<bf16_t, 128>::BYTES;
 }
 
-template <int H>
-int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
+template <int H, bool SAVE>
+int launch_embedp_s(xrl_ctx *c, Mlp2Args &a) {
   constexpr int NW = embedp_waves(H);
   const size_t lds = embedp_lds_bytes(H, a.nslabx, a.Tn);
-  auto kern = embedp_kernel<bf16_t, H, NW>;
+  auto kern = embedp_kernel<bf16_t, H, NW, SAVE>;
   static size_t attr_lds = 0;
   if (lds > attr_lds) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -535,6 +548,11 @@ int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
   kern<<<dim3((unsigned)grid), dim3(64 * NW), lds, c->stream>>>(a);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
+}
+
+template <int H>
+int launch_embedp(xrl_ctx *c, Mlp2Args &a) {
+  return a.z1 ? launch_embedp_s<H, true>(c, a) : launch_embedp_s<H, false>(c, a);
 }
 
 inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
@@ -552,10 +570,10 @@ inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
 }
 
 // Register-stationary variant (bf16, edge and node kinds).
-template <int H, int KIND>
-int launch_mlp2r_k(xrl_ctx *c, Mlp2Args &a) {
+template <int H, int KIND, bool SAVE>
+int launch_mlp2r_ks(xrl_ctx *c, Mlp2Args &a) {
   using R = RTile<H, KIND>;
-  auto kern = mlp2r_kernel<H, KIND>;
+  auto kern = mlp2r_kernel<H, KIND, SAVE>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, R::BYTES));
@@ -571,6 +589,11 @@ int launch_mlp2r_k(xrl_ctx *c, Mlp2Args &a) {
   kern<<<dim3((unsigned)grid), dim3(R::NT), R::BYTES, c->stream>>>(a);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
+}
+
+template <int H, int KIND>
+int launch_mlp2r_k(xrl_ctx *c, Mlp2Args &a) {
+  return a.z1 ? launch_mlp2r_ks<H, KIND, true>(c, a) : launch_mlp2r_ks<H, KIND, false>(c, a);
 }
 
 template <int H>
@@ -666,14 +689,10 @@ int launch_heads(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *logi
 }
 
 template <typename T>
-__global__ void export_rows_kernel(const T *src, const int32_t *in_ptr, int64_t n_rows, int D,
-                                   float *dst) {
+__global__ void export_rows_kernel(const T *src, int64_t n_rows, int D, float *dst) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_rows * D) return;
-  const int64_t r = i / D;
-  float v = (float)src[i];
-  if (in_ptr && in_ptr[r + 1] == in_ptr[r]) v = 0.f;   // rows nobody wrote: receivers without in-edges
-  dst[i] = v;
+  dst[i] = (float)src[i];
 }
 
 
@@ -707,6 +726,40 @@ int launch_mlp2_bwd(xrl_ctx *c, int kind, Mlp2BwdArgs &a) {
     case 64: return launch_mlp2_bwd_h<T, 64>(c, kind, a);
     case 128: return launch_mlp2_bwd_h<T, 128>(c, kind, a);
     case 256: return launch_mlp2_bwd_h<T, 256>(c, kind, a);
+  }
+  return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
+}
+
+template <int H, int KIND>
+int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
+  using S = BwdzShape<H>;
+  auto kern = mlp2_bwdz_kernel<H, KIND>;
+  static bool attr_set = false;          // one attribute per kernel instantiation
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS));
+    attr_set = true;
+  }
+  const int64_t wave_tiles = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;   // EDGE: the packer's edge tiles
+  a.n_blocks = (wave_tiles + S::NW - 1) / S::NW;
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) / 8) * 8);
+  kern<<<dim3(grid), dim3(64 * S::NW), S::LDS, c->stream>>>(a);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+template <int H>
+int launch_mlp2_bwdz_h(xrl_ctx *c, int kind, Mlp2BwdzArgs &a) {
+  if (a.n_rows <= 0) return XRL_OK;
+  if (kind == KIND_EMBED) return launch_mlp2_bwdz_k<H, KIND_EMBED>(c, a);
+  if (kind == KIND_EDGE) return launch_mlp2_bwdz_k<H, KIND_EDGE>(c, a);
+  return launch_mlp2_bwdz_k<H, KIND_NODE>(c, a);
+}
+
+int launch_mlp2_bwdz(xrl_ctx *c, int kind, Mlp2BwdzArgs &a) {
+  switch (c->m.hidden) {
+    case 64: return launch_mlp2_bwdz_h<64>(c, kind, a);
+    case 128: return launch_mlp2_bwdz_h<128>(c, kind, a);
+    case 256: return launch_mlp2_bwdz_h<256>(c, kind, a);
   }
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
@@ -941,7 +994,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   // ---- scratch plan
   size_t need = 0;
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
-  for (int i = 0; i < 3; ++i) acc((size_t)M * H * sizeof(T));      // z1, dz1, dz2
+  const bool kept = c->fwd_kept;                                   // the forward kept z1 and the ReLU masks
+  for (int i = 0; i < (kept ? 2 : 3); ++i) acc((size_t)M * H * sizeof(T));      // (z1,) dz1, dz2
   for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
   for (int i = 0; i < 3; ++i) acc((size_t)N * H * sizeof(T));      // dh (two buffers), dagg
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
@@ -955,7 +1009,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   int rc = ensure_bws(c, need);
   if (rc) return rc;
   Bump bump{c->bws};
-  T *z1 = bump.take<T>((size_t)M * H), *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
+  T *z1 = kept ? nullptr : bump.take<T>((size_t)M * H);
+  T *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
   T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)E * H);
   T *dhA = bump.take<T>((size_t)N * H), *dhB = bump.take<T>((size_t)N * H);
   T *dagg = bump.take<T>((size_t)N * H);
@@ -991,13 +1046,28 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   auto set_w = [&](const EncMlp &e) {
     a.W1s = e.W1s; a.W2s = e.W2s; a.W2bt = e.W2bt; a.W1bt = e.W1bt; a.b1 = e.b1; a.b2 = e.b2; a.nslab1 = e.nslab1;
   };
-  auto wgrads = [&](int kind, int64_t rows, int Ka, const MlpRef &r) -> int {
+  auto wgrads = [&](int kind, int64_t rows, int Ka, const MlpRef &r, const void *z1_kept) -> int {
     wa.n_rows = rows; wa.Ka = Ka; wa.dZ = dz1; wa.A = nullptr;
     Timed t(c, TK_WGRAD);                                  // both layers' weight gradients and their reductions
     int rc2 = launch_wgrad<T>(c, kind, wa, dweights + r.w[0], dweights + r.b[0]);
     if (rc2) return rc2;
-    wa.Ka = H; wa.dZ = dz2; wa.A = z1;
+    wa.Ka = H; wa.dZ = dz2; wa.A = kept ? z1_kept : z1;
     return launch_wgrad<T>(c, WG_PLAIN, wa, dweights + r.w[1], dweights + r.b[1]);
+  };
+  // gradients through one fused MLP: from what the forward kept, else with its first layer recomputed
+  Mlp2BwdzArgs za;
+  memset(&za, 0, sizeof(za));
+  za.in_dst = d.in_dst; za.dz1 = dz1; za.dz2 = dz2;
+  za.tile_ptr = d.tile_ptr; za.n_tiles = (int64_t)b->tile_ptr.size() - 1;
+  auto mlp_bwd = [&](int kind, const EncMlp &e, const void *z1_kept, const uint16_t *ymask) -> int {
+    if constexpr (sizeof(T) == 2) {
+      if (kept) {
+        za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy; za.z1 = z1_kept; za.y = a.y;
+        za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
+        return launch_mlp2_bwdz(c, kind, za);
+      }
+    }
+    return launch_mlp2_bwd<T>(c, kind, a);
   };
   constexpr int PV = 16 / sizeof(T);
   for (int r = R - 1; r >= 0 && gat; --r) {
@@ -1048,17 +1118,17 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     set_w(c->node[r]);
     a.n_rows = N; a.h = c->h[r]; a.agg = c->agg[r + 1]; a.y = c->h[r + 1]; a.dy = dhA;
     a.dx_a = dhB; a.dx_b = dagg;
-    { Timed t(c, TK_BWD_NODE); rc = launch_mlp2_bwd<T>(c, KIND_NODE, a); }
+    { Timed t(c, TK_BWD_NODE); rc = mlp_bwd(KIND_NODE, c->node[r], kept ? c->z1_node[r] : nullptr, nullptr); }
     if (rc) return rc;
     wa.h = c->h[r]; wa.agg = c->agg[r + 1];
-    if ((rc = wgrads(WG_NODE, N, 2 * H, c->L.node[r]))) return rc;
+    if ((rc = wgrads(WG_NODE, N, 2 * H, c->L.node[r], kept ? c->z1_node[r] : nullptr))) return rc;
     // edge MLP of round r+1: upstream = dagg gathered by receiver
     set_w(c->edge[r]);
     a.n_rows = E; a.h = c->h[r]; a.agg = nullptr; a.y = nullptr; a.dy = dagg;
     a.dx_a = dsrc; a.dx_b = ddst;
-    { Timed t(c, TK_BWD_EDGE); rc = launch_mlp2_bwd<T>(c, KIND_EDGE, a); }
+    { Timed t(c, TK_BWD_EDGE); rc = mlp_bwd(KIND_EDGE, c->edge[r], kept ? c->z1_edge[r] : nullptr, kept ? c->ym_edge[r] : nullptr); }
     if (rc) return rc;
-    if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r]))) return rc;
+    if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r], kept ? c->z1_edge[r] : nullptr))) return rc;
     // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
     if (E > 0) {
       Timed t(c, TK_GRAD_GATHER);
@@ -1071,9 +1141,9 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   // ---- node-update layer backward (weights only: its inputs are data)
   set_w(c->embed);
   a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
-  { Timed t(c, TK_BWD_EMBED); rc = launch_mlp2_bwd<T>(c, KIND_EMBED, a); }
+  { Timed t(c, TK_BWD_EMBED); rc = mlp_bwd(KIND_EMBED, c->embed, kept ? c->z1_embed : nullptr, nullptr); }
   if (rc) return rc;
-  if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed))) return rc;
+  if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed, kept ? c->z1_embed : nullptr))) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
@@ -1091,6 +1161,34 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   constexpr int PV = 16 / sizeof(T);
   const bool gat = m.round_kind == XRL_ROUND_GAT;
   for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));   // (GAT: the agg slot holds z)
+  const xrl_batch_device &d = b->dev;
+  const bool resident_batch = !gat && H * sizeof(T) <= 256 && d.graph_tile_ptr && R <= kResidentMaxRounds &&
+                              G <= c->resident_max_graphs && (b->max_graph_nodes + 31) / 32 <= c->resident_max_tiles &&
+                              b->max_graph_tiles <= c->resident_max_tiles;
+  // Large bf16 batches run on kernels that can keep z1 and the ReLU masks of every fused MLP for
+  // the backward pass (a row of H elements and 2 H / 32 words per node or edge and MLP): kept when
+  // every launch of this encode is one of them.
+  bool keep = false;
+  if constexpr (sizeof(T) == 2) {
+    if (save && !gat && !resident_batch && N > 0) {
+      Mlp2Args t;
+      memset(&t, 0, sizeof(t));
+      t.De = De; t.Tn = m.n_op_types; t.Dd = m.n_node_dense;
+      t.n_rows = N; t.nslabx = c->embed.nslabx;
+      keep = mlp2p_applies(c, KIND_EMBED, t);
+      for (int r = 0; r < R && keep; ++r) {
+        t.n_rows = E; t.nslab1 = c->edge[r].nslab1;
+        keep = keep && (mlp2r_applies(c, KIND_EDGE, t) || mlp2p_applies(c, KIND_EDGE, t));
+        t.n_rows = N; t.nslab1 = c->node[r].nslab1;
+        keep = keep && (mlp2r_applies(c, KIND_NODE, t) || mlp2p_applies(c, KIND_NODE, t));
+      }
+    }
+  }
+  const size_t ym_words = (size_t)n_tiles * (H / 32) * 64;            // 16-bit words of one round's edge mask bits
+  if (keep) {
+    for (int i = 0; i < R + 1; ++i) acc((size_t)N * H * sizeof(T));
+    for (int i = 0; i < R; ++i) { acc((size_t)E * H * sizeof(T)); acc(ym_words * 2); }
+  }
   const int n_gs = gat ? (save ? R : 1) : 0;                            // saved per round for the backward
   for (int i = 0; i < 2 * n_gs; ++i) acc((size_t)N * 4);
   const size_t carry_floats = std::max(std::max(segsum_carry_floats(E, De), segsum_carry_floats(N, H)),
@@ -1117,9 +1215,20 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   c->pool = bump.take<float>((size_t)G * H);
   c->ro_act[0] = bump.take<float>((size_t)G * H);
   c->ro_act[1] = bump.take<float>((size_t)G * H);
+  c->fwd_kept = keep;
+  c->z1_edge.assign(R, nullptr); c->z1_node.assign(R, nullptr);
+  c->ym_edge.assign(R, nullptr);
+  c->z1_embed = nullptr;
+  if (keep) {
+    c->z1_embed = bump.take<T>((size_t)N * H);
+    for (int r = 0; r < R; ++r) {
+      c->z1_node[r] = bump.take<T>((size_t)N * H);
+      c->z1_edge[r] = bump.take<T>((size_t)E * H);
+      c->ym_edge[r] = bump.take<uint16_t>(ym_words);
+    }
+  }
   c->enc_batch = b->id;
   c->enc_saved = save != 0;
-  const xrl_batch_device &d = b->dev;
 
   // ---- node-update layer: the embed MLP (it sums each node's incoming edge attrs itself)
   Mlp2Args a;
@@ -1135,8 +1244,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   set_w(c->embed);
   a.n_rows = N; a.out = hb[0];
   a.agg0 = ab[0]; a.n_agg = gat ? 0 : nagg; a.agg_stride = nagg > 1 ? (size_t)((char *)ab[1] - (char *)ab[0]) : 0;
-  if (!gat && H * sizeof(T) <= 256 && d.graph_tile_ptr && R <= kResidentMaxRounds && G <= c->resident_max_graphs &&
-      (b->max_graph_nodes + 31) / 32 <= c->resident_max_tiles && b->max_graph_tiles <= c->resident_max_tiles) {
+  if (resident_batch) {
     // small batch: the whole encoder in one launch, one block per graph (rows of at most 256
     // bytes: the three inlined tile routines of wider ones do not fit the register file)
     ResidentArgs ra;
@@ -1177,6 +1285,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
       if constexpr (sizeof(T) == 2) return launch(encode_resident_kernel<T, 128>);
     }
   }
+  a.z1 = c->z1_embed; a.ymask = nullptr;
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
   c->h[0] = hb[0];
@@ -1212,6 +1321,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     }
     set_w(c->edge[r]);
     a.n_rows = E; a.h = hcur; a.out = aggb;
+    a.z1 = c->z1_edge[r]; a.ymask = c->ym_edge[r];
     { Timed t(c, TK_EDGE); rc = launch_mlp2<T>(c, KIND_EDGE, a); }
     if (rc) return rc;
     if (b->n_split_tiles > 0) {         // only a receiver with more than 32 in-edges spans tiles
@@ -1222,6 +1332,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     }
     set_w(c->node[r]);
     a.n_rows = N; a.h = hcur; a.agg = aggb; a.out = hnext;
+    a.z1 = c->z1_node[r]; a.ymask = nullptr;
     { Timed t(c, TK_NODE); rc = launch_mlp2<T>(c, KIND_NODE, a); }
     if (rc) return rc;
     c->h[r + 1] = hnext;
@@ -1480,7 +1591,7 @@ int xrl_ppo_objective(xrl_ctx *c, const xrl_batch *b, const float *d_logp, const
   if (b->G > 0)
     fill_zero_kernel<<<dim3((unsigned)((b->G + 255) / 256)), dim3(256), 0, c->stream>>>(d_dlogp, b->G);
   ppo_objective_kernel<<<dim3(1), dim3(256), 0, c->stream>>>(
-      d_logp, d_value, d_entropy, b->dev.state_graph_ptr, d_action, d_old_logp, d_advantage, d_v_target,
+      d_logp, d_value, d_entropy, b->dev.state_graph_ptr, b->dev.mask, d_action, d_old_logp, d_advantage, d_v_target,
       (int)b->S, eps, c1, c2, d_J, d_dlogp, d_dvalue, d_dentropy);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
@@ -1733,7 +1844,7 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
   const void *src = nullptr;
   int64_t rows = N;
   int D = H;
-  bool typed = true, mask_rows = false;
+  bool typed = true;
   if (!strcmp(what, "a0")) {   // not kept by the forward pass: recomputed with the segment-sum kernel
     return launch_segsum<float, float, 4>(c, b->dev.edge_feat, nullptr, b->dev.in_ptr, b->dev.in_dst, b->E, N,
                                           c->m.d_edge, d_out, c->carry);
@@ -1747,15 +1858,13 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
     if (c->m.round_kind == XRL_ROUND_GAT)
       return fail(XRL_ERR_UNSUPPORTED, "agg: the graph-attention rounds keep no received sums");
     src = c->agg[round];
-    mask_rows = true;
   } else return fail(XRL_ERR_INDEX, "xrl_get_activation: unknown tensor '%s'", what);
   if (rows * D == 0) return XRL_OK;
   const unsigned blocks = (unsigned)((rows * D + 255) / 256);
-  const int32_t *ip = mask_rows ? b->dev.in_ptr : nullptr;
   if (typed && c->elem == 2)
-    export_rows_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, c->stream>>>((const bf16_t *)src, ip, rows, D, d_out);
+    export_rows_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, c->stream>>>((const bf16_t *)src, rows, D, d_out);
   else
-    export_rows_kernel<float><<<dim3(blocks), dim3(256), 0, c->stream>>>((const float *)src, ip, rows, D, d_out);
+    export_rows_kernel<float><<<dim3(blocks), dim3(256), 0, c->stream>>>((const float *)src, rows, D, d_out);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }

@@ -3,9 +3,14 @@
 Tolerances (per output tensor, elementwise |x - ref| <= atol + rtol |ref|, scale = max|ref|):
   fp32 path: rtol 1e-5, atol 1e-5 * scale;  bf16 path: rtol 2e-2, atol 1e-3 * max(1, scale).
   logp is a difference of logits (logit - logsumexp), so its scale is max(|logp|, |logit|).
-  bf16 embeddings: the 22 chained bf16 layers leave a rounding error of up to about 2.5e-3 of the
-  tensor's scale on elements that are themselves small; they are asserted at atol 4e-3 * scale and
-  the share of elements beyond the 1e-3 bound is asserted to stay below 3 %.
+  bf16 embeddings: the stated bound on the transformer- and ResNet-shaped configurations (hidden
+  128; measured worst excess over 2e-2 |ref|: 2e-4 and 6e-4 of the scale). Elsewhere the absolute
+  term is 2.5e-3 * scale and at most 3 % of the elements may lie beyond the stated bound: at hidden
+  256 the contractions are twice as long, and the rounding of the weights to bf16 is common to
+  all nodes of a graph, so it does not average out in the per-graph sum of a thousand node
+  states (measured worst excess 2.2e-3 of the scale and 1.2 % of the elements on the
+  Inception-shaped configuration, 1.3e-3 and 0.4 % on the update minibatch); the small ragged
+  cases (a few graphs, halved or op-dominated weights) reach 1.3e-3 to 1.9e-3 on a few elements.
   bf16 per-node intermediates (millions of elements, checked as a debugging aid): atol 2e-2 * scale.
 Integer outputs (action) and mask handling (-inf / exact zeros) are compared bit-exactly; the
 action is also checked to be the first maximum of the GPU's own logits.
@@ -36,8 +41,8 @@ def tol(precision, ref, scale=None):
         # 2^-9 sqrt(K) rms|x w|, roughly 1e-3 of the tensor's scale per layer; over five rounds
         # the far tail of millions of elements reaches 1.3e-2 of the scale.
         return (2e-2, 2e-2 * max(1.0, m))
-    if precision == "bf16-emb":
-        return (2e-2, 4e-3 * max(1.0, m))
+    if precision == "bf16-emb256":
+        return (2e-2, 2.5e-3 * max(1.0, m))
     return (1e-5, 1e-5 * m) if precision == "fp32" else (2e-2, 1e-3 * max(1.0, m))
 
 
@@ -52,6 +57,59 @@ def assert_close(got, ref, precision, what, scale=None):
                              f"got {got[i]!r} ref {ref[i]!r} (rtol {rtol}, atol {atol:.3g})")
 
 
+def check_emb(got, ref, model, what, scale=None, contract=False):
+    """Embeddings at the path's tolerance. bf16: the stated bound (absolute term 1e-3 of the scale)
+    with contract=True -- the transformer- and ResNet-shaped configurations at hidden 128; else the
+    absolute term is 2.5e-3 of the scale and at most 3 % of the elements may lie beyond the stated
+    bound (see the module docstring)."""
+    prec = model["precision"]
+    if prec == "bf16" and not contract:
+        assert_close(got, ref, "bf16-emb256", what, scale=scale)
+        rtol, atol = tol("bf16", ref, scale)
+        over = np.abs(got - ref) > atol + rtol * np.abs(ref)
+        assert over.mean() < 0.03, f"{what}: {over.mean():.3%} of elements beyond rtol 2e-2 / atol 1e-3*scale"
+    else:
+        assert_close(got, ref, prec, what, scale=scale)
+
+
+def check_heads_against_oracle(pv, rp, state, prec, what=""):
+    """Outputs of xrl_policy_value (numpy arrays) against the oracle's for the same states: logit,
+    logp, value, entropy at the path's tolerance; masked slots -inf; action = first maximum of the
+    GPU's own logits, and the oracle's action wherever the oracle's two best valid logits are
+    further apart than twice the logit tolerance. Where they are not (a near tie: several actions
+    are correct at the path's precision) the chosen slot must be one whose oracle logit lies
+    within that distance of the oracle's best. Returns the number of near-tie states."""
+    mask = np.asarray(state["slot_mask"]).astype(bool)
+    sgp = np.asarray(state["state_graph_ptr"])
+    logit, logp = pv["logit"], pv["logp"]
+    lscale = float(np.abs(rp["logit"]).max())
+    assert_close(logit, rp["logit"], prec, what + "logit")
+    assert_close(logp[mask], rp["logp"][mask], prec, what + "logp", scale=lscale)
+    assert np.all(np.isneginf(logp[~mask])), "masked slots must have logp = -inf"
+    # a head's output is a sum of terms that may cancel (a state's value can lie near zero), so
+    # the absolute term is taken at the scale of the heads' outputs in this batch, as for logp
+    assert_close(pv["value"], rp["value"], prec, what + "value", scale=lscale)
+    assert_close(pv["entropy"], rp["entropy"], prec, what + "entropy")
+    near_ties = 0
+    for s in range(len(sgp) - 1):
+        j0, j1 = sgp[s], sgp[s + 1]
+        l = np.where(mask[j0:j1], logit[j0:j1], -np.inf)
+        assert pv["action"][s] == int(np.argmax(l)), "action must be the first max of the GPU's own logits"
+        ro = np.sort(rp["logit"][j0:j1][mask[j0:j1]])
+        gap = ro[-1] - ro[-2] if ro.size > 1 else np.inf
+        rtol, atol = tol(prec, rp["logit"])
+        thr = 2 * (atol + rtol * abs(ro[-1]))
+        if gap > thr:
+            assert pv["action"][s] == rp["action"][s], f"state {s}: action differs from the oracle's"
+        else:
+            near_ties += 1
+            chosen = j0 + int(pv["action"][s])
+            assert mask[chosen] and rp["logit"][chosen] >= ro[-1] - thr, f"state {s}: action is not a near-best slot"
+    sums = np.add.reduceat(np.where(mask, np.exp(logp.astype(np.float64)), 0.0), sgp[:-1])
+    np.testing.assert_allclose(sums, 1.0, atol=1e-5)
+    return near_ties
+
+
 def oracle_model(model):
     return O.default_model(**{k: model[k] for k in ("n_op_types", "n_node_dense", "d_edge", "d_global",
                                                     "hidden", "rounds", "mlp_layers", "head_hidden",
@@ -63,7 +121,7 @@ def weights_for(model, seed=11):
     return synth.init_weights(rng, O.weight_layout(oracle_model(model)), bias_range=0.1)
 
 
-def run_case(xrl, model, state, w, check_inter=True):
+def run_case(xrl, model, state, w, check_inter=True, contract_emb=False):
     import torch
     prec = model["precision"]
     om = oracle_model(model)
@@ -84,42 +142,13 @@ def run_case(xrl, model, state, w, check_inter=True):
                              cat(lambda i: i["agg"][r - 1]), pi, f"agg[{r}]")
         assert_close(enc.get_activation(batch, "pool").cpu().numpy(),
                      np.stack([i["pool"] for i in inter]), pi, "pool")
-    if prec == "fp32":
-        assert_close(emb.cpu().numpy(), ref_emb, prec, "emb")
-    else:
-        assert_close(emb.cpu().numpy(), ref_emb, "bf16-emb", "emb")
-        rtol, atol = tol("bf16", ref_emb)
-        over = np.abs(emb.cpu().numpy() - ref_emb) > atol + rtol * np.abs(ref_emb)
-        assert over.mean() < 0.03, f"emb: {over.mean():.3%} of elements beyond rtol 2e-2 / atol 1e-3*scale"
+    check_emb(emb.cpu().numpy(), ref_emb, model, "emb", contract=contract_emb)
     # heads: compare on the oracle's own embeddings path (end to end), then the discrete parts
     rp = O.policy_value(om, w, ref_emb, state)
-    mask = np.asarray(state["slot_mask"]).astype(bool)
-    logp = pv["logp"].cpu().numpy()
-    logit = pv["logit"].cpu().numpy()
-    assert_close(logit, rp["logit"], prec, "logit")
-    assert_close(logp[mask], rp["logp"][mask], prec, "logp", scale=float(np.abs(rp["logit"]).max()))
-    assert np.all(np.isneginf(logp[~mask])), "masked slots must have logp = -inf"
-    # a head's output is a sum of terms that may cancel (a state's value can lie near zero), so
-    # the absolute term is taken at the scale of the heads' outputs in this batch, as for logp
-    assert_close(pv["value"].cpu().numpy(), rp["value"], prec, "value", scale=float(np.abs(rp["logit"]).max()))
-    assert_close(pv["entropy"].cpu().numpy(), rp["entropy"], prec, "entropy")
-    action = pv["action"].cpu().numpy()
-    sgp = state["state_graph_ptr"]
-    near_ties = 0
-    for s in range(len(sgp) - 1):
-        j0, j1 = sgp[s], sgp[s + 1]
-        l = np.where(mask[j0:j1], logit[j0:j1], -np.inf)
-        assert action[s] == int(np.argmax(l)), "action must be the first max of the GPU's own logits"
-        ro = np.sort(rp["logit"][j0:j1][mask[j0:j1]])
-        gap = ro[-1] - ro[-2] if ro.size > 1 else np.inf
-        rtol, atol = tol(prec, rp["logit"])
-        if gap > 2 * (atol + rtol * abs(ro[-1])):
-            assert action[s] == rp["action"][s], f"state {s}: action differs from the oracle's"
-        else:
-            near_ties += 1
-    p = np.exp(logp[mask].astype(np.float64))
-    sums = np.add.reduceat(np.where(mask, np.exp(logp.astype(np.float64)), 0.0), sgp[:-1])
-    np.testing.assert_allclose(sums, 1.0, atol=1e-5)
+    near_ties = check_heads_against_oracle({k: v.cpu().numpy() for k, v in pv.items()}, rp, state, prec)
+    print(f"states whose two best logits are closer than twice the logit tolerance: {near_ties} of {state['n_states']}")
+    if prec == "fp32":
+        assert near_ties == 0, f"{near_ties} near-tie states at the fp32 tolerance"
     # run-to-run determinism: bit-identical embeddings
     emb2 = enc.encode(batch, save_for_backward=False)
     torch.cuda.synchronize()
@@ -138,7 +167,7 @@ def test_config1_tiny_fp32(xrl):
 def test_config2_transformer(xrl, precision):
     model, state = synth.make_config(2)
     model["precision"] = precision
-    run_case(xrl, model, state, weights_for(model))
+    run_case(xrl, model, state, weights_for(model), contract_emb=True)
 
 
 @pytest.mark.parametrize("hidden,precision", [(64, "bf16"), (256, "fp32"), (256, "bf16")])
@@ -174,10 +203,13 @@ def test_graph_attention_rounds(xrl, hidden, precision):
 
 
 @pytest.mark.parametrize("cfg", [3, 4, 5])
-def test_full_size_sampled_graphs(xrl, cfg):
-    """Configurations 3-5 at full size, in the launch configuration the benchmark times: the
-    embeddings and logits of sampled graphs against the oracle run on those graphs alone (graphs
-    are independent), and the properties that hold at any size for the rest."""
+def test_full_size_whole_states_and_sampled_graphs(xrl, cfg):
+    """Configurations 3-5 at full size, in the launch configuration the benchmark times. Whole
+    states against the oracle run on those states alone (graphs, and states, are independent):
+    configuration 4's single state of 257 graphs, the two states with the fewest slots of
+    configurations 3 and 5 -- embeddings, logits, logp, value, entropy at the path's tolerance,
+    the action under the near-tie rule. Also sampled graphs elsewhere in the batch, and for every
+    state the properties that hold at any size."""
     import torch
     model, state = synth.make_config(cfg)
     w = weights_for(model)
@@ -189,20 +221,33 @@ def test_full_size_sampled_graphs(xrl, cfg):
     torch.cuda.synchronize()
     G, sgp = batch.G, np.asarray(state["state_graph_ptr"])
     mask = np.asarray(state["slot_mask"]).astype(bool)
+    S = len(sgp) - 1
+    # ---- whole states
+    pick = np.sort(np.argsort(np.diff(sgp), kind="stable")[:min(2, S)])
+    sub = synth.state_subset(state, pick)
+    gsel = np.concatenate([np.arange(sgp[s], sgp[s + 1]) for s in pick])
+    ref_emb = O.encode(om, w, sub)
+    rp = O.policy_value(om, w, ref_emb, sub)
+    gi, si = torch.from_numpy(gsel).cuda(), torch.from_numpy(pick).cuda()
+    check_emb(emb[gi].cpu().numpy(), ref_emb, model, f"emb of states {pick.tolist()}", contract=cfg == 3)
+    got = dict(logit=pv["logit"][gi].cpu().numpy(), logp=pv["logp"][gi].cpu().numpy(),
+               value=pv["value"][si].cpu().numpy(), entropy=pv["entropy"][si].cpu().numpy(),
+               action=pv["action"][si].cpu().numpy())
+    near = check_heads_against_oracle(got, rp, sub, model["precision"], f"states {pick.tolist()}: ")
+    print(f"config {cfg}: states {pick.tolist()} ({len(gsel)} graphs) whole; near-tie states: {near}")
+    # ---- sampled graphs elsewhere
     rng = np.random.Generator(np.random.PCG64(11 + cfg))
-    sample = sorted(set([0, G - 1, int(sgp[(len(sgp) - 1) // 2])] + rng.integers(0, G, 3).tolist()))
-    assert 0 <= sample[0] and sample[-1] < G
+    sample = sorted(set([0, G - 1, int(sgp[S // 2])] + rng.integers(0, G, 3).tolist()))
     idx = torch.tensor(sample, device="cuda")
-    got_emb = emb[idx].cpu().numpy()
-    got_logit = pv["logit"][idx].cpu().numpy()
-    ref_emb = np.stack([O.encode(om, w, state, graphs=[g])[0] for g in sample])
-    scale = float(np.abs(ref_emb).max())
-    assert_close(got_emb, ref_emb, "bf16-emb", "emb of sampled graphs", scale=scale)
+    s_emb = np.stack([O.encode(om, w, state, graphs=[g])[0] for g in sample])
+    check_emb(emb[idx].cpu().numpy(), s_emb, model, "emb of sampled graphs", scale=float(np.abs(ref_emb).max()),
+              contract=cfg == 3)
     one_state = dict(state_graph_ptr=np.array([0, len(sample)]), slot_mask=np.ones(len(sample), np.uint8))
-    ref_logit = O.policy_value(om, w, ref_emb, one_state)["logit"]           # logits are per graph
-    assert_close(got_logit, ref_logit, "bf16", "logit of sampled graphs", scale=float(np.abs(ref_logit).max()))
-    # whole batch: finite, masked slots -inf, probabilities of each state sum to 1, action = first
-    # max of the state's valid logits
+    s_logit = O.policy_value(om, w, s_emb, one_state)["logit"]               # logits are per graph
+    assert_close(pv["logit"][idx].cpu().numpy(), s_logit, "bf16", "logit of sampled graphs",
+                 scale=float(np.abs(rp["logit"]).max()))
+    # ---- whole batch: finite, masked slots -inf, probabilities of each state sum to 1, action =
+    # first max of the state's valid logits
     logp = pv["logp"].cpu().numpy()
     logit = pv["logit"].cpu().numpy()
     assert np.isfinite(emb.cpu().numpy()).all() and np.isfinite(logit).all()
@@ -210,16 +255,60 @@ def test_full_size_sampled_graphs(xrl, cfg):
     sums = np.add.reduceat(np.where(mask, np.exp(logp.astype(np.float64)), 0.0), sgp[:-1])
     np.testing.assert_allclose(sums, 1.0, atol=1e-4)
     action = pv["action"].cpu().numpy()
-    for s in range(len(sgp) - 1):
-        l = np.where(mask[sgp[s]:sgp[s + 1]], logit[sgp[s]:sgp[s + 1]], -np.inf)
-        assert action[s] == int(np.argmax(l))
+    for s_ in range(S):
+        l = np.where(mask[sgp[s_]:sgp[s_ + 1]], logit[sgp[s_]:sgp[s_ + 1]], -np.inf)
+        assert action[s_] == int(np.argmax(l))
     batch.free()
+    enc.close()
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_candidate_permutation(xrl, precision):
+    """Permuting a state's candidates permutes logp and the embeddings and leaves value, entropy
+    and the chosen graph unchanged (the policy scores slots with a shared MLP; the value head sees
+    a mean): on the GPU, against its own unpermuted run. Graphs are encoded independently, so the
+    embeddings must match bit for bit; the per-state sums run in slot order, so value, entropy and
+    logp agree to rounding."""
+    import torch
+    model, state = synth.make_config(2, n_cand=20)
+    model["precision"] = precision
+    w = weights_for(model)
+    rng = np.random.Generator(np.random.PCG64(41))
+    G = len(state["slot_mask"])
+    perm = np.concatenate([[0], 1 + rng.permutation(G - 1)])          # slot 0 stays the current graph
+    gnp, gep = state["graph_node_ptr"], state["graph_edge_ptr"]
+    nsel = np.concatenate([np.arange(gnp[g], gnp[g + 1]) for g in perm])
+    esel = np.concatenate([np.arange(gep[g], gep[g + 1]) for g in perm])
+    pstate = dict(state, graph_node_ptr=np.concatenate([[0], np.cumsum(np.diff(gnp)[perm])]).astype(np.int32),
+                  graph_edge_ptr=np.concatenate([[0], np.cumsum(np.diff(gep)[perm])]).astype(np.int32),
+                  node_op=state["node_op"][nsel], node_dense=state["node_dense"][nsel],
+                  edge_src=state["edge_src"][esel], edge_dst=state["edge_dst"][esel],
+                  edge_feat=state["edge_feat"][esel], graph_global=state["graph_global"][perm],
+                  slot_mask=state["slot_mask"][perm])
+    enc = xrl.Encoder(model, w)
+    outs = []
+    for st in (state, pstate):
+        batch = enc.pack(st)
+        emb = enc.encode(batch)
+        pv = enc.policy_value(batch, emb)
+        torch.cuda.synchronize()
+        outs.append((emb.cpu().numpy(), {k: v.cpu().numpy() for k, v in pv.items()}))
+        batch.free()
+    (e0, p0), (e1, p1) = outs
+    np.testing.assert_array_equal(e1, e0[perm])
+    np.testing.assert_array_equal(p1["logit"], p0["logit"][perm])
+    m = state["slot_mask"][perm].astype(bool)
+    np.testing.assert_allclose(p1["logp"][m], p0["logp"][perm][m], rtol=0, atol=2e-6 * np.abs(p0["logit"]).max())
+    assert np.all(np.isneginf(p1["logp"][~m]))
+    np.testing.assert_allclose(p1["value"], p0["value"], rtol=1e-5, atol=1e-5 * np.abs(p0["logit"]).max())
+    np.testing.assert_allclose(p1["entropy"], p0["entropy"], rtol=1e-5, atol=1e-6)
+    assert perm[p1["action"][0]] == p0["action"][0]
     enc.close()
 
 
 def test_config3_resnet_subset_bf16(xrl):
     model, state = synth.make_config(3, n_states=4)
-    run_case(xrl, model, state, weights_for(model), check_inter=False)
+    run_case(xrl, model, state, weights_for(model), check_inter=False, contract_emb=True)
 
 
 def hub_state(rng, model, n_hub_in):
@@ -299,6 +388,98 @@ def test_paper_feature_dimensions(xrl, hidden, precision):
     state["graph_global"] = np.zeros((len(state["slot_mask"]), model["d_global"]), np.float32)
     np.testing.assert_array_equal(state["edge_feat"], O.edge_features_from_shapes(shapes).astype(np.float32))
     run_case(xrl, model, state, weights_for(model))
+
+
+def heads_only_state(rng, model, n_states, n_cand, fixed=False):
+    """States of one-node graphs (the heads only see embeddings): 1 to n_cand + 1 slots per state,
+    or exactly n_cand + 1 with fixed=True; random masks, slot 0 valid."""
+    slots = np.concatenate([[1], rng.integers(2, n_cand + 2, n_states - 1)]).astype(np.int64)[:n_states]
+    if fixed:
+        slots[:] = n_cand + 1
+    G = int(slots.sum())
+    sgp = np.concatenate([[0], np.cumsum(slots)]).astype(np.int32)
+    mask = (rng.random(G) > 0.3).astype(np.uint8)
+    mask[sgp[:-1]] = 1
+    Dd, De = model["n_node_dense"], model["d_edge"]
+    return dict(n_states=n_states, state_graph_ptr=sgp,
+                graph_node_ptr=np.arange(G + 1, dtype=np.int32), graph_edge_ptr=np.zeros(G + 1, np.int32),
+                node_op=rng.integers(0, model["n_op_types"], G).astype(np.int32),
+                node_dense=rng.integers(0, 13, (G, Dd)).astype(np.float32),
+                edge_src=np.zeros(0, np.int32), edge_dst=np.zeros(0, np.int32),
+                edge_feat=np.zeros((0, De), np.float32),
+                graph_global=rng.standard_normal((G, model["d_global"])).astype(np.float32), slot_mask=mask)
+
+
+@pytest.mark.parametrize("hidden,n_states,n_cand,fixed,calls", [
+    (128, 32, 64, True, 50),      # 2080 slots: the ResNet-shaped configuration's heads, single-launch kernel
+    (256, 1, 256, True, 50),      # 257 slots in one state: the Inception-shaped configuration's
+    (64, 60, 170, False, 3),      # about 5000 slots: beyond the single-launch kernel, two kernels
+    (256, 40, 300, False, 3)])
+def test_heads_repeated_calls_and_large_batches(xrl, hidden, n_states, n_cand, fixed, calls):
+    """Policy and value heads on random embeddings, called many times on one batch: every call
+    bit-identical (the single-launch kernel hands logits from the slots' blocks to the block that
+    finishes a state through per-state counters, which it resets itself), and against the oracle on
+    the same embeddings; forward and backward (demb, head weight gradients, masked rows zero), on
+    both sides of the 4096-slot limit of the single-launch kernel."""
+    import torch
+    import grad_checks as GC
+    rng = np.random.Generator(np.random.PCG64(19))
+    model, _ = synth.make_config(1)
+    model.update(hidden=hidden, rounds=1)
+    state = heads_only_state(rng, model, n_states, n_cand, fixed)
+    G, S = len(state["slot_mask"]), n_states
+    w = weights_for(model)
+    om = oracle_model(model)
+    emb = rng.standard_normal((G, hidden)).astype(np.float32)
+    rp = O.policy_value(om, w, emb.astype(np.float64), state)
+    enc = xrl.Encoder(model, w)
+    batch = enc.pack(state)
+    d_emb = torch.from_numpy(emb).cuda()
+    first = None
+    for _ in range(calls):
+        pv = enc.policy_value(batch, d_emb)
+        torch.cuda.synchronize()
+        if first is None:
+            first = {k: v.clone() for k, v in pv.items()}
+        else:
+            for k in first:
+                assert torch.equal(first[k], pv[k]), f"{k}: calls differ"
+    check_heads_against_oracle({k: v.cpu().numpy() for k, v in first.items()}, rp, state, "fp32")
+    # backward
+    dlogp, dvalue, dentropy = synth.upstream_grads(rng, G, S)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dws = []
+    for _ in range(2):
+        dw = torch.zeros(enc.n_weights, dtype=torch.float32, device="cuda")
+        demb = enc.policy_value_backward(batch, d_emb, t(dlogp), t(dvalue), t(dentropy), dw)
+        torch.cuda.synchronize()
+        dws.append((dw.cpu().numpy(), demb.cpu().numpy()))
+    np.testing.assert_array_equal(dws[0][0], dws[1][0])
+    np.testing.assert_array_equal(dws[0][1], dws[1][1])
+    bh = O.zero_grads(om)
+    ref_demb, ref_heads = O.policy_value_backward(om, w, emb.astype(np.float64), state, dlogp, dvalue, dentropy, bound=bh)
+    m = state["slot_mask"].astype(bool)
+    assert np.all(dws[0][1][~m] == 0.0)
+    np.testing.assert_allclose(dws[0][1], ref_demb, rtol=1e-5,
+                               atol=1e-5 * max(1.0, float(np.abs(rp["logit"]).max())) * np.abs(ref_demb).max())
+    L = float(np.abs(rp["logit"]).max())
+    GC.check_fp32(dws[0][0], ref_heads, O.flatten(om, bh), om, only=("policy", "value"), kappa=2e-6 + 1e-5 * max(1.0, L))
+    batch.free()
+    enc.close()
+
+
+def test_readout_of_few_huge_graphs(xrl):
+    """More than 4096 nodes per graph on average: the readout runs as a segment sum over node
+    ranges plus the row MLP instead of one block per graph. Sum and mean, fp32 and bf16."""
+    rng = np.random.Generator(np.random.PCG64(23))
+    for precision, readout in (("fp32", "sum"), ("bf16", "mean")):
+        model, _ = synth.make_config(1)
+        model.update(hidden=64, rounds=1, precision=precision, readout=readout)
+        g1 = synth.layered_dag(rng, 9000)
+        g2 = synth.layered_dag(rng, 30)
+        state = synth.concat_states([([g1, g2], np.array([1, 1], np.uint8))])
+        assert len(state["node_op"]) > 4096 * 2
+        run_case(xrl, model, state, weights_for(model) * 0.5, check_inter=False)
 
 
 @pytest.mark.parametrize("hidden,n_states,n_cand", [(64, 1, 3), (128, 7, 40), (256, 3, 130)])
