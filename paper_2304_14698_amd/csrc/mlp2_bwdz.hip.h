@@ -12,7 +12,10 @@
 // dz1) shrink to two, which lets eight waves share a compute unit at H = 256. The weights go
 // through the same double-buffered LDS groups, fetched once per block of NW waves. A wave's tile
 // is 32 consecutive rows; for EDGE it is an edge tile of the packer (at most 32 edges), because
-// the kept mask bits are per tile and lane of the forward kernel.
+// the kept mask bits are per tile and lane of the forward kernel. Those tiles are cut at receiver
+// boundaries, so with FOLD (batches in which no receiver has more than 32 in-edges) the gradients
+// w.r.t. h_receiver are summed per receiver across the lanes of the tile, as the forward sums the
+// messages, and leave as one row per receiver instead of one per edge.
 #pragma once
 #include "mlp2_bwd.hip.h"
 
@@ -28,6 +31,8 @@ struct Mlp2BwdzArgs {
   int64_t n_tiles;             // (EDGE)
   void *dz1, *dz2;             // [rows, H] bf16
   void *dx_a, *dx_b;           // EDGE: d h_sender, d h_receiver [E, H]; NODE: d h, d agg [N, H]; EMBED: unused
+                               // EDGE with FOLD: dx_b [N, H] = d h_receiver summed per receiver (rows of
+                               // receivers without in-edges are not written)
 };
 
 // Weight fragments for NW waves, UG units of UF fragments per group, through LDS: every wave
@@ -73,8 +78,9 @@ struct BwdzShape {
   static constexpr size_t LDS = (size_t)NW * BlockStage<bf16_t>::BYTES + 2 * (size_t)(UF * UG) * 1024;
 };
 
-template <int H, int KIND>
+template <int H, int KIND, bool FOLD>
 __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(const Mlp2BwdzArgs a) {
+  static_assert(!FOLD || KIND == KIND_EDGE, "only the edge MLP's receiver-side gradients are summed");
   using T = bf16_t;
   using S = BwdzShape<H>;
   constexpr int MB = S::MB, QB = S::QB, UF = S::UF, UG = S::UG, NW = S::NW;
@@ -116,9 +122,18 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
 
   // ---------------- dz2^T = dy^T * [y^T > 0], stored and kept as operand slabs
   bf16x8 dz2s[MB][QB];
+  [[maybe_unused]] int fold_rem = 0, fold_dsel = -1;          // FOLD: edges after this one with its receiver; row of the total
   {
     int64_t drow = row;
     if constexpr (KIND == KIND_EDGE) drow = a.in_dst[row];
+    if constexpr (FOLD) {
+      const bool valid = l32 < n_valid;
+      const int dst = (int)drow, up = __shfl_up(dst, 1);      // lane 32 reads lane 31, but is a head anyway
+      const bool head = valid && (l32 == 0 || up != dst);
+      const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << n_valid);
+      fold_rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
+      fold_dsel = head ? dst : -1;
+    }
     const T *dyrow = (const T *)a.dy + (size_t)drow * H + 4 * g;
     [[maybe_unused]] const T *yrow = KIND == KIND_EDGE ? nullptr : (const T *)a.y + (size_t)row * H + 4 * g;
     [[maybe_unused]] uint32_t ym[MB];
@@ -198,7 +213,26 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
 #pragma unroll
         for (int q = 0; q < QB; ++q) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg.get(u, mb * QB + q), dz1s[mb][q], d, 0, 0, 0);
       if (u == UG - 1) wg.next(g0 + UG < KB);
-      store_block_via_lds<T, H>((T *)(kb < MB ? a.dx_a : a.dx_b), row0, n_valid, kb % MB, lane, d, stage);
+      if (FOLD && kb >= MB) {
+        // segmented suffix sum across the lanes of each receiver's run (see edge_tile_sum)
+#pragma unroll
+        for (int dd = 1; dd < 32; dd <<= 1) {
+          if (__any(fold_rem >= dd)) {
+            const float takef = fold_rem >= dd ? 1.f : 0.f;
+            const int from = ((lane + dd) & 63) << 2;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float v = d[r];
+              const float t = dd == 1 ? __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, false))
+                                      : __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(v)));
+              d[r] = fmaf(t, takef, v);
+            }
+          }
+        }
+        store_block_rows_via_lds<T, H>((T *)a.dx_b, fold_dsel, kb % MB, lane, d, stage);
+      } else {
+        store_block_via_lds<T, H>((T *)(kb < MB ? a.dx_a : a.dx_b), row0, n_valid, kb % MB, lane, d, stage);
+      }
     }
   }
 }

@@ -73,8 +73,14 @@ template <int KIND>
 __device__ __forceinline__ RTileRows rtile_rows(const Mlp2Args &a, int64_t wt) {
   RTileRows t;
   if constexpr (KIND == KIND_EDGE) {
-    t.r0 = a.tile_ptr[wt];
-    t.nv = a.tile_ptr[wt + 1] - (int)t.r0;
+    // wt is uniform: read the tile table through the scalar unit (the constant address space; the
+    // table is never written on the device). As an ordinary load it would be a vector load whose
+    // result is needed in scalar registers at once, and the wait for it also waits for every row
+    // prefetch issued just before.
+    typedef const __attribute__((address_space(4))) int32_t *cptr;
+    cptr tp = (cptr)(uintptr_t)a.tile_ptr;
+    t.r0 = tp[wt];
+    t.nv = tp[wt + 1] - (int)t.r0;
   } else {
     t.r0 = wt * 32;
     const int64_t left = a.n_rows - t.r0;
@@ -97,9 +103,11 @@ __device__ __forceinline__ RFetch rtile_index(const Mlp2Args &a, const RTileRows
   using R = RTile<H, KIND>;
   RFetch f;
   const int32_t *ip = w < R::MB / 2 ? a.in_src : a.in_dst;     // EDGE: first half senders, second half receivers
+  int lq = lane / R::LPR;                                       // (opaque: recomputed per call, not four registers
+  asm volatile("" : "+v"(lq));                                  //  of per-instruction row numbers kept across the loop)
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int r = R::RPI * ((4 * w + j) % (H / 16)) + lane / R::LPR;
+    const int r = R::RPI * ((4 * w + j) % (H / 16)) + lq;
     const int64_t row = t.r0 + (r < t.nv ? r : t.nv - 1);
     if constexpr (KIND == KIND_EDGE) f.src[j] = ip[row];
     else f.src[j] = (int)row;
@@ -111,10 +119,12 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
                                             char *xbuf) {
   using R = RTile<H, KIND>;
   const bf16_t *base = (KIND == KIND_NODE && w >= R::MB / 2) ? (const bf16_t *)a.agg : (const bf16_t *)a.h;
+  int lv = lane;
+  asm volatile("" : "+v"(lv));
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int q = 4 * w + j, r = R::RPI * (q % (H / 16)) + lane / R::LPR;
-    const int piece = (lane % R::LPR) ^ (r & R::SWM);
+    const int q = 4 * w + j, r = R::RPI * (q % (H / 16)) + lv / R::LPR;
+    const int piece = (lv % R::LPR) ^ (r & R::SWM);
     lds_direct_load16(base + (size_t)f.src[j] * H + piece * 8,
                       __builtin_amdgcn_readfirstlane(lds_address(xbuf) + q * 1024));
   }
@@ -150,7 +160,8 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
   int *drow = (int *)(sbuf + R::SBUF);                         // EDGE: destination row of each staged row
   float(*b1l)[2][16] = (float(*)[2][16])(sbuf + R::SBUF + 256), (*b2l)[2][16] = b1l + MB;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // (uniform: what derives from it stays in scalar registers)
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
   const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
   const int64_t per_xcd = (n_wt + 7) / 8;
@@ -242,7 +253,12 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
     if constexpr (SAVE) {
       static_assert(!SAVE || H == 256, "the staging layout below is laid out for eight waves");
       typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-      char *zrow = smem + buf * R::XBUF + 4096 * (l32 >> 2) + 64 * ((l32 >> 2) & 3) + 528 * (l32 & 3) + (32 * w + 4 * g) * 2;
+      // (addresses from an opaque copy of the lane id: computed here in every tile instead of
+      // living in registers across the loop, which has none to spare)
+      int lv = lane;
+      asm volatile("" : "+v"(lv));
+      const int r_ = lv & 31, g_ = lv >> 5;
+      char *zrow = smem + buf * R::XBUF + 4096 * (r_ >> 2) + 64 * ((r_ >> 2) & 3) + 528 * (r_ & 3) + (32 * w + 4 * g_) * 2;
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const u32x4 z = __builtin_bit_cast(u32x4, relu_operand<T>(acc, q));   // features 16 q + 4 g + {0..3}, + 8
@@ -271,7 +287,11 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
       }
     }
     if constexpr (SAVE && KIND == KIND_EDGE) {
-      if (wt < a.n_tiles) a.ymask[((size_t)wt * MB + w) * 64 + lane] = lane_mask_bits(acc);
+      __builtin_amdgcn_sched_barrier(0);
+      int lv = lane;
+      asm volatile("" : "+v"(lv));
+      a.ymask[((size_t)wt * MB + w) * 64 + lv] = lane_mask_bits(acc);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // ---------------- epilogue on this wave's 32 features
     T *out = (T *)a.out;
@@ -333,14 +353,19 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
       }
     }
     if constexpr (SAVE) {
+      __builtin_amdgcn_sched_barrier(0);                         // (after the output rows: not interleaved with them)
       // this wave's four rows of relu(z1), from its own part of the tile's input buffer
       const char *zreg = smem + buf * R::XBUF + 4096 * w + 64 * (w & 3);
+      int lv = lane;
+      asm volatile("" : "+v"(lv));
+      const int r_ = lv & 31, g_ = lv >> 5;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int j = 2 * i + g, r = 4 * w + j;
-        const f32x4 v = *(const f32x4 *)(zreg + 528 * j + 16 * l32);
-        if (r < cur.nv) *(f32x4 *)((char *)((T *)a.z1 + (size_t)(cur.r0 + r) * H) + 16 * l32) = v;
+        const int j = 2 * i + g_, r = 4 * w + j;
+        const f32x4 v = *(const f32x4 *)(zreg + 528 * j + 16 * r_);
+        if (r < cur.nv) *(f32x4 *)((char *)((T *)a.z1 + (size_t)(cur.r0 + r) * H) + 16 * r_) = v;
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     // the buffer this tile used is free now: rows of the tile after next, indices one further
     if (wt + 2 * nbx < t_end) rtile_fetch<H, KIND>(a, nn, fn, w, lane, smem + buf * R::XBUF);

@@ -266,3 +266,27 @@ __device__ __forceinline__ void store_block_via_lds(TO *base, int64_t row0, int 
   }
   wave_lds_fence();
 }
+
+// Same staging, but row r of the tile goes to row dsel (this lane's value for its own row l % 32;
+// negative = the row is not stored): the rows of a tile scattered to per-row destinations.
+template <typename TO, int H>
+__device__ __forceinline__ void store_block_rows_via_lds(TO *base, int dsel, int fb, int lane, const f32x16 &d,
+                                                         char *stage) {
+  using S = BlockStage<TO>;
+  const int l32 = lane & 31, g = lane >> 5;
+  char *wp = stage + l32 * S::RS + 4 * g * (int)sizeof(TO);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float v[4] = {d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]};
+    store4<TO>((TO *)(wp + 8 * q * (int)sizeof(TO)), v);
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int k = 0; k < 32 / S::RPI; ++k) {
+    const int r = k * S::RPI + lane / S::LPR;
+    const int dr = __shfl(dsel, r);
+    const f32x4 v = *(const f32x4 *)(stage + r * S::RS + (lane % S::LPR) * 16);
+    if (dr >= 0) *(f32x4 *)((char *)(base + (size_t)dr * H + 32 * fb) + (lane % S::LPR) * 16) = v;
+  }
+  wave_lds_fence();
+}

@@ -200,12 +200,13 @@ __global__ __launch_bounds__(256) void edge_tile_fixup(const int32_t *tile_ptr, 
 // over n's out-edges (edge ids out_pos[k], k in [out_ptr[n], out_ptr[n+1])) of d_send[e]. One
 // group of D / VEC lanes per node, each lane a 16-byte column slice; the edges are taken in index
 // order and summed in fp32, so the result is run-to-run identical. One pass over dh instead of
-// one per direction.
+// one per direction. recv_summed: d_recv is [n_nodes, D], already summed per receiver (rows of nodes
+// without in-edges hold nothing and are not read).
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, const T *d_send,
                                                                const int32_t *in_ptr, const int32_t *out_ptr,
                                                                const int32_t *out_pos, int64_t n_nodes, int D,
-                                                               T *dh) {
+                                                               T *dh, int recv_summed) {
   const int lpr = D / VEC;
   const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n = gt / lpr;
@@ -215,10 +216,18 @@ __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, 
   T *o = dh + (size_t)n * D + c;
   float acc[VEC], v[VEC];
   RowVec<T, VEC>::load(o, acc);
-  for (int e = e0; e < e1; ++e) {
-    RowVec<T, VEC>::load(d_recv + (size_t)e * D + c, v);
+  if (recv_summed) {
+    if (e1 > e0) {
+      RowVec<T, VEC>::load(d_recv + (size_t)n * D + c, v);
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+      for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+    }
+  } else {
+    for (int e = e0; e < e1; ++e) {
+      RowVec<T, VEC>::load(d_recv + (size_t)e * D + c, v);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+    }
   }
   for (int k = k0; k < k1; ++k) {
     RowVec<T, VEC>::load(d_send + (size_t)out_pos[k] * D + c, v);

@@ -730,10 +730,10 @@ int launch_mlp2_bwd(xrl_ctx *c, int kind, Mlp2BwdArgs &a) {
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
 
-template <int H, int KIND>
+template <int H, int KIND, bool FOLD>
 int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
   using S = BwdzShape<H>;
-  auto kern = mlp2_bwdz_kernel<H, KIND>;
+  auto kern = mlp2_bwdz_kernel<H, KIND, FOLD>;
   static bool attr_set = false;          // one attribute per kernel instantiation
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS));
@@ -748,18 +748,19 @@ int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
 }
 
 template <int H>
-int launch_mlp2_bwdz_h(xrl_ctx *c, int kind, Mlp2BwdzArgs &a) {
+int launch_mlp2_bwdz_h(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold) {
   if (a.n_rows <= 0) return XRL_OK;
-  if (kind == KIND_EMBED) return launch_mlp2_bwdz_k<H, KIND_EMBED>(c, a);
-  if (kind == KIND_EDGE) return launch_mlp2_bwdz_k<H, KIND_EDGE>(c, a);
-  return launch_mlp2_bwdz_k<H, KIND_NODE>(c, a);
+  if (kind == KIND_EMBED) return launch_mlp2_bwdz_k<H, KIND_EMBED, false>(c, a);
+  if (kind == KIND_EDGE) return fold ? launch_mlp2_bwdz_k<H, KIND_EDGE, true>(c, a) : launch_mlp2_bwdz_k<H, KIND_EDGE, false>(c, a);
+  return launch_mlp2_bwdz_k<H, KIND_NODE, false>(c, a);
 }
 
-int launch_mlp2_bwdz(xrl_ctx *c, int kind, Mlp2BwdzArgs &a) {
+// fold (EDGE): dx_b receives the gradients w.r.t. h_receiver summed per receiver, [N, H]
+int launch_mlp2_bwdz(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold) {
   switch (c->m.hidden) {
-    case 64: return launch_mlp2_bwdz_h<64>(c, kind, a);
-    case 128: return launch_mlp2_bwdz_h<128>(c, kind, a);
-    case 256: return launch_mlp2_bwdz_h<256>(c, kind, a);
+    case 64: return launch_mlp2_bwdz_h<64>(c, kind, a, fold);
+    case 128: return launch_mlp2_bwdz_h<128>(c, kind, a, fold);
+    case 256: return launch_mlp2_bwdz_h<256>(c, kind, a, fold);
   }
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
@@ -995,8 +996,12 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   size_t need = 0;
   auto acc = [&](size_t bytes) { need += align_up(bytes); };
   const bool kept = c->fwd_kept;                                   // the forward kept z1 and the ReLU masks
+  // the per-edge gradients w.r.t. h_receiver leave the edge kernel already summed per receiver
+  // (edge tiles end at receiver boundaries unless a receiver has more than 32 in-edges)
+  const bool fold = kept && b->n_split_tiles == 0;
   for (int i = 0; i < (kept ? 2 : 3); ++i) acc((size_t)M * H * sizeof(T));      // (z1,) dz1, dz2
-  for (int i = 0; i < 2; ++i) acc((size_t)E * H * sizeof(T));      // per-edge d h_sender, d h_receiver
+  acc((size_t)E * H * sizeof(T));                                  // per-edge d h_sender
+  acc((size_t)M * H * sizeof(T));                                  // d h_receiver: per edge, or summed per receiver
   for (int i = 0; i < 3; ++i) acc((size_t)N * H * sizeof(T));      // dh (two buffers), dagg
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
@@ -1011,7 +1016,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   Bump bump{c->bws};
   T *z1 = kept ? nullptr : bump.take<T>((size_t)M * H);
   T *dz1 = bump.take<T>((size_t)M * H), *dz2 = bump.take<T>((size_t)M * H);
-  T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)E * H);
+  T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)M * H);
   T *dhA = bump.take<T>((size_t)N * H), *dhB = bump.take<T>((size_t)N * H);
   T *dagg = bump.take<T>((size_t)N * H);
   float *partial = bump.take<float>(part);
@@ -1064,7 +1069,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
       if (kept) {
         za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy; za.z1 = z1_kept; za.y = a.y;
         za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
-        return launch_mlp2_bwdz(c, kind, za);
+        return launch_mlp2_bwdz(c, kind, za, fold);
       }
     }
     return launch_mlp2_bwd<T>(c, kind, a);
@@ -1134,7 +1139,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
       Timed t(c, TK_GRAD_GATHER);
       const int64_t threads = N * (H / PV);
       node_grad_gather_kernel<T, PV><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(
-          ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB);
+          ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB, fold ? 1 : 0);
     }
     std::swap(dhA, dhB);
   }
