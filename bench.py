@@ -216,7 +216,7 @@ def main():
     kern = {}
     names = ("embed", "edge", "edge_fixup", "node", "gat_linear", "gat_aggregate", "pool", "readout", "heads", "resident")
     if backward:
-        names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad", "grad_gather", "gat_bwd")
+        names += ("bwd_edge", "bwd_node", "bwd_embed", "wgrad_edge", "wgrad_node", "wgrad_embed", "grad_gather", "gat_bwd")
     for k in names:
         tot, n = enc.read_timing(k)
         kern[k] = dict(avg_us=(tot / n * 1e3 if n else 0.0), launches_per_step=n / args.steps)
@@ -227,49 +227,79 @@ def main():
     b = 2 if bf16 else 4
     hv = batch.host_view()
     n_recv = int((np.diff(hv["in_ptr"]) > 0).sum())
+    n_tiles = len(hv["tile_ptr"]) - 1
+    Tn = model["n_op_types"]
+    # Large bf16 batches run on the forward kernels that keep relu(z1) (and the edge MLP's output
+    # mask bits) for the backward pass, and on the backward kernels that start from them.
+    kept = (backward and bf16 and args.round_kind == "mlp" and kern["resident"]["launches_per_step"] == 0
+            and min(N, E) >= int(os.environ.get("XRL_PERSISTENT_MIN_ROWS", 8192)))
+    zk = 1 if kept else 0
     # Algorithmic work per launch of each kernel (multiply-add = 2 flop; b = bytes per stored
-    # activation). The backward kernels recompute the first layer (and, for the edge kind, the
-    # second) of the forward: that recomputation is counted, it runs on the matrix cores.
+    # activation): flops of the products the kernel is there for, and the bytes of its inputs read
+    # once and its outputs written once (rows gathered several times count once). A kernel whose
+    # flops / bytes lies below the ridge of the two peaks is rated against HBM, else against the
+    # matrix cores.
+    NH, EH = N * H * b, E * H * b
+    idx_e = 4 * (2 * E + n_tiles)
     work = {
-        "embed": dict(kernel="node-update layer: sum of incoming edge attributes + embed MLP", bound="mfma",
+        "embed": dict(kernel="node-update layer: sum of incoming edge attributes + embed MLP",
                       flops=2.0 * N * H * (De + Dd + H),
-                      bytes=E * De * 4 + N * (4 + 4 * Dd) + 4 * (N + 1) + N * H * b),
-        "edge": dict(kernel="edge MLP + per-receiver sum (one launch per round)", bound="mfma",
+                      bytes=E * De * 4 + N * (4 + 4 * Dd) + 4 * (N + 1) + NH * (1 + zk)),
+        "edge": dict(kernel="edge MLP + per-receiver sum (one launch per round)",
                      flops=2.0 * E * H * (3 * H + De),
-                     bytes=N * H * b + E * De * 4 + 4 * (2 * E + E // 32) + n_recv * H * b),
-        "node": dict(kernel="node MLP (one launch per round)", bound="mfma",
-                     flops=2.0 * N * H * 3 * H, bytes=3 * N * H * b),
-        "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", bound="hbm",
-                     flops=0.0, bytes=N * H * b + 4 * (G + 1) + G * H * 4),
-        "bwd_edge": dict(kernel="backward through the edge MLP (one launch per round)", bound="mfma",
-                         flops=2.0 * E * H * (6 * H + De), bytes=None),
-        "bwd_node": dict(kernel="backward through the node MLP (one launch per round)", bound="mfma",
-                         flops=2.0 * N * H * 5 * H, bytes=None),
-        "bwd_embed": dict(kernel="backward through the embed MLP", bound="mfma",
-                          flops=2.0 * N * H * (De + Dd + 2 * H), bytes=None),
-        # both layers' weight gradients of one MLP and their reductions; the launches of a step
-        # differ (R edge MLPs, R node MLPs, the embed MLP): flops = the step's total / its launches
-        "wgrad": dict(kernel="weight gradients dW = X^T dZ of one MLP, both layers (edge, node and embed MLPs averaged)",
-                      bound="mfma", bytes=None,
-                      flops=(R * (2.0 * E * H * (3 * H + De) + 2.0 * N * H * 3 * H)
-                             + 2.0 * N * H * (De + model["n_op_types"] + Dd + H)) / max(2 * R + 1, 1)),
-        "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", bound="hbm",
-                            flops=0.0, bytes=2 * E * H * b + 2 * N * H * b + 4 * (2 * N + E)),
+                     bytes=NH + E * De * 4 + idx_e + n_recv * H * b + zk * (EH + n_tiles * (H // 32) * 128)),
+        "node": dict(kernel="node MLP (one launch per round)", flops=2.0 * N * H * 3 * H, bytes=(3 + zk) * NH),
+        "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", flops=0.0,
+                     bytes=NH + 4 * (G + 1) + G * H * 4),
+        "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", flops=0.0,
+                            bytes=(EH + n_recv * H * b if kept else 2 * EH) + 2 * NH + 4 * (2 * N + E)),
     }
+    if kept:
+        work.update({
+            "bwd_edge": dict(kernel="backward through the edge MLP from the kept forward (one launch per round)",
+                             flops=2.0 * E * H * 3 * H,
+                             bytes=n_recv * H * b + EH + n_tiles * (H // 32) * 128 + 4 * (E + n_tiles) + 3 * EH + n_recv * H * b),
+            "bwd_node": dict(kernel="backward through the node MLP from the kept forward (one launch per round)",
+                             flops=2.0 * N * H * 3 * H, bytes=7 * NH),
+            "bwd_embed": dict(kernel="backward through the embed MLP from the kept forward", flops=2.0 * N * H * H, bytes=5 * NH),
+            "wgrad_edge": dict(kernel="weight gradients of one edge MLP, both layers",
+                               flops=2.0 * E * H * (3 * H + De + 2), bytes=NH + 4 * EH + E * De * 4 + 8 * E),
+            "wgrad_node": dict(kernel="weight gradients of one node MLP, both layers",
+                               flops=2.0 * N * H * (3 * H + 2), bytes=5 * NH),
+            "wgrad_embed": dict(kernel="weight gradients of the embed MLP, both layers",
+                                flops=2.0 * N * H * (De + Tn + Dd + H + 2), bytes=3 * NH + E * De * 4 + N * (8 + 4 * Dd)),
+        })
+    else:
+        # small batches and fp32: the backward kernels recompute the first layer (and, for the edge
+        # kind, the second) of the forward on the matrix cores; that recomputation is counted
+        work.update({
+            "bwd_edge": dict(kernel="backward through the edge MLP (one launch per round)", flops=2.0 * E * H * (6 * H + De),
+                             bytes=None),
+            "bwd_node": dict(kernel="backward through the node MLP (one launch per round)", flops=2.0 * N * H * 5 * H, bytes=None),
+            "bwd_embed": dict(kernel="backward through the embed MLP", flops=2.0 * N * H * (De + Dd + 2 * H), bytes=None),
+            "wgrad_edge": dict(kernel="weight gradients of one edge MLP, both layers", flops=2.0 * E * H * (3 * H + De + 2), bytes=None),
+            "wgrad_node": dict(kernel="weight gradients of one node MLP, both layers", flops=2.0 * N * H * (3 * H + 2), bytes=None),
+            "wgrad_embed": dict(kernel="weight gradients of the embed MLP, both layers",
+                                flops=2.0 * N * H * (De + Tn + Dd + H + 2), bytes=None),
+        })
+    ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)           # flop per byte at which the two peaks meet
     report = {}
     for k, wk in work.items():
         if k not in kern or kern[k]["launches_per_step"] == 0 or kern[k]["avg_us"] <= 0:
             continue
-        s = kern[k]["avg_us"] * 1e-6
-        e = dict(kernel=wk["kernel"], bound=wk["bound"], avg_launch_us=kern[k]["avg_us"],
-                 launches_per_step=kern[k]["launches_per_step"],
+        sec = kern[k]["avg_us"] * 1e-6
+        e = dict(kernel=wk["kernel"], avg_launch_us=kern[k]["avg_us"], launches_per_step=kern[k]["launches_per_step"],
                  share_of_step=kern[k]["avg_us"] * kern[k]["launches_per_step"] * 1e-3 / ms)
-        if wk["bound"] == "mfma":
-            e.update(achieved=wk["flops"] / s / 1e12, peak=peak, unit="TFLOP/s", flops_per_launch=wk["flops"])
-            if wk["bytes"] is not None:
-                e.update(algorithmic_bytes_per_launch=wk["bytes"], hbm_frac=wk["bytes"] / s / 1e9 / PEAK_HBM_GBS)
+        hbm = wk["bytes"] is not None and (wk["flops"] == 0 or wk["flops"] / wk["bytes"] < ridge)
+        if hbm:
+            e.update(bound="hbm", achieved=wk["bytes"] / sec / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
+                     algorithmic_bytes_per_launch=wk["bytes"])
+            if wk["flops"]:
+                e.update(flops_per_launch=wk["flops"], mfma_frac=wk["flops"] / sec / 1e12 / peak)
         else:
-            e.update(achieved=wk["bytes"] / s / 1e9, peak=PEAK_HBM_GBS, unit="GB/s", algorithmic_bytes_per_launch=wk["bytes"])
+            e.update(bound="mfma", achieved=wk["flops"] / sec / 1e12, peak=peak, unit="TFLOP/s", flops_per_launch=wk["flops"])
+            if wk["bytes"] is not None:
+                e.update(algorithmic_bytes_per_launch=wk["bytes"], hbm_frac=wk["bytes"] / sec / 1e9 / PEAK_HBM_GBS)
         e["frac"] = e["achieved"] / e["peak"]
         e["traffic"] = measured_traffic(args.config, model["precision"], k)
         report[k] = e
@@ -293,7 +323,7 @@ def main():
         res["kernels"] = {k: v for k, v in report.items() if k != top}
     if kern["resident"]["launches_per_step"] > 0:
         # small batch: the encoder ran as one launch (a block per graph), rated as a whole
-        enc_flops = 2.0 * N * H * (De + model["n_op_types"] + Dd + H) + R * (work["edge"]["flops"] + 2.0 * N * H * 3 * H)
+        enc_flops = 2.0 * N * H * (De + Tn + Dd + H) + R * (work["edge"]["flops"] + 2.0 * N * H * 3 * H)
         enc_s = kern["resident"]["avg_us"] * 1e-6
         enc_bytes = (R + 1) * N * H * b + R * n_recv * H * b + E * De * 4 + 4 * (3 * E + 3 * N) + G * H * 4
         res["roofline"] = dict(bound="mfma", kernel="one-launch encoder (node-update layer, all rounds, readout)",

@@ -279,9 +279,11 @@ int xrl_mlp_backward(xrl_ctx *ctx, const xrl_batch *b, int32_t kind, int32_t rou
  * "edge_fixup", "node", "pool", "readout", "heads"} (the steps of Section 3.4 / 3.3.2 in
  * execution order; "gat_linear", "gat_aggregate" with XRL_ROUND_GAT; "resident" = the whole
  * encoder of a small batch in one launch). Backward (Section 3.3.4):
- * {"bwd_edge", "bwd_node", "bwd_embed"} = gradients through the fused MLPs, "wgrad" = both
- * layers' weight gradients of one MLP with their reductions, "grad_gather" = per-node sum of the
- * per-edge gradients; "gat_bwd" = one attention round's backward. Errors: NULL, INDEX, HIP. */
+ * {"bwd_edge", "bwd_node", "bwd_embed"} = gradients through the fused MLPs, {"wgrad_edge",
+ * "wgrad_node", "wgrad_embed"} = both layers' weight gradients of one such MLP with their
+ * reductions ("wgrad": the same for a single product through xrl_weight_gradient), "grad_gather" =
+ * per-node sum of the per-edge gradients; "gat_bwd" = one attention round's backward.
+ * Errors: NULL, INDEX, HIP. */
 int xrl_set_timing(xrl_ctx *ctx, int enabled);
 int xrl_read_timing(xrl_ctx *ctx, const char *kernel, double *total_ms, int64_t *launches);
 

@@ -123,19 +123,14 @@ __device__ __forceinline__ void layer2_lds(const f32x16 (&acc1)[H / 32], const t
   }
 }
 
-// Stores what a SAVE kernel keeps for the backward pass from a wave tile held as features x rows
-// accumulators (lane = row): relu(z1) rows [row0, row0 + nv) of a.z1 through the staging buffer
-// (one 32-feature block at a time with BLOCKWISE staging, else whole rows) and, EDGE (tile wt), the
-// mask bits of y.
-template <typename T, int H, int KIND, bool BLOCKWISE>
-__device__ __forceinline__ void save_forward_tile(const Mlp2Args &a, const f32x16 (&acc1)[H / 32],
-                                                  const f32x16 (&acc2)[H / 32], int64_t row0, int nv, int64_t wt,
-                                                  int lane, char *stage) {
+// What a SAVE kernel keeps for the backward pass from a wave tile held as features x rows
+// accumulators (lane = row). Before layer 2 (which consumes layer 1's accumulators block by block,
+// so they need not stay live beyond it): relu(z1) rows [row0, row0 + nv) of a.z1 through the
+// staging buffer, one 32-feature block at a time with BLOCKWISE staging, else whole rows.
+template <typename T, int H, bool BLOCKWISE>
+__device__ __forceinline__ void save_hidden_tile(const Mlp2Args &a, const f32x16 (&acc1)[H / 32], int64_t row0, int nv,
+                                                 int lane, char *stage) {
   constexpr int MB = H / 32;
-  if constexpr (KIND == KIND_EDGE) {
-#pragma unroll
-    for (int nb = 0; nb < MB; ++nb) a.ymask[((size_t)wt * MB + nb) * 64 + lane] = lane_mask_bits(acc2[nb]);
-  }
   T *z1 = (T *)a.z1;
   if constexpr (BLOCKWISE) {
 #pragma unroll
@@ -150,6 +145,14 @@ __device__ __forceinline__ void save_forward_tile(const Mlp2Args &a, const f32x1
       return r < nv ? z1 + (size_t)(row0 + r) * H : nullptr;
     });
   }
+}
+// After layer 2, EDGE (tile wt): the mask bits of y.
+template <int H>
+__device__ __forceinline__ void save_edge_output_mask(const Mlp2Args &a, const f32x16 (&acc2)[H / 32], int64_t wt, int lane) {
+  int lv = lane;                        // (opaque: the address is formed here, not kept in registers across tiles)
+  asm volatile("" : "+v"(lv));
+#pragma unroll
+  for (int nb = 0; nb < H / 32; ++nb) a.ymask[((size_t)wt * (H / 32) + nb) * 64 + lv] = lane_mask_bits(acc2[nb]);
 }
 
 template <typename T, int H, int KIND, int NW, bool SAVE>
@@ -264,15 +267,16 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     }
     // ---------------- layer 2 (features x rows)
     f32x16 acc2[MB];
-    layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
     if constexpr (SAVE) {
       if constexpr (KIND == KIND_NODE) {
         const int64_t left = a.n_rows - wt * 32;
-        save_forward_tile<T, H, KIND, false>(a, acc1, acc2, wt * 32, left < 32 ? (int)left : 32, wt, lane, stage);
+        save_hidden_tile<T, H, false>(a, acc1, wt * 32, left < 32 ? (int)left : 32, lane, stage);
       } else {
-        save_forward_tile<T, H, KIND, false>(a, acc1, acc2, meta_e0, nv, wt, lane, stage);
+        save_hidden_tile<T, H, false>(a, acc1, meta_e0, nv, lane, stage);
       }
     }
+    layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+    if constexpr (SAVE && KIND == KIND_EDGE) save_edge_output_mask<H>(a, acc2, wt, lane);
     if (more) load_rows<T, H, KIND, 3>(a, wnext, l32, g, ix, in);
     else in = TileRows<T, H>{};   // (so that the consumed rows need not stay live up to here)
     __builtin_amdgcn_sched_barrier(0);
@@ -376,12 +380,12 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) Operand<float>::mma(W1l[(s * MB + mb) * 64 + lane], x, acc1[mb]);
     }
+    const int64_t left = a.n_rows - row0;
+    const int n_valid = left < 32 ? (int)left : 32;
+    if constexpr (SAVE) save_hidden_tile<T, H, BIG>(a, acc1, row0, n_valid, lane, stage);
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
     T *out = (T *)a.out;
-    const int64_t left = a.n_rows - row0;
-    const int n_valid = left < 32 ? (int)left : 32;
-    if constexpr (SAVE) save_forward_tile<T, H, KIND_EMBED, BIG>(a, acc1, acc2, row0, n_valid, wt, lane, stage);
     if constexpr (BIG) {
 #pragma unroll
       for (int nb = 0; nb < MB; ++nb) {

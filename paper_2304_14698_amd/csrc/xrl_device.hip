@@ -95,10 +95,12 @@ struct EncMlp {           // device pointers of one encoder MLP
 
 // kernels whose launches can be timed with HIP events (xrl_set_timing / xrl_read_timing)
 enum { TK_EMBED = 0, TK_EDGE, TK_EDGE_FIXUP, TK_NODE, TK_POOL, TK_READOUT, TK_HEADS, TK_GAT_LINEAR,
-       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_GAT_BWD, TK_RESIDENT, TK_COUNT };
+       TK_GAT_AGGREGATE, TK_BWD_EDGE, TK_BWD_NODE, TK_BWD_EMBED, TK_WGRAD, TK_GRAD_GATHER, TK_GAT_BWD, TK_RESIDENT,
+       TK_WGRAD_EDGE, TK_WGRAD_NODE, TK_WGRAD_EMBED, TK_COUNT };
 static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup", "node", "pool", "readout",
                                                   "heads", "gat_linear", "gat_aggregate", "bwd_edge", "bwd_node",
-                                                  "bwd_embed", "wgrad", "grad_gather", "gat_bwd", "resident"};
+                                                  "bwd_embed", "wgrad", "grad_gather", "gat_bwd", "resident",
+                                                  "wgrad_edge", "wgrad_node", "wgrad_embed"};
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
 
@@ -1053,7 +1055,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   };
   auto wgrads = [&](int kind, int64_t rows, int Ka, const MlpRef &r, const void *z1_kept) -> int {
     wa.n_rows = rows; wa.Ka = Ka; wa.dZ = dz1; wa.A = nullptr;
-    Timed t(c, TK_WGRAD);                                  // both layers' weight gradients and their reductions
+    // both layers' weight gradients of this MLP and their reductions
+    Timed t(c, kind == WG_EDGE ? TK_WGRAD_EDGE : (kind == WG_NODE ? TK_WGRAD_NODE : TK_WGRAD_EMBED));
     int rc2 = launch_wgrad<T>(c, kind, wa, dweights + r.w[0], dweights + r.b[0]);
     if (rc2) return rc2;
     wa.Ka = H; wa.dZ = dz2; wa.A = kept ? z1_kept : z1;
