@@ -28,8 +28,11 @@ PEAK_HBM_GBS = 8000.0
 # (factors 2.000 and 1.000). An entry is valid only for the kernel sources it was taken with: the
 # hash covers the files the kernel is built from (comments and blank space apart); otherwise null.
 TRAFFIC = {
-    (2, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="b660f3c7d5a8681c",
-                              bytes_per_launch=(11193.8 * 2.000 + 11599.5 * 1.000) * 1024),
+    # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
+    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="af5e992d6bbe5f8b",
+                                  bytes_per_launch=(13123474.7 * 2.000 + 35311455.0 * 1.000) * 1024),
+    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="af5e992d6bbe5f8b",
+                                  bytes_per_launch=(7687175.6 * 2.000 + 33044068.7 * 1.000) * 1024),
 }
 
 
