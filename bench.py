@@ -139,6 +139,9 @@ def main():
                          "reference that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure the machine's own MFMA and copy rates (reported as measured_peaks)")
+    ap.add_argument("--edit-pack", action="store_true",
+                    help="also time packing + upload of a configuration-2-shaped state (12 transformer blocks, 128 "
+                         "candidates) given as whole graphs and given as edits of the current graph (edit_pack)")
     ap.add_argument("--backward", action="store_true",
                     help="a step also runs both backward calls (always on for configuration 5)")
     args = ap.parse_args()
@@ -367,6 +370,28 @@ def main():
                                   achieved=seg_bytes / seg_s / 1e9, peak=PEAK_HBM_GBS, unit="GB/s",
                                   frac=seg_bytes / seg_s / 1e9 / PEAK_HBM_GBS)
         del vals, out
+    if args.edit_pack:
+        # host packing + H2D of one rewrite step's state, both ways (best of 40 after one warm-up)
+        erng = np.random.Generator(np.random.PCG64(synth.BASE_SEED + 11))
+        base = synth.shuffle_edges(erng, synth.transformer_dag(erng, 12))
+        edit_state, full_state = synth.make_edit_states(erng, [base], 128)
+        em = dict(model, hidden=128)
+        eenc = xrl.Encoder(em, synth.init_weights(erng, xrl.weight_layout(em)))
+
+        def best(fn):
+            ts = []
+            for _ in range(41):
+                t0 = time.perf_counter()
+                bt = fn()
+                torch.cuda.synchronize()
+                ts.append(time.perf_counter() - t0)
+                bt.free()
+            return min(ts[1:]) * 1e3
+        res["edit_pack"] = dict(workload=f"1 state, 128 candidates of a {base.n_nodes}-node / {base.n_edges}-edge graph",
+                                whole_graphs_ms=best(lambda: eenc.pack(full_state)),
+                                edits_ms=best(lambda: eenc.pack_edits(edit_state)),
+                                note="host packing + upload; the marshalling of the numpy arrays is included on both sides")
+        eenc.close()
     if args.peaks:
         tf, gb = enc.measure_peaks()
         res["measured_peaks"] = dict(mfma_bf16_tflops=tf, copy_gbs=gb,

@@ -87,6 +87,47 @@ typedef struct xrl_state_desc {
   const uint8_t *slot_mask;       /* [G] 1 = slot may be chosen; each state's first must be 1 */
 } xrl_state_desc;
 
+/* The same states with every candidate given as an edit of its state's current graph (Section
+ * 3.3.2: a candidate is the current graph with one rewrite rule applied, i.e. a local change of a
+ * few nodes). All host memory. Per state: the current graph in full (node and edge arrays as in
+ * xrl_state_desc, ranges cur_node_ptr / cur_edge_ptr) and its candidates [state_cand_ptr[s],
+ * state_cand_ptr[s+1]); per candidate c:
+ *   del_node[del_node_ptr[c] ..)  nodes of the current graph that disappear (local ids, strictly
+ *                                 ascending); their edges disappear with them
+ *   del_edge[del_edge_ptr[c] ..)  further edges of the current graph that disappear (indices into
+ *                                 the current graph's own edge list, strictly ascending)
+ *   add_node_*[add_node_ptr[c] ..) new nodes
+ *   add_edge_*[add_edge_ptr[c] ..) new edges; an endpoint is a node id of the current graph (which
+ *                                 must survive) or n_current + k for the candidate's k-th new node
+ * The candidate graph this stands for: the surviving nodes of the current graph in their order,
+ * then the new nodes; the surviving edges in their order, then the new edges. Graphs are listed
+ * as in xrl_state_desc (per state: current graph, then its candidates), which is the order of
+ * graph_global and slot_mask, G = n_states + number of candidates. */
+typedef struct xrl_edit_state_desc {
+  int32_t n_states;
+  const int32_t *cur_node_ptr;    /* [S+1] node range of each state's current graph, starts at 0 */
+  const int32_t *cur_edge_ptr;    /* [S+1] edge range of each state's current graph, starts at 0 */
+  const int32_t *node_op;         /* current graphs: [Nc] operator id                            */
+  const float *node_dense;        /* [Nc, n_node_dense]                                          */
+  const int32_t *edge_src;        /* [Ec] sender, local to the current graph                     */
+  const int32_t *edge_dst;        /* [Ec] receiver                                               */
+  const float *edge_feat;         /* [Ec, d_edge]                                                */
+  const int32_t *state_cand_ptr;  /* [S+1] candidate range of each state, starts at 0            */
+  const int32_t *del_node_ptr;    /* [C+1] */
+  const int32_t *del_node;
+  const int32_t *del_edge_ptr;    /* [C+1] */
+  const int32_t *del_edge;
+  const int32_t *add_node_ptr;    /* [C+1] */
+  const int32_t *add_node_op;
+  const float *add_node_dense;    /* [total new nodes, n_node_dense]                             */
+  const int32_t *add_edge_ptr;    /* [C+1] */
+  const int32_t *add_edge_src;
+  const int32_t *add_edge_dst;
+  const float *add_edge_feat;     /* [total new edges, d_edge]                                   */
+  const float *graph_global;      /* [S + C, d_global] or NULL for zeros                         */
+  const uint8_t *slot_mask;       /* [S + C] 1 = slot may be chosen; each state's first must be 1 */
+} xrl_edit_state_desc;
+
 /* Read-only view of a packed batch's host arrays (valid until xrl_batch_free). Edges are stored
  * sorted by global receiver id, ties in input order ("receiver order"). */
 typedef struct xrl_packed_view {
@@ -135,6 +176,16 @@ int xrl_weight_tensor(const xrl_model_desc *model, int32_t index, char *name, si
  * validates, converts endpoints to global node ids, sorts edges by receiver (stable) and builds
  * the sender-side index. Errors: NULL, SHAPE, INDEX, VALUE (non-finite attribute), MASK. */
 int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *state, xrl_batch **out);
+/* xrl_pack_state_edits: the same packed batch as xrl_pack_state on the candidate graphs the edits
+ * stand for (every array of xrl_batch_host_view identical; in_eid counts edges in the order stated
+ * above), built from the current graph's receiver-ordered edge lists by merging instead of
+ * sorting every candidate from scratch; only the current graphs and the edits are validated.
+ * xrl_batch_upload of such a batch sends the attributes of the current graphs and of the new
+ * nodes and edges once, plus one index per node and edge, and a kernel fills the per-node and
+ * per-edge attribute arrays on the device (about half the bytes of the plain upload).
+ * Errors: NULL, SHAPE, INDEX (an id out of range, not ascending, an endpoint on a deleted node),
+ * VALUE, MASK, OOM. */
+int xrl_pack_state_edits(const xrl_model_desc *model, const xrl_edit_state_desc *state, xrl_batch **out);
 int xrl_batch_dims(const xrl_batch *b, int64_t *S, int64_t *G, int64_t *N, int64_t *E);
 int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *view);
 int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is accepted          */

@@ -41,6 +41,14 @@ class StateDesc(C.Structure):
                 ("edge_feat", C.c_void_p), ("graph_global", C.c_void_p), ("slot_mask", C.c_void_p)]
 
 
+class EditStateDesc(C.Structure):
+    _fields_ = [("n_states", C.c_int32)] + [(k, C.c_void_p) for k in (
+        "cur_node_ptr", "cur_edge_ptr", "node_op", "node_dense", "edge_src", "edge_dst", "edge_feat",
+        "state_cand_ptr", "del_node_ptr", "del_node", "del_edge_ptr", "del_edge", "add_node_ptr",
+        "add_node_op", "add_node_dense", "add_edge_ptr", "add_edge_src", "add_edge_dst", "add_edge_feat",
+        "graph_global", "slot_mask")]
+
+
 class PackedView(C.Structure):
     _fields_ = [("S", C.c_int64), ("G", C.c_int64), ("N", C.c_int64), ("E", C.c_int64),
                 ("state_graph_ptr", C.c_void_p), ("graph_node_ptr", C.c_void_p),
@@ -51,7 +59,7 @@ class PackedView(C.Structure):
                 ("n_graph_tiles", C.c_int64), ("graph_tile_ptr", C.c_void_p), ("gtile_ptr", C.c_void_p)]
 
 
-EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state",
+EXPORTS = ["xrl_weight_count", "xrl_weight_tensor_count", "xrl_weight_tensor", "xrl_pack_state", "xrl_pack_state_edits",
            "xrl_batch_dims", "xrl_batch_host_view", "xrl_batch_free", "xrl_create",
            "xrl_set_weights", "xrl_destroy", "xrl_batch_upload", "xrl_encode", "xrl_policy_value",
            "xrl_policy_value_static",
@@ -76,6 +84,7 @@ def load_library():
     lib.xrl_weight_tensor.argtypes = [C.POINTER(ModelDesc), i32, C.c_char_p, C.c_size_t,
                                       C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.xrl_pack_state.argtypes = [C.POINTER(ModelDesc), C.POINTER(StateDesc), C.POINTER(vp)]
+    lib.xrl_pack_state_edits.argtypes = [C.POINTER(ModelDesc), C.POINTER(EditStateDesc), C.POINTER(vp)]
     lib.xrl_batch_dims.argtypes = [vp] + [C.POINTER(i64)] * 4
     lib.xrl_batch_host_view.argtypes = [vp, C.POINTER(PackedView)]
     lib.xrl_batch_free.argtypes = [vp]
@@ -151,8 +160,21 @@ def _ptr(a):
 class Batch:
     """A packed meta-batch (host side; device side after Encoder.upload)."""
 
-    def __init__(self, model, state):
+    def __init__(self, model, state, edits=False):
         lib = load_library()
+        self.handle = C.c_void_p()
+        self.model = dict(model)
+        if edits:
+            # candidates given as edits of each state's current graph (see xrl_edit_state_desc)
+            f32 = ("node_dense", "edge_feat", "add_node_dense", "add_edge_feat", "graph_global")
+            keep = {k: _arr(state.get(k), np.float32 if k in f32 else (np.uint8 if k == "slot_mask" else np.int32))
+                    for k, _ in EditStateDesc._fields_[1:]}
+            sd = EditStateDesc(int(state["n_states"]), *[_ptr(keep[k]) for k, _ in EditStateDesc._fields_[1:]])
+            _check(lib.xrl_pack_state_edits(C.byref(model_desc(model)), C.byref(sd), C.byref(self.handle)))
+            d = [C.c_int64() for _ in range(4)]
+            _check(lib.xrl_batch_dims(self.handle, *[C.byref(x) for x in d]))
+            self.S, self.G, self.N, self.E = (int(x.value) for x in d)
+            return
         self._keep = dict(
             sgp=_arr(state["state_graph_ptr"], np.int32), gnp=_arr(state["graph_node_ptr"], np.int32),
             gep=_arr(state["graph_edge_ptr"], np.int32), op=_arr(state["node_op"], np.int32),
@@ -163,8 +185,6 @@ class Batch:
         sd = StateDesc(int(state["n_states"]), _ptr(k["sgp"]), _ptr(k["gnp"]), _ptr(k["gep"]),
                        _ptr(k["op"]), _ptr(k["dense"]), _ptr(k["src"]), _ptr(k["dst"]),
                        _ptr(k["ef"]), _ptr(k["gg"]), _ptr(k["mask"]))
-        self.handle = C.c_void_p()
-        self.model = dict(model)
         _check(lib.xrl_pack_state(C.byref(model_desc(model)), C.byref(sd), C.byref(self.handle)))
         self._keep = None                      # host inputs are only borrowed during the call
         d = [C.c_int64() for _ in range(4)]
@@ -206,6 +226,11 @@ class Batch:
 
 def pack_state(model, state):
     return Batch(model, state)
+
+
+def pack_state_edits(model, edit_state):
+    """Packs states whose candidates are edits of the current graph (xrl_pack_state_edits)."""
+    return Batch(model, edit_state, edits=True)
 
 
 def edge_features_from_shapes(shapes, M=4096.0):
@@ -251,6 +276,9 @@ class Encoder:
 
     def pack(self, state):
         return self.upload(Batch(self.model, state))
+
+    def pack_edits(self, edit_state):
+        return self.upload(Batch(self.model, edit_state, edits=True))
 
     def _empty(self, shape, dtype=None):
         t = self.torch

@@ -1468,6 +1468,21 @@ int xrl_destroy(xrl_ctx *c) {
   return XRL_OK;
 }
 
+namespace {
+// out[i, :] = from[i] >= 0 ? base[from[i], :] : added[-1 - from[i], :], rows of `width` 4-byte words:
+// the per-node and per-edge attribute arrays of a batch packed from edits, filled on the device
+// from the current graphs' attributes and the new items'.
+__global__ void expand_rows_kernel(const int32_t *from, int64_t n, int width, const uint32_t *base, const uint32_t *added,
+                                   uint32_t *out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n * width) return;
+  const int64_t r = i / width;
+  const int j = (int)(i - r * width);
+  const int32_t f = from[r];
+  out[i] = f >= 0 ? base[(size_t)f * width + j] : added[(size_t)(-1 - f) * width + j];
+}
+}  // namespace
+
 int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   if (!c || !b) return fail(XRL_ERR_NULL, "xrl_batch_upload: NULL argument");
   if (b->uploaded) return XRL_OK;
@@ -1482,6 +1497,12 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
                o_gg = plan((size_t)G * Dg * 4), o_mask = plan(G),
                o_tile = plan(b->tile_ptr.size() * 4), o_gtile = plan(b->gtile_ptr.size() * 4),
                o_gtp = plan(b->graph_tile_ptr.size() * 4);
+  // packed from edits: the attribute arrays are filled on the device from these
+  const bool ed = b->from_edits;
+  const size_t o_nf = ed ? plan(N * 4) : 0, o_ef2 = ed ? plan(E * 4) : 0,
+               o_bop = ed ? plan(b->base_node_op.size() * 4) : 0, o_nop = ed ? plan(b->new_node_op.size() * 4) : 0,
+               o_bnd = ed ? plan(b->base_node_dense.size() * 4) : 0, o_nnd = ed ? plan(b->new_node_dense.size() * 4) : 0,
+               o_bef = ed ? plan(b->base_edge_feat.size() * 4) : 0, o_nef = ed ? plan(b->new_edge_feat.size() * 4) : 0;
   char *blk = nullptr;
   hipError_t e = hipMalloc((void **)&blk, off);
   if (e != hipSuccess) {
@@ -1498,15 +1519,37 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   };
   HIP_TRY(cp(o_sgp, b->state_graph_ptr.data(), (S + 1) * 4));
   HIP_TRY(cp(o_gnp, b->graph_node_ptr.data(), (G + 1) * 4));
-  HIP_TRY(cp(o_op, b->node_op.data(), N * 4));
+  if (!ed) HIP_TRY(cp(o_op, b->node_op.data(), N * 4));
   HIP_TRY(cp(o_inp, b->in_ptr.data(), (N + 1) * 4));
   HIP_TRY(cp(o_ins, b->in_src.data(), E * 4));
   HIP_TRY(cp(o_ind, b->in_dst.data(), E * 4));
   HIP_TRY(cp(o_outp, b->out_ptr.data(), (N + 1) * 4));
   HIP_TRY(cp(o_outpos, b->out_pos.data(), E * 4));
   HIP_TRY(cp(o_ng, b->node_graph.data(), N * 4));
-  HIP_TRY(cp(o_nd, b->node_dense.data(), (size_t)N * Dd * 4));
-  HIP_TRY(cp(o_ef, b->edge_feat.data(), (size_t)E * De * 4));
+  if (!ed) {
+    HIP_TRY(cp(o_nd, b->node_dense.data(), (size_t)N * Dd * 4));
+    HIP_TRY(cp(o_ef, b->edge_feat.data(), (size_t)E * De * 4));
+  } else {
+    HIP_TRY(cp(o_nf, b->node_from.data(), N * 4));
+    HIP_TRY(cp(o_ef2, b->edge_from.data(), E * 4));
+    HIP_TRY(cp(o_bop, b->base_node_op.data(), b->base_node_op.size() * 4));
+    HIP_TRY(cp(o_nop, b->new_node_op.data(), b->new_node_op.size() * 4));
+    HIP_TRY(cp(o_bnd, b->base_node_dense.data(), b->base_node_dense.size() * 4));
+    HIP_TRY(cp(o_nnd, b->new_node_dense.data(), b->new_node_dense.size() * 4));
+    HIP_TRY(cp(o_bef, b->base_edge_feat.data(), b->base_edge_feat.size() * 4));
+    HIP_TRY(cp(o_nef, b->new_edge_feat.data(), b->new_edge_feat.size() * 4));
+    auto expand = [&](size_t o_from, int64_t n, int width, size_t o_base, size_t o_new, size_t o_out) {
+      const int64_t total = n * width;
+      if (total > 0)
+        expand_rows_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->stream>>>(
+            (const int32_t *)(blk + o_from), n, width, (const uint32_t *)(blk + o_base), (const uint32_t *)(blk + o_new),
+            (uint32_t *)(blk + o_out));
+    };
+    expand(o_nf, N, 1, o_bop, o_nop, o_op);
+    expand(o_nf, N, Dd, o_bnd, o_nnd, o_nd);
+    expand(o_ef2, E, De, o_bef, o_nef, o_ef);
+    HIP_TRY(hipGetLastError());
+  }
   HIP_TRY(cp(o_gg, b->graph_global.data(), (size_t)G * Dg * 4));
   HIP_TRY(cp(o_mask, b->mask.data(), G));
   HIP_TRY(cp(o_tile, b->tile_ptr.data(), b->tile_ptr.size() * 4));

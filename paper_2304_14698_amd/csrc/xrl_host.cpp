@@ -170,6 +170,68 @@ bool run_ranges(const std::vector<int64_t> &cut, F fn) {
   for (auto &x : th) x.join();
   return ok;
 }
+
+// Edge tiles of the message kernels and the per-graph tiles of the one-launch encoder, from the
+// packed in_ptr / graph_node_ptr (serial: a tile boundary depends on the ones before it).
+void build_tile_tables(xrl_batch *b) {
+  const int64_t N = b->N, E = b->E, G = b->G;
+  {  // Edge tiles of the message kernels: consecutive receiver-order edges, at most 32 per tile,
+       // cut at receiver boundaries so that a receiver's in-edges share a tile. Only a receiver
+       // with more than 32 in-edges is split (into full tiles plus a remainder that later
+       // receivers may join); its pieces are recombined by the carry fix-up.
+      b->tile_ptr.clear();
+      b->tile_ptr.push_back(0);
+      b->n_split_tiles = 0;
+      int32_t fill = 0;                 // edges in the open tile
+      for (int64_t n = 0; n < N; ++n) {
+        int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
+        if (d == 0) continue;
+        if (fill + d > 32 && fill > 0) {
+          b->tile_ptr.push_back(b->in_ptr[n]);
+          fill = 0;
+        }
+        while (d > 32) {                // fill == 0 here
+          b->tile_ptr.push_back(b->tile_ptr.back() + 32);
+          b->n_split_tiles++;
+          d -= 32;
+        }
+        fill += d;
+      }
+      if (fill > 0) b->tile_ptr.push_back((int32_t)E);
+    }
+    b->max_graph_nodes = 0;
+    for (int64_t g = 0; g < G; ++g)
+      b->max_graph_nodes = std::max(b->max_graph_nodes, b->graph_node_ptr[g + 1] - b->graph_node_ptr[g]);
+    b->gtile_ptr.clear();
+    b->graph_tile_ptr.clear();
+    b->max_graph_tiles = 0;
+    if (G <= kGraphTileMaxGraphs) {   // the same rule graph by graph (see xrl_batch)
+      bool ok = true;
+      b->graph_tile_ptr.push_back(0);
+      for (int64_t g = 0; g < G && ok; ++g) {
+        int32_t fill = 0;
+        const int32_t n1 = b->graph_node_ptr[g + 1];
+        for (int32_t n = b->graph_node_ptr[g]; n < n1; ++n) {
+          const int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
+          if (d == 0) continue;
+          if (d > 32) { ok = false; break; }
+          if (fill + d > 32 || fill == 0) {
+            b->gtile_ptr.push_back(b->in_ptr[n]);
+            fill = 0;
+          }
+          fill += d;
+        }
+        b->max_graph_tiles = std::max(b->max_graph_tiles, (int32_t)b->gtile_ptr.size() - b->graph_tile_ptr.back());
+        b->graph_tile_ptr.push_back((int32_t)b->gtile_ptr.size());
+      }
+      if (ok) {
+        b->gtile_ptr.push_back((int32_t)E);
+      } else {
+        b->gtile_ptr.clear();
+        b->graph_tile_ptr.clear();
+      }
+    }
+}
 }  // namespace
 
 extern "C" {
@@ -355,65 +417,258 @@ int xrl_pack_state(const xrl_model_desc *model, const xrl_state_desc *st, xrl_ba
       }
     });
     if (!sorted) throw std::bad_alloc();
-    {  // Edge tiles of the message kernels: consecutive receiver-order edges, at most 32 per tile,
-       // cut at receiver boundaries so that a receiver's in-edges share a tile. Only a receiver
-       // with more than 32 in-edges is split (into full tiles plus a remainder that later
-       // receivers may join); its pieces are recombined by the carry fix-up.
-      b->tile_ptr.clear();
-      b->tile_ptr.push_back(0);
-      b->n_split_tiles = 0;
-      int32_t fill = 0;                 // edges in the open tile
-      for (int64_t n = 0; n < N; ++n) {
-        int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
-        if (d == 0) continue;
-        if (fill + d > 32 && fill > 0) {
-          b->tile_ptr.push_back(b->in_ptr[n]);
-          fill = 0;
-        }
-        while (d > 32) {                // fill == 0 here
-          b->tile_ptr.push_back(b->tile_ptr.back() + 32);
-          b->n_split_tiles++;
-          d -= 32;
-        }
-        fill += d;
-      }
-      if (fill > 0) b->tile_ptr.push_back((int32_t)E);
-    }
-    b->max_graph_nodes = 0;
-    for (int64_t g = 0; g < G; ++g)
-      b->max_graph_nodes = std::max(b->max_graph_nodes, b->graph_node_ptr[g + 1] - b->graph_node_ptr[g]);
-    b->gtile_ptr.clear();
-    b->graph_tile_ptr.clear();
-    b->max_graph_tiles = 0;
-    if (G <= kGraphTileMaxGraphs) {   // the same rule graph by graph (see xrl_batch)
-      bool ok = true;
-      b->graph_tile_ptr.push_back(0);
-      for (int64_t g = 0; g < G && ok; ++g) {
-        int32_t fill = 0;
-        const int32_t n1 = b->graph_node_ptr[g + 1];
-        for (int32_t n = b->graph_node_ptr[g]; n < n1; ++n) {
-          const int32_t d = b->in_ptr[n + 1] - b->in_ptr[n];
-          if (d == 0) continue;
-          if (d > 32) { ok = false; break; }
-          if (fill + d > 32 || fill == 0) {
-            b->gtile_ptr.push_back(b->in_ptr[n]);
-            fill = 0;
-          }
-          fill += d;
-        }
-        b->max_graph_tiles = std::max(b->max_graph_tiles, (int32_t)b->gtile_ptr.size() - b->graph_tile_ptr.back());
-        b->graph_tile_ptr.push_back((int32_t)b->gtile_ptr.size());
-      }
-      if (ok) {
-        b->gtile_ptr.push_back((int32_t)E);
-      } else {
-        b->gtile_ptr.clear();
-        b->graph_tile_ptr.clear();
-      }
-    }
+    build_tile_tables(b);
   } catch (const std::bad_alloc &) {
     delete b;
     return fail(XRL_ERR_OOM, "xrl_pack_state: out of host memory");
+  }
+  *out = b;
+  return XRL_OK;
+}
+
+int xrl_pack_state_edits(const xrl_model_desc *model, const xrl_edit_state_desc *st, xrl_batch **out) {
+  if (!model || !st || !out) return fail(XRL_ERR_NULL, "xrl_pack_state_edits: NULL argument");
+  *out = nullptr;
+  Layout L;
+  int rc = build_layout(*model, L);
+  if (rc) return rc;
+  const int64_t S = st->n_states;
+  if (S < 0) return fail(XRL_ERR_SHAPE, "n_states = %lld is negative", (long long)S);
+  if (!st->cur_node_ptr || !st->cur_edge_ptr || !st->state_cand_ptr || !st->del_node_ptr || !st->del_edge_ptr ||
+      !st->add_node_ptr || !st->add_edge_ptr || !st->slot_mask)
+    return fail(XRL_ERR_NULL, "xrl_pack_state_edits: a ptr array or slot_mask is NULL");
+  if ((rc = check_ptr(st->cur_node_ptr, S, "cur_node_ptr"))) return rc;
+  if ((rc = check_ptr(st->cur_edge_ptr, S, "cur_edge_ptr"))) return rc;
+  if ((rc = check_ptr(st->state_cand_ptr, S, "state_cand_ptr"))) return rc;
+  const int64_t C = st->state_cand_ptr[S], G = S + C;
+  if ((rc = check_ptr(st->del_node_ptr, C, "del_node_ptr"))) return rc;
+  if ((rc = check_ptr(st->del_edge_ptr, C, "del_edge_ptr"))) return rc;
+  if ((rc = check_ptr(st->add_node_ptr, C, "add_node_ptr"))) return rc;
+  if ((rc = check_ptr(st->add_edge_ptr, C, "add_edge_ptr"))) return rc;
+  const int64_t Nc = st->cur_node_ptr[S], Ec = st->cur_edge_ptr[S];
+  const int64_t n_dn = st->del_node_ptr[C], n_de = st->del_edge_ptr[C], n_an = st->add_node_ptr[C], n_ae = st->add_edge_ptr[C];
+  const int Dd = model->n_node_dense, De = model->d_edge, Dg = model->d_global;
+  if (Nc > 0 && (!st->node_op || (Dd > 0 && !st->node_dense))) return fail(XRL_ERR_NULL, "node_op or node_dense is NULL");
+  if (Ec > 0 && (!st->edge_src || !st->edge_dst || !st->edge_feat))
+    return fail(XRL_ERR_NULL, "edge_src, edge_dst or edge_feat is NULL");
+  if ((n_dn > 0 && !st->del_node) || (n_de > 0 && !st->del_edge) || (n_an > 0 && (!st->add_node_op || (Dd > 0 && !st->add_node_dense))) ||
+      (n_ae > 0 && (!st->add_edge_src || !st->add_edge_dst || !st->add_edge_feat)))
+    return fail(XRL_ERR_NULL, "xrl_pack_state_edits: an edit array is NULL");
+  // graph g of the batch: state s's current graph, or candidate c
+  std::vector<int32_t> sgp(S + 1), g_state(G), g_cand(G);
+  for (int64_t s = 0, g = 0; s < S; ++s) {
+    sgp[s] = (int32_t)g;
+    g_state[g] = (int32_t)s; g_cand[g] = -1; ++g;
+    for (int32_t c = st->state_cand_ptr[s]; c < st->state_cand_ptr[s + 1]; ++c, ++g) { g_state[g] = (int32_t)s; g_cand[g] = c; }
+    sgp[s + 1] = (int32_t)g;
+  }
+  for (int64_t s = 0; s < S; ++s)
+    if (st->slot_mask[sgp[s]] == 0) return fail(XRL_ERR_MASK, "state %lld masks its No-Op slot (its first graph)", (long long)s);
+  // ---- the current graphs and the new items (what is validated; everything else is copied from them)
+  for (int64_t i = 0; i < Nc; ++i)
+    if (st->node_op[i] < 0 || st->node_op[i] >= model->n_op_types)
+      return fail(XRL_ERR_INDEX, "node %lld: op id %d outside [0, %d)", (long long)i, st->node_op[i], model->n_op_types);
+  for (int64_t i = 0; i < n_an; ++i)
+    if (st->add_node_op[i] < 0 || st->add_node_op[i] >= model->n_op_types)
+      return fail(XRL_ERR_INDEX, "new node %lld: op id %d outside [0, %d)", (long long)i, st->add_node_op[i], model->n_op_types);
+  for (int64_t s = 0; s < S; ++s) {
+    const int32_t n = st->cur_node_ptr[s + 1] - st->cur_node_ptr[s];
+    for (int64_t e = st->cur_edge_ptr[s]; e < st->cur_edge_ptr[s + 1]; ++e)
+      if (st->edge_src[e] < 0 || st->edge_src[e] >= n || st->edge_dst[e] < 0 || st->edge_dst[e] >= n)
+        return fail(XRL_ERR_INDEX, "edge %lld of state %lld's current graph: endpoint (%d -> %d) outside [0, %d)", (long long)e,
+                    (long long)s, st->edge_src[e], st->edge_dst[e], n);
+  }
+  int64_t where = 0;
+  if (Dd > 0 && !all_finite(st->node_dense, Nc * Dd, &where)) return fail(XRL_ERR_VALUE, "node_dense[%lld] is not finite", (long long)where);
+  if (Dd > 0 && !all_finite(st->add_node_dense, n_an * Dd, &where)) return fail(XRL_ERR_VALUE, "add_node_dense[%lld] is not finite", (long long)where);
+  if (!all_finite(st->edge_feat, Ec * De, &where)) return fail(XRL_ERR_VALUE, "edge_feat[%lld] is not finite", (long long)where);
+  if (!all_finite(st->add_edge_feat, n_ae * De, &where)) return fail(XRL_ERR_VALUE, "add_edge_feat[%lld] is not finite", (long long)where);
+  if (st->graph_global && !all_finite(st->graph_global, G * Dg, &where)) return fail(XRL_ERR_VALUE, "graph_global[%lld] is not finite", (long long)where);
+  // ---- the edits, and the size of every graph
+  std::vector<int32_t> gnp(G + 1, 0), gep(G + 1, 0);
+  {
+    std::vector<uint8_t> dead;                     // per node of the state's current graph
+    for (int64_t g = 0; g < G; ++g) {
+      const int64_t s = g_state[g];
+      const int32_t n = st->cur_node_ptr[s + 1] - st->cur_node_ptr[s];
+      const int64_t e0 = st->cur_edge_ptr[s], e1 = st->cur_edge_ptr[s + 1];
+      if (g_cand[g] < 0) { gnp[g + 1] = n; gep[g + 1] = (int32_t)(e1 - e0); continue; }
+      const int64_t c = g_cand[g];
+      dead.assign(n, 0);
+      for (int32_t k = st->del_node_ptr[c]; k < st->del_node_ptr[c + 1]; ++k) {
+        const int32_t v = st->del_node[k];
+        if (v < 0 || v >= n || (k > st->del_node_ptr[c] && v <= st->del_node[k - 1]))
+          return fail(XRL_ERR_INDEX, "candidate %lld: del_node[%d] = %d out of range or not ascending", (long long)c, k, v);
+        dead[v] = 1;
+      }
+      int32_t kept = 0;
+      int32_t kd = st->del_edge_ptr[c];
+      const int32_t kd1 = st->del_edge_ptr[c + 1];
+      for (int32_t k = kd; k < kd1; ++k) {
+        const int32_t v = st->del_edge[k];
+        if (v < 0 || v >= e1 - e0 || (k > kd && v <= st->del_edge[k - 1]))
+          return fail(XRL_ERR_INDEX, "candidate %lld: del_edge[%d] = %d out of range or not ascending", (long long)c, k, v);
+      }
+      for (int64_t e = e0; e < e1; ++e) {
+        if (kd < kd1 && st->del_edge[kd] == e - e0) { ++kd; continue; }
+        if (!dead[st->edge_src[e]] && !dead[st->edge_dst[e]]) ++kept;
+      }
+      const int32_t n_new = st->add_node_ptr[c + 1] - st->add_node_ptr[c];
+      for (int32_t k = st->add_edge_ptr[c]; k < st->add_edge_ptr[c + 1]; ++k)
+        for (const int32_t v : {st->add_edge_src[k], st->add_edge_dst[k]})
+          if (v < 0 || v >= n + n_new || (v < n && dead[v]))
+            return fail(XRL_ERR_INDEX, "candidate %lld: new edge %d has endpoint %d outside its graph or on a deleted node", (long long)c, k, v);
+      gnp[g + 1] = n - (st->del_node_ptr[c + 1] - st->del_node_ptr[c]) + n_new;
+      gep[g + 1] = kept + (st->add_edge_ptr[c + 1] - st->add_edge_ptr[c]);
+    }
+    int64_t nn = 0, ee = 0;
+    for (int64_t g = 0; g < G; ++g) {
+      nn += gnp[g + 1]; ee += gep[g + 1];
+      if (nn > INT32_MAX || ee > INT32_MAX) return fail(XRL_ERR_SHAPE, "the batch has more than 2^31 - 1 nodes or edges");
+      gnp[g + 1] = (int32_t)nn; gep[g + 1] = (int32_t)ee;
+    }
+  }
+  const int64_t N = gnp[G], E = gep[G];
+
+  xrl_batch *b = new (std::nothrow) xrl_batch();
+  if (!b) return fail(XRL_ERR_OOM, "xrl_pack_state_edits: out of host memory");
+  try {
+    static std::atomic<uint64_t> next_id{(uint64_t)1 << 62};
+    b->id = next_id++;
+    b->model = *model;
+    b->S = S; b->G = G; b->N = N; b->E = E;
+    b->from_edits = true;
+    b->state_graph_ptr = sgp;
+    b->graph_node_ptr = gnp;
+    b->mask.resize(G);
+    for (int64_t g = 0; g < G; ++g) b->mask[g] = st->slot_mask[g] ? 1 : 0;
+    if (st->graph_global) b->graph_global.assign(st->graph_global, st->graph_global + G * Dg);
+    else b->graph_global.assign((size_t)(G * Dg), 0.0f);
+    for (int64_t s = 0; s < S; ++s) b->max_slots = std::max(b->max_slots, sgp[s + 1] - sgp[s]);
+    // (node_op, node_dense and edge_feat of the batch are not written here: the device fills its
+    // copies from node_from / edge_from, and xrl_batch_host_view fills the host's on demand)
+    b->node_graph.resize(N);
+    b->in_ptr.assign(N + 1, 0); b->out_ptr.assign(N + 1, 0);
+    b->in_src.resize(E); b->in_dst.resize(E); b->in_eid.resize(E); b->out_pos.resize(E);
+    b->node_from.resize(N); b->edge_from.resize(E);
+    b->base_node_op.assign(st->node_op, st->node_op + Nc);
+    b->base_node_dense.assign(st->node_dense, st->node_dense + (Dd > 0 ? Nc * Dd : 0));
+    b->base_edge_feat.assign(st->edge_feat, st->edge_feat + Ec * De);
+    b->new_node_op.assign(st->add_node_op, st->add_node_op + n_an);
+    b->new_node_dense.assign(st->add_node_dense, st->add_node_dense + (Dd > 0 ? n_an * Dd : 0));
+    b->new_edge_feat.assign(st->add_edge_feat, st->add_edge_feat + n_ae * De);
+    // ---- the current graph of every state in receiver order once: its in-edge lists (edge ids
+    // ascending inside a receiver's list, i.e. the stable order)
+    std::vector<int32_t> bin_ptr(Nc + S + 1, 0), bin_eid(Ec);
+    for (int64_t s = 0; s < S; ++s) {
+      const int32_t nb = st->cur_node_ptr[s], n = st->cur_node_ptr[s + 1] - nb;
+      const int64_t e0 = st->cur_edge_ptr[s], e1 = st->cur_edge_ptr[s + 1];
+      int32_t *ip = bin_ptr.data() + nb + s;          // [n + 1] of this state
+      for (int64_t e = e0; e < e1; ++e) ip[st->edge_dst[e] + 1]++;
+      for (int32_t i = 0; i < n; ++i) ip[i + 1] += ip[i];
+      std::vector<int32_t> cur(ip, ip + n);
+      for (int64_t e = e0; e < e1; ++e) bin_eid[e0 + cur[st->edge_dst[e]]++] = (int32_t)(e - e0);
+    }
+    // ---- every graph by merging; graph ranges on separate threads
+    const int T = pack_thread_count(N + E);
+    std::vector<int64_t> cut(T + 1, G);
+    cut[0] = 0;
+    for (int t = 1, g = 0; t < T; ++t) {
+      const int64_t want = (N + E) * t / T;
+      while (g < G && (int64_t)gnp[g] + gep[g] < want) ++g;
+      cut[t] = g;
+    }
+    const bool merged = run_ranges(cut, [&](int, int64_t g0, int64_t g1) {
+      std::vector<int32_t> newid, erank, cur, add_order;
+      std::vector<uint8_t> dead;
+      for (int64_t g = g0; g < g1; ++g) {
+        const int64_t s = g_state[g], c = g_cand[g];
+        const int32_t nb = st->cur_node_ptr[s], n = st->cur_node_ptr[s + 1] - nb;
+        const int64_t e0 = st->cur_edge_ptr[s], e1 = st->cur_edge_ptr[s + 1];
+        const int32_t *ip = bin_ptr.data() + nb + s;
+        const int32_t base = gnp[g], ng = gnp[g + 1] - base, eb = gep[g];
+        const int32_t an0 = c < 0 ? 0 : st->add_node_ptr[c], n_new = c < 0 ? 0 : st->add_node_ptr[c + 1] - an0;
+        const int32_t ae0 = c < 0 ? 0 : st->add_edge_ptr[c], n_ae_c = c < 0 ? 0 : st->add_edge_ptr[c + 1] - ae0;
+        // surviving nodes -> new ids; surviving edges -> rank in the candidate's edge list
+        dead.assign(n, 0);
+        if (c >= 0)
+          for (int32_t k = st->del_node_ptr[c]; k < st->del_node_ptr[c + 1]; ++k) dead[st->del_node[k]] = 1;
+        newid.assign(n + n_new, -1);
+        int32_t nk = 0;
+        for (int32_t i = 0; i < n; ++i)
+          if (!dead[i]) newid[i] = nk++;
+        for (int32_t k = 0; k < n_new; ++k) newid[n + k] = nk + k;
+        erank.assign(e1 - e0, -1);
+        int32_t ek = 0;
+        {
+          int32_t kd = c < 0 ? 0 : st->del_edge_ptr[c];
+          const int32_t kd1 = c < 0 ? 0 : st->del_edge_ptr[c + 1];
+          for (int64_t e = e0; e < e1; ++e) {
+            if (kd < kd1 && st->del_edge[kd] == e - e0) { ++kd; continue; }
+            if (!dead[st->edge_src[e]] && !dead[st->edge_dst[e]]) erank[e - e0] = ek++;
+          }
+        }
+        // new edges grouped by receiver, in their own order inside a group
+        add_order.resize(n_ae_c);
+        for (int32_t k = 0; k < n_ae_c; ++k) add_order[k] = k;
+        std::stable_sort(add_order.begin(), add_order.end(), [&](int32_t x, int32_t y) {
+          return newid[st->add_edge_dst[ae0 + x]] < newid[st->add_edge_dst[ae0 + y]];
+        });
+        // nodes
+        for (int32_t i = 0; i < n; ++i) {
+          if (dead[i]) continue;
+          const int32_t v = base + newid[i];
+          b->node_graph[v] = (int32_t)g;
+          b->node_from[v] = nb + i;
+        }
+        for (int32_t k = 0; k < n_new; ++k) {
+          const int32_t v = base + nk + k;
+          b->node_graph[v] = (int32_t)g;
+          b->node_from[v] = -1 - (an0 + k);
+        }
+        // receiver order: per receiver its surviving in-edges (edge ids ascending), then its new ones
+        int32_t p = eb, ka = 0;
+        int32_t *inp = b->in_ptr.data() + base + 1, *outp = b->out_ptr.data() + base + 1;
+        int32_t vcur = 0;
+        for (int32_t i = 0; i < n + n_new; ++i) {
+          if (i < n && dead[i]) continue;
+          const int32_t v = vcur++;                  // == newid[i]
+          if (i < n) {
+            for (int32_t q = ip[i]; q < ip[i + 1]; ++q) {
+              const int32_t el = bin_eid[e0 + q];
+              if (erank[el] < 0) continue;
+              const int64_t e = e0 + el;
+              b->in_src[p] = base + newid[st->edge_src[e]];
+              b->in_dst[p] = base + v;
+              b->in_eid[p] = eb + erank[el];
+              b->edge_from[p] = (int32_t)e;
+              ++p;
+            }
+          }
+          for (; ka < n_ae_c && newid[st->add_edge_dst[ae0 + add_order[ka]]] == v; ++ka) {
+            const int32_t k = ae0 + add_order[ka];
+            b->in_src[p] = base + newid[st->add_edge_src[k]];
+            b->in_dst[p] = base + v;
+            b->in_eid[p] = eb + ek + add_order[ka];
+            b->edge_from[p] = -1 - k;
+            ++p;
+          }
+          inp[v] = p;                                // end of v's in-edges
+        }
+        // sender-side index: receiver-order positions grouped by sender, ascending position
+        for (int32_t v = 0; v < ng; ++v) outp[v] = 0;
+        for (int32_t q = eb; q < p; ++q) outp[b->in_src[q] - base]++;
+        cur.assign(ng, 0);
+        int32_t ro = eb;
+        for (int32_t v = 0; v < ng; ++v) { cur[v] = ro; ro += outp[v]; outp[v] = ro; }
+        for (int32_t q = eb; q < p; ++q) b->out_pos[cur[b->in_src[q] - base]++] = q;
+      }
+    });
+    if (!merged) throw std::bad_alloc();
+    build_tile_tables(b);
+  } catch (const std::bad_alloc &) {
+    delete b;
+    return fail(XRL_ERR_OOM, "xrl_pack_state_edits: out of host memory");
   }
   *out = b;
   return XRL_OK;
@@ -451,8 +706,23 @@ int xrl_batch_dims(const xrl_batch *b, int64_t *S, int64_t *G, int64_t *N, int64
   return XRL_OK;
 }
 
-int xrl_batch_host_view(const xrl_batch *b, xrl_packed_view *v) {
-  if (!b || !v) return fail(XRL_ERR_NULL, "xrl_batch_host_view: NULL argument");
+int xrl_batch_host_view(const xrl_batch *cb, xrl_packed_view *v) {
+  if (!cb || !v) return fail(XRL_ERR_NULL, "xrl_batch_host_view: NULL argument");
+  xrl_batch *b = const_cast<xrl_batch *>(cb);
+  if (b->from_edits && b->edge_feat.size() != (size_t)b->E * b->model.d_edge) {
+    // packed from edits: the per-edge attribute rows are written out on first request
+    const int De = b->model.d_edge;
+    try {
+      b->edge_feat.resize((size_t)b->E * De);
+    } catch (const std::bad_alloc &) {
+      return fail(XRL_ERR_OOM, "xrl_batch_host_view: out of host memory");
+    }
+    for (int64_t p = 0; p < b->E; ++p) {
+      const int32_t f = b->edge_from[p];
+      const float *src = f >= 0 ? &b->base_edge_feat[(size_t)f * De] : &b->new_edge_feat[(size_t)(-1 - f) * De];
+      memcpy(&b->edge_feat[(size_t)p * De], src, sizeof(float) * De);
+    }
+  }
   v->S = b->S; v->G = b->G; v->N = b->N; v->E = b->E;
   v->state_graph_ptr = b->state_graph_ptr.data();
   v->graph_node_ptr = b->graph_node_ptr.data();

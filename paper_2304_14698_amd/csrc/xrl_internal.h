@@ -84,6 +84,13 @@ struct xrl_batch {
   RawVec<float> node_dense, edge_feat;
   std::vector<float> graph_global;
   std::vector<uint8_t> mask;
+  // Batches packed from edits (xrl_pack_state_edits): where each node's and each receiver-order
+  // edge's attributes come from -- an index into the current graphs' arrays (>= 0) or, as -1 - k,
+  // into the new nodes' / edges' arrays -- and those compact attribute arrays. Empty otherwise.
+  RawVec<int32_t> node_from, edge_from;
+  RawVec<int32_t> base_node_op, new_node_op;
+  RawVec<float> base_node_dense, new_node_dense, base_edge_feat, new_edge_feat;
+  bool from_edits = false;
   xrl_batch_device dev;
   bool uploaded = false;
   uint64_t id = 0;  // unique per packed batch; ties saved activations to their batch

@@ -234,3 +234,59 @@ def local_rewrite(rng, g, n_del, n_ins, by_block=False, reach=3):
     efeat = np.concatenate([efeat, rng.standard_normal((ne, D_EDGE)).astype(np.float32)])
     p = rng.permutation(len(src))
     return Graph(op, dense, layer, block, src[p], dst[p], efeat[p])
+
+
+def local_rewrite_edit(rng, g, n_del, n_ins, by_block=False, reach=3, n_del_edges=0):
+    """A candidate as an edit of g (the form a rewrite engine produces): nodes of g that
+    disappear, further edges of g that disappear, new nodes, new edges. An endpoint of a new edge
+    is a surviving node id of g, or g.n_nodes + k for the k-th new node. Same locality rules as
+    local_rewrite. Returns a dict of arrays."""
+    n = g.n_nodes
+    anchor = int(rng.integers(0, n))
+    near = np.flatnonzero(g.block == g.block[anchor]) if by_block else np.flatnonzero(np.abs(g.layer - g.layer[anchor]) <= reach)
+    n_del = min(n_del, max(len(near) - 1, 0), n - 1)
+    dele = np.sort(rng.choice(near, size=n_del, replace=False)) if n_del > 0 else np.zeros(0, np.int64)
+    keep = np.ones(n, dtype=bool)
+    keep[dele] = False
+    alive_edges = np.flatnonzero(keep[g.src] & keep[g.dst])
+    n_del_edges = min(n_del_edges, len(alive_edges))
+    dedge = np.sort(rng.choice(alive_edges, size=n_del_edges, replace=False)) if n_del_edges > 0 else np.zeros(0, np.int64)
+    nl = np.clip(g.layer[anchor] + rng.integers(-1, 2, size=n_ins), 0, None).astype(np.int32)
+    new_src, new_dst = [], []
+    for j in range(n_ins):
+        v, L = n + j, int(nl[j])
+        below = np.flatnonzero(keep & (g.layer >= L - reach) & (g.layer <= L - 1))
+        above = np.flatnonzero(keep & (g.layer >= L + 1) & (g.layer <= L + reach))
+        for pool, is_pred in ((below, True), (above, False)):
+            if len(pool) == 0:
+                continue
+            k = min(int(rng.integers(1, 3)), len(pool))
+            for u in rng.choice(pool, size=k, replace=False):
+                if is_pred:
+                    new_src.append(int(u)); new_dst.append(v)
+                else:
+                    new_src.append(v); new_dst.append(int(u))
+    ne = len(new_src)
+    return dict(del_node=dele.astype(np.int32), del_edge=dedge.astype(np.int32),
+                add_node_op=rng.integers(0, N_OP_TYPES, size=n_ins).astype(np.int32),
+                add_node_dense=rng.integers(0, 13, size=(n_ins, N_NODE_DENSE)).astype(np.float32),
+                add_edge_src=np.array(new_src, dtype=np.int32), add_edge_dst=np.array(new_dst, dtype=np.int32),
+                add_edge_feat=rng.standard_normal((ne, D_EDGE)).astype(np.float32))
+
+
+def apply_edit(g, ed):
+    """The candidate graph an edit stands for: surviving nodes of g in their order, then the new
+    nodes; surviving edges of g in their order, then the new edges."""
+    n = g.n_nodes
+    keep = np.ones(n, dtype=bool)
+    keep[ed["del_node"]] = False
+    n_new = len(ed["add_node_op"])
+    newid = np.concatenate([np.cumsum(keep, dtype=np.int64) - 1, int(keep.sum()) + np.arange(n_new)])
+    ekeep = keep[g.src] & keep[g.dst]
+    ekeep[ed["del_edge"]] = False
+    src = np.concatenate([newid[g.src[ekeep]], newid[ed["add_edge_src"]]]).astype(np.int32)
+    dst = np.concatenate([newid[g.dst[ekeep]], newid[ed["add_edge_dst"]]]).astype(np.int32)
+    return Graph(np.concatenate([g.op[keep], ed["add_node_op"]]).astype(np.int32),
+                 np.concatenate([g.dense[keep], ed["add_node_dense"]]).astype(np.float32),
+                 np.concatenate([g.layer[keep], np.zeros(n_new, np.int32)]), np.concatenate([g.block[keep], np.zeros(n_new, np.int32)]),
+                 src, dst, np.concatenate([g.efeat[ekeep], ed["add_edge_feat"]]).astype(np.float32))

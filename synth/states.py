@@ -165,3 +165,49 @@ def random_states(rng, model, n_states, max_graphs=6, max_nodes=120, edge_factor
                 edge_feat=(rng.standard_normal((E, De)) * 0.3).astype(np.float32),
                 graph_global=rng.standard_normal((G, Dg)).astype(np.float32),
                 slot_mask=np.array(mask, np.uint8))
+
+
+def make_edit_states(rng, bases, n_cand, touch=(1, 6), by_block=True, mask_p=0.1, n_del_edges=(0, 2)):
+    """States whose candidates are edits of the current graph. bases: one current Graph per state;
+    n_cand: candidates per state (an int or one per state). Returns (edit_state, state): the dict
+    of arrays xrl_pack_state_edits takes, and the ordinary state (every candidate written out as
+    the graph its edit stands for) that it must pack identically to."""
+    S = len(bases)
+    counts = [n_cand] * S if np.isscalar(n_cand) else list(n_cand)
+    edits, full = [], []
+    for s in range(S):
+        g = bases[s]
+        graphs, eds = [g], []
+        for _ in range(counts[s]):
+            t = int(rng.integers(touch[0], touch[1] + 1))
+            nd = int(rng.integers(0, t + 1))
+            ed = G.local_rewrite_edit(rng, g, nd, t - nd, by_block=by_block,
+                                      n_del_edges=int(rng.integers(n_del_edges[0], n_del_edges[1] + 1)))
+            eds.append(ed)
+            graphs.append(G.apply_edit(g, ed))
+        mask = (rng.random(counts[s] + 1) >= mask_p).astype(np.uint8)
+        mask[0] = 1
+        edits.append(eds)
+        full.append((graphs, mask))
+    state = concat_states(full)
+    flat = [ed for eds in edits for ed in eds]
+    ptr = lambda key: np.concatenate([[0], np.cumsum([len(ed[key]) for ed in flat])]).astype(np.int32)
+    cat = lambda key, shape, dt: (np.concatenate([ed[key] for ed in flat]) if flat else np.zeros(shape, dt)).astype(dt).reshape((-1,) + shape[1:])
+    edit_state = dict(
+        n_states=S,
+        cur_node_ptr=np.concatenate([[0], np.cumsum([g.n_nodes for g in bases])]).astype(np.int32),
+        cur_edge_ptr=np.concatenate([[0], np.cumsum([g.n_edges for g in bases])]).astype(np.int32),
+        node_op=np.concatenate([g.op for g in bases]).astype(np.int32),
+        node_dense=np.concatenate([g.dense for g in bases]).astype(np.float32),
+        edge_src=np.concatenate([g.src for g in bases]).astype(np.int32),
+        edge_dst=np.concatenate([g.dst for g in bases]).astype(np.int32),
+        edge_feat=np.concatenate([g.efeat for g in bases]).astype(np.float32),
+        state_cand_ptr=np.concatenate([[0], np.cumsum(counts)]).astype(np.int32),
+        del_node_ptr=ptr("del_node"), del_node=cat("del_node", (0,), np.int32),
+        del_edge_ptr=ptr("del_edge"), del_edge=cat("del_edge", (0,), np.int32),
+        add_node_ptr=ptr("add_node_op"), add_node_op=cat("add_node_op", (0,), np.int32),
+        add_node_dense=cat("add_node_dense", (0, G.N_NODE_DENSE), np.float32),
+        add_edge_ptr=ptr("add_edge_src"), add_edge_src=cat("add_edge_src", (0,), np.int32),
+        add_edge_dst=cat("add_edge_dst", (0,), np.int32), add_edge_feat=cat("add_edge_feat", (0, G.D_EDGE), np.float32),
+        graph_global=state["graph_global"], slot_mask=state["slot_mask"])
+    return edit_state, state

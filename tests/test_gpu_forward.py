@@ -642,3 +642,32 @@ def test_one_launch_encoder_equals_streaming_path(xrl, hidden, precision, rounds
         for x, y in zip(a1, a0):
             assert torch.equal(x, y)
         assert torch.equal(g1, g0)
+
+
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_states_packed_from_edits(xrl, precision):
+    """A state whose candidates are given as edits of the current graph (xrl_pack_state_edits; the
+    attribute arrays are filled on the device from the current graph's and the new items'):
+    embeddings and head outputs bit-identical to the same state packed from whole graphs, which is
+    itself checked against the oracle."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(61))
+    bases = [synth.shuffle_edges(rng, synth.transformer_dag(rng, 6)) for _ in range(2)]
+    edit_state, state = synth.make_edit_states(rng, bases, [30, 7])
+    model, _ = synth.make_config(2)
+    model.update(precision=precision, rounds=3)
+    w = weights_for(model)
+    enc = xrl.Encoder(model, w)
+    outs = []
+    for batch in (enc.pack(state), enc.pack_edits(edit_state)):
+        emb = enc.encode(batch, save_for_backward=True)
+        pv = enc.policy_value(batch, emb)
+        a0 = enc.get_activation(batch, "a0")
+        torch.cuda.synchronize()
+        outs.append((emb.clone(), {k: v.clone() for k, v in pv.items()}, a0.clone()))
+        batch.free()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][2], outs[1][2])
+    for k in outs[0][1]:
+        assert torch.equal(outs[0][1][k], outs[1][1][k]), k
+    enc.close()
+    run_case(xrl, model, state, w, check_inter=False)
