@@ -200,7 +200,14 @@ int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is acc
  * XRL_RESIDENT_MAX_GRAPHS (default 256; 0 = never) and XRL_RESIDENT_MAX_TILES (default 4) =
  * largest batch, in graphs and in 32-row tiles of nodes or edges per graph, that xrl_encode runs
  * as one launch with a block per graph (message-passing rounds of the MLP kind, rows of at most
- * 256 bytes, no receiver of more than 32 in-edges; results identical to the other path's). */
+ * 256 bytes, no receiver of more than 32 in-edges; results identical to the other path's);
+ * XRL_CLUSTER_MAX_GRAPHS (default 48; 0 = never) = largest batch of graphs of more tiles than
+ * that which xrl_encode runs as one launch with several blocks per graph, used when a block per
+ * four tiles of the largest graph fits the GPU at once (the few dozen candidates of one rewriting
+ * step, Section 4.2; same results). Its blocks wait for each other; XRL_CLUSTER_SPIN_LIMIT =
+ * polls after which such a wait gives up (default 2^21, about two seconds): the launch then
+ * finishes with invalid embeddings, and the next xrl_encode on the context returns XRL_ERR_HIP
+ * (once), after which the context works again. */
 int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip_stream,
                xrl_ctx **out);
 int xrl_set_weights(xrl_ctx *ctx, const float *weights_host);
@@ -211,7 +218,9 @@ int xrl_batch_upload(xrl_ctx *ctx, xrl_batch *b);
 /* ---- forward --------------------------------------------------------------------------------
  * xrl_encode: the GNN of Section 3.4 on every graph of the batch. d_emb: device [G, hidden]
  * fp32, the graph representations. save_for_backward != 0 keeps the per-round node states and
- * received sums inside ctx for xrl_encode_backward (overwritten by the next xrl_encode). */
+ * received sums inside ctx for xrl_encode_backward (overwritten by the next xrl_encode).
+ * Errors: NULL, SHAPE, OOM, HIP (also: an earlier one-launch encode on this context did not
+ * complete, see XRL_CLUSTER_SPIN_LIMIT). */
 int xrl_encode(xrl_ctx *ctx, const xrl_batch *b, float *d_emb, int save_for_backward);
 
 /* xrl_policy_value: heads of Section 3.3.2 on the embeddings. Per slot j: logit = policy MLP of

@@ -34,6 +34,12 @@ struct ResidentArgs {
   int mean;
   float *pool;
   RowMlpArgs readout;
+  // several blocks per graph (encode_cluster_kernel)
+  int K;                                 // blocks per graph
+  int G;                                 // graphs
+  unsigned *arrived;                     // [G] per-graph arrival counters, zero between launches
+  unsigned *fault;                       // host-mapped word, set when a wait gives up
+  unsigned spin_limit;                   // polls after which a wait gives up
 };
 
 // Copies `bytes` (a multiple of 16) from global memory into LDS with all 256 threads, eight
@@ -109,5 +115,114 @@ __global__ __launch_bounds__(256) void encode_resident_kernel(const ResidentArgs
     }
     __syncthreads();
   }
+  graph_readout_block<T, VEC>((const T *)ra.h[ra.rounds], n0, n1, gi, H, ra.mean, ra.pool, ra.readout, (float *)smem);
+}
+
+// ---- several blocks per graph ------------------------------------------------------------------
+// The same phases with a graph's tiles dealt over K blocks (K * G at most the number of CUs and
+// one block per CU, so every block of the launch is resident while any of them waits): tile j of a
+// phase goes to block j % K, wave (j / K) % 4. Where the one-block form has a block barrier, the
+// blocks of a graph meet at a counter in global memory: a block's waves finish their stores
+// (block barrier), one thread publishes them (release fence at device scope) and adds one to the
+// graph's counter, the block copies the next phase's weights into LDS while the others arrive,
+// the thread waits for the counter to reach K * (phases so far) and takes an acquire fence, and a
+// second block barrier lets the other waves go on. The wait is bounded: a block that is not
+// released within about two seconds reports through `fault` and goes on, so the grid always
+// drains (the results are then wrong, and the next call on the context says so).
+// Blocks b, b + 8, b + 16, ... hold one graph: the dispatcher deals consecutive blocks over the
+// eight XCDs, so a graph's rows pass from block to block through one L2 (a placement that only
+// matters for speed: the fences are device-wide).
+constexpr unsigned kClusterSpinLimit = 1u << 21;   // default of ResidentArgs::spin_limit
+
+__device__ __forceinline__ void cluster_arrive(unsigned *ctr) {
+  __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void cluster_wait(unsigned *ctr, unsigned target, unsigned *fault, unsigned spin_limit) {
+  unsigned spins = 0;
+  while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+    __builtin_amdgcn_s_sleep(2);
+    if (++spins > spin_limit) {
+      __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      break;
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+template <typename T, int H>
+__global__ __launch_bounds__(256) void encode_cluster_kernel(const ResidentArgs ra) {
+  extern __shared__ __align__(16) char smem[];
+  constexpr int VEC = 16 / (int)sizeof(T), MB = H / 32;
+  constexpr int W2_BYTES = MB * (32 / (2 * VEC)) * MB * 1024;
+  const int K = ra.K;
+  const int q = blockIdx.x >> 3;
+  const int gi = (q / K) * 8 + (blockIdx.x & 7), kb = q % K;
+  if (gi >= ra.G) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char *stage = smem + wave * RowStage<T, H>::BYTES;
+  char *w1l = smem + 4 * RowStage<T, H>::BYTES, *w2l = w1l + ra.w1_bytes_max, *tabl = w2l + W2_BYTES;
+  const int n0 = ra.graph_node_ptr[gi], n1 = ra.graph_node_ptr[gi + 1];
+  const int t0 = ra.graph_tile_ptr[gi], t1 = ra.graph_tile_ptr[gi + 1];
+  const int n_node_tiles = (n1 - n0 + 31) / 32;
+  unsigned *ctr = ra.arrived + gi;
+  unsigned met = 0;   // meetings so far
+
+  // end of a phase: publish, copy the next phase's matrices, wait for the graph's other blocks
+  auto meet = [&](const void *W1s, const void *W2s, int nslab1) {
+    __syncthreads();
+    if (threadIdx.x == 0) cluster_arrive(ctr);
+    if (W1s) {
+      fill_lds(w1l, W1s, nslab1 * MB * 1024);
+      fill_lds(w2l, W2s, W2_BYTES);
+    }
+    ++met;
+    if (threadIdx.x == 0) cluster_wait(ctr, met * (unsigned)K, ra.fault, ra.spin_limit);
+    __syncthreads();
+  };
+
+  Mlp2Args a = ra.base;
+  fill_lds(w1l, a.W1x, a.nslabx * MB * 1024);
+  fill_lds(w2l, a.W2s, W2_BYTES);
+  fill_lds(tabl, a.table, a.Tn * H * 4);
+  a.W1x = w1l; a.W2s = w2l; a.table = (const float *)tabl;
+  __syncthreads();
+  for (int j = kb + K * wave; j < n_node_tiles; j += 4 * K) {
+    const int left = n1 - n0 - 32 * j;
+    mlp2_wave_tile<float, T, H, KIND_EMBED>(a, n0 + 32 * j, left < 32 ? left : 32, 0, stage, lane);
+  }
+  a.W1s = w1l;
+  if (ra.rounds == 0 && kb != 0) {
+    __syncthreads();
+    if (threadIdx.x == 0) cluster_arrive(ctr);
+    return;
+  }
+  if (ra.rounds > 0) meet(ra.edge[0].W1s, ra.edge[0].W2s, ra.edge[0].nslab1);
+  else meet(nullptr, nullptr, 0);
+  for (int r = 0; r < ra.rounds; ++r) {
+    a.b1 = ra.edge[r].b1; a.b2 = ra.edge[r].b2; a.nslab1 = ra.edge[r].nslab1;
+    a.n_rows = ra.E; a.h = ra.h[r]; a.out = ra.agg[r];
+    for (int wt = t0 + kb + K * wave; wt < t1; wt += 4 * K) {
+      const int e0 = ra.gtile_ptr[wt];
+      mlp2_wave_tile<T, T, H, KIND_EDGE>(a, e0, ra.gtile_ptr[wt + 1] - e0, wt, stage, lane);
+    }
+    meet(ra.node[r].W1s, ra.node[r].W2s, ra.node[r].nslab1);
+    a.b1 = ra.node[r].b1; a.b2 = ra.node[r].b2; a.nslab1 = ra.node[r].nslab1;
+    a.agg = ra.agg[r]; a.out = ra.h[r + 1];
+    for (int j = kb + K * wave; j < n_node_tiles; j += 4 * K) {
+      const int left = n1 - n0 - 32 * j;
+      mlp2_wave_tile<T, T, H, KIND_NODE>(a, n0 + 32 * j, left < 32 ? left : 32, 0, stage, lane);
+    }
+    if (r + 1 == ra.rounds && kb != 0) {
+      // the graph's first block does the readout: the others only report that their rows are out
+      __syncthreads();
+      if (threadIdx.x == 0) cluster_arrive(ctr);
+      return;
+    }
+    if (r + 1 < ra.rounds) meet(ra.edge[r + 1].W1s, ra.edge[r + 1].W2s, ra.edge[r + 1].nslab1);
+    else meet(nullptr, nullptr, 0);
+  }
+  // (every block of the graph has arrived for the last time: the counter can go back to zero)
+  if (threadIdx.x == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   graph_readout_block<T, VEC>((const T *)ra.h[ra.rounds], n0, n1, gi, H, ra.mean, ra.pool, ra.readout, (float *)smem);
 }

@@ -103,6 +103,7 @@ static const char *const kTimedNames[TK_COUNT] = {"embed", "edge", "edge_fixup",
                                                   "wgrad_edge", "wgrad_node", "wgrad_embed"};
 
 constexpr int64_t kMaxFusedSlots = 4096;   // largest G the single-launch heads kernel takes
+constexpr int64_t kClusterMaxGraphs = 256; // largest G of the one-launch encoder with several blocks per graph
 
 // Scratch of xrl_policy_value_static, the entry point that allocates nothing: per-state counters,
 // the logits when the caller does not ask for them, and the per-state mean embeddings. One copy
@@ -129,6 +130,11 @@ struct xrl_ctx {
   int64_t resident_max_tiles = 0;    // ... and the most 32-row tiles (nodes, or edges) of one graph (XRL_RESIDENT_MAX_TILES)
   float *d_w = nullptr;         // flat fp32 weights
   int32_t *d_counter = nullptr; // kMaxFusedSlots per-state counters of policy_value_kernel, zero between launches
+  unsigned *d_arrived = nullptr; // kClusterMaxGraphs per-graph counters of encode_cluster_kernel, zero between launches
+  unsigned *h_fault = nullptr;   // pinned host word a kernel sets when one of its bounded waits gives up ...
+  unsigned *d_fault = nullptr;   // ... and the address kernels write it through
+  int64_t cluster_max_graphs = 0; // largest batch (graphs) for the one-launch encoder with several blocks per graph
+  unsigned cluster_spin_limit = kClusterSpinLimit;   // polls after which one of its waits gives up (XRL_CLUSTER_SPIN_LIMIT)
   int device = 0;               // the device that was current at xrl_create
   char *static_ws = nullptr;    // this device's copy of `scratch` (its device address)
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
@@ -1170,9 +1176,20 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   const bool gat = m.round_kind == XRL_ROUND_GAT;
   for (int i = 0; i < nh + nagg; ++i) acc((size_t)N * H * sizeof(T));   // (GAT: the agg slot holds z)
   const xrl_batch_device &d = b->dev;
-  const bool resident_batch = !gat && H * sizeof(T) <= 256 && d.graph_tile_ptr && R <= kResidentMaxRounds &&
-                              G <= c->resident_max_graphs && (b->max_graph_nodes + 31) / 32 <= c->resident_max_tiles &&
-                              b->max_graph_tiles <= c->resident_max_tiles;
+  const bool resident_ok = !gat && H * sizeof(T) <= 256 && d.graph_tile_ptr && R <= kResidentMaxRounds;
+  const int64_t graph_tiles = std::max<int64_t>((b->max_graph_nodes + 31) / 32, b->max_graph_tiles);
+  // blocks per graph of the one-launch encoder: one while a graph's phase is a single pass of a
+  // block's four waves; otherwise as many as give every tile of a phase a wave of its own, if
+  // that many are resident at once (at most one block per CU; graphs padded to a multiple of 8)
+  int cluster_k = 0;
+  if (resident_ok && c->resident_max_graphs > 0 && G <= c->cluster_max_graphs && G > 0 &&
+      graph_tiles > c->resident_max_tiles) {
+    const int64_t slots = c->n_cu / (8 * ((G + 7) / 8));
+    cluster_k = (int)((graph_tiles + 3) / 4);
+    if (cluster_k > slots) cluster_k = 0;   // a phase would take a second pass: the launch-per-phase path is as fast
+  }
+  const bool resident_batch = resident_ok && ((G <= c->resident_max_graphs && graph_tiles <= c->resident_max_tiles) ||
+                                              cluster_k > 0);
   // Large bf16 batches run on kernels that can keep z1 and the ReLU masks of every fused MLP for
   // the backward pass (a row of H elements and 2 H / 32 words per node or edge and MLP): kept when
   // every launch of this encode is one of them.
@@ -1281,16 +1298,23 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     const size_t w2_bytes = (size_t)MB * (32 / (2 * PV)) * MB * 1024;
     const size_t lds = std::max((size_t)4 * RowStage<T, 128>::BYTES + ra.w1_bytes_max + w2_bytes + (size_t)m.n_op_types * H * 4,
                                 (size_t)(256 * PV + 2 * dmax) * sizeof(float));
+    ra.K = cluster_k; ra.G = (int)G; ra.arrived = c->d_arrived; ra.fault = c->d_fault; ra.spin_limit = c->cluster_spin_limit;
     if (lds <= (size_t)c->max_lds) {
       Timed t(c, TK_RESIDENT);
+      const unsigned grid = cluster_k > 0 ? (unsigned)(8 * ((G + 7) / 8) * cluster_k) : (unsigned)G;
       auto launch = [&](auto kern) -> int {
         if (lds > 65536) HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        kern<<<dim3((unsigned)G), dim3(256), lds, c->stream>>>(ra);
+        kern<<<dim3(grid), dim3(256), lds, c->stream>>>(ra);
         HIP_TRY(hipGetLastError());
         return XRL_OK;
       };
-      if (H == 64) return launch(encode_resident_kernel<T, 64>);
-      if constexpr (sizeof(T) == 2) return launch(encode_resident_kernel<T, 128>);
+      if (cluster_k > 0) {   // (grid <= number of CUs and a block fits a CU: every block is resident)
+        if (H == 64) return launch(encode_cluster_kernel<T, 64>);
+        if constexpr (sizeof(T) == 2) return launch(encode_cluster_kernel<T, 128>);
+      } else {
+        if (H == 64) return launch(encode_resident_kernel<T, 64>);
+        if constexpr (sizeof(T) == 2) return launch(encode_resident_kernel<T, 128>);
+      }
     }
   }
   a.z1 = c->z1_embed; a.ymask = nullptr;
@@ -1416,6 +1440,12 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   c->resident_max_tiles = 4;
   if (const char *e = getenv("XRL_RESIDENT_MAX_GRAPHS")) c->resident_max_graphs = atoll(e);
   if (const char *e = getenv("XRL_RESIDENT_MAX_TILES")) c->resident_max_tiles = atoll(e);
+  // ... and with several blocks per graph, for the few dozen larger graphs of one rewriting step
+  // (measured, one state of 14 / 31 / 51 graphs: 338-node graphs 97 / 107 / 125 us against
+  // 120 / 122 / 125 us for a launch per phase; 565-node graphs 105 / 128 us against 120 / 127 us)
+  c->cluster_max_graphs = 48;
+  if (const char *e = getenv("XRL_CLUSTER_MAX_GRAPHS")) c->cluster_max_graphs = std::min<int64_t>(atoll(e), kClusterMaxGraphs);
+  if (const char *e = getenv("XRL_CLUSTER_SPIN_LIMIT")) c->cluster_spin_limit = (unsigned)std::max<long long>(0, std::min<long long>(atoll(e), kClusterSpinLimit));
   {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
@@ -1426,7 +1456,8 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   }
   // the weights, followed by 1 KB of zeros (16-byte aligned) that kernels read in place of absent rows
   const size_t w_bytes = align_up(sizeof(float) * L.total);
-  const size_t tail_bytes = 1024 + sizeof(int32_t) * kMaxFusedSlots;   // zero row, heads' counters
+  // zero row, heads' counters, the one-launch encoder's counters
+  const size_t tail_bytes = 1024 + sizeof(int32_t) * kMaxFusedSlots + sizeof(unsigned) * kClusterMaxGraphs;
   e = hipMalloc((void **)&c->d_w, w_bytes + tail_bytes);
   if (e != hipSuccess) {
     delete c;
@@ -1434,10 +1465,20 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   }
   c->zero_row = (char *)c->d_w + w_bytes;
   c->d_counter = (int32_t *)((char *)c->zero_row + 1024);
+  c->d_arrived = (unsigned *)(c->d_counter + kMaxFusedSlots);
   e = hipMemset(c->zero_row, 0, tail_bytes);
   if (e != hipSuccess) {
     xrl_destroy(c);
     return fail(XRL_ERR_HIP, "hipMemset: %s", hipGetErrorString(e));
+  }
+  e = hipHostMalloc((void **)&c->h_fault, sizeof(unsigned), hipHostMallocMapped);
+  if (e == hipSuccess) {
+    *c->h_fault = 0;
+    e = hipHostGetDevicePointer((void **)&c->d_fault, c->h_fault, 0);
+  }
+  if (e != hipSuccess) {
+    xrl_destroy(c);
+    return fail(XRL_ERR_HIP, "pinned status word: %s", hipGetErrorString(e));
   }
   rc = upload_weights(c, weights_host);
   if (!rc) rc = static_scratch(c->device, &c->static_ws);
@@ -1458,6 +1499,7 @@ int xrl_destroy(xrl_ctx *c) {
   if (!c) return XRL_OK;
   (void)hipStreamSynchronize(c->stream);
   if (c->d_w) (void)hipFree(c->d_w);
+  if (c->h_fault) (void)hipHostFree(c->h_fault);
   if (c->d_swz) (void)hipFree(c->d_swz);
   if (c->ws) (void)hipFree(c->ws);
   if (c->hws) (void)hipFree(c->hws);
@@ -1581,6 +1623,15 @@ int xrl_encode(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save_for_backwa
   if (rc) return rc;
   if (!d_emb && b->G > 0) return fail(XRL_ERR_NULL, "xrl_encode: d_emb is NULL");
   if (b->G == 0) return XRL_OK;
+  if (*(volatile unsigned *)c->h_fault) {
+    // an earlier one-launch encode gave up a wait between its blocks: its embeddings were wrong.
+    // Its counters are put back to zero (after everything queued so far) before anything else runs.
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipMemsetAsync(c->d_arrived, 0, sizeof(unsigned) * kClusterMaxGraphs, c->stream);
+    *c->h_fault = 0;
+    return fail(XRL_ERR_HIP, "xrl_encode: an earlier xrl_encode on this context did not complete (a wait between the "
+                             "blocks of its one-launch form ran out); its embeddings are invalid");
+  }
   return c->elem == 2 ? encode_impl<bf16_t>(c, b, d_emb, save_for_backward)
                       : encode_impl<float>(c, b, d_emb, save_for_backward);
 }

@@ -644,6 +644,96 @@ def test_one_launch_encoder_equals_streaming_path(xrl, hidden, precision, rounds
         assert torch.equal(g1, g0)
 
 
+def _encode_with_activations(xrl, model, st, w, rounds, repeats=1):
+    import torch
+    enc = xrl.Encoder(model, w)
+    enc.set_timing(True)
+    batch = enc.pack(st)
+    emb = enc.encode(batch, save_for_backward=True)
+    torch.cuda.synchronize()
+    _, launches = enc.read_timing("resident")
+    _, embed_launches = enc.read_timing("embed")
+    first = emb.clone()
+    for _ in range(repeats - 1):          # (the per-graph counters must be back at zero after every launch)
+        emb = enc.encode(batch, save_for_backward=True)
+        torch.cuda.synchronize()
+        assert torch.equal(emb, first)
+    acts = [enc.get_activation(batch, "h", r) for r in range(rounds + 1)]
+    acts += [enc.get_activation(batch, "agg", r) for r in range(1, rounds + 1)]
+    acts.append(enc.get_activation(batch, "pool"))
+    g = torch.Generator(device="cpu").manual_seed(5)
+    demb = torch.randn(emb.shape, generator=g).cuda()
+    dw = torch.zeros(enc.n_weights, dtype=torch.float32, device="cuda")
+    enc.encode_backward(batch, demb, dw)
+    torch.cuda.synchronize()
+    batch.free()
+    enc.close()
+    return first, acts, dw, launches, embed_launches
+
+
+@pytest.mark.parametrize("cfg,n_cand,hidden,precision,rounds",
+                         [(2, 13, 128, "bf16", 5), (3, 30, 128, "bf16", 5), (3, 9, 64, "fp32", 2), (2, 6, 64, "bf16", 3)])
+def test_one_launch_encoder_several_blocks_per_graph(xrl, cfg, n_cand, hidden, precision, rounds, monkeypatch):
+    """One state of a few dozen candidates of 338- and 565-node graphs (the agent's own step,
+    Section 4.2) is encoded by one launch in which several blocks share a graph and meet at a
+    counter between the phases. Same tiles and arithmetic as the launch-per-phase path:
+    embeddings, every saved activation and the gradients of the backward pass that follows are
+    bit-identical to those of a context that never uses the one-launch forms; repeated launches
+    give the same embeddings (the counters return to zero); the fp32 case also goes against the
+    oracle."""
+    import torch
+    model, state = synth.make_config(cfg, n_states=1, n_cand=n_cand)
+    model.update(hidden=hidden, precision=precision, rounds=rounds)
+    w = weights_for(model)
+    if precision == "fp32":
+        run_case(xrl, model, state, w)
+    e1, a1, g1, launches, embeds = _encode_with_activations(xrl, model, state, w, rounds, repeats=12)
+    assert launches == 1 and embeds == 0
+    monkeypatch.setenv("XRL_RESIDENT_MAX_GRAPHS", "0")
+    e0, a0, g0, launches, embeds = _encode_with_activations(xrl, model, state, w, rounds)
+    assert launches == 0 and embeds == 1
+    assert torch.equal(e1, e0)
+    for x, y in zip(a1, a0):
+        assert torch.equal(x, y)
+    if state["node_op"].shape[0] < 8192:
+        assert torch.equal(g1, g0)
+    else:
+        # (from 8192 rows on, the launch-per-phase forward keeps relu(z1) and its backward reads it;
+        # the backward after a one-launch forward recomputes it and sums the weight gradients in
+        # another order: same gradients up to bf16 rounding)
+        assert float((g1 - g0).norm() / g0.norm()) < 2e-2
+
+
+def test_one_launch_encoder_wait_that_gives_up(xrl, monkeypatch):
+    """The waits between the blocks of a graph are bounded. With the bound forced to zero polls
+    from the host, a block whose partners have not arrived yet goes on at once: the launch still
+    finishes (every access stays inside the batch's arrays), the next xrl_encode reports the
+    invalid result once, and the context then works again."""
+    import torch
+    model, state = synth.make_config(3, n_states=1, n_cand=13)
+    w = weights_for(model)
+    enc = xrl.Encoder(model, w)
+    batch = enc.pack(state)
+    good = enc.encode(batch).clone()
+    torch.cuda.synchronize()
+    enc.close()
+    monkeypatch.setenv("XRL_CLUSTER_SPIN_LIMIT", "0")
+    enc = xrl.Encoder(model, w)
+    batch = enc.pack(state)
+    enc.encode(batch)
+    torch.cuda.synchronize()
+    with pytest.raises(xrl.XrlError, match="did not complete"):
+        enc.encode(batch)
+    monkeypatch.delenv("XRL_CLUSTER_SPIN_LIMIT")
+    enc2 = xrl.Encoder(model, w)            # (the limit is read when a context is made)
+    batch2 = enc2.pack(state)
+    again = enc2.encode(batch2)
+    torch.cuda.synchronize()
+    assert torch.equal(again, good)
+    batch.free(); batch2.free()
+    enc.close(); enc2.close()
+
+
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_states_packed_from_edits(xrl, precision):
     """A state whose candidates are given as edits of the current graph (xrl_pack_state_edits; the
