@@ -59,7 +59,7 @@ typedef struct xrl_model_desc {
   int32_t d_global;       /* global attribute width (initialised to 0 by the paper)           */
   int32_t hidden;         /* H: 64, 128 or 256                                                */
   int32_t rounds;         /* number of message-passing layers, >= 0                           */
-  int32_t mlp_layers;     /* affine layers per encoder transform; the GPU path supports 2     */
+  int32_t mlp_layers;     /* affine layers per encoder transform; the GPU path supports 1, 2  */
   int32_t head_hidden[2];
   int32_t readout;        /* XRL_READOUT_SUM (the paper's sum) or XRL_READOUT_MEAN            */
   int32_t precision;      /* XRL_PREC_FP32 or XRL_PREC_BF16                                   */
@@ -192,7 +192,10 @@ int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is acc
 
 /* ---- context --------------------------------------------------------------------------------
  * weights_host: xrl_weight_count floats. hip_stream: a hipStream_t (NULL = default stream).
- * Errors: NULL, UNSUPPORTED (hidden not in {64,128,256}, mlp_layers != 2, ...), VALUE, HIP, OOM.
+ * Errors: NULL, UNSUPPORTED (hidden not in {64,128,256}, mlp_layers not 1 or 2, ...), VALUE, HIP, OOM.
+ * mlp_layers = 1 (one learned matrix per layer, Section 3.4 as printed) runs on the two-layer kernels
+ * with an identity second layer, which changes no result; weights and gradients keep the one-layer
+ * layout of xrl_weight_tensor.
  * Environment, read here: XRL_PERSISTENT_MIN_ROWS = row count from which the persistent MLP
  * kernels replace the streaming one (default 8192; 0 = always; results agree within rounding);
  * XRL_WGRAD_WIDE_MIN_ROWS = row count from which the weight-gradient kernel uses 256-column

@@ -133,6 +133,16 @@ struct xrl_ctx {
   unsigned *d_arrived = nullptr; // kClusterMaxGraphs per-graph counters of encode_cluster_kernel, zero between launches
   unsigned *h_fault = nullptr;   // pinned host word a kernel sets when one of its bounded waits gives up ...
   unsigned *d_fault = nullptr;   // ... and the address kernels write it through
+  // mlp_layers = 1 (the layers of Section 3.4 exactly as printed: one learned matrix each) runs on the
+  // two-layer kernels: the context's own model and layout (m, L) have a second layer whose matrix
+  // is the identity and whose bias is zero -- relu(relu(z) I + 0) = relu(z) exactly, in both
+  // precisions -- and the caller's one-layer vector is spread into that layout on upload. The
+  // backward passes run on an internal gradient vector whose real tensors are then added to the
+  // caller's (the identity layers' gradients are dropped).
+  bool single_layer = false;
+  Layout Lu;                      // the caller's layout (single_layer)
+  float *d_dw_int = nullptr;      // [L.total] internal gradient vector (single_layer)
+  int32_t *d_wmap = nullptr;      // [Lu.total] index in the internal vector of each of the caller's weights
   int64_t cluster_max_graphs = 0; // largest batch (graphs) for the one-launch encoder with several blocks per graph
   unsigned cluster_spin_limit = kClusterSpinLimit;   // polls after which one of its waits gives up (XRL_CLUSTER_SPIN_LIMIT)
   int device = 0;               // the device that was current at xrl_create
@@ -221,10 +231,36 @@ extern "C" void xrl_batch_release_device(xrl_batch *b) {
 
 namespace {
 
-int upload_weights(xrl_ctx *c, const float *w) {
+// Internal index of the first element of the caller's tensor `t` (single-layer contexts): the tensor of
+// the same name in the internal layout.
+int64_t internal_offset(const xrl_ctx *c, const WeightTensor &t) {
+  for (const WeightTensor &u : c->L.tensors)
+    if (u.name == t.name) return u.offset;
+  return -1;
+}
+
+int upload_weights(xrl_ctx *c, const float *w_user) {
   const xrl_model_desc &m = c->m;
-  for (int64_t i = 0; i < c->L.total; ++i)
-    if (!std::isfinite(w[i])) return fail(XRL_ERR_VALUE, "weights[%lld] is not finite", (long long)i);
+  const int64_t n_user = c->single_layer ? c->Lu.total : c->L.total;
+  for (int64_t i = 0; i < n_user; ++i)
+    if (!std::isfinite(w_user[i])) return fail(XRL_ERR_VALUE, "weights[%lld] is not finite", (long long)i);
+  std::vector<float> spread;
+  if (c->single_layer) {
+    spread.assign((size_t)c->L.total, 0.f);
+    for (const WeightTensor &t : c->Lu.tensors) {
+      const int64_t n = t.cols > 0 ? t.rows * t.cols : t.rows;
+      memcpy(spread.data() + internal_offset(c, t), w_user + t.offset, sizeof(float) * (size_t)n);
+    }
+    const int H = m.hidden;
+    auto identity = [&](const MlpRef &r) {
+      for (int k = 0; k < H; ++k) spread[(size_t)r.w[1] + (size_t)k * H + k] = 1.f;
+    };
+    identity(c->L.embed);
+    identity(c->L.readout);
+    for (const MlpRef &r : c->L.edge) identity(r);
+    for (const MlpRef &r : c->L.node) identity(r);
+  }
+  const float *w = c->single_layer ? spread.data() : w_user;
   const int V = c->elem == 2 ? 8 : 4, H = m.hidden;
   // build the fragment-ordered blob on the host
   std::vector<char> blob;
@@ -685,7 +721,13 @@ int launch_heads(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *logi
     const RowMlpArgs pa = rowmlp_args(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, pact);
     policy_value_kernel<<<dim3((unsigned)(b->G + b->S)), dim3(256), 0, c->stream>>>(
         pa, d.mask, d.state_graph_ptr, (int)b->G, (int)b->S, H, c->d_counter, logp, entropy, action, zmean, va);
-    HIP_TRY(hipGetLastError());
+    const hipError_t le = hipGetLastError();
+    if (le != hipSuccess) {
+      // (a launch that the runtime rejected has not run; one that failed later may have left
+      // counters of unfinished states above zero: they go back to zero before the next use)
+      (void)hipMemsetAsync(c->d_counter, 0, sizeof(int32_t) * kMaxFusedSlots, c->stream);
+      return fail(XRL_ERR_HIP, "policy_value_kernel: %s", hipGetErrorString(le));
+    }
     return XRL_OK;
   }
   int rc = launch_rowmlp(c, c->L.policy, false, d_emb, H, nullptr, 0, b->G, logit, pact);
@@ -1404,13 +1446,18 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
                xrl_ctx **out) {
   if (!model || !weights_host || !out) return fail(XRL_ERR_NULL, "xrl_create: NULL argument");
   *out = nullptr;
-  Layout L;
-  int rc = build_layout(*model, L);
+  Layout L, Lu;
+  int rc = build_layout(*model, Lu);
   if (rc) return rc;
   if (model->hidden != 64 && model->hidden != 128 && model->hidden != 256)
     return fail(XRL_ERR_UNSUPPORTED, "hidden = %d: the kernels cover 64, 128 and 256", model->hidden);
-  if (model->mlp_layers != 2)
-    return fail(XRL_ERR_UNSUPPORTED, "mlp_layers = %d: the kernels cover 2", model->mlp_layers);
+  if (model->mlp_layers != 1 && model->mlp_layers != 2)
+    return fail(XRL_ERR_UNSUPPORTED, "mlp_layers = %d: the kernels cover 1 and 2", model->mlp_layers);
+  xrl_model_desc model_int = *model;
+  model_int.mlp_layers = 2;
+  if ((rc = build_layout(model_int, L))) return rc;
+  const bool single_layer = model->mlp_layers == 1;
+  model = &model_int;
   if (model->d_edge % 4 != 0)
     return fail(XRL_ERR_UNSUPPORTED, "d_edge = %d: the kernels need a multiple of 4", model->d_edge);
   if (model->head_hidden[0] > 512 || model->head_hidden[1] > 512 || model->d_global > 256 ||
@@ -1426,6 +1473,8 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   if (!c) return fail(XRL_ERR_OOM, "xrl_create: out of host memory");
   c->m = *model;
   c->L = L;
+  c->single_layer = single_layer;
+  if (single_layer) c->Lu = Lu;
   c->stream = (hipStream_t)hip_stream;
   c->elem = model->precision == XRL_PREC_BF16 ? 2 : 4;
   // Row count from which the persistent kernels replace the streaming one (tuning knob; the
@@ -1481,6 +1530,17 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
     return fail(XRL_ERR_HIP, "pinned status word: %s", hipGetErrorString(e));
   }
   rc = upload_weights(c, weights_host);
+  if (!rc && c->single_layer) {
+    std::vector<int32_t> wmap((size_t)c->Lu.total);
+    for (const WeightTensor &t : c->Lu.tensors) {
+      const int64_t n = t.cols > 0 ? t.rows * t.cols : t.rows, o = internal_offset(c, t);
+      for (int64_t i = 0; i < n; ++i) wmap[(size_t)(t.offset + i)] = (int32_t)(o + i);
+    }
+    e = hipMalloc((void **)&c->d_dw_int, sizeof(float) * (size_t)c->L.total);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_wmap, sizeof(int32_t) * wmap.size());
+    if (e == hipSuccess) e = hipMemcpy(c->d_wmap, wmap.data(), sizeof(int32_t) * wmap.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) rc = fail(XRL_ERR_OOM, "internal gradient vector: %s", hipGetErrorString(e));
+  }
   if (!rc) rc = static_scratch(c->device, &c->static_ws);
   if (rc) {
     xrl_destroy(c);
@@ -1500,6 +1560,8 @@ int xrl_destroy(xrl_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   if (c->d_w) (void)hipFree(c->d_w);
   if (c->h_fault) (void)hipHostFree(c->h_fault);
+  if (c->d_dw_int) (void)hipFree(c->d_dw_int);
+  if (c->d_wmap) (void)hipFree(c->d_wmap);
   if (c->d_swz) (void)hipFree(c->d_swz);
   if (c->ws) (void)hipFree(c->ws);
   if (c->hws) (void)hipFree(c->hws);
@@ -1699,6 +1761,38 @@ int xrl_ppo_objective(xrl_ctx *c, const xrl_batch *b, const float *d_logp, const
   return XRL_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// user[i] += internal[map[i]]: the real tensors of a single-layer context's internal gradient vector,
+// added to the caller's
+__global__ void add_mapped_kernel(float *user, const float *internal, const int32_t *map, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) user[i] += internal[map[i]];
+}
+
+// Runs a backward pass that adds weight gradients into a vector of the context's own layout: the
+// caller's vector itself, or (single-layer contexts) the internal one, zeroed first and folded
+// into the caller's afterwards.
+template <typename Run>
+int with_weight_gradients(xrl_ctx *c, float *d_dweights, Run run) {
+  if (!c->single_layer) return run(d_dweights);
+  const int64_t n = c->L.total, nu = c->Lu.total;
+  fill_zero_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream>>>(c->d_dw_int, n);
+  HIP_TRY(hipGetLastError());
+  const int rc = run(c->d_dw_int);
+  if (rc) return rc;
+  add_mapped_kernel<<<dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, c->stream>>>(d_dweights, c->d_dw_int, c->d_wmap, nu);
+  HIP_TRY(hipGetLastError());
+  return XRL_OK;
+}
+
+int policy_value_backward_run(xrl_ctx *c, const xrl_batch *b, const float *d_emb, const float *d_dlogp,
+                              const float *d_dvalue, const float *d_dentropy, float *d_demb, float *d_dweights);
+}  // namespace
+
+extern "C" {
+
 int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb,
                               const float *d_dlogp, const float *d_dvalue,
                               const float *d_dentropy, float *d_demb, float *d_dweights) {
@@ -1707,6 +1801,17 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   if (b->S == 0) return XRL_OK;
   if (!d_emb || !d_dlogp || !d_dvalue || !d_dentropy || !d_demb || !d_dweights)
     return fail(XRL_ERR_NULL, "xrl_policy_value_backward: NULL device pointer");
+  return with_weight_gradients(c, d_dweights, [&](float *dw) {
+    return policy_value_backward_run(c, b, d_emb, d_dlogp, d_dvalue, d_dentropy, d_demb, dw);
+  });
+}
+
+}  // extern "C"
+
+namespace {
+int policy_value_backward_run(xrl_ctx *c, const xrl_batch *b, const float *d_emb, const float *d_dlogp,
+                              const float *d_dvalue, const float *d_dentropy, float *d_demb, float *d_dweights) {
+  int rc = XRL_OK;
   if ((uintptr_t)d_emb & 15)
     return fail(XRL_ERR_SHAPE, "xrl_policy_value_backward: d_emb must be 16-byte aligned");
   const int H = c->m.hidden, h0 = c->m.head_hidden[0], h1 = c->m.head_hidden[1];
@@ -1749,6 +1854,9 @@ int xrl_policy_value_backward(xrl_ctx *c, const xrl_batch *b, const float *d_emb
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
+}  // namespace
+
+extern "C" {
 
 int xrl_encode_backward(xrl_ctx *c, const xrl_batch *b, const float *d_demb, float *d_dweights) {
   int rc = check_batch(c, b, "xrl_encode_backward");
@@ -1757,8 +1865,9 @@ int xrl_encode_backward(xrl_ctx *c, const xrl_batch *b, const float *d_demb, flo
   if (!d_demb || !d_dweights) return fail(XRL_ERR_NULL, "xrl_encode_backward: NULL device pointer");
   if (!c->enc_saved || c->enc_batch != b->id)
     return fail(XRL_ERR_STATE, "xrl_encode_backward: the batch's last xrl_encode did not save for backward");
-  return c->elem == 2 ? encode_backward_impl<bf16_t>(c, b, d_demb, d_dweights)
-                      : encode_backward_impl<float>(c, b, d_demb, d_dweights);
+  return with_weight_gradients(c, d_dweights, [&](float *dw) {
+    return c->elem == 2 ? encode_backward_impl<bf16_t>(c, b, d_demb, dw) : encode_backward_impl<float>(c, b, d_demb, dw);
+  });
 }
 
 int xrl_set_timing(xrl_ctx *c, int enabled) {

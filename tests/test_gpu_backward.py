@@ -201,6 +201,20 @@ def test_backward_paper_feature_dimensions(xrl, precision):
     run_backward_case(xrl, model, state, weights_for(model))
 
 
+@pytest.mark.parametrize("round_kind,cfg,hidden,precision", [("gat", 1, 64, "fp32"), ("gat", 2, 128, "bf16"),
+                                                             ("mlp", 1, 64, "fp32"), ("mlp", 2, 128, "bf16"),
+                                                             ("mlp", 4, 256, "bf16")])
+def test_backward_single_learned_matrix_per_layer(xrl, round_kind, cfg, hidden, precision):
+    """mlp_layers = 1 (Section 3.4's layers with their single learned matrix; with graph-attention
+    rounds the network as printed): gradients of every tensor of the one-layer layout against the
+    oracle's reverse mode, criteria of the two-layer cases. The library differentiates its
+    two-layer kernels with an identity second layer and drops that layer's gradient."""
+    model, state = synth.make_config(cfg, n_cand=12 if cfg != 1 else None)
+    model.update(hidden=hidden, precision=precision, rounds=2, round_kind=round_kind, mlp_layers=1)
+    gat = round_kind == "gat"
+    run_backward_case(xrl, model, state, weights_for(model), bf16_rel=0.3 if gat else 0.15, bf16_cos=0.95 if gat else 0.98)
+
+
 @pytest.mark.parametrize("hidden", [128, 256])
 def test_backward_wide_weight_gradient_tiles(xrl, hidden, monkeypatch):
     """The 256-column tiles of the weight-gradient kernel (used from 2^20 rows on) forced onto a

@@ -89,7 +89,12 @@ def check_heads_against_oracle(pv, rp, state, prec, what=""):
     # a head's output is a sum of terms that may cancel (a state's value can lie near zero), so
     # the absolute term is taken at the scale of the heads' outputs in this batch, as for logp
     assert_close(pv["value"], rp["value"], prec, what + "value", scale=lscale)
-    assert_close(pv["entropy"], rp["entropy"], prec, what + "entropy")
+    # entropy = -sum p logp: an error d in logp changes it by at most d sum p |logp| = d * entropy
+    # (the changes of p sum to zero), and logp is held to an absolute error of rtol * lscale above, so
+    # the entropy's relative term is that of the path times max(1, lscale)
+    ert, eat = tol(prec, rp["entropy"])
+    eerr = np.abs(pv["entropy"].astype(np.float64) - rp["entropy"]) - (eat + ert * max(1.0, lscale) * np.abs(rp["entropy"]) + 1e-30)   # (+ fp32 underflow)
+    assert eerr.size == 0 or eerr.max() <= 0, f"{what}entropy: {(eerr > 0).sum()}/{eerr.size} outside tolerance (logit scale {lscale:.3g})"
     near_ties = 0
     for s in range(len(sgp) - 1):
         j0, j1 = sgp[s], sgp[s + 1]
@@ -388,6 +393,41 @@ def test_paper_feature_dimensions(xrl, hidden, precision):
     state["graph_global"] = np.zeros((len(state["slot_mask"]), model["d_global"]), np.float32)
     np.testing.assert_array_equal(state["edge_feat"], O.edge_features_from_shapes(shapes).astype(np.float32))
     run_case(xrl, model, state, weights_for(model))
+
+
+def paper_feature_state(xrl, model, state, seed=31):
+    """`state` with the state description the paper prints (Section 3.3.2): operator type one-hot
+    only, edge attribute = tensor shape over M = 4096 from the library's featuriser, zero global
+    attribute. `model` must have n_op_types = 40, n_node_dense = 0, d_edge = 4."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    E, N = len(state["edge_src"]), len(state["node_op"])
+    extents = np.array([1, 3, 12, 64, 128, 197, 256, 768, 1000, 3072])
+    shapes = [list(rng.choice(extents, size=int(rng.integers(1, 5)))) for _ in range(E)]
+    return dict(state, node_op=rng.integers(0, 40, N).astype(np.int32), node_dense=np.zeros((N, 0), np.float32),
+                edge_feat=xrl.edge_features_from_shapes(shapes),
+                graph_global=np.zeros((len(state["slot_mask"]), model["d_global"]), np.float32))
+
+
+@pytest.mark.parametrize("round_kind,hidden,precision", [("gat", 64, "fp32"), ("gat", 128, "bf16"), ("gat", 256, "bf16"),
+                                                         ("mlp", 64, "fp32"), ("mlp", 128, "bf16"), ("mlp", 256, "bf16")])
+def test_single_learned_matrix_per_layer(xrl, round_kind, hidden, precision):
+    """mlp_layers = 1: the node-update and global-update layers with the single learned matrix of
+    Section 3.4's equations -- with graph-attention rounds and the printed state description this
+    is the network as the paper prints it, end to end -- and, with MLP rounds, single-matrix
+    message and update functions. The library runs them on its two-layer kernels with an identity
+    second layer, which is exact, so the criteria are those of the two-layer cases. A ragged batch
+    and (fp32) a batch with a receiver of in-degree 300, zero-edge, single-node and empty graphs."""
+    model, state = synth.make_config(4, n_cand=4)
+    model.update(hidden=hidden, precision=precision, rounds=3, round_kind=round_kind, mlp_layers=1,
+                 n_op_types=40, n_node_dense=0, d_edge=4)
+    run_case(xrl, model, paper_feature_state(xrl, model, state), weights_for(model))
+    if precision == "fp32":
+        # (bf16: sums over 300 in-edges with a single matrix and no second layer's bias take the node
+        # states outside the range the bf16 criterion was derived for)
+        model, state = synth.make_config(1)
+        model.update(hidden=hidden, precision=precision, rounds=2, round_kind=round_kind, mlp_layers=1)
+        rng = np.random.Generator(np.random.PCG64(5))
+        run_case(xrl, model, hub_state(rng, model, 300), weights_for(model, seed=12))
 
 
 def heads_only_state(rng, model, n_states, n_cand, fixed=False):

@@ -219,7 +219,7 @@ def test_device_calls_fail_cleanly_without_gpu_or_upload():
     assert lib.xrl_create(None, None, None, None) == xrl.ERR["NULL"]
     w = np.zeros(xrl.weight_count(model), np.float32)
     h = C.c_void_p()
-    for kw in (dict(hidden=96), dict(mlp_layers=1)):
+    for kw in (dict(hidden=96), dict(mlp_layers=3)):
         md = xrl.model_desc(base_model(**kw))
         w2 = np.zeros(xrl.weight_count(base_model(**kw)), np.float32)
         assert lib.xrl_create(C.byref(md), w2.ctypes.data, None, C.byref(h)) == xrl.ERR["UNSUPPORTED"]
