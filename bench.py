@@ -235,8 +235,8 @@ def main():
     n_recv = int((np.diff(hv["in_ptr"]) > 0).sum())
     n_tiles = len(hv["tile_ptr"]) - 1
     Tn = model["n_op_types"]
-    # Large bf16 batches run on the forward kernels that keep relu(z1) (and the edge MLP's output
-    # mask bits) for the backward pass, and on the backward kernels that start from them.
+    # Large bf16 batches run on the forward kernels that keep relu(z1) and the ReLU mask bits of z1
+    # and y for the backward pass, and on the backward kernels that start from the bits.
     kept = (backward and bf16 and args.round_kind == "mlp" and kern["resident"]["launches_per_step"] == 0
             and min(N, E) >= int(os.environ.get("XRL_PERSISTENT_MIN_ROWS", 8192)))
     zk = 1 if kept else 0
@@ -247,14 +247,16 @@ def main():
     # matrix cores.
     NH, EH = N * H * b, E * H * b
     idx_e = 4 * (2 * E + n_tiles)
+    # the kept forward's mask bits of one MLP's z1 or y: 16 bits per lane, 32-feature block and wave tile
+    mask_e, mask_n = n_tiles * (H // 32) * 128, ((N + 31) // 32) * (H // 32) * 128
     work = {
         "embed": dict(kernel="node-update layer: sum of incoming edge attributes + embed MLP",
                       flops=2.0 * N * H * (De + Dd + H),
-                      bytes=E * De * 4 + N * (4 + 4 * Dd) + 4 * (N + 1) + NH * (1 + zk)),
+                      bytes=E * De * 4 + N * (4 + 4 * Dd) + 4 * (N + 1) + NH * (1 + zk) + zk * 2 * mask_n),
         "edge": dict(kernel="edge MLP + per-receiver sum (one launch per round)",
                      flops=2.0 * E * H * (3 * H + De),
-                     bytes=NH + E * De * 4 + idx_e + n_recv * H * b + zk * (EH + n_tiles * (H // 32) * 128)),
-        "node": dict(kernel="node MLP (one launch per round)", flops=2.0 * N * H * 3 * H, bytes=(3 + zk) * NH),
+                     bytes=NH + E * De * 4 + idx_e + n_recv * H * b + zk * (EH + 2 * mask_e)),
+        "node": dict(kernel="node MLP (one launch per round)", flops=2.0 * N * H * 3 * H, bytes=(3 + zk) * NH + zk * 2 * mask_n),
         "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", flops=0.0,
                      bytes=NH + 4 * (G + 1) + G * H * 4),
         "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", flops=0.0,
@@ -264,10 +266,11 @@ def main():
         work.update({
             "bwd_edge": dict(kernel="backward through the edge MLP from the kept forward (one launch per round)",
                              flops=2.0 * E * H * 3 * H,
-                             bytes=n_recv * H * b + EH + n_tiles * (H // 32) * 128 + 4 * (E + n_tiles) + 3 * EH + n_recv * H * b),
+                             bytes=n_recv * H * b + 2 * mask_e + 4 * (E + n_tiles) + 3 * EH + n_recv * H * b),
             "bwd_node": dict(kernel="backward through the node MLP from the kept forward (one launch per round)",
-                             flops=2.0 * N * H * 3 * H, bytes=7 * NH),
-            "bwd_embed": dict(kernel="backward through the embed MLP from the kept forward", flops=2.0 * N * H * H, bytes=5 * NH),
+                             flops=2.0 * N * H * 3 * H, bytes=5 * NH + 2 * mask_n),
+            "bwd_embed": dict(kernel="backward through the embed MLP from the kept forward", flops=2.0 * N * H * H,
+                              bytes=3 * NH + 2 * mask_n),
             "wgrad_edge": dict(kernel="weight gradients of one edge MLP, both layers",
                                flops=2.0 * E * H * (3 * H + De + 2), bytes=NH + 4 * EH + E * De * 4 + 8 * E),
             "wgrad_node": dict(kernel="weight gradients of one node MLP, both layers",

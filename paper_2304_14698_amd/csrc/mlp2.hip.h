@@ -44,9 +44,11 @@ struct Mlp2Args {
   int n_agg;               //        the message kernels never write
   void *out;               // [N, H] operand type
   void *z1;                // kernels instantiated to keep the forward for the backward pass: the hidden
-  uint16_t *ymask;         //   activation relu(z1) [rows, H] operand type and, EDGE (whose per-edge output is
-                           //   not stored), the ReLU mask of y: [n_tiles][H / 32][64 lanes] words, bit r of
-                           //   lane l = accumulator register r of that lane (its edge, its feature block) > 0
+  uint16_t *z1mask;        //   activation relu(z1) [rows, H] operand type (an operand of the weight gradient)
+  uint16_t *ymask;         //   and the ReLU masks of z1 and of y, which is all the backward through the MLP
+                           //   needs of the forward: [tiles][H / 32][64 lanes] words, bit r of lane l =
+                           //   accumulator register r of that lane (its row, its feature block) > 0. Tiles are
+                           //   the kernel's wave tiles: edge tiles, or 32 consecutive nodes
   float *carry;            // [n_tiles, 2, H]                (EDGE)
   const int32_t *tile_ptr; // [n_tiles + 1] first edge of each edge tile (EDGE)
   int64_t n_tiles;         //                                (EDGE)

@@ -1,18 +1,18 @@
 // Backward of the fused two-layer ReLU MLPs from what the forward pass kept (Section 3.3.4: one
 // back-propagation through the GNN of Section 3.4), bf16, for the batches whose forward kernels
-// store the hidden activation relu(z1) [rows, H] (and, for the edge MLP, whose per-edge output y is
-// never stored, the mask bits of y > 0). With them the backward needs no forward arithmetic at
-// all and no gathered input rows:
+// store the ReLU masks of the hidden pre-activation z1 and of the output y as bits (16 per lane,
+// 32-feature block and wave tile) next to the hidden activation relu(z1) [rows, H] that the weight
+// gradient needs. With the bits the backward needs no forward arithmetic, no gathered input rows
+// and no activation rows at all:
 //     dz2 = dy * [y > 0],  dz1 = (dz2 W2^T) * [z1 > 0],  dx = dz1 W1^T
-// [y > 0] comes from the stored output (NODE: the next node states, EMBED: the first) or from the
-// kept mask bits (EDGE), [z1 > 0] from the kept relu(z1). dz2 and dz1 are stored for the
-// weight-gradient kernel, which reads z1 from the forward's copy. Everything is kept transposed
+// dz2 and dz1 are stored for the weight-gradient kernel, which reads relu(z1) from the forward's
+// copy. Everything is kept transposed
 // (features x rows: lane = row, registers = features), each result already laid out as the next
 // contraction's B operand, as in mlp2_bwd_kernel; the three live tiles of that kernel (z1, dz2,
 // dz1) shrink to two, which lets eight waves share a compute unit at H = 256. The weights go
 // through the same double-buffered LDS groups, fetched once per block of NW waves. A wave's tile
-// is 32 consecutive rows; for EDGE it is an edge tile of the packer (at most 32 edges), because
-// the kept mask bits are per tile and lane of the forward kernel. Those tiles are cut at receiver
+// is the forward kernel's wave tile, because the mask bits are per tile and lane of that kernel: 32
+// consecutive nodes, or for EDGE an edge tile of the packer (at most 32 edges). Those tiles are cut at receiver
 // boundaries, so with FOLD (batches in which no receiver has more than 32 in-edges) the gradients
 // w.r.t. h_receiver are summed per receiver across the lanes of the tile, as the forward sums the
 // messages, and leave as one row per receiver instead of one per edge.
@@ -23,9 +23,8 @@ struct Mlp2BwdzArgs {
   int64_t n_rows, n_blocks;
   const void *W2bt, *W1bt;     // contraction over the weight's columns (see swizzle_chain)
   const void *dy;              // upstream gradient [N, H] bf16 (EDGE: indexed by receiver)
-  const void *z1;              // relu(z1) [rows, H] bf16, kept by the forward
-  const void *y;               // the forward's output [N, H] bf16 (NODE, EMBED)
-  const uint16_t *ymask;       // EDGE: [n_tiles][H / 32][64] mask bits of y (see Mlp2Args)
+  const uint16_t *z1mask;      // [tiles][H / 32][64] mask bits of z1 and of y, kept by the forward (see
+  const uint16_t *ymask;       //   Mlp2Args); tiles = the edge tiles (EDGE), else 32 consecutive rows
   const int32_t *in_dst;       // [E] (EDGE)
   const int32_t *tile_ptr;     // [n_tiles + 1] (EDGE)
   int64_t n_tiles;             // (EDGE)
@@ -78,88 +77,107 @@ struct BwdzShape {
   static constexpr size_t LDS = (size_t)NW * BlockStage<bf16_t>::BYTES + 2 * (size_t)(UF * UG) * 1024;
 };
 
+// One block per group of NW tiles, one tile per wave. (A persistent form -- as many blocks as are
+// resident at once, each looping over its share with the next group's mask bits and dy rows
+// requested a product ahead -- measured slower: 11.5 against 9.9 ms for the node MLP of the largest
+// configuration.)
 template <int H, int KIND, bool FOLD>
 __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(const Mlp2BwdzArgs a) {
   static_assert(!FOLD || KIND == KIND_EDGE, "only the edge MLP's receiver-side gradients are summed");
   using T = bf16_t;
   using S = BwdzShape<H>;
+  using BS = BlockStage<T>;
   constexpr int MB = S::MB, QB = S::QB, UF = S::UF, UG = S::UG, NW = S::NW;
   using WG = WeightGroupsN<UF, UG, NW>;
   const int64_t per_xcd = (a.n_blocks + 7) / 8;
   const int64_t tile = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (tile >= a.n_blocks) return;                             // (the whole block)
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, g = lane >> 5;
-  int64_t wt = tile * NW + wave;                              // this wave's tile
+  const int lane = threadIdx.x & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  extern __shared__ __align__(16) char smem[];
+  char *stage = smem + wave * BS::BYTES;
+  WG wg;
+  wg.buf = reinterpret_cast<f32x4 (*)[WG::GF][64]>(smem + NW * BS::BYTES);
+  wg.wave = wave; wg.lane = lane;
+
+  // this wave's tile: waves past the last tile take the last one and store nothing (they still
+  // meet the barriers, and their mask reads stay inside the arrays)
+  const int64_t n_wt = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;
+  int64_t wt = tile * NW + wave;
+  const bool none = wt >= n_wt;
+  if (none) wt = n_wt - 1;
   int64_t row0;
   int n_valid;
   if constexpr (KIND == KIND_EDGE) {
-    const bool none = wt >= a.n_tiles;                        // (waves past the last tile still meet the barriers)
-    if (none) wt = a.n_tiles - 1;
     row0 = a.tile_ptr[wt];
     n_valid = none ? 0 : a.tile_ptr[wt + 1] - (int)row0;
   } else {
     row0 = wt * 32;
     const int64_t left = a.n_rows - row0;
-    n_valid = left < 32 ? (left > 0 ? (int)left : 0) : 32;
+    n_valid = none ? 0 : (left < 32 ? (int)left : 32);
   }
   int64_t row = row0 + l32;
   if (row >= a.n_rows) row = a.n_rows - 1;                    // clamp loads; stores are guarded
-  extern __shared__ __align__(16) char smem[];
-  char *stage = smem + wave * BlockStage<T>::BYTES;
-  WG wg;
-  wg.buf = reinterpret_cast<f32x4 (*)[WG::GF][64]>(smem + NW * BlockStage<T>::BYTES);
-  wg.wave = wave; wg.lane = lane;
-
-  // one 32-feature block of this lane's row of a row-major [rows, H] array, in accumulator order
-  auto load_block = [&](const T *rowp, int nb, f32x16 &d) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float v[4];
-      load4<T>(rowp + 32 * nb + 8 * q, v);
-      d[4 * q] = v[0]; d[4 * q + 1] = v[1]; d[4 * q + 2] = v[2]; d[4 * q + 3] = v[3];
-    }
-  };
-
-  // ---------------- dz2^T = dy^T * [y^T > 0], stored and kept as operand slabs
-  bf16x8 dz2s[MB][QB];
+  int drow = (int)row;                                        // the row of dy this lane's row reads: itself, or its receiver
+  if constexpr (KIND == KIND_EDGE) drow = a.in_dst[row];
   [[maybe_unused]] int fold_rem = 0, fold_dsel = -1;          // FOLD: edges after this one with its receiver; row of the total
-  {
-    int64_t drow = row;
-    if constexpr (KIND == KIND_EDGE) drow = a.in_dst[row];
-    if constexpr (FOLD) {
-      const bool valid = l32 < n_valid;
-      const int dst = (int)drow, up = __shfl_up(dst, 1);      // lane 32 reads lane 31, but is a head anyway
-      const bool head = valid && (l32 == 0 || up != dst);
-      const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << n_valid);
-      fold_rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
-      fold_dsel = head ? dst : -1;
-    }
-    const T *dyrow = (const T *)a.dy + (size_t)drow * H + 4 * g;
-    [[maybe_unused]] const T *yrow = KIND == KIND_EDGE ? nullptr : (const T *)a.y + (size_t)row * H + 4 * g;
-    [[maybe_unused]] uint32_t ym[MB];
-    if constexpr (KIND == KIND_EDGE) {
+  if constexpr (FOLD) {
+    const bool valid = l32 < n_valid;
+    const int up = __shfl_up(drow, 1);                        // lane 32 reads lane 31, but is a head anyway
+    const bool head = valid && (l32 == 0 || up != drow);
+    const uint64_t heads = ((uint64_t)(uint32_t)__ballot(head)) | ((uint64_t)1 << n_valid);
+    fold_rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
+    fold_dsel = head ? drow : -1;
+  }
+  // mask bits of y (low half) and z1 (high half) of this lane's row, per 32-feature block
+  uint32_t yz[MB];
 #pragma unroll
-      for (int nb = 0; nb < MB; ++nb) ym[nb] = a.ymask[((size_t)wt * MB + nb) * 64 + lane];
+  for (int nb = 0; nb < MB; ++nb) {
+    const uint32_t y = a.ymask[((size_t)wt * MB + nb) * 64 + lane];
+    const uint32_t z = a.z1mask[((size_t)wt * MB + nb) * 64 + lane];
+    yz[nb] = y | (z << 16);
+  }
+
+  // ---------------- dz2^T = dy^T * [y^T > 0], stored and kept as operand slabs.
+  // The tile's dy rows are read as whole 64-byte pieces (four lanes per row, sixteen rows per
+  // instruction: read with lane = row directly, every load instruction would touch 64 different
+  // cache lines for 8 bytes each) and turned into the accumulator layout (lane = row) through the
+  // wave's staging buffer. All of it is requested first and transposed before the first store: a
+  // wait for a load that follows stores also waits for those stores to be acknowledged (one
+  // counter, in order), which would put a memory round trip into every block.
+  bf16x8 dz2s[MB][QB];
+  {
+    bf16x4 dyq[MB][4];
+    {
+      f32x4 raw[MB][32 / BS::RPI];
+#pragma unroll
+      for (int k = 0; k < 32 / BS::RPI; ++k) {
+        const int src = __shfl(drow, k * BS::RPI + lane / BS::LPR);
+        const char *p = (const char *)((const T *)a.dy + (size_t)src * H) + (lane % BS::LPR) * 16;
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb) raw[nb][k] = *(const f32x4 *)(p + 64 * nb);
+      }
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) {
+#pragma unroll
+        for (int k = 0; k < 32 / BS::RPI; ++k)
+          *(f32x4 *)(stage + (k * BS::RPI + lane / BS::LPR) * BS::RS + (lane % BS::LPR) * 16) = raw[nb][k];
+        wave_lds_fence();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dyq[nb][q] = *(const bf16x4 *)(stage + l32 * BS::RS + 16 * q + 8 * g);
+        wave_lds_fence();
+      }
     }
-    f32x16 dyc, yc, dyn, yn;
-    load_block(dyrow, 0, dyc);
-    if constexpr (KIND != KIND_EDGE) load_block(yrow, 0, yc);
 #pragma unroll
     for (int nb = 0; nb < MB; ++nb) {
-      if (nb + 1 < MB) {
-        load_block(dyrow, nb + 1, dyn);
-        if constexpr (KIND != KIND_EDGE) load_block(yrow, nb + 1, yn);
-      }
       f32x16 d;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if constexpr (KIND == KIND_EDGE) d[r] = (ym[nb] >> r) & 1u ? dyc[r] : 0.f;
-        else d[r] = yc[r] > 0.f ? dyc[r] : 0.f;
-      }
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) d[4 * q + j] = (yz[nb] >> (4 * q + j)) & 1u ? (float)dyq[nb][q][j] : 0.f;
       store_block_via_lds<T, H>((T *)a.dz2, row0, n_valid, nb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz2s[nb][q] = acc_slab<T>(d, q);
-      if (nb + 1 < MB) { dyc = dyn; yc = yn; }
     }
   }
 
@@ -168,15 +186,11 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
   {
     const bf16x8 *W2b = (const bf16x8 *)a.W2bt + lane;
     auto idx_from = [&](int u0) { return [=](int u, int j) { return j * MB + u0 + u; }; };
-    const T *zrow = (const T *)a.z1 + (size_t)row * H + 4 * g;
-    f32x16 zc, zn;
-    load_block(zrow, 0, zc);
     wg.begin(W2b, idx_from(0));
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const int g0 = mb / UG * UG, u = mb % UG;
       if (u == 0 && g0 + UG < MB) wg.fetch(W2b, idx_from(g0 + UG));
-      if (mb + 1 < MB) load_block(zrow, mb + 1, zn);
       f32x16 d;
 #pragma unroll
       for (int r = 0; r < 16; ++r) d[r] = 0.f;
@@ -186,11 +200,10 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
         for (int q = 0; q < QB; ++q) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg.get(u, nb * QB + q), dz2s[nb][q], d, 0, 0, 0);
       if (u == UG - 1) wg.next(g0 + UG < MB);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) d[r] = zc[r] > 0.f ? d[r] : 0.f;
+      for (int r = 0; r < 16; ++r) d[r] = (yz[mb] >> (16 + r)) & 1u ? d[r] : 0.f;
       store_block_via_lds<T, H>((T *)a.dz1, row0, n_valid, mb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz1s[mb][q] = acc_slab<T>(d, q);
-      if (mb + 1 < MB) zc = zn;
     }
   }
 

@@ -128,10 +128,16 @@ __device__ __forceinline__ void layer2_lds(const f32x16 (&acc1)[H / 32], const t
 // so they need not stay live beyond it): relu(z1) rows [row0, row0 + nv) of a.z1 through the
 // staging buffer, one 32-feature block at a time with BLOCKWISE staging, else whole rows.
 template <typename T, int H, bool BLOCKWISE>
-__device__ __forceinline__ void save_hidden_tile(const Mlp2Args &a, const f32x16 (&acc1)[H / 32], int64_t row0, int nv,
-                                                 int lane, char *stage) {
+__device__ __forceinline__ void save_hidden_tile(const Mlp2Args &a, const f32x16 (&acc1)[H / 32], int64_t wt, int64_t row0,
+                                                 int nv, int lane, char *stage) {
   constexpr int MB = H / 32;
   T *z1 = (T *)a.z1;
+  {
+    int lv = lane;                      // (opaque: the address is formed here, not kept in registers across tiles)
+    asm volatile("" : "+v"(lv));
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) a.z1mask[((size_t)wt * MB + mb) * 64 + lv] = lane_mask_bits(acc1[mb]);
+  }
   if constexpr (BLOCKWISE) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -146,9 +152,9 @@ __device__ __forceinline__ void save_hidden_tile(const Mlp2Args &a, const f32x16
     });
   }
 }
-// After layer 2, EDGE (tile wt): the mask bits of y.
+// After layer 2 (tile wt): the mask bits of y.
 template <int H>
-__device__ __forceinline__ void save_edge_output_mask(const Mlp2Args &a, const f32x16 (&acc2)[H / 32], int64_t wt, int lane) {
+__device__ __forceinline__ void save_output_mask(const Mlp2Args &a, const f32x16 (&acc2)[H / 32], int64_t wt, int lane) {
   int lv = lane;                        // (opaque: the address is formed here, not kept in registers across tiles)
   asm volatile("" : "+v"(lv));
 #pragma unroll
@@ -270,13 +276,13 @@ __global__ __launch_bounds__(64 * NW) void mlp2p_kernel(const Mlp2Args a) {
     if constexpr (SAVE) {
       if constexpr (KIND == KIND_NODE) {
         const int64_t left = a.n_rows - wt * 32;
-        save_hidden_tile<T, H, false>(a, acc1, wt * 32, left < 32 ? (int)left : 32, lane, stage);
+        save_hidden_tile<T, H, false>(a, acc1, wt, wt * 32, left < 32 ? (int)left : 32, lane, stage);
       } else {
-        save_hidden_tile<T, H, false>(a, acc1, meta_e0, nv, lane, stage);
+        save_hidden_tile<T, H, false>(a, acc1, wt, meta_e0, nv, lane, stage);
       }
     }
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
-    if constexpr (SAVE && KIND == KIND_EDGE) save_edge_output_mask<H>(a, acc2, wt, lane);
+    if constexpr (SAVE) save_output_mask<H>(a, acc2, wt, lane);
     if (more) load_rows<T, H, KIND, 3>(a, wnext, l32, g, ix, in);
     else in = TileRows<T, H>{};   // (so that the consumed rows need not stay live up to here)
     __builtin_amdgcn_sched_barrier(0);
@@ -382,9 +388,10 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     }
     const int64_t left = a.n_rows - row0;
     const int n_valid = left < 32 ? (int)left : 32;
-    if constexpr (SAVE) save_hidden_tile<T, H, BIG>(a, acc1, row0, n_valid, lane, stage);
+    if constexpr (SAVE) save_hidden_tile<T, H, BIG>(a, acc1, wt, row0, n_valid, lane, stage);
     f32x16 acc2[MB];
     layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+    if constexpr (SAVE) save_output_mask<H>(a, acc2, wt, lane);
     T *out = (T *)a.out;
     if constexpr (BIG) {
 #pragma unroll

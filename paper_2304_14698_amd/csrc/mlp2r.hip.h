@@ -139,7 +139,7 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
   }
 }
 
-// SAVE: also keeps the forward for the backward pass (a.z1, a.ymask; see Mlp2Args). relu(z1) leaves
+// SAVE: also keeps the forward for the backward pass (a.z1, a.z1mask, a.ymask; see Mlp2Args). relu(z1) leaves
 // as whole rows through the input buffer of the tile itself, which is idle between the end of
 // layer 1 and the prefetch of the tile after next: after the first barrier every wave writes its
 // 32 features of all rows there, after the second barrier wave w reads rows 4w .. 4w+3 back and
@@ -249,6 +249,11 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
 #pragma unroll
     for (int q = 0; q < 2; ++q)
       *(bf16x8 *)(zbuf + ((2 * w + q) * 64 + lane) * 16) = relu_operand<T>(acc, q);
+    if constexpr (SAVE) {
+      int lv = lane;
+      asm volatile("" : "+v"(lv));
+      a.z1mask[((size_t)wt * MB + w) * 64 + lv] = lane_mask_bits(acc);
+    }
     __syncthreads();
     if constexpr (SAVE) {
       static_assert(!SAVE || H == 256, "the staging layout below is laid out for eight waves");
@@ -286,7 +291,7 @@ __global__ __launch_bounds__((RTile<H, KIND>::NT), (RTile<H, KIND>::WAVES_PER_SI
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    if constexpr (SAVE && KIND == KIND_EDGE) {
+    if constexpr (SAVE) {
       __builtin_amdgcn_sched_barrier(0);
       int lv = lane;
       asm volatile("" : "+v"(lv));

@@ -174,7 +174,8 @@ struct xrl_ctx {
   bool fwd_kept = false;
   void *z1_embed = nullptr;
   std::vector<void *> z1_edge, z1_node;
-  std::vector<uint16_t *> ym_edge;
+  std::vector<uint16_t *> ym_edge, ym_node, zm_edge, zm_node;   // mask bits of y and of z1, per round
+  uint16_t *ym_embed = nullptr, *zm_embed = nullptr;
   // optional per-kernel timing
   bool timing = false;
   struct Span { int kind; hipEvent_t a, b; };
@@ -790,8 +791,8 @@ int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
     attr_set = true;
   }
   const int64_t wave_tiles = KIND == KIND_EDGE ? a.n_tiles : (a.n_rows + 31) / 32;   // EDGE: the packer's edge tiles
-  a.n_blocks = (wave_tiles + S::NW - 1) / S::NW;
-  const unsigned grid = (unsigned)(((a.n_blocks + 7) / 8) * 8);
+  a.n_blocks = (wave_tiles + S::NW - 1) / S::NW;               // groups of NW tiles
+  const unsigned grid = (unsigned)((a.n_blocks + 7) / 8 * 8);
   kern<<<dim3(grid), dim3(64 * S::NW), S::LDS, c->stream>>>(a);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
@@ -1115,11 +1116,11 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   memset(&za, 0, sizeof(za));
   za.in_dst = d.in_dst; za.dz1 = dz1; za.dz2 = dz2;
   za.tile_ptr = d.tile_ptr; za.n_tiles = (int64_t)b->tile_ptr.size() - 1;
-  auto mlp_bwd = [&](int kind, const EncMlp &e, const void *z1_kept, const uint16_t *ymask) -> int {
+  auto mlp_bwd = [&](int kind, const EncMlp &e, const uint16_t *z1mask, const uint16_t *ymask) -> int {
     if constexpr (sizeof(T) == 2) {
       if (kept) {
-        za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy; za.z1 = z1_kept; za.y = a.y;
-        za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
+        za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy;
+        za.z1mask = z1mask; za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
         return launch_mlp2_bwdz(c, kind, za, fold);
       }
     }
@@ -1174,7 +1175,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     set_w(c->node[r]);
     a.n_rows = N; a.h = c->h[r]; a.agg = c->agg[r + 1]; a.y = c->h[r + 1]; a.dy = dhA;
     a.dx_a = dhB; a.dx_b = dagg;
-    { Timed t(c, TK_BWD_NODE); rc = mlp_bwd(KIND_NODE, c->node[r], kept ? c->z1_node[r] : nullptr, nullptr); }
+    { Timed t(c, TK_BWD_NODE); rc = mlp_bwd(KIND_NODE, c->node[r], kept ? c->zm_node[r] : nullptr, kept ? c->ym_node[r] : nullptr); }
     if (rc) return rc;
     wa.h = c->h[r]; wa.agg = c->agg[r + 1];
     if ((rc = wgrads(WG_NODE, N, 2 * H, c->L.node[r], kept ? c->z1_node[r] : nullptr))) return rc;
@@ -1182,7 +1183,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     set_w(c->edge[r]);
     a.n_rows = E; a.h = c->h[r]; a.agg = nullptr; a.y = nullptr; a.dy = dagg;
     a.dx_a = dsrc; a.dx_b = ddst;
-    { Timed t(c, TK_BWD_EDGE); rc = mlp_bwd(KIND_EDGE, c->edge[r], kept ? c->z1_edge[r] : nullptr, kept ? c->ym_edge[r] : nullptr); }
+    { Timed t(c, TK_BWD_EDGE); rc = mlp_bwd(KIND_EDGE, c->edge[r], kept ? c->zm_edge[r] : nullptr, kept ? c->ym_edge[r] : nullptr); }
     if (rc) return rc;
     if ((rc = wgrads(WG_EDGE, E, 2 * H + De, c->L.edge[r], kept ? c->z1_edge[r] : nullptr))) return rc;
     // dh[r] = d(node MLP)/dh + sum over in-edges of d h_receiver + sum over out-edges of d h_sender
@@ -1197,7 +1198,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   // ---- node-update layer backward (weights only: its inputs are data)
   set_w(c->embed);
   a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
-  { Timed t(c, TK_BWD_EMBED); rc = mlp_bwd(KIND_EMBED, c->embed, kept ? c->z1_embed : nullptr, nullptr); }
+  { Timed t(c, TK_BWD_EMBED); rc = mlp_bwd(KIND_EMBED, c->embed, kept ? c->zm_embed : nullptr, kept ? c->ym_embed : nullptr); }
   if (rc) return rc;
   if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed, kept ? c->z1_embed : nullptr))) return rc;
   HIP_TRY(hipGetLastError());
@@ -1251,10 +1252,12 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
       }
     }
   }
-  const size_t ym_words = (size_t)n_tiles * (H / 32) * 64;            // 16-bit words of one round's edge mask bits
+  const size_t ym_words = (size_t)n_tiles * (H / 32) * 64;            // 16-bit words of one edge MLP's mask bits (z1 or y)
+  const size_t nm_words = (size_t)((N + 31) / 32) * (H / 32) * 64;    // ... of a node-side MLP's
   if (keep) {
     for (int i = 0; i < R + 1; ++i) acc((size_t)N * H * sizeof(T));
-    for (int i = 0; i < R; ++i) { acc((size_t)E * H * sizeof(T)); acc(ym_words * 2); }
+    for (int i = 0; i < R; ++i) { acc((size_t)E * H * sizeof(T)); acc(ym_words * 2); acc(ym_words * 2); }
+    for (int i = 0; i < 2 * (R + 1); ++i) acc(nm_words * 2);
   }
   const int n_gs = gat ? (save ? R : 1) : 0;                            // saved per round for the backward
   for (int i = 0; i < 2 * n_gs; ++i) acc((size_t)N * 4);
@@ -1284,14 +1287,20 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
   c->ro_act[1] = bump.take<float>((size_t)G * H);
   c->fwd_kept = keep;
   c->z1_edge.assign(R, nullptr); c->z1_node.assign(R, nullptr);
-  c->ym_edge.assign(R, nullptr);
-  c->z1_embed = nullptr;
+  c->ym_edge.assign(R, nullptr); c->zm_edge.assign(R, nullptr);
+  c->ym_node.assign(R, nullptr); c->zm_node.assign(R, nullptr);
+  c->z1_embed = nullptr; c->ym_embed = c->zm_embed = nullptr;
   if (keep) {
     c->z1_embed = bump.take<T>((size_t)N * H);
+    c->zm_embed = bump.take<uint16_t>(nm_words);
+    c->ym_embed = bump.take<uint16_t>(nm_words);
     for (int r = 0; r < R; ++r) {
       c->z1_node[r] = bump.take<T>((size_t)N * H);
       c->z1_edge[r] = bump.take<T>((size_t)E * H);
+      c->zm_edge[r] = bump.take<uint16_t>(ym_words);
       c->ym_edge[r] = bump.take<uint16_t>(ym_words);
+      c->zm_node[r] = bump.take<uint16_t>(nm_words);
+      c->ym_node[r] = bump.take<uint16_t>(nm_words);
     }
   }
   c->enc_batch = b->id;
@@ -1359,7 +1368,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
       }
     }
   }
-  a.z1 = c->z1_embed; a.ymask = nullptr;
+  a.z1 = c->z1_embed; a.z1mask = c->zm_embed; a.ymask = c->ym_embed;
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
   c->h[0] = hb[0];
@@ -1395,7 +1404,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     }
     set_w(c->edge[r]);
     a.n_rows = E; a.h = hcur; a.out = aggb;
-    a.z1 = c->z1_edge[r]; a.ymask = c->ym_edge[r];
+    a.z1 = c->z1_edge[r]; a.z1mask = c->zm_edge[r]; a.ymask = c->ym_edge[r];
     { Timed t(c, TK_EDGE); rc = launch_mlp2<T>(c, KIND_EDGE, a); }
     if (rc) return rc;
     if (b->n_split_tiles > 0) {         // only a receiver with more than 32 in-edges spans tiles
@@ -1406,7 +1415,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     }
     set_w(c->node[r]);
     a.n_rows = N; a.h = hcur; a.agg = aggb; a.out = hnext;
-    a.z1 = c->z1_node[r]; a.ymask = nullptr;
+    a.z1 = c->z1_node[r]; a.z1mask = c->zm_node[r]; a.ymask = c->ym_node[r];
     { Timed t(c, TK_NODE); rc = launch_mlp2<T>(c, KIND_NODE, a); }
     if (rc) return rc;
     c->h[r + 1] = hnext;
