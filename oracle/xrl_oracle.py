@@ -275,12 +275,14 @@ def zero_grads(model):
     return {name: np.zeros(shape, dtype=F) for name, shape in weight_layout(model)}
 
 
-def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound=None):
+def policy_value_backward(model, w, emb, state, dlogp, dvalue, dentropy, bound=None, fw=None):
     """Gradient of L = sum_valid dlogp_j logp_j + sum_s dvalue_s value_s + sum_s dentropy_s
     entropy_s w.r.t. the embeddings [G, H] and the head weights (flat vector, zero elsewhere).
-    Masked slots get exactly zero everywhere (invalid-action masking, Section 3.3.2)."""
+    Masked slots get exactly zero everywhere (invalid-action masking, Section 3.3.2).
+    fw: the result of policy_value on the same arguments, if the caller already has it."""
     W = unflatten(model, w)
-    fw = policy_value(model, w, emb, state)
+    if fw is None:
+        fw = policy_value(model, w, emb, state)
     sgp, mask = state["state_graph_ptr"], np.asarray(state["slot_mask"]).astype(bool)
     S, G = len(sgp) - 1, emb.shape[0]
     dlogit = np.zeros(G)

@@ -138,14 +138,12 @@ __device__ __forceinline__ void cluster_arrive(unsigned *ctr) {
   __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void cluster_wait(unsigned *ctr, unsigned target, unsigned *fault, unsigned spin_limit) {
+  // (spin_limit polls at most; with a limit of 0 the wait cannot see anything arrive and gives up at once)
   unsigned spins = 0;
-  while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+  bool arrived = false;
+  while (spins++ < spin_limit && !(arrived = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target))
     __builtin_amdgcn_s_sleep(2);
-    if (++spins > spin_limit) {
-      __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-      break;
-    }
-  }
+  if (!arrived) __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 

@@ -33,6 +33,11 @@ from zero, asserted, so that both sides differentiate the same piecewise-linear 
   The same cases pass the fp32 criterion in fp32 with no allowance, so what the bf16 runs add is
   rounding, not arithmetic.
 
+In the chained test (heads + encoder) the first layer of each head also gets 1e-5 max|emb| times the
+bound of its bias gradient (sum over rows of |dz|): the embeddings it multiplies carry the forward's
+absolute error. Hidden units of the heads within 1e-5 of zero are treated like the encoder's
+(heads_flip_allowance).
+
 Heads (fp32 in both modes), on given embeddings: |g - ref| <= 1e-5 |ref| + 1e-5 scale + kappa B
 with kappa = 2e-6 + 1e-5 max(1, L), L = the largest |logit|: the forward's tolerance admits an
 absolute error of 1e-5 L in logp (a difference of logits), i.e. a relative error of 1e-5 L in every
@@ -115,6 +120,30 @@ def flip_allowance(om, w, state, demb, eps=1e-5, graphs=None, max_flips=4000):
     return A, n_near
 
 
+def heads_flip_allowance(om, w, emb, state, dlogp, dvalue, dentropy, eps=1e-5, max_flips=200):
+    """The same allowance for the heads' own ReLUs (their hidden layers), on the head tensors: for
+    every hidden pre-activation of the policy or value head that the oracle has within eps of its
+    layer's scale of zero, the heads' reverse mode is run with that mask inverted, and the
+    absolute changes of the head gradients are summed. Returns (A, number of such units)."""
+    fw = O.policy_value(om, w, emb, state)
+    base = O.policy_value_backward(om, w, emb, state, dlogp, dvalue, dentropy, fw=fw)[1]
+    A = np.zeros_like(base)
+    n_near = 0
+    for key in ("c_pi", "c_v"):
+        for x, z in fw[key][:-1]:                      # (the last layer of a head has no ReLU)
+            if not z.size:
+                continue
+            for i in np.argwhere(np.abs(z) <= eps * max(1.0, float(np.abs(z).max()))):
+                i = tuple(i)
+                n_near += 1
+                assert n_near <= max_flips, "too many undecided ReLU masks in the heads"
+                old = z[i]
+                z[i] = -old if old != 0.0 else 1e-300
+                A += np.abs(O.policy_value_backward(om, w, emb, state, dlogp, dvalue, dentropy, fw=fw)[1] - base)
+                z[i] = old
+    return A, n_near
+
+
 def check_fp32(got, ref, bound, om, allowance=None, only=None, kappa=2e-6, atol=1e-5):
     bad = []
     gscale = float(np.abs(ref).max())
@@ -130,7 +159,9 @@ def check_fp32(got, ref, bound, om, allowance=None, only=None, kappa=2e-6, atol=
         if np.any(err > 0):
             i = int(np.argmax(err))
             bad.append(f"{name}: {(err > 0).sum()}/{g.size} outside tolerance, worst [{i}] got {g[i]:.9g} "
-                       f"ref {r[i]:.9g} scale {scale:.3g} B {B[i]:.3g} tol {tol[i]:.3g}")
+                       f"ref {r[i]:.9g} scale {scale:.3g} B {B[i]:.3g} tol {tol[i]:.3g}; first indices "
+                       f"{np.flatnonzero(err > 0)[:12].tolist()}, largest (error - other terms) / B "
+                       f"{float(((np.abs(g - r) - (tol - kappa * B)) / np.maximum(B, 1e-300)).max()):.3g}")
     assert not bad, "\n".join(bad)
 
 

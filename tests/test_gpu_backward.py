@@ -118,7 +118,20 @@ def run_backward_case(xrl, model, state, w, seed=3, bf16_rel=0.15, bf16_cos=0.98
     if prec == "fp32":
         np.testing.assert_allclose(d, ref_demb, rtol=1e-4, atol=1e-5 * max(1.0, L) * np.abs(ref_demb).max())
         A, n_near = GC.flip_allowance(om, w, state, ref_demb)
-        print(f"undecided ReLU masks (|z| <= 1e-5 scale) in the oracle: {n_near}; largest |logit| {L:.3g}")
+        Ah, n_heads = GC.heads_flip_allowance(om, w, O.encode(om, w, state), state, dlogp, dvalue, dentropy)
+        A = A + Ah
+        # the heads' first layers multiply the embeddings, which the forward holds to 1e-5 of their
+        # scale and no better (a feature that is nearly off has an error far above 1e-5 of its own
+        # value): dW0[k, f] may be off by that times sum_g |dz[g, f]|, which is the bound of db0[f]
+        emb_scale = float(np.abs(O.encode(om, w, state)).max())
+        bflat = O.flatten(om, ba)
+        tens = {name: (sl, shape) for name, sl, shape in GC.tensors(om)}
+        for head in head_names:
+            slw, shape = tens[f"{head}.W0"]
+            slb, _ = tens[f"{head}.b0"]
+            A[slw] += (1e-5 * emb_scale * np.broadcast_to(bflat[slb], shape)).ravel()
+        print(f"undecided ReLU masks (|z| <= 1e-5 scale) in the oracle: {n_near} in the encoder, {n_heads} in the heads; "
+              f"largest |logit| {L:.3g}")
         GC.check_fp32(dw_all, ref_all, O.flatten(om, ba), om, allowance=A, kappa=4e-5 + 1e-5 * L, atol=atol)
     else:
         assert cosine(dw_all.astype(np.float64), ref_all) >= 0.9
