@@ -23,6 +23,8 @@ struct Mlp2BwdzArgs {
   int64_t n_rows, n_blocks;
   const void *W2bt, *W1bt;     // contraction over the weight's columns (see swizzle_chain)
   const void *dy;              // upstream gradient [N, H] bf16 (EDGE: indexed by receiver)
+  const int32_t *dy_index;     // NODE, EMBED, optional: row n reads dy[dy_index[n]] (the gradient of the
+                               // per-graph sum, one row per graph, for the layer the readout sums)
   const uint16_t *z1mask;      // [tiles][H / 32][64] mask bits of z1 and of y, kept by the forward (see
   const uint16_t *ymask;       //   Mlp2Args); tiles = the edge tiles (EDGE), else 32 consecutive rows
   const int32_t *in_dst;       // [E] (EDGE)
@@ -120,6 +122,7 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
   if (row >= a.n_rows) row = a.n_rows - 1;                    // clamp loads; stores are guarded
   int drow = (int)row;                                        // the row of dy this lane's row reads: itself, or its receiver
   if constexpr (KIND == KIND_EDGE) drow = a.in_dst[row];
+  else if (a.dy_index) drow = a.dy_index[row];
   [[maybe_unused]] int fold_rem = 0, fold_dsel = -1;          // FOLD: edges after this one with its receiver; row of the total
   if constexpr (FOLD) {
     const bool valid = l32 < n_valid;

@@ -1015,7 +1015,8 @@ __global__ void demb_combine_kernel(float *demb, const float *dzs, const float *
 }
 
 // dh[n, :] = dx[graph(n), :H] (divided by the graph's node count for the mean readout), stored in
-// the operand type like every later dh; one thread per four columns
+// the operand type like every later dh; one thread per four columns. node_graph null: one row per
+// graph (n = the graph)
 template <typename T>
 __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *node_graph,
                                        const int32_t *graph_node_ptr, int mean, int64_t N, int H, T *dh) {
@@ -1023,7 +1024,7 @@ __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *
   const int q = H / 4;
   if (i >= N * q) return;
   const int64_t n = i / q;
-  const int f = (int)(i - n * q) * 4, gph = node_graph[n];
+  const int f = (int)(i - n * q) * 4, gph = node_graph ? node_graph[n] : (int)n;
   float v[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) v[j] = dx[(size_t)gph * ldx + f + j];
@@ -1084,9 +1085,19 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   float *ract[3] = {c->ro_act[0], c->ro_act[1], nullptr};
   if ((rc = launch_rowmlp_bwd(c, c->L.readout, true, ract, d_demb, G, rdz, rdx))) return rc;
   if ((rc = launch_small_wgrads(c, c->L.readout, c->pool, H, d.graph_global, Dg, ract, rdz, G, dweights, partial, part))) return rc;
-  if (N > 0)
-    broadcast_dpool_kernel<T><<<dim3((unsigned)((N * (H / 4) + 255) / 256)), dim3(256), 0, c->stream>>>(
-        rdx, H + Dg, d.node_graph, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, N, H, dhA);
+  // The gradient w.r.t. the last node states is the pool's, the same row for every node of a graph.
+  // From the kept forward, the first backward kernel reads it through the nodes' graph ids from a
+  // [G, H] table (the kernel below with the graphs as its "nodes"); otherwise it is written out per node.
+  const bool dpool_table = kept && !gat;
+  if (N > 0) {
+    if (dpool_table)
+      broadcast_dpool_kernel<T><<<dim3((unsigned)((G * (H / 4) + 255) / 256)), dim3(256), 0, c->stream>>>(
+          rdx, H + Dg, nullptr, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, G, H, dhA);
+    else
+      broadcast_dpool_kernel<T><<<dim3((unsigned)((N * (H / 4) + 255) / 256)), dim3(256), 0, c->stream>>>(
+          rdx, H + Dg, d.node_graph, d.graph_node_ptr, m.readout == XRL_READOUT_MEAN, N, H, dhA);
+  }
+  bool dy_by_graph = dpool_table;          // until the first backward kernel has consumed the table
 
   Mlp2BwdArgs a;
   memset(&a, 0, sizeof(a));
@@ -1121,6 +1132,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
       if (kept) {
         za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy;
         za.z1mask = z1mask; za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
+        za.dy_index = (dy_by_graph && kind != KIND_EDGE) ? d.node_graph : nullptr;
+        dy_by_graph = false;
         return launch_mlp2_bwdz(c, kind, za, fold);
       }
     }
