@@ -872,6 +872,16 @@ int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
                                                                                          dw, dbias);
   };
   if constexpr (sizeof(T) == 2) {
+    if (kind == WG_EMBED && a.a0) {
+      // the node-update layer's first matrix: its input columns are synthesised per row (sums of
+      // incoming edge attributes, precomputed by the caller; one-hot operator type; dense attributes)
+      const Wgrad2Plan p = wgrad2_plan(a.n_rows, (a.Ka + 1 + 127) / 128, c->n_cu, 2);
+      int rc = launch_wgrad2<H, WG_EMBED, 128>(c, a, p, 0, p.kt * 128, -1);
+      if (rc) return rc;
+      reduce(a.partial, p.ny, p.kt * 128, a.Ka, dW, db);
+      HIP_TRY(hipGetLastError());
+      return XRL_OK;
+    }
     if (kind != WG_EMBED) {                                // transpose-read kernel
       int rc;
       const int k_main = kind == WG_PLAIN ? a.Ka : 2 * H;  // the H-wide column parts
@@ -1037,6 +1047,19 @@ __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *
   store4<T>(dh + (size_t)n * H + f, v);
 }
 
+// a0[n, :] = sum over node n's in-edges (receiver order, which is the node-update kernel's order) of
+// their attribute rows; one thread per node and four columns
+__global__ void edge_attr_sum_kernel(const float *edge_feat, const int32_t *in_ptr, int64_t N, int De, float *a0) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int q = De / 4;
+  if (i >= N * q) return;
+  const int64_t n = i / q;
+  const int k0 = (int)(i - n * q) * 4;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int e = in_ptr[n]; e < in_ptr[n + 1]; ++e) s += *(const f32x4 *)(edge_feat + (size_t)e * De + k0);
+  *(f32x4 *)(a0 + (size_t)n * De + k0) = s;
+}
+
 template <typename T>
 int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, float *dweights) {
   const xrl_model_desc &m = c->m;
@@ -1055,6 +1078,8 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   acc((size_t)E * H * sizeof(T));                                  // per-edge d h_sender
   acc((size_t)M * H * sizeof(T));                                  // d h_receiver: per edge, or summed per receiver
   for (int i = 0; i < 3; ++i) acc((size_t)N * H * sizeof(T));      // dh (two buffers), dagg
+  const bool embed_a0 = sizeof(T) == 2 && De > 0 && N > 0;          // the node-update layer's weight gradient reads a0
+  if (embed_a0) acc((size_t)N * De * 4);
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
   acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
@@ -1071,6 +1096,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)M * H);
   T *dhA = bump.take<T>((size_t)N * H), *dhB = bump.take<T>((size_t)N * H);
   T *dagg = bump.take<T>((size_t)N * H);
+  float *a0 = embed_a0 ? bump.take<float>((size_t)N * De) : nullptr;
   float *partial = bump.take<float>(part);
   float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
   float *rdx = bump.take<float>((size_t)G * (H + Dg));
@@ -1213,6 +1239,11 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
   { Timed t(c, TK_BWD_EMBED); rc = mlp_bwd(KIND_EMBED, c->embed, kept ? c->zm_embed : nullptr, kept ? c->ym_embed : nullptr); }
   if (rc) return rc;
+  if (embed_a0) {
+    const int64_t threads = N * (De / 4);
+    edge_attr_sum_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(d.edge_feat, d.in_ptr, N, De, a0);
+    wa.a0 = a0;
+  }
   if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed, kept ? c->z1_embed : nullptr))) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
