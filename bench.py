@@ -29,10 +29,10 @@ PEAK_HBM_GBS = 8000.0
 # hash covers the files the kernel is built from (comments and blank space apart); otherwise null.
 TRAFFIC = {
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
-    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="af5e992d6bbe5f8b",
-                                  bytes_per_launch=(13123474.7 * 2.000 + 35311455.0 * 1.000) * 1024),
-    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="af5e992d6bbe5f8b",
-                                  bytes_per_launch=(7687175.6 * 2.000 + 33044068.7 * 1.000) * 1024),
+    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
+                                  bytes_per_launch=(4110331.7 * 2.000 + 31959793.7 * 1.000) * 1024),
+    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
+                                  bytes_per_launch=(3545337.5 * 2.000 + 31020797.3 * 1.000) * 1024),
 }
 
 
