@@ -24,7 +24,6 @@ struct WgradArgs {
   const int32_t *node_op;
   const float *node_dense;
   int De, Tn, Dd;
-  const float *a0;          // EMBED on the transpose-read kernel: [N, De] per-node sums of incoming edge attributes
   const void *dZ;           // [rows, H] operand type
   float *partial;           // [n_chunks, KaP, H], KaP = 64 * gridDim.x
 };
@@ -248,22 +247,6 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
         // select on the loaded value here made the compiler wait for the load on the spot.)
         const vec v = *(const vec *)(nbase + (size_t)row * H);
         x[c] = on ? v : Operand<T>::zero();
-      } else if constexpr (KIND == WG_EMBED) {
-        // [sum of incoming edge attributes | one-hot operator type | dense attributes | 1 | 0 ...]:
-        // which of them a thread's eight columns are is fixed for the whole kernel
-        const int op = a.node_op[row];
-        vec v;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int k = xc + j;
-          float f = 0.f;
-          if (k < a.De) f = a.a0[(size_t)row * a.De + k];
-          else if (k < a.De + a.Tn) f = k - a.De == op ? 1.f : 0.f;
-          else if (k < a.De + a.Tn + a.Dd) f = a.node_dense[(size_t)row * a.Dd + (k - a.De - a.Tn)];
-          else if (k == a.Ka) f = 1.f;
-          v[j] = (T)f;
-        }
-        x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (KIND == WG_EDGE) {              // [edge attributes | 1 | 0 ...]
         // every lane loads and uses an attribute (times 0 or 1, plus the bias column's 1): a
         // select would let the compiler move the loads into branches with waits behind them
@@ -360,6 +343,7 @@ __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int k
   constexpr int RS = 32;
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;
+  static_assert(KIND != WG_EMBED, "the embed layer's input rows are written out first and go through WG_PLAIN");
   extern __shared__ __align__(16) char smem[];              // wgrad2_lds_bytes<H, TA>()
   char(*Xs)[RS * XS] = reinterpret_cast<char(*)[RS * XS]>(smem);
   char(*Zs)[RS * ZS] = reinterpret_cast<char(*)[RS * ZS]>(smem + 2 * RS * XS);
@@ -383,7 +367,7 @@ __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int k
   const bool do_bias = bias_row >= 0 && kq == 0;
   float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (r_end > r_begin) {
-    if (KIND == WG_EMBED || (KIND != WG_PLAIN && ka0 >= 2 * H)) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
+    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
     else wgrad2_run<H, KIND, false, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
   }
   if (do_bias) {

@@ -872,16 +872,6 @@ int launch_wgrad_h(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
                                                                                          dw, dbias);
   };
   if constexpr (sizeof(T) == 2) {
-    if (kind == WG_EMBED && a.a0) {
-      // the node-update layer's first matrix: its input columns are synthesised per row (sums of
-      // incoming edge attributes, precomputed by the caller; one-hot operator type; dense attributes)
-      const Wgrad2Plan p = wgrad2_plan(a.n_rows, (a.Ka + 1 + 127) / 128, c->n_cu, 2);
-      int rc = launch_wgrad2<H, WG_EMBED, 128>(c, a, p, 0, p.kt * 128, -1);
-      if (rc) return rc;
-      reduce(a.partial, p.ny, p.kt * 128, a.Ka, dW, db);
-      HIP_TRY(hipGetLastError());
-      return XRL_OK;
-    }
     if (kind != WG_EMBED) {                                // transpose-read kernel
       int rc;
       const int k_main = kind == WG_PLAIN ? a.Ka : 2 * H;  // the H-wide column parts
@@ -941,6 +931,35 @@ int launch_wgrad(xrl_ctx *c, int kind, WgradArgs &a, float *dW, float *db) {
     case 256: return launch_wgrad_h<T, 256>(c, kind, a, dW, db);
   }
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
+}
+
+// dW[Kx, H] += X[:, :Kx]^T dZ and db += 1^T dZ for X = a.A [rows, a.Ka] (a.Ka = Kx rounded up to 8, the
+// columns past Kx zero): the plain product, whose tile also holds the all-ones column at a.Ka
+template <typename T>
+int launch_wgrad_embed_rows(xrl_ctx *c, WgradArgs &a, int Kx, float *dW, float *db) {
+  if constexpr (sizeof(T) == 2) {
+    if (a.n_rows <= 0) return XRL_OK;
+    auto run = [&](auto h) -> int {
+      constexpr int H = decltype(h)::value;
+      const Wgrad2Plan p = wgrad2_plan(a.n_rows, (a.Ka + 1 + 127) / 128, c->n_cu, 2);
+      const int KaP = p.kt * 128;
+      int rc = launch_wgrad2<H, WG_PLAIN, 128>(c, a, p, 0, KaP, -1);
+      if (rc) return rc;
+      const int64_t cnt_w = (int64_t)Kx * H;
+      if (cnt_w > 0)
+        wgrad_reduce_kernel<<<dim3((unsigned)((cnt_w + 31) / 32)), dim3(256), 0, c->stream>>>(a.partial, p.ny, KaP, Kx, H, dW, nullptr);
+      wgrad_reduce_kernel<<<dim3((unsigned)((H + 31) / 32)), dim3(256), 0, c->stream>>>(a.partial + (size_t)a.Ka * H, p.ny, KaP, 0, H,
+                                                                                     nullptr, db);
+      HIP_TRY(hipGetLastError());
+      return XRL_OK;
+    };
+    switch (c->m.hidden) {
+      case 64: return run(std::integral_constant<int, 64>());
+      case 128: return run(std::integral_constant<int, 128>());
+      case 256: return run(std::integral_constant<int, 256>());
+    }
+  }
+  return fail(XRL_ERR_UNSUPPORTED, "launch_wgrad_embed_rows: bf16 contexts only");
 }
 
 int launch_rowmlp_bwd(xrl_ctx *c, const MlpRef &r, bool relu_last, float *const *act, const float *dout,
@@ -1047,17 +1066,34 @@ __global__ void broadcast_dpool_kernel(const float *dx, int ldx, const int32_t *
   store4<T>(dh + (size_t)n * H + f, v);
 }
 
-// a0[n, :] = sum over node n's in-edges (receiver order, which is the node-update kernel's order) of
-// their attribute rows; one thread per node and four columns
-__global__ void edge_attr_sum_kernel(const float *edge_feat, const int32_t *in_ptr, int64_t N, int De, float *a0) {
+// The node-update layer's input rows written out for its weight gradient (bf16 path):
+// X[n, :] = [sum over node n's in-edges (receiver order: the node-update kernel's order) of their
+// attribute rows | one-hot operator type | dense attributes | zeros up to Kp columns]; one thread per
+// node and eight columns.
+__global__ void embed_input_rows_kernel(const float *edge_feat, const int32_t *in_ptr, const int32_t *node_op,
+                                        const float *node_dense, int64_t N, int De, int Tn, int Dd, int Kp, bf16_t *X) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int q = De / 4;
+  const int q = Kp / 8;
   if (i >= N * q) return;
   const int64_t n = i / q;
-  const int k0 = (int)(i - n * q) * 4;
-  f32x4 s = {0.f, 0.f, 0.f, 0.f};
-  for (int e = in_ptr[n]; e < in_ptr[n + 1]; ++e) s += *(const f32x4 *)(edge_feat + (size_t)e * De + k0);
-  *(f32x4 *)(a0 + (size_t)n * De + k0) = s;
+  const int k0 = (int)(i - n * q) * 8;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = 0.f;
+  if (k0 < De) {
+    for (int e = in_ptr[n]; e < in_ptr[n + 1]; ++e)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (k0 + j < De) v[j] += edge_feat[(size_t)e * De + k0 + j];
+  }
+  const int op = node_op[n];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int k = k0 + j;
+    if (k >= De && k < De + Tn) v[j] = k - De == op ? 1.f : 0.f;
+    else if (k >= De + Tn && k < De + Tn + Dd) v[j] = node_dense[(size_t)n * Dd + (k - De - Tn)];
+  }
+  *(bf16x8 *)(X + (size_t)n * Kp + k0) = pack_bf16x8(v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]);
 }
 
 template <typename T>
@@ -1078,8 +1114,10 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   acc((size_t)E * H * sizeof(T));                                  // per-edge d h_sender
   acc((size_t)M * H * sizeof(T));                                  // d h_receiver: per edge, or summed per receiver
   for (int i = 0; i < 3; ++i) acc((size_t)N * H * sizeof(T));      // dh (two buffers), dagg
-  const bool embed_a0 = sizeof(T) == 2 && De > 0 && N > 0;          // the node-update layer's weight gradient reads a0
-  if (embed_a0) acc((size_t)N * De * 4);
+  // bf16: the node-update layer's input rows are written out for its weight gradient, Kp columns
+  const int Kx = De + m.n_op_types + m.n_node_dense, Kp = (Kx + 7) / 8 * 8;
+  const bool embed_rows = sizeof(T) == 2 && N > 0;
+  if (embed_rows) acc((size_t)N * Kp * 2);
   const size_t part = std::max(wgrad_partial_floats(M, 2 * H + De, H, c->n_cu), wgrad_partial_floats(M, H, H, c->n_cu));
   acc(part * 4);
   acc((size_t)G * H * 4); acc((size_t)G * H * 4); acc((size_t)G * (H + Dg) * 4);
@@ -1096,7 +1134,7 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   T *dsrc = bump.take<T>((size_t)E * H), *ddst = bump.take<T>((size_t)M * H);
   T *dhA = bump.take<T>((size_t)N * H), *dhB = bump.take<T>((size_t)N * H);
   T *dagg = bump.take<T>((size_t)N * H);
-  float *a0 = embed_a0 ? bump.take<float>((size_t)N * De) : nullptr;
+  bf16_t *xrows = embed_rows ? bump.take<bf16_t>((size_t)N * Kp) : nullptr;
   float *partial = bump.take<float>(part);
   float *rdz[3] = {bump.take<float>((size_t)G * H), bump.take<float>((size_t)G * H), nullptr};
   float *rdx = bump.take<float>((size_t)G * (H + Dg));
@@ -1239,12 +1277,20 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   a.n_rows = N; a.h = nullptr; a.agg = nullptr; a.y = c->h[0]; a.dy = dhA; a.dx_a = nullptr; a.dx_b = nullptr;
   { Timed t(c, TK_BWD_EMBED); rc = mlp_bwd(KIND_EMBED, c->embed, kept ? c->zm_embed : nullptr, kept ? c->ym_embed : nullptr); }
   if (rc) return rc;
-  if (embed_a0) {
-    const int64_t threads = N * (De / 4);
-    edge_attr_sum_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(d.edge_feat, d.in_ptr, N, De, a0);
-    wa.a0 = a0;
+  if constexpr (sizeof(T) == 2) {
+    // first layer: dW1 = X^T dz1 on the transpose-read kernel, X written out once; its Kx real rows
+    // and the bias row (row Kp of the slices' partial tiles) are reduced separately
+    Timed t(c, TK_WGRAD_EMBED);
+    const int64_t threads = N * (Kp / 8);
+    embed_input_rows_kernel<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(
+        d.edge_feat, d.in_ptr, d.node_op, d.node_dense, N, De, m.n_op_types, m.n_node_dense, Kp, xrows);
+    wa.n_rows = N; wa.Ka = Kp; wa.dZ = dz1; wa.A = xrows;
+    if ((rc = launch_wgrad_embed_rows<T>(c, wa, Kx, dweights + c->L.embed.w[0], dweights + c->L.embed.b[0]))) return rc;
+    wa.Ka = H; wa.dZ = dz2; wa.A = kept ? c->z1_embed : z1;
+    if ((rc = launch_wgrad<T>(c, WG_PLAIN, wa, dweights + c->L.embed.w[1], dweights + c->L.embed.b[1]))) return rc;
+  } else {
+    if ((rc = wgrads(WG_EMBED, N, Kx, c->L.embed, nullptr))) return rc;
   }
-  if ((rc = wgrads(WG_EMBED, N, De + m.n_op_types + m.n_node_dense, c->L.embed, kept ? c->z1_embed : nullptr))) return rc;
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }
