@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC = {
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
     (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
-                                  bytes_per_launch=(4110331.7 * 2.000 + 31959793.7 * 1.000) * 1024),
+                                  bytes_per_launch=(4106514.1 * 2.000 + 31949759.8 * 1.000) * 1024),
     (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
-                                  bytes_per_launch=(3545337.5 * 2.000 + 31020797.3 * 1.000) * 1024),
+                                  bytes_per_launch=(3546471.3 * 2.000 + 31018993.3 * 1.000) * 1024),
 }
 
 
