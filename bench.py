@@ -28,6 +28,16 @@ PEAK_HBM_GBS = 8000.0
 # (factors 2.000 and 1.000). An entry is valid only for the kernel sources it was taken with: the
 # hash covers the files the kernel is built from (comments and blank space apart); otherwise null.
 TRAFFIC = {
+    # configuration 2 (profiles/forward_config2_bf16_hbm_traffic.md): persistent forward kernels, weights in LDS
+    (2, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="84159bc71519750d",
+                              bytes_per_launch=(11145.7 * 2.000 + 11599.5 * 1.000) * 1024),
+    (2, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="84159bc71519750d",
+                              bytes_per_launch=(18659.3 * 2.000 + 18218.2 * 1.000) * 1024),
+    # configuration 4 (profiles/forward_config4_bf16_kernel_stats_and_traffic.md): register-stationary forward kernels
+    (4, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="22272a55474e8791",
+                              bytes_per_launch=(89445.1 * 2.000 + 70572.0 * 1.000) * 1024),
+    (4, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="22272a55474e8791",
+                              bytes_per_launch=(164022.0 * 2.000 + 162434.5 * 1.000) * 1024),
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
     (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
                                   bytes_per_launch=(4106514.1 * 2.000 + 31949759.8 * 1.000) * 1024),
