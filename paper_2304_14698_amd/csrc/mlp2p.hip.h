@@ -123,6 +123,41 @@ __device__ __forceinline__ void layer2_lds(const f32x16 (&acc1)[H / 32], const t
   }
 }
 
+// The same product for half of the output feature blocks (nb0 .. nb0 + H / 64 - 1) from relu(z1)
+// already converted to operand fragments: with H = 256 the two full sets of fp32 accumulators and
+// the weight fragments in flight do not fit a wave's 256 registers, fragments (a quarter of the
+// accumulators' size) plus half of the outputs do. Every output accumulates its chunks in the
+// order of layer2_lds, so the results are the same bits.
+template <typename T, int H>
+__device__ __forceinline__ void layer2_half_lds(const typename Operand<T>::vec (&zf)[H / (2 * Operand<T>::V)],
+                                                const typename Operand<T>::vec *W2l, const float (*b2l)[2][16], int lane,
+                                                int g, int nb0, f32x16 (&acc2)[H / 64]) {
+  using Opd = Operand<T>;
+  using vec = typename Opd::vec;
+  constexpr int MB = H / 32, HB = MB / 2, NC2 = H / (2 * Opd::V);
+#pragma unroll
+  for (int i = 0; i < HB; ++i) acc2[i] = *(const f32x16 *)&b2l[nb0 + i][g][0];
+  vec wc[HB];
+#pragma unroll
+  for (int i = 0; i < HB; ++i) wc[i] = W2l[(nb0 + i) * 64 + lane];
+#pragma unroll
+  for (int c = 0; c < NC2; ++c) {
+    vec wn[HB];
+    if (c + 1 < NC2) {
+#pragma unroll
+      for (int i = 0; i < HB; ++i) wn[i] = W2l[((c + 1) * MB + nb0 + i) * 64 + lane];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < HB; ++i) Opd::mma(wc[i], zf[c], acc2[i]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (c + 1 < NC2) {
+#pragma unroll
+      for (int i = 0; i < HB; ++i) wc[i] = wn[i];
+    }
+  }
+}
+
 // What a SAVE kernel keeps for the backward pass from a wave tile held as features x rows
 // accumulators (lane = row). Before layer 2 (which consumes layer 1's accumulators block by block,
 // so they need not stay live beyond it): relu(z1) rows [row0, row0 + nv) of a.z1 through the
@@ -363,22 +398,48 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   }
   __syncthreads();
 
+  // a tile's row data (op type, in-edge range) is requested one tile ahead, before the previous
+  // tile's stores: a load behind stores is not complete before they are
+  auto tile_row = [&](int64_t t) {
+    const int64_t r = t * 32 + l32;
+    return r < a.n_rows ? r : a.n_rows - 1;
+  };
+  EmbedRow er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt < t_end ? wt : 0));
   for (; wt < t_end; wt += stride) {
     asm volatile("" ::: "memory");
     const int64_t row0 = wt * 32;
-    const int64_t row = row0 + l32 < a.n_rows ? row0 + l32 : a.n_rows - 1;
-    const EmbedRow er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
+    const EmbedRow er = er_next;
     // ---------------- layer 1: bias + the op type's row of W1, then the fp32 columns on the MFMAs
     f32x16 acc1[MB];
     const f32x4 *trow = tab + (size_t)er.op * (H / 4) + g;
+    if constexpr (BIG) {
+      // the table row comes from memory: every piece is requested first, straight into the
+      // accumulators, and the bias is added after the one wait (loaded piece by piece into a
+      // temporary, each load was waited for by itself: H / 8 memory round trips per tile)
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const f32x4 t = trow[8 * mb + 2 * q];
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 t = trow[8 * mb + 2 * q];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] += t[j];
+          for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] = t[j];
+        }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const f32x16 b = *(const f32x16 *)&b1l[mb][g][0];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[mb][r] += b[r];
+      }
+    } else {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 t = trow[8 * mb + 2 * q];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] += t[j];
+        }
       }
     }
     for (int s = 0; s < a.nslabx; ++s) {
@@ -388,19 +449,38 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
     }
     const int64_t left = a.n_rows - row0;
     const int n_valid = left < 32 ? (int)left : 32;
+    er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt + stride < t_end ? wt + stride : wt));
+    asm volatile("" : "+v"(er_next.op), "+v"(er_next.e0), "+v"(er_next.e1));   // arrived before the first store
     if constexpr (SAVE) save_hidden_tile<T, H, BIG>(a, acc1, wt, row0, n_valid, lane, stage);
-    f32x16 acc2[MB];
-    layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
-    if constexpr (SAVE) save_output_mask<H>(a, acc2, wt, lane);
     T *out = (T *)a.out;
     if constexpr (BIG) {
+      // relu(z1) as operand fragments first, then the output feature blocks in two halves, each
+      // leaving through the staging buffer before the other is formed
+      vec zf[NC2];
 #pragma unroll
-      for (int nb = 0; nb < MB; ++nb) {
+      for (int c = 0; c < NC2; ++c) zf[c] = relu_operand<T>(acc1[c / QB], c % QB);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc2[nb][r] = relu_f32(acc2[nb][r]);
-        store_block_via_lds<T, H>(out, row0, n_valid, nb, lane, acc2[nb], stage);
+      for (int hb = 0; hb < 2; ++hb) {
+        constexpr int HB = MB / 2;
+        f32x16 acc2[HB];
+        layer2_half_lds<T, H>(zf, W2l, b2l, lane, g, hb * HB, acc2);
+        if constexpr (SAVE) {
+          int lv = lane;                // (opaque: the address is formed here, not kept in registers across tiles)
+          asm volatile("" : "+v"(lv));
+#pragma unroll
+          for (int i = 0; i < HB; ++i) a.ymask[((size_t)wt * MB + hb * HB + i) * 64 + lv] = lane_mask_bits(acc2[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc2[i][r] = relu_f32(acc2[i][r]);
+          store_block_via_lds<T, H>(out, row0, n_valid, hb * HB + i, lane, acc2[i], stage);
+        }
       }
     } else {
+      f32x16 acc2[MB];
+      layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
+      if constexpr (SAVE) save_output_mask<H>(a, acc2, wt, lane);
       store_rows_via_lds<T, H, true>(acc2, stage, lane, [&](int r) -> T * {
         return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
       });
