@@ -312,8 +312,8 @@ int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32
  * xrl_encode_backward computes it (Section 3.3.4), exposed so that the product can be checked and
  * timed on its own. kind XRL_WG_PLAIN: X = d_x [n_rows, H]. XRL_WG_EDGE: X = [h[sender] |
  * h[receiver] | edge attributes] over the batch's E edges in receiver order, d_x = h [N, H].
- * XRL_WG_NODE: X = [h | received sums], d_x = h, d_x2 = the sums, both [N, H], the sums' rows of
- * nodes without in-edges zero as xrl_encode leaves them (n_rows is ignored for these two kinds).
+ * XRL_WG_NODE: X = [h | received sums], d_x = h, d_x2 = the sums, both [N, H]; the sums' rows of
+ * nodes without in-edges are not read and count as zero (n_rows is ignored for these two kinds).
  * d_x, d_x2 and d_dZ [rows, H] are device arrays in the ctx's operand type (fp32, or bf16 bit
  * patterns); d_dW [K, H] (K = columns of X) and d_db [H] are device fp32 and are accumulated
  * into. Deterministic. Uses the backward's scratch. Errors: NULL, STATE, INDEX, SHAPE, OOM, HIP. */

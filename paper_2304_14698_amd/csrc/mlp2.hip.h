@@ -28,6 +28,9 @@ struct Mlp2Args {
   int nslab1;              // slabs of layer 1's (zero-padded) input width
   const void *h;           // [N, H] operand type            (EDGE, NODE)
   const void *agg;         // [N, H] operand type            (NODE)
+  const int32_t *agg_src;  // [N] NODE: the row of agg that holds a node's received sum, -1 for a node without
+                           //   in-edges (the message kernels never write its row: zeros are read in its place);
+                           //   nullptr: every node reads its own row
   const int32_t *in_ptr;   // [N + 1]                        (all kinds)
   const int32_t *in_src;   // [E]                            (EDGE)
   const int32_t *in_dst;   // [E]                            (EDGE)
@@ -41,7 +44,7 @@ struct Mlp2Args {
   const void *zero_row;    // 1 KB of zeros (source of rows that are absent)
   void *agg0;              // EMBED: first of n_agg received-sum buffers [N, H], agg_stride bytes apart;
   size_t agg_stride;       //        the embed kernel zeroes their rows of nodes without in-edges, which
-  int n_agg;               //        the message kernels never write
+  int n_agg;               //        the message kernels never write (0 when the readers go by agg_src)
   void *out;               // [N, H] operand type
   void *z1;                // kernels instantiated to keep the forward for the backward pass: the hidden
   uint16_t *z1mask;        //   activation relu(z1) [rows, H] operand type (an operand of the weight gradient)
@@ -296,8 +299,9 @@ __device__ __forceinline__ void mlp2_wave_tile(const Mlp2Args &a, const int64_t 
       pb = (const T *)a.h + (size_t)a.in_dst[row] * H + g * V;
     } else {
       pa = (const T *)a.h + (size_t)row * H + g * V;
-      pb = (const T *)a.agg + (size_t)row * H + g * V;   // (rows of nodes without in-edges were zeroed
-    }                                                    //  by the embed kernel)
+      const int64_t ar = a.agg_src ? (int64_t)a.agg_src[row] : row;
+      pb = ar < 0 ? (const T *)a.zero_row + g * V : (const T *)a.agg + (size_t)ar * H + g * V;
+    }
     vec xa[HS], xb[HS];
 #pragma unroll
     for (int s = 0; s < HS; ++s) xa[s] = *(const vec *)(pa + s * SL);

@@ -33,6 +33,8 @@ struct Mlp2BwdArgs {
   const float *b1, *b2;
   int nslab1;
   const void *h, *agg;       // forward inputs, operand type
+  const int32_t *agg_src;    // NODE: [N] row of agg per node, -1 = none (zeros are read); or nullptr
+  const void *zero_row;      // 1 KB of zeros
   const void *y;             // saved forward output [N, H] operand type      (NODE, EMBED)
   const void *dy;            // upstream gradient [N, H], operand type (EDGE: indexed by receiver)
   const int32_t *in_ptr, *in_src, *in_dst;
@@ -184,7 +186,8 @@ __global__ __launch_bounds__(256) void mlp2_bwd_kernel(const Mlp2BwdArgs a) {
       pb = (const T *)a.h + (size_t)dst * H + g * V;
     } else if constexpr (KIND == KIND_NODE) {
       pa = (const T *)a.h + (size_t)row * H + g * V;
-      pb = (const T *)a.agg + (size_t)row * H + g * V;
+      const int64_t ar = a.agg_src ? (int64_t)a.agg_src[row] : row;
+      pb = ar < 0 ? (const T *)a.zero_row + g * V : (const T *)a.agg + (size_t)ar * H + g * V;
     } else {
       er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, row);
     }

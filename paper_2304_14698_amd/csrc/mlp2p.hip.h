@@ -25,12 +25,12 @@ struct TileRows {
 
 struct TileIndex {
   int e0, nv;       // EDGE: the tile's edges are [e0, e0 + nv)
-  int src;          // EDGE: sender of this lane's edge
+  int src;          // EDGE: sender of this lane's edge; NODE: row of the received sums to read, -1 = none
   EdgeTileMeta m;   // EDGE: receivers
 };
 
 struct TileBounds {
-  int e0, e1;       // EDGE: the tile's edges are [e0, e1)
+  int e0, e1;       // EDGE: the tile's edges are [e0, e1); NODE: e0 = first node of the tile
 };
 template <int KIND>
 __device__ __forceinline__ TileBounds load_bounds(const Mlp2Args &a, int64_t wt) {
@@ -38,6 +38,8 @@ __device__ __forceinline__ TileBounds load_bounds(const Mlp2Args &a, int64_t wt)
   if constexpr (KIND == KIND_EDGE) {
     b.e0 = a.tile_ptr[wt];
     b.e1 = a.tile_ptr[wt + 1];
+  } else {
+    b.e0 = (int)(wt * 32);
   }
   return b;
 }
@@ -49,6 +51,11 @@ __device__ __forceinline__ TileIndex load_index(const Mlp2Args &a, const TileBou
     ix.nv = b.e1 - b.e0;
     ix.src = a.in_src[ix.e0 + (l32 < ix.nv ? l32 : ix.nv - 1)];
     ix.m = load_edge_meta(a.in_dst, a.n_rows, ix.e0, ix.nv, l32);
+  } else {
+    const int64_t row = (int64_t)b.e0 + l32 < a.n_rows ? (int64_t)b.e0 + l32 : a.n_rows - 1;
+    ix.e0 = b.e0;
+    ix.nv = 0;
+    ix.src = a.agg_src[row];   // (must be given: a load under a condition would be waited for on the spot)
   }
   return ix;
 }
@@ -84,7 +91,7 @@ __device__ __forceinline__ void load_rows(const Mlp2Args &a, int64_t wt, int l32
       for (int k = 0; k < HS; ++k) in.x[k] = *(const vec *)(hp + k * SL);
     }
     if constexpr ((PARTS & 2) != 0) {
-      const T *ap = (const T *)a.agg + (size_t)row * H + g * V;
+      const T *ap = ix.src < 0 ? (const T *)a.zero_row + g * V : (const T *)a.agg + (size_t)ix.src * H + g * V;
 #pragma unroll
       for (int k = 0; k < HS; ++k) in.x[HS + k] = *(const vec *)(ap + k * SL);
     }

@@ -93,7 +93,8 @@ __device__ __forceinline__ RTileRows rtile_rows(const Mlp2Args &a, int64_t wt) {
 // wave; instruction q = 4w + j covers row parts q * RPI .. of the tile (the first H / 16
 // instructions the sender / node-state rows, the others the receiver / received-sum rows), and
 // wave 0 also fetches the edge attributes. src[j] is the global row the lane reads for
-// instruction j (rows past the tile's last repeat it and are never stored). Nothing here branches
+// instruction j (rows past the tile's last repeat it and are never stored; NODE: the node's entry
+// of agg_src, which must be given: -1 = zeros in place of its received sum). Nothing here branches
 // on a loaded value, so the index loads can stay in flight until the rows are fetched a tile later.
 struct RFetch {
   int src[4];
@@ -110,7 +111,8 @@ __device__ __forceinline__ RFetch rtile_index(const Mlp2Args &a, const RTileRows
     const int r = R::RPI * ((4 * w + j) % (H / 16)) + lq;
     const int64_t row = t.r0 + (r < t.nv ? r : t.nv - 1);
     if constexpr (KIND == KIND_EDGE) f.src[j] = ip[row];
-    else f.src[j] = (int)row;
+    else f.src[j] = a.agg_src[row];   // (requested by every wave, whichever part it fetches: a load under a
+                                      //  condition would be waited for on the spot, behind the row prefetch)
   }
   return f;
 }
@@ -125,8 +127,12 @@ __device__ __forceinline__ void rtile_fetch(const Mlp2Args &a, const RTileRows &
   for (int j = 0; j < 4; ++j) {
     const int q = 4 * w + j, r = R::RPI * (q % (H / 16)) + lv / R::LPR;
     const int piece = (lv % R::LPR) ^ (r & R::SWM);
-    lds_direct_load16(base + (size_t)f.src[j] * H + piece * 8,
-                      __builtin_amdgcn_readfirstlane(lds_address(xbuf) + q * 1024));
+    int64_t srow = f.src[j];
+    if constexpr (KIND == KIND_NODE) {
+      if (w < R::MB / 2) srow = t.r0 + (r < t.nv ? r : t.nv - 1);   // the node's own state
+    }
+    const bf16_t *rowp = srow < 0 ? (const bf16_t *)a.zero_row : base + (size_t)srow * H;
+    lds_direct_load16(rowp + piece * 8, __builtin_amdgcn_readfirstlane(lds_address(xbuf) + q * 1024));
   }
   if constexpr (KIND == KIND_EDGE) {
     if (w == 0) {                                               // 32 rows x 32 bytes of raw fp32 attributes

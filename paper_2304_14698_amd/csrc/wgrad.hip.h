@@ -19,6 +19,8 @@ struct WgradArgs {
   int Ka;                   // real columns of X; column Ka is the all-ones bias column
   const void *A;            // PLAIN: [rows, Ka] operand type (Ka == H)
   const void *h, *agg;      // EDGE / NODE sources, operand type
+  const int32_t *agg_src;   // NODE, transpose-read kernel: [N] row of agg per node, -1 = none (zeros are read)
+  const void *zero_row;     // 1 KB of zeros
   const int32_t *in_ptr, *in_src, *in_dst;
   const float *edge_feat;
   const int32_t *node_op;
@@ -228,6 +230,9 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
     for (int c = 0; c < 2; ++c) {
       ix[c] = 0;
       if constexpr (!TAIL && KIND == WG_EDGE) ix[c] = idx_arr[row_of(st, c)];
+      if constexpr (!TAIL && KIND == WG_NODE) {
+        ix[c] = a.agg_src[row_of(st, c)];   // (every thread, under no condition: see load_x)
+      }
     }
   };
   auto load_x = [&](int st, const int (&ix)[2], vec (&x)[2]) {
@@ -243,9 +248,12 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
         const vec v = *(const vec *)(gbase + (size_t)ix[c] * H);
         x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (!TAIL && KIND == WG_NODE) {
-        // (the forward zeroed the received sums of nodes without in-edges: read as they are. A
-        // select on the loaded value here made the compiler wait for the load on the spot.)
-        const vec v = *(const vec *)(nbase + (size_t)row * H);
+        // (the received sum of a node without in-edges is read from a row of zeros: the select
+        // is on the address, formed from an index requested a stage earlier. A select on the
+        // loaded value here made the compiler wait for the load on the spot.)
+        const int64_t srow = second ? (int64_t)ix[c] : row;
+        const T *p = srow < 0 ? (const T *)a.zero_row + (xc - H) : nbase + (size_t)srow * H;
+        const vec v = *(const vec *)p;
         x[c] = on ? v : Operand<T>::zero();
       } else if constexpr (KIND == WG_EDGE) {              // [edge attributes | 1 | 0 ...]
         // every lane loads and uses an attribute (times 0 or 1, plus the bias column's 1): a

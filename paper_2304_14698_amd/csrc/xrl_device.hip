@@ -148,6 +148,8 @@ struct xrl_ctx {
   int device = 0;               // the device that was current at xrl_create
   char *static_ws = nullptr;    // this device's copy of `scratch` (its device address)
   void *zero_row = nullptr;     // 1 KB of zeros behind the weights
+  bool agg_skip = false;        // last encode: the received-sum rows of nodes without in-edges were not written
+                                // (their readers go by the batch's agg_src)
   char *d_swz = nullptr;        // fragment-ordered encoder weights
   size_t swz_bytes = 0;
   EncMlp embed;
@@ -739,10 +741,17 @@ int launch_heads(xrl_ctx *c, const xrl_batch *b, const float *d_emb, float *logi
   return XRL_OK;
 }
 
+// row_src (or nullptr): the row of src to export for each row, -1 = a row of zeros
 template <typename T>
-__global__ void export_rows_kernel(const T *src, int64_t n_rows, int D, float *dst) {
+__global__ void export_rows_kernel(const T *src, int64_t n_rows, int D, const int32_t *row_src, float *dst) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_rows * D) return;
+  if (row_src) {
+    const int64_t r = i / D;
+    const int32_t s = row_src[r];
+    dst[i] = s < 0 ? 0.f : (float)src[(int64_t)s * D + (i - r * D)];
+    return;
+  }
   dst[i] = (float)src[i];
 }
 
@@ -1172,6 +1181,10 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   WgradArgs wa;
   memset(&wa, 0, sizeof(wa));
   wa.in_ptr = d.in_ptr; wa.in_src = d.in_src; wa.in_dst = d.in_dst; wa.edge_feat = d.edge_feat;
+  // (after a forward of one launch per layer the received sums of nodes without in-edges were never written)
+  a.zero_row = wa.zero_row = c->zero_row;
+  wa.agg_src = d.agg_src;
+  if (c->agg_skip) a.agg_src = d.agg_src;
   wa.node_op = d.node_op; wa.node_dense = d.node_dense; wa.De = De; wa.Tn = m.n_op_types; wa.Dd = m.n_node_dense;
   wa.partial = partial;
   auto set_w = [&](const EncMlp &e) {
@@ -1415,6 +1428,7 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
     // bytes: the three inlined tile routines of wider ones do not fit the register file)
     ResidentArgs ra;
     memset(&ra, 0, sizeof(ra));
+    c->agg_skip = false;               // (the node-update layer zeroes the rows nobody else writes)
     ra.base = a;
     ra.rounds = R; ra.E = E;
     ra.graph_node_ptr = d.graph_node_ptr; ra.graph_tile_ptr = d.graph_tile_ptr; ra.gtile_ptr = d.gtile_ptr;
@@ -1458,6 +1472,10 @@ int encode_impl(xrl_ctx *c, const xrl_batch *b, float *d_emb, int save) {
       }
     }
   }
+  // one launch per layer: the node MLPs (and whatever reads the received sums afterwards) take
+  // zeros for nodes without in-edges through agg_src, so nobody has to write those rows
+  a.n_agg = 0; a.agg_src = d.agg_src;
+  c->agg_skip = !gat;
   a.z1 = c->z1_embed; a.z1mask = c->zm_embed; a.ymask = c->ym_embed;
   { Timed t(c, TK_EMBED); rc = launch_mlp2<T>(c, KIND_EMBED, a); }
   if (rc) return rc;
@@ -1684,6 +1702,11 @@ __global__ void expand_rows_kernel(const int32_t *from, int64_t n, int width, co
   const int32_t f = from[r];
   out[i] = f >= 0 ? base[(size_t)f * width + j] : added[(size_t)(-1 - f) * width + j];
 }
+// agg_src of a batch: n for a node with in-edges, -1 for one without
+__global__ void agg_src_kernel(const int32_t *in_ptr, int64_t n, int32_t *agg_src) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) agg_src[i] = in_ptr[i + 1] > in_ptr[i] ? (int32_t)i : -1;
+}
 }  // namespace
 
 int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
@@ -1699,7 +1722,7 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
                o_nd = plan((size_t)N * Dd * 4), o_ef = plan((size_t)E * De * 4),
                o_gg = plan((size_t)G * Dg * 4), o_mask = plan(G),
                o_tile = plan(b->tile_ptr.size() * 4), o_gtile = plan(b->gtile_ptr.size() * 4),
-               o_gtp = plan(b->graph_tile_ptr.size() * 4);
+               o_gtp = plan(b->graph_tile_ptr.size() * 4), o_as = plan(N * 4);
   // packed from edits: the attribute arrays are filled on the device from these
   const bool ed = b->from_edits;
   const size_t o_nf = ed ? plan(N * 4) : 0, o_ef2 = ed ? plan(E * 4) : 0,
@@ -1724,6 +1747,11 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   HIP_TRY(cp(o_gnp, b->graph_node_ptr.data(), (G + 1) * 4));
   if (!ed) HIP_TRY(cp(o_op, b->node_op.data(), N * 4));
   HIP_TRY(cp(o_inp, b->in_ptr.data(), (N + 1) * 4));
+  if (N > 0) {
+    agg_src_kernel<<<dim3((unsigned)((N + 255) / 256)), dim3(256), 0, c->stream>>>((const int32_t *)(blk + o_inp), N,
+                                                                                  (int32_t *)(blk + o_as));
+    HIP_TRY(hipGetLastError());
+  }
   HIP_TRY(cp(o_ins, b->in_src.data(), E * 4));
   HIP_TRY(cp(o_ind, b->in_dst.data(), E * 4));
   HIP_TRY(cp(o_outp, b->out_ptr.data(), (N + 1) * 4));
@@ -1775,6 +1803,7 @@ int xrl_batch_upload(xrl_ctx *c, xrl_batch *b) {
   d.tile_ptr = (int32_t *)(blk + o_tile);
   d.gtile_ptr = b->graph_tile_ptr.empty() ? nullptr : (int32_t *)(blk + o_gtile);
   d.graph_tile_ptr = b->graph_tile_ptr.empty() ? nullptr : (int32_t *)(blk + o_gtp);
+  d.agg_src = (int32_t *)(blk + o_as);
   b->uploaded = true;
   return XRL_OK;
 }
@@ -2107,6 +2136,7 @@ int xrl_weight_gradient(xrl_ctx *c, const xrl_batch *b, int32_t kind, const void
   memset(&wa, 0, sizeof(wa));
   const xrl_batch_device &d = b->dev;
   wa.in_ptr = d.in_ptr; wa.in_src = d.in_src; wa.in_dst = d.in_dst; wa.edge_feat = d.edge_feat;
+  wa.agg_src = d.agg_src; wa.zero_row = c->zero_row;
   wa.node_op = d.node_op; wa.node_dense = d.node_dense; wa.De = De; wa.Tn = c->m.n_op_types; wa.Dd = c->m.n_node_dense;
   wa.partial = (float *)c->bws;
   wa.n_rows = n_rows; wa.Ka = Ka; wa.dZ = d_dZ;
@@ -2155,6 +2185,7 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
   int64_t rows = N;
   int D = H;
   bool typed = true;
+  const int32_t *row_src = nullptr;
   if (!strcmp(what, "a0")) {   // not kept by the forward pass: recomputed with the segment-sum kernel
     return launch_segsum<float, float, 4>(c, b->dev.edge_feat, nullptr, b->dev.in_ptr, b->dev.in_dst, b->E, N,
                                           c->m.d_edge, d_out, c->carry);
@@ -2168,13 +2199,14 @@ int xrl_get_activation(xrl_ctx *c, const xrl_batch *b, const char *what, int32_t
     if (c->m.round_kind == XRL_ROUND_GAT)
       return fail(XRL_ERR_UNSUPPORTED, "agg: the graph-attention rounds keep no received sums");
     src = c->agg[round];
+    if (c->agg_skip) row_src = b->dev.agg_src;   // rows of nodes without in-edges were never written
   } else return fail(XRL_ERR_INDEX, "xrl_get_activation: unknown tensor '%s'", what);
   if (rows * D == 0) return XRL_OK;
   const unsigned blocks = (unsigned)((rows * D + 255) / 256);
   if (typed && c->elem == 2)
-    export_rows_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, c->stream>>>((const bf16_t *)src, rows, D, d_out);
+    export_rows_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, c->stream>>>((const bf16_t *)src, rows, D, row_src, d_out);
   else
-    export_rows_kernel<float><<<dim3(blocks), dim3(256), 0, c->stream>>>((const float *)src, rows, D, d_out);
+    export_rows_kernel<float><<<dim3(blocks), dim3(256), 0, c->stream>>>((const float *)src, rows, D, row_src, d_out);
   HIP_TRY(hipGetLastError());
   return XRL_OK;
 }

@@ -62,6 +62,7 @@ struct xrl_batch_device {
   int32_t *in_ptr = nullptr, *in_src = nullptr, *in_dst = nullptr;
   int32_t *out_ptr = nullptr, *out_pos = nullptr, *node_graph = nullptr, *tile_ptr = nullptr;
   int32_t *gtile_ptr = nullptr, *graph_tile_ptr = nullptr;   // null unless the batch has per-graph tiles
+  int32_t *agg_src = nullptr;   // [N] n for a node with in-edges, -1 for one without (filled on the device)
   float *node_dense = nullptr, *edge_feat = nullptr, *graph_global = nullptr;
   uint8_t *mask = nullptr;
 };
