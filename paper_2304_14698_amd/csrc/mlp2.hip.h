@@ -243,6 +243,27 @@ __device__ __forceinline__ f32x4 embed_columns(const EmbedRow &r, const float *e
   return x;
 }
 
+// The same four columns with every load under no condition (an absent edge, a column of the other
+// kind or past the last one reads a row of zeros through the load address; up to four in-edges,
+// the rest in a loop), so that no load waits for another. Sums in the order of embed_columns
+// (adding the zeros changes nothing).
+__device__ __forceinline__ f32x4 embed_columns_ahead(const EmbedRow &r, const float *edge_feat, const float *zeros,
+                                                     int De, int Dd, int k0) {
+  const int n = k0 < De ? r.e1 - r.e0 : 0;
+  const float *p = edge_feat + (size_t)r.e0 * De + k0;
+  f32x4 v[4], d;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = *(const f32x4 *)(e < n ? p + (size_t)e * De : zeros);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) d[j] = *(k0 >= De && k0 + j < De + Dd ? r.dense + (k0 + j - De) : zeros);
+  f32x4 x = v[0];
+#pragma unroll
+  for (int e = 1; e < 4; ++e) x += v[e];
+  for (int e = 4; e < n; ++e) x += *(const f32x4 *)(p + (size_t)e * De);
+  x += d;
+  return x;
+}
+
 // EMBED: zero rows of the received-sum buffers for the tile's nodes without in-edges (`no_in`:
 // this lane's node, lane = row l % 32), whole rows, 16 bytes per lane.
 template <typename T, int H>

@@ -363,7 +363,8 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   float(*b2l)[2][16] = b1l + MB;
   char *stage = (char *)(b2l + MB) + (threadIdx.x >> 6) * (BIG ? BlockStage<T>::BYTES : RowStage<T, H>::BYTES);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // tile counters stay in scalar registers
   const int nbx = gridDim.x / 8, xcd = blockIdx.x % 8, lid = blockIdx.x / 8;
   const int64_t n_wt = (a.n_rows + 31) / 32;
   const int64_t per_xcd = (n_wt + 7) / 8;
@@ -405,39 +406,61 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
   }
   __syncthreads();
 
-  // a tile's row data (op type, in-edge range) is requested one tile ahead, before the previous
-  // tile's stores: a load behind stores is not complete before they are
+  // Everything a tile reads from memory is requested a tile ahead (its row data -- op type, in-edge
+  // range -- two tiles ahead) and has arrived before the previous tile's first store: loads and
+  // stores complete in order, so a load requested behind a tile's stores would not be there before
+  // they are, and a wave that is alone on its SIMD (H = 256) would sit through every drain.
   auto tile_row = [&](int64_t t) {
     const int64_t r = t * 32 + l32;
     return r < a.n_rows ? r : a.n_rows - 1;
   };
-  EmbedRow er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt < t_end ? wt : 0));
-  for (; wt < t_end; wt += stride) {
-    asm volatile("" ::: "memory");
-    const int64_t row0 = wt * 32;
-    const EmbedRow er = er_next;
-    // ---------------- layer 1: bias + the op type's row of W1, then the fp32 columns on the MFMAs
-    f32x16 acc1[MB];
-    const f32x4 *trow = tab + (size_t)er.op * (H / 4) + g;
+  auto next_tile = [&](int64_t t) { return t + stride < t_end ? t + stride : t; };
+  constexpr int NSX = 2;                             // slabs of fp32 input columns at most (the launcher checks)
+  f32x4 xs[NSX];                                     // the tile's fp32 input columns, one vector per slab
+  [[maybe_unused]] f32x16 pre[BIG ? MB : 1];         // BIG: the op type's table row
+  auto request = [&](const EmbedRow &r) {
+    int gv = g;                         // (opaque: the columns' offsets are formed here in every tile instead of
+    asm volatile("" : "+v"(gv));        //  living in registers, of which the loop has none to spare)
+#pragma unroll
+    for (int sl = 0; sl < NSX; ++sl)
+      if (sl < a.nslabx) xs[sl] = embed_columns_ahead(r, a.edge_feat, (const float *)a.zero_row, a.De, a.Dd, sl * 8 + gv * 4);
     if constexpr (BIG) {
-      // the table row comes from memory: every piece is requested first, straight into the
-      // accumulators, and the bias is added after the one wait (loaded piece by piece into a
-      // temporary, each load was waited for by itself: H / 8 memory round trips per tile)
+      const f32x4 *trow = tab + (size_t)r.op * (H / 4) + gv;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const f32x4 t = trow[8 * mb + 2 * q];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc1[mb][4 * q + j] = t[j];
+          for (int j = 0; j < 4; ++j) pre[mb][4 * q + j] = t[j];
         }
+    }
+  };
+  EmbedRow er = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt < t_end ? wt : 0));
+  EmbedRow er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt < t_end ? next_tile(wt) : 0));
+  request(er);
+  auto arrived = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  arrived();
+  for (; wt < t_end; wt += stride) {
+    asm volatile("" ::: "memory");
+    const int64_t row0 = wt * 32;
+    const int64_t left = a.n_rows - row0;
+    const int n_valid = left < 32 ? (int)left : 32;
+    // ---------------- layer 1: bias + the op type's row of W1, then the fp32 columns on the MFMAs
+    f32x16 acc1[MB];
+    if constexpr (BIG) {
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         const f32x16 b = *(const f32x16 *)&b1l[mb][g][0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc1[mb][r] += b[r];
+        for (int r = 0; r < 16; ++r) acc1[mb][r] = pre[mb][r] + b[r];
       }
     } else {
+      const f32x4 *trow = tab + (size_t)er.op * (H / 4) + g;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         acc1[mb] = *(const f32x16 *)&b1l[mb][g][0];
@@ -449,31 +472,50 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
         }
       }
     }
-    for (int s = 0; s < a.nslabx; ++s) {
-      const f32x4 x = embed_columns(er, a.edge_feat, a.De, a.Dd, s * 8 + g * 4);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) Operand<float>::mma(W1l[(s * MB + mb) * 64 + lane], x, acc1[mb]);
-    }
-    const int64_t left = a.n_rows - row0;
-    const int n_valid = left < 32 ? (int)left : 32;
-    er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(wt + stride < t_end ? wt + stride : wt));
-    asm volatile("" : "+v"(er_next.op), "+v"(er_next.e0), "+v"(er_next.e1));   // arrived before the first store
-    if constexpr (SAVE) save_hidden_tile<T, H, BIG>(a, acc1, wt, row0, n_valid, lane, stage);
+    for (int sl = 0; sl < NSX; ++sl)
+      if (sl < a.nslabx) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) Operand<float>::mma(W1l[(sl * MB + mb) * 64 + lane], xs[sl], acc1[mb]);
+      }
+    // ---------------- the next tile's requests (its row data arrived a tile ago)
+    er = er_next;
+    request(er);
+    er_next = load_embed_row(a.node_op, a.in_ptr, a.node_dense, a.Dd, tile_row(next_tile(next_tile(wt))));
     T *out = (T *)a.out;
     if constexpr (BIG) {
-      // relu(z1) as operand fragments first, then the output feature blocks in two halves, each
-      // leaving through the staging buffer before the other is formed
+      // relu(z1) as operand fragments first (they are also what is kept of it), then the output
+      // feature blocks in two halves, each leaving through the staging buffer before the other
+      // is formed. The first half's products run under the requests' round trip; nothing is
+      // stored before they have arrived.
+      constexpr int HB = MB / 2;
+      [[maybe_unused]] uint16_t zbits[MB];
+      if constexpr (SAVE) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) zbits[mb] = lane_mask_bits(acc1[mb]);
+      }
       vec zf[NC2];
 #pragma unroll
       for (int c = 0; c < NC2; ++c) zf[c] = relu_operand<T>(acc1[c / QB], c % QB);
 #pragma unroll
       for (int hb = 0; hb < 2; ++hb) {
-        constexpr int HB = MB / 2;
         f32x16 acc2[HB];
         layer2_half_lds<T, H>(zf, W2l, b2l, lane, g, hb * HB, acc2);
+        if (hb == 0) {
+          arrived();
+          if constexpr (SAVE) {
+            int lv = lane;              // (opaque: the address is formed here, not kept in registers across tiles)
+            asm volatile("" : "+v"(lv));
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) a.z1mask[((size_t)wt * MB + mb) * 64 + lv] = zbits[mb];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+              store_block_fragments_via_lds<H>((T *)a.z1, row0, n_valid, mb, lv, zf[2 * mb], zf[2 * mb + 1], stage);
+          }
+        }
+        int lv = lane;                  // (opaque, as above)
+        asm volatile("" : "+v"(lv));
         if constexpr (SAVE) {
-          int lv = lane;                // (opaque: the address is formed here, not kept in registers across tiles)
-          asm volatile("" : "+v"(lv));
 #pragma unroll
           for (int i = 0; i < HB; ++i) a.ymask[((size_t)wt * MB + hb * HB + i) * 64 + lv] = lane_mask_bits(acc2[i]);
         }
@@ -481,10 +523,12 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
         for (int i = 0; i < HB; ++i) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc2[i][r] = relu_f32(acc2[i][r]);
-          store_block_via_lds<T, H>(out, row0, n_valid, hb * HB + i, lane, acc2[i], stage);
+          store_block_via_lds<T, H>(out, row0, n_valid, hb * HB + i, lv, acc2[i], stage);
         }
       }
     } else {
+      arrived();                                             // before the first store (as above)
+      if constexpr (SAVE) save_hidden_tile<T, H, false>(a, acc1, wt, row0, n_valid, lane, stage);
       f32x16 acc2[MB];
       layer2_lds<T, H>(acc1, W2l, b2l, lane, g, acc2);
       if constexpr (SAVE) save_output_mask<H>(a, acc2, wt, lane);
@@ -492,6 +536,5 @@ __global__ __launch_bounds__(64 * NW) void embedp_kernel(const Mlp2Args a) {
         return row0 + r < a.n_rows ? out + (size_t)(row0 + r) * H : nullptr;
       });
     }
-    zero_source_rows<T, H>(a, row0, n_valid, er.e0 == er.e1, lane);
   }
 }

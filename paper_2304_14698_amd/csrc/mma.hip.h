@@ -267,6 +267,31 @@ __device__ __forceinline__ void store_block_via_lds(TO *base, int64_t row0, int 
   wave_lds_fence();
 }
 
+// The same for a block already held as two bf16 operand fragments (relu_operand of accumulator
+// registers 0..7 and 8..15: features 4 g + {0..3} + 8 k, k = 0..3, of the lane's row).
+template <int H>
+__device__ __forceinline__ void store_block_fragments_via_lds(bf16_t *base, int64_t row0, int n_valid, int fb, int lane,
+                                                              const bf16x8 &f0, const bf16x8 &f1, char *stage) {
+  using S = BlockStage<bf16_t>;
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const int l32 = lane & 31, g = lane >> 5;
+  char *wp = stage + l32 * S::RS + 4 * g * 2;
+  const u32x4 z0 = __builtin_bit_cast(u32x4, f0), z1 = __builtin_bit_cast(u32x4, f1);
+  *(u32x2 *)(wp) = u32x2{z0[0], z0[1]};
+  *(u32x2 *)(wp + 16) = u32x2{z0[2], z0[3]};
+  *(u32x2 *)(wp + 32) = u32x2{z1[0], z1[1]};
+  *(u32x2 *)(wp + 48) = u32x2{z1[2], z1[3]};
+  wave_lds_fence();
+#pragma unroll
+  for (int k = 0; k < 32 / S::RPI; ++k) {
+    const int r = k * S::RPI + lane / S::LPR;
+    const f32x4 v = *(const f32x4 *)(stage + r * S::RS + (lane % S::LPR) * 16);
+    if (r < n_valid)
+      *(f32x4 *)((char *)(base + (size_t)(row0 + r) * H + 32 * fb) + (lane % S::LPR) * 16) = v;
+  }
+  wave_lds_fence();
+}
+
 // Same staging, but row r of the tile goes to row dsel (this lane's value for its own row l % 32;
 // negative = the row is not stored): the rows of a tile scattered to per-row destinations.
 template <typename TO, int H>

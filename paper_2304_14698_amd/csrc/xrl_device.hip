@@ -608,7 +608,7 @@ inline bool mlp2p_applies(const xrl_ctx *c, int kind, const Mlp2Args &a) {
   if (a.n_rows < c->p_min_rows) return false;
   if (kind == KIND_EMBED) {
     const int pieces = 4 * 64 * embedp_waves(H);             // see embedp_kernel
-    return a.nslabx * (H / 32) * 64 <= pieces && (H > 128 || a.Tn * (H / 4) <= pieces) &&
+    return a.nslabx <= 2 && a.nslabx * (H / 32) * 64 <= pieces && (H > 128 || a.Tn * (H / 4) <= pieces) &&
            embedp_lds_bytes(H, a.nslabx, a.Tn) <= (size_t)c->max_lds;
   }
   if (H > 128) return false;

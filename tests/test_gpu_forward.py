@@ -395,6 +395,23 @@ def test_paper_feature_dimensions(xrl, hidden, precision):
     run_case(xrl, model, state, weights_for(model))
 
 
+@pytest.mark.parametrize("hidden,precision,d_edge,n_dense", [(128, "bf16", 4, 3), (256, "bf16", 8, 5), (128, "bf16", 12, 9),
+                                                             (256, "bf16", 16, 7), (64, "fp32", 12, 9)])
+def test_other_attribute_widths(xrl, hidden, precision, d_edge, n_dense):
+    """Attribute widths other than the synthetic configurations': a dense node attribute width that
+    is no multiple of 4 (the node-update kernel reads those columns one by one), and edge + dense
+    attributes of more than 16 columns, which is more than the persistent node-update kernel takes
+    (the library then runs the streaming one). Config-2-shaped state, large enough for the
+    persistent kernels."""
+    model, state = synth.make_config(2, n_cand=16)
+    model.update(hidden=hidden, precision=precision, rounds=2, d_edge=d_edge, n_node_dense=n_dense)
+    rng = np.random.Generator(np.random.PCG64(77))
+    E, N = len(state["edge_src"]), len(state["node_op"])
+    state = dict(state, node_dense=rng.standard_normal((N, n_dense)).astype(np.float32),
+                 edge_feat=(0.5 * rng.standard_normal((E, d_edge))).astype(np.float32))
+    run_case(xrl, model, state, weights_for(model))
+
+
 def paper_feature_state(xrl, model, state, seed=31):
     """`state` with the state description the paper prints (Section 3.3.2): operator type one-hot
     only, edge attribute = tensor shape over M = 4096 from the library's featuriser, zero global
