@@ -29,20 +29,20 @@ PEAK_HBM_GBS = 8000.0
 # hash covers the files the kernel is built from (comments and blank space apart); otherwise null.
 TRAFFIC = {
     # configuration 2 (profiles/forward_config2_bf16_hbm_traffic.md): persistent forward kernels, weights in LDS
-    (2, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="84159bc71519750d",
-                              bytes_per_launch=(11145.7 * 2.000 + 11599.5 * 1.000) * 1024),
-    (2, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="84159bc71519750d",
-                              bytes_per_launch=(18659.3 * 2.000 + 18218.2 * 1.000) * 1024),
+    (2, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="c1095d7066032095",
+                              bytes_per_launch=(11154.7 * 2.000 + 11599.5 * 1.000) * 1024),
+    (2, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2p.hip.h"), sha256_16="c1095d7066032095",
+                              bytes_per_launch=(15508.5 * 2.000 + 18218.2 * 1.000) * 1024),
     # configuration 4 (profiles/forward_config4_bf16_kernel_stats_and_traffic.md): register-stationary forward kernels
-    (4, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="22272a55474e8791",
-                              bytes_per_launch=(89445.1 * 2.000 + 70572.0 * 1.000) * 1024),
-    (4, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="22272a55474e8791",
-                              bytes_per_launch=(164022.0 * 2.000 + 162434.5 * 1.000) * 1024),
+    (4, "bf16", "edge"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="b61a512bcdbfb016",
+                              bytes_per_launch=(89442.7 * 2.000 + 70572.0 * 1.000) * 1024),
+    (4, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="b61a512bcdbfb016",
+                              bytes_per_launch=(118742.4 * 2.000 + 162434.5 * 1.000) * 1024),
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
-    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
-                                  bytes_per_launch=(4106514.1 * 2.000 + 31949759.8 * 1.000) * 1024),
-    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="0830d95b7a432567",
-                                  bytes_per_launch=(3546471.3 * 2.000 + 31018993.3 * 1.000) * 1024),
+    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
+                                  bytes_per_launch=(4109032.0 * 2.000 + 31960335.6 * 1.000) * 1024),
+    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
+                                  bytes_per_launch=(3546723.2 * 2.000 + 31028175.1 * 1.000) * 1024),
 }
 
 
@@ -266,7 +266,8 @@ def main():
         "edge": dict(kernel="edge MLP + per-receiver sum (one launch per round)",
                      flops=2.0 * E * H * (3 * H + De),
                      bytes=NH + E * De * 4 + idx_e + n_recv * H * b + zk * (EH + 2 * mask_e)),
-        "node": dict(kernel="node MLP (one launch per round)", flops=2.0 * N * H * 3 * H, bytes=(3 + zk) * NH + zk * 2 * mask_n),
+        "node": dict(kernel="node MLP (one launch per round)", flops=2.0 * N * H * 3 * H,
+                     bytes=(2 + zk) * NH + n_recv * H * b + 4 * N + zk * 2 * mask_n),   # received sums: nodes with in-edges only
         "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", flops=0.0,
                      bytes=NH + 4 * (G + 1) + G * H * 4),
         "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", flops=0.0,
@@ -284,7 +285,7 @@ def main():
             "wgrad_edge": dict(kernel="weight gradients of one edge MLP, both layers",
                                flops=2.0 * E * H * (3 * H + De + 2), bytes=NH + 4 * EH + E * De * 4 + 8 * E),
             "wgrad_node": dict(kernel="weight gradients of one node MLP, both layers",
-                               flops=2.0 * N * H * (3 * H + 2), bytes=5 * NH),
+                               flops=2.0 * N * H * (3 * H + 2), bytes=4 * NH + n_recv * H * b + 4 * N),
             "wgrad_embed": dict(kernel="weight gradients of the embed MLP, both layers",
                                 flops=2.0 * N * H * (De + Tn + Dd + H + 2), bytes=3 * NH + E * De * 4 + N * (8 + 4 * Dd)),
         })
