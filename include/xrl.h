@@ -301,8 +301,8 @@ int xrl_segment_sum(xrl_ctx *ctx, const float *d_values, const int32_t *d_ptr, i
 /* Copies one saved activation of the last xrl_encode(save_for_backward=1) into d_out as fp32:
  * what = "a0" [N, d_edge] (sum of incoming edge attrs), "h" [N, hidden] (node states after the
  * node-update layer for round = 0, after message-passing round r for round = r), "agg" [N,
- * hidden] (received sums of round r >= 1 as the node MLP reads them: rows of receivers without
- * in-edges hold the zeros the node-update kernel wrote there), "pool"
+ * hidden] (received sums of round r >= 1 as the node MLP reads them: zeros for nodes without
+ * in-edges), "pool"
  * [G, hidden] (per-graph sum or mean). */
 int xrl_get_activation(xrl_ctx *ctx, const xrl_batch *b, const char *what, int32_t round,
                        float *d_out);
