@@ -1090,10 +1090,20 @@ __global__ void embed_input_rows_kernel(const float *edge_feat, const int32_t *i
 #pragma unroll
   for (int j = 0; j < 8; ++j) v[j] = 0.f;
   if (k0 < De) {
-    for (int e = in_ptr[n]; e < in_ptr[n + 1]; ++e)
+    // (De is a multiple of 4 and k0 of 8: columns k0 .. k0+3 are attributes, k0+4 .. k0+7 all or none)
+    const bool two = k0 + 8 <= De;
+    const int e1 = in_ptr[n + 1];
+    for (int e = in_ptr[n]; e < e1; ++e) {
+      const float *p = edge_feat + (size_t)e * De + k0;
+      const f32x4 lo = *(const f32x4 *)p;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (k0 + j < De) v[j] += edge_feat[(size_t)e * De + k0 + j];
+      for (int j = 0; j < 4; ++j) v[j] += lo[j];
+      if (two) {
+        const f32x4 hi = *(const f32x4 *)(p + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[4 + j] += hi[j];
+      }
+    }
   }
   const int op = node_op[n];
 #pragma unroll
