@@ -40,9 +40,9 @@ TRAFFIC = {
                               bytes_per_launch=(118742.4 * 2.000 + 162434.5 * 1.000) * 1024),
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
     (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
-                                  bytes_per_launch=(4109032.0 * 2.000 + 31960335.6 * 1.000) * 1024),
+                                  bytes_per_launch=(4111135.0 * 2.000 + 31975203.8 * 1.000) * 1024),
     (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
-                                  bytes_per_launch=(3546723.2 * 2.000 + 31028175.1 * 1.000) * 1024),
+                                  bytes_per_launch=(3543741.8 * 2.000 + 31029747.6 * 1.000) * 1024),
 }
 
 
