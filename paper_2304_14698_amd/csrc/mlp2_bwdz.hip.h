@@ -22,11 +22,14 @@
 struct Mlp2BwdzArgs {
   int64_t n_rows, n_blocks;
   const void *W2bt, *W1bt;     // contraction over the weight's columns (see swizzle_chain)
-  const void *dy;              // upstream gradient [N, H] bf16 (EDGE: indexed by receiver)
+  const void *dy;              // upstream gradient [N, H] bf16 (EDGE: indexed by receiver); kernels instantiated
+                               // with GIVEN: dz2 itself, already masked by [y > 0] (then ymask and dz2 are unused)
   const int32_t *dy_index;     // NODE, EMBED, optional: row n reads dy[dy_index[n]] (the gradient of the
                                // per-graph sum, one row per graph, for the layer the readout sums)
   const uint16_t *z1mask;      // [tiles][H / 32][64] mask bits of z1 and of y, kept by the forward (see
   const uint16_t *ymask;       //   Mlp2Args); tiles = the edge tiles (EDGE), else 32 consecutive rows
+  const int32_t *agg_src;      // [N] (NODE) negative for a node without in-edges: its row of dx_b, the gradient
+                               // w.r.t. a received sum that nobody sent, is not stored (nobody reads it)
   const int32_t *in_dst;       // [E] (EDGE)
   const int32_t *tile_ptr;     // [n_tiles + 1] (EDGE)
   int64_t n_tiles;             // (EDGE)
@@ -83,9 +86,12 @@ struct BwdzShape {
 // resident at once, each looping over its share with the next group's mask bits and dy rows
 // requested a product ahead -- measured slower: 11.5 against 9.9 ms for the node MLP of the largest
 // configuration.)
-template <int H, int KIND, bool FOLD>
+// GIVEN (NODE, EMBED): the kernel that produced the upstream gradient has already applied [y > 0]
+// and left the result where the weight gradient reads dz2, so it is neither masked nor stored here.
+template <int H, int KIND, bool FOLD, bool GIVEN = false>
 __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(const Mlp2BwdzArgs a) {
   static_assert(!FOLD || KIND == KIND_EDGE, "only the edge MLP's receiver-side gradients are summed");
+  static_assert(!GIVEN || KIND != KIND_EDGE, "the edge MLP's upstream gradient is gathered per receiver");
   using T = bf16_t;
   using S = BwdzShape<H>;
   using BS = BlockStage<T>;
@@ -132,11 +138,14 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
     fold_rem = valid ? __builtin_ctzll(heads >> (l32 + 1)) : 0;
     fold_dsel = head ? drow : -1;
   }
+  [[maybe_unused]] int recv_dsel = -1;                        // NODE: this lane's row if it has in-edges
+  if constexpr (KIND == KIND_NODE) recv_dsel = (l32 < n_valid && a.agg_src[row] >= 0) ? (int)row : -1;
   // mask bits of y (low half) and z1 (high half) of this lane's row, per 32-feature block
   uint32_t yz[MB];
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) {
-    const uint32_t y = a.ymask[((size_t)wt * MB + nb) * 64 + lane];
+    uint32_t y = 0xffffu;
+    if constexpr (!GIVEN) y = a.ymask[((size_t)wt * MB + nb) * 64 + lane];
     const uint32_t z = a.z1mask[((size_t)wt * MB + nb) * 64 + lane];
     yz[nb] = y | (z << 16);
   }
@@ -178,7 +187,7 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
       for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int j = 0; j < 4; ++j) d[4 * q + j] = (yz[nb] >> (4 * q + j)) & 1u ? (float)dyq[nb][q][j] : 0.f;
-      store_block_via_lds<T, H>((T *)a.dz2, row0, n_valid, nb, lane, d, stage);
+      if constexpr (!GIVEN) store_block_via_lds<T, H>((T *)a.dz2, row0, n_valid, nb, lane, d, stage);
 #pragma unroll
       for (int q = 0; q < QB; ++q) dz2s[nb][q] = acc_slab<T>(d, q);
     }
@@ -246,6 +255,8 @@ __global__ __launch_bounds__((64 * BwdzShape<H>::NW)) void mlp2_bwdz_kernel(cons
           }
         }
         store_block_rows_via_lds<T, H>((T *)a.dx_b, fold_dsel, kb % MB, lane, d, stage);
+      } else if (KIND == KIND_NODE && kb >= MB) {
+        store_block_rows_via_lds<T, H>((T *)a.dx_b, recv_dsel, kb % MB, lane, d, stage);
       } else {
         store_block_via_lds<T, H>((T *)(kb < MB ? a.dx_a : a.dx_b), row0, n_valid, kb % MB, lane, d, stage);
       }

@@ -202,11 +202,16 @@ __global__ __launch_bounds__(256) void edge_tile_fixup(const int32_t *tile_ptr, 
 // order and summed in fp32, so the result is run-to-run identical. One pass over dh instead of
 // one per direction. recv_summed: d_recv is [n_nodes, D], already summed per receiver (rows of nodes
 // without in-edges hold nothing and are not read).
+// masked_out (or nullptr: the sum replaces dh): the sum goes there instead, multiplied by the ReLU
+// mask of the layer that produced h -- ymask, the mask bits a forward kernel kept for its output
+// (see Mlp2Args: [tiles of 32 nodes][D / 32][64 lanes] words; VEC must be 8) -- which is the dz2 the
+// backward through that layer starts from.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, const T *d_send,
                                                                const int32_t *in_ptr, const int32_t *out_ptr,
                                                                const int32_t *out_pos, int64_t n_nodes, int D,
-                                                               T *dh, int recv_summed) {
+                                                               T *dh, int recv_summed, T *masked_out = nullptr,
+                                                               const uint16_t *ymask = nullptr) {
   const int lpr = D / VEC;
   const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n = gt / lpr;
@@ -233,6 +238,20 @@ __global__ __launch_bounds__(256) void node_grad_gather_kernel(const T *d_recv, 
     RowVec<T, VEC>::load(d_send + (size_t)out_pos[k] * D + c, v);
 #pragma unroll
     for (int j = 0; j < VEC; ++j) acc[j] += v[j];
+  }
+  if constexpr (VEC == 8) {
+    if (masked_out) {
+      // features c .. c+3 are accumulator registers 4 (c % 32 / 8) .. +3 of lane n % 32 of the node's
+      // tile and feature block, features c+4 .. c+7 the same registers of lane n % 32 + 32
+      const size_t w = ((size_t)(n / 32) * (D / 32) + c / 32) * 64 + (size_t)(n % 32);
+      const unsigned lo = ymask[w] >> (4 * (c % 32 / 8)), hi = ymask[w + 32] >> (4 * (c % 32 / 8));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc[j] = (lo >> j) & 1u ? acc[j] : 0.f;
+        acc[4 + j] = (hi >> j) & 1u ? acc[4 + j] : 0.f;
+      }
+      o = masked_out + (size_t)n * D + c;
+    }
   }
 #pragma unroll
   for (int q = 0; q < VEC / 4; ++q) store4<T>(o + 4 * q, acc + 4 * q);

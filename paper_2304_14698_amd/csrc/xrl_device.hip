@@ -790,10 +790,10 @@ int launch_mlp2_bwd(xrl_ctx *c, int kind, Mlp2BwdArgs &a) {
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
 
-template <int H, int KIND, bool FOLD>
+template <int H, int KIND, bool FOLD, bool GIVEN = false>
 int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
   using S = BwdzShape<H>;
-  auto kern = mlp2_bwdz_kernel<H, KIND, FOLD>;
+  auto kern = mlp2_bwdz_kernel<H, KIND, FOLD, GIVEN>;
   static bool attr_set = false;          // one attribute per kernel instantiation
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS));
@@ -808,19 +808,21 @@ int launch_mlp2_bwdz_k(xrl_ctx *c, Mlp2BwdzArgs &a) {
 }
 
 template <int H>
-int launch_mlp2_bwdz_h(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold) {
+int launch_mlp2_bwdz_h(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold, bool given) {
   if (a.n_rows <= 0) return XRL_OK;
-  if (kind == KIND_EMBED) return launch_mlp2_bwdz_k<H, KIND_EMBED, false>(c, a);
+  if (kind == KIND_EMBED)
+    return given ? launch_mlp2_bwdz_k<H, KIND_EMBED, false, true>(c, a) : launch_mlp2_bwdz_k<H, KIND_EMBED, false>(c, a);
   if (kind == KIND_EDGE) return fold ? launch_mlp2_bwdz_k<H, KIND_EDGE, true>(c, a) : launch_mlp2_bwdz_k<H, KIND_EDGE, false>(c, a);
-  return launch_mlp2_bwdz_k<H, KIND_NODE, false>(c, a);
+  return given ? launch_mlp2_bwdz_k<H, KIND_NODE, false, true>(c, a) : launch_mlp2_bwdz_k<H, KIND_NODE, false>(c, a);
 }
 
-// fold (EDGE): dx_b receives the gradients w.r.t. h_receiver summed per receiver, [N, H]
-int launch_mlp2_bwdz(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold) {
+// fold (EDGE): dx_b receives the gradients w.r.t. h_receiver summed per receiver, [N, H].
+// given (NODE, EMBED): a.dy is dz2 already (the gradient gather applied the layer's output mask)
+int launch_mlp2_bwdz(xrl_ctx *c, int kind, Mlp2BwdzArgs &a, bool fold, bool given) {
   switch (c->m.hidden) {
-    case 64: return launch_mlp2_bwdz_h<64>(c, kind, a, fold);
-    case 128: return launch_mlp2_bwdz_h<128>(c, kind, a, fold);
-    case 256: return launch_mlp2_bwdz_h<256>(c, kind, a, fold);
+    case 64: return launch_mlp2_bwdz_h<64>(c, kind, a, fold, given);
+    case 128: return launch_mlp2_bwdz_h<128>(c, kind, a, fold, given);
+    case 256: return launch_mlp2_bwdz_h<256>(c, kind, a, fold, given);
   }
   return fail(XRL_ERR_UNSUPPORTED, "hidden = %d", c->m.hidden);
 }
@@ -1214,14 +1216,18 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
   memset(&za, 0, sizeof(za));
   za.in_dst = d.in_dst; za.dz1 = dz1; za.dz2 = dz2;
   za.tile_ptr = d.tile_ptr; za.n_tiles = (int64_t)b->tile_ptr.size() - 1;
+  bool dz2_given = false;
   auto mlp_bwd = [&](int kind, const EncMlp &e, const uint16_t *z1mask, const uint16_t *ymask) -> int {
     if constexpr (sizeof(T) == 2) {
       if (kept) {
         za.n_rows = a.n_rows; za.W2bt = e.W2bt; za.W1bt = e.W1bt; za.dy = a.dy;
-        za.z1mask = z1mask; za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b;
+        za.z1mask = z1mask; za.ymask = ymask; za.dx_a = a.dx_a; za.dx_b = a.dx_b; za.agg_src = d.agg_src;
         za.dy_index = (dy_by_graph && kind != KIND_EDGE) ? d.node_graph : nullptr;
         dy_by_graph = false;
-        return launch_mlp2_bwdz(c, kind, za, fold);
+        const bool given = dz2_given && kind != KIND_EDGE;   // (the gather of the round above left dz2 in place)
+        if (given) za.dy = dz2;
+        if (kind != KIND_EDGE) dz2_given = false;
+        return launch_mlp2_bwdz(c, kind, za, fold, given);
       }
     }
     return launch_mlp2_bwd<T>(c, kind, a);
@@ -1290,8 +1296,17 @@ int encode_backward_impl(xrl_ctx *c, const xrl_batch *b, const float *d_demb, fl
     if (E > 0) {
       Timed t(c, TK_GRAD_GATHER);
       const int64_t threads = N * (H / PV);
+      // from the kept forward: the sum leaves multiplied by the output mask of the layer that
+      // produced h[r] (the node MLP of the round below, or the node-update layer), as that layer's
+      // dz2 -- its backward kernel then neither reads the mask nor stores dz2
+      T *masked_out = nullptr;
+      const uint16_t *mask = nullptr;
+      if constexpr (sizeof(T) == 2) {
+        if (kept) { masked_out = dz2; mask = r > 0 ? c->ym_node[r - 1] : c->ym_embed; }
+      }
       node_grad_gather_kernel<T, PV><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream>>>(
-          ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB, fold ? 1 : 0);
+          ddst, dsrc, d.in_ptr, d.out_ptr, d.out_pos, N, H, dhB, fold ? 1 : 0, masked_out, mask);
+      dz2_given = masked_out != nullptr;
     }
     std::swap(dhA, dhB);
   }
