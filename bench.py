@@ -39,10 +39,12 @@ TRAFFIC = {
     (4, "bf16", "node"): dict(sources=("mma.hip.h", "mlp2.hip.h", "mlp2r.hip.h"), sha256_16="b61a512bcdbfb016",
                               bytes_per_launch=(118742.4 * 2.000 + 162434.5 * 1.000) * 1024),
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
-    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
-                                  bytes_per_launch=(4111135.0 * 2.000 + 31975203.8 * 1.000) * 1024),
-    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="5f3ac0c774c9e8b4",
-                                  bytes_per_launch=(3543741.8 * 2.000 + 31029747.6 * 1.000) * 1024),
+    (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="4137d3e1b408b425",
+                                  # mean of the five launches: four with dz2 given by the gradient gather, the topmost round's
+                                  bytes_per_launch=(0.8 * (4635061.5 * 2.000 + 20977725.5 * 1.000) +
+                                                    0.2 * (958278.3 * 2.000 + 29068182.9 * 1.000)) * 1024),
+    (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="4137d3e1b408b425",
+                                  bytes_per_launch=(3541507.1 * 2.000 + 31031205.9 * 1.000) * 1024),
 }
 
 
@@ -271,7 +273,7 @@ def main():
         "pool": dict(kernel="per-graph readout sum (fused with the readout MLP)", flops=0.0,
                      bytes=NH + 4 * (G + 1) + G * H * 4),
         "grad_gather": dict(kernel="per-node sum of the per-edge gradients (receiver and sender side)", flops=0.0,
-                            bytes=(EH + n_recv * H * b if kept else 2 * EH) + 2 * NH + 4 * (2 * N + E)),
+                            bytes=(EH + n_recv * H * b + mask_n if kept else 2 * EH) + 2 * NH + 4 * (2 * N + E)),
     }
     if kept:
         work.update({
@@ -279,9 +281,13 @@ def main():
                              flops=2.0 * E * H * 3 * H,
                              bytes=n_recv * H * b + 2 * mask_e + 4 * (E + n_tiles) + 3 * EH + n_recv * H * b),
             "bwd_node": dict(kernel="backward through the node MLP from the kept forward (one launch per round)",
-                             flops=2.0 * N * H * 3 * H, bytes=5 * NH + 2 * mask_n),
+                             # dz2 arrives masked from the gradient gather and is read (NH) instead of stored; the
+                             # topmost round reads the per-graph table and stores dz2 itself (NH either way);
+                             # dz1, dh, and the dagg rows of the nodes with in-edges are written
+                             flops=2.0 * N * H * 3 * H,
+                             bytes=3 * NH + n_recv * H * b + mask_n * (1 + 1 / max(R, 1)) + 4 * N),
             "bwd_embed": dict(kernel="backward through the embed MLP from the kept forward", flops=2.0 * N * H * H,
-                              bytes=3 * NH + 2 * mask_n),
+                              bytes=2 * NH + mask_n),
             "wgrad_edge": dict(kernel="weight gradients of one edge MLP, both layers",
                                flops=2.0 * E * H * (3 * H + De + 2), bytes=NH + 4 * EH + E * De * 4 + 8 * E),
             "wgrad_node": dict(kernel="weight gradients of one node MLP, both layers",
