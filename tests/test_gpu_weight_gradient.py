@@ -44,9 +44,11 @@ def run(xrl, model, state, kinds=("plain", "edge", "node"), n_plain=None):
     N, E = batch.N, batch.E
     h64, h = operand(rng, (N, H), prec)
     agg64, agg = operand(rng, (N, H), prec)
-    no_in = np.diff(v["in_ptr"]) == 0                # the forward leaves these rows of the sums at zero
+    # the sums' rows of nodes without in-edges count as zero and are not read (the forward never
+    # writes them): poisoned on the device
+    no_in = np.diff(v["in_ptr"]) == 0
     agg64[no_in] = 0.0
-    agg[torch.from_numpy(no_in).cuda()] = 0
+    agg[torch.from_numpy(no_in).cuda()] = float("nan")
     feat = v["edge_feat"].astype(np.float32)
     if prec == "bf16":
         feat = torch.from_numpy(feat).to(torch.bfloat16).to(torch.float32).numpy()   # as the kernel rounds them
