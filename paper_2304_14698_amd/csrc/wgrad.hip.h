@@ -194,14 +194,15 @@ __device__ __forceinline__ bf16x8 lds_tr_operand(const char *p, int row_stride) 
 // the middle of the loop. TAIL = the tile holds columns past the gathered / direct ones (edge
 // attributes, the all-ones bias column, padding); such tiles are whole for the EDGE and NODE
 // kinds (2H is a multiple of 128), PLAIN uses the one formulation for all its tiles.
-template <int H, int KIND, bool TAIL, int TA>
+template <int H, int KIND, bool TAIL, int TA, int RS>
 __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t r_begin, int64_t r_end,
-                                           char (*Xs)[32 * (TA * 2 + 64)], char (*Zs)[32 * (H * 2 + 64)],
+                                           char (*Xs)[RS * (TA * 2 + 64)], char (*Zs)[RS * (H * 2 + 64)],
                                            f32x16 (&acc)[2][H / 64 > 0 ? H / 64 : 1], bool do_bias,
                                            float (&bsum)[8]) {
   using T = bf16_t;
   using vec = bf16x8;
-  constexpr int RS = 32, NT = 2 * TA;                      // TA / 64 x 2 waves
+  constexpr int NT = 2 * TA;                               // TA / 64 x 2 waves
+  constexpr int XV = RS / 16;                              // X vectors per thread per stage
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;         // LDS row strides, bytes
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;              // 32-column blocks of dZ per wave
   constexpr int ZV = RS * (H / 8) / NT;                    // dZ vectors per thread per stage
@@ -210,7 +211,7 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   const int wa = wave % (TA / 64), wb = wave / (TA / 64);
   const int n_stage = (int)((r_end - r_begin + RS - 1) / RS);
 
-  // ---- this thread's two X vectors per stage: rows xr, xr + 16 of the stage, columns xc .. xc+7
+  // ---- this thread's XV X vectors per stage: rows xr, xr + 16, .. of the stage, columns xc .. xc+7
   const int xr = tid / (TA / 8), xcl = tid % (TA / 8), xc = ka0 + 8 * xcl;
   const bool second = xc >= H;                             // EDGE: receiver's state; NODE: aggregate
   [[maybe_unused]] const int32_t *idx_arr = second ? a.in_dst : a.in_src;
@@ -225,9 +226,9 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   };
   auto live = [&](int st, int c) { return r_begin + (int64_t)st * RS + xr + 16 * c < r_end; };
   // row indices (EDGE) of stage st, which may be past the end
-  auto load_idx = [&](int st, int (&ix)[2]) {
+  auto load_idx = [&](int st, int (&ix)[XV]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < XV; ++c) {
       ix[c] = 0;
       if constexpr (!TAIL && KIND == WG_EDGE) ix[c] = idx_arr[row_of(st, c)];
       if constexpr (!TAIL && KIND == WG_NODE) {
@@ -235,9 +236,9 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
       }
     }
   };
-  auto load_x = [&](int st, const int (&ix)[2], vec (&x)[2]) {
+  auto load_x = [&](int st, const int (&ix)[XV], vec (&x)[XV]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < XV; ++c) {
       const int64_t row = row_of(st, c);
       const bool on = live(st, c);
       if constexpr (KIND == WG_PLAIN) {
@@ -282,9 +283,9 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
       z[c] = on ? v : Operand<T>::zero();
     }
   };
-  auto commit = [&](int buf, const vec (&x)[2], const vec (&z)[ZV]) {
+  auto commit = [&](int buf, const vec (&x)[XV], const vec (&z)[ZV]) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) *(vec *)(Xs[buf] + (xr + 16 * c) * XS + xcl * 16) = x[c];
+    for (int c = 0; c < XV; ++c) *(vec *)(Xs[buf] + (xr + 16 * c) * XS + xcl * 16) = x[c];
 #pragma unroll
     for (int c = 0; c < ZV; ++c) {
       const int vi = tid + NT * c, rl = vi / (H / 8), cc = vi % (H / 8);
@@ -300,8 +301,8 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
 #pragma unroll
       for (int j = 0; j < 8; ++j) bsum[j] += (float)z[c][j];
   };
-  int ix0[2], ix1[2];
-  vec xn[2], zn[ZV];
+  int ix0[XV], ix1[XV];
+  vec xn[XV], zn[ZV];
   load_idx(0, ix0);
   load_idx(1, ix1);
   load_x(0, ix0, xn);
@@ -314,7 +315,7 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
   const int xoff = (8 * g + L / 4) * XS + (32 * (2 * wa) + 16 * half + 4 * (L % 4)) * 2;
   const int zoff = (8 * g + L / 4) * ZS + (32 * (wb * NB) + 16 * half + 4 * (L % 4)) * 2;
   for (int st = 0; st < n_stage; ++st) {
-    int ix2[2];
+    int ix2[XV];
     load_idx(st + 2 < n_stage ? st + 2 : st, ix2);
     const int sn = st + 1 < n_stage ? st + 1 : st;         // (the last iteration re-reads its own stage)
     load_x(sn, ix1, xn);
@@ -335,7 +336,8 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
     commit((st + 1) & 1, xn, zn);
     if (do_bias && st + 1 < n_stage) add_bias(zn);
     __syncthreads();
-    ix1[0] = ix2[0]; ix1[1] = ix2[1];
+#pragma unroll
+    for (int c = 0; c < XV; ++c) ix1[c] = ix2[c];
   }
 }
 
@@ -345,10 +347,11 @@ __device__ __forceinline__ void wgrad2_run(const WgradArgs &a, int ka0, int64_t 
 // bias_row >= 0: the column sums of dZ are taken on the vector ALU by the first tile's block of
 // every row slice and stored as row bias_row of the slice's partial (then no tile has to hold the
 // all-ones column); KaP = rows per slice of the partial array.
-template <int H, int KIND, int TA>
+// RS = rows per stage, 32 or 64: a stage is what a block has in flight from memory while it
+// multiplies the previous one, and 32 rows are too few to cover the latency with one block per CU.
+template <int H, int KIND, int TA, int RS = 32>
 __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int kt, int ny, int ka_base, int KaP,
                                                         int bias_row) {
-  constexpr int RS = 32;
   constexpr int XS = TA * 2 + 64, ZS = H * 2 + 64;
   constexpr int NB = H / 64 > 0 ? H / 64 : 1;
   static_assert(KIND != WG_EMBED, "the embed layer's input rows are written out first and go through WG_PLAIN");
@@ -375,8 +378,8 @@ __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int k
   const bool do_bias = bias_row >= 0 && kq == 0;
   float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (r_end > r_begin) {
-    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
-    else wgrad2_run<H, KIND, false, TA>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
+    if (KIND != WG_PLAIN && ka0 >= 2 * H) wgrad2_run<H, KIND, true, TA, RS>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
+    else wgrad2_run<H, KIND, false, TA, RS>(a, ka0, r_begin, r_end, Xs, Zs, acc, do_bias, bsum);
   }
   if (do_bias) {
     // thread t holds columns 8 (t % (H / 8)) ..; the 2 TA / (H / 8) threads of a column chunk are
@@ -404,8 +407,8 @@ __global__ __launch_bounds__(2 * TA) void wgrad2_kernel(const WgradArgs a, int k
         out[(size_t)(32 * m + acc_row(r, g)) * H + 32 * i] = acc[m][i][r];
 }
 
-template <int H, int TA>
-constexpr size_t wgrad2_lds_bytes() { return 2 * 32 * (size_t)(TA * 2 + 64) + 2 * 32 * (size_t)(H * 2 + 64); }
+template <int H, int TA, int RS = 32>
+constexpr size_t wgrad2_lds_bytes() { return 2 * RS * (size_t)(TA * 2 + 64) + 2 * RS * (size_t)(H * 2 + 64); }
 
 // dW[k, f] += sum over chunks of partial[chunk, k, f] for k < Ka; db[f] += row Ka (db may be null:
 // a product without a bias row). A block handles

@@ -849,8 +849,9 @@ inline size_t wgrad_partial_floats(int64_t n_rows, int Ka, int H, int n_cu) {
 
 template <int H, int KIND, int TA>
 int launch_wgrad2(xrl_ctx *c, const WgradArgs &a, const Wgrad2Plan &p, int ka_base, int KaP, int bias_row) {
-  constexpr size_t lds = wgrad2_lds_bytes<H, TA>();
-  auto kern = wgrad2_kernel<H, KIND, TA>;
+  constexpr int RS = TA == 256 ? 64 : 32;      // the wide tiles run one block per CU: 64 rows in flight per stage
+  constexpr size_t lds = wgrad2_lds_bytes<H, TA, RS>();
+  auto kern = wgrad2_kernel<H, KIND, TA, RS>;
   static bool attr_set = false;          // one attribute per kernel instantiation
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
