@@ -41,10 +41,10 @@ TRAFFIC = {
     # configuration 5 (profiles/step_config5_bf16_hbm_traffic.md): backward through the node / edge MLP
     (5, "bf16", "bwd_node"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="4137d3e1b408b425",
                                   # mean of the five launches: four with dz2 given by the gradient gather, the topmost round's
-                                  bytes_per_launch=(0.8 * (4635061.5 * 2.000 + 20977725.5 * 1.000) +
-                                                    0.2 * (958278.3 * 2.000 + 29068182.9 * 1.000)) * 1024),
+                                  bytes_per_launch=(0.8 * (4635006.5 * 2.000 + 20977475.7 * 1.000) +
+                                                    0.2 * (947049.9 * 2.000 + 29040546.5 * 1.000)) * 1024),
     (5, "bf16", "bwd_edge"): dict(sources=("mma.hip.h", "mlp2_bwd.hip.h", "mlp2_bwdz.hip.h"), sha256_16="4137d3e1b408b425",
-                                  bytes_per_launch=(3541507.1 * 2.000 + 31031205.9 * 1.000) * 1024),
+                                  bytes_per_launch=(3545704.0 * 2.000 + 31035381.9 * 1.000) * 1024),
 }
 
 

@@ -199,7 +199,7 @@ int xrl_batch_free(xrl_batch *b);   /* frees host and device copies; NULL is acc
  * Environment, read here: XRL_PERSISTENT_MIN_ROWS = row count from which the persistent MLP
  * kernels replace the streaming one (default 8192; 0 = always; results agree within rounding);
  * XRL_WGRAD_WIDE_MIN_ROWS = row count from which the weight-gradient kernel uses 256-column
- * tiles (default 2^20; same sums in a different, equally fixed order);
+ * tiles (default 2^18 at hidden = 256, else 2^20; same sums in a different, equally fixed order);
  * XRL_RESIDENT_MAX_GRAPHS (default 256; 0 = never) and XRL_RESIDENT_MAX_TILES (default 4) =
  * largest batch, in graphs and in 32-row tiles of nodes or edges per graph, that xrl_encode runs
  * as one launch with a block per graph (message-passing rounds of the MLP kind, rows of at most

@@ -1624,6 +1624,8 @@ int xrl_create(const xrl_model_desc *model, const float *weights_host, void *hip
   // default is where they start to win; 0 = always, a huge value = never)
   c->p_min_rows = 8192;
   if (const char *e = getenv("XRL_PERSISTENT_MIN_ROWS")) c->p_min_rows = atoll(e);
+  // (measured: at H = 256 the 256-column tiles win from about 300 k rows on, at H = 128 from 1 M)
+  c->wide_min_rows = model->hidden >= 256 ? (1 << 18) : (1 << 20);
   if (const char *e = getenv("XRL_WGRAD_WIDE_MIN_ROWS")) c->wide_min_rows = atoll(e);
   // Batches the one-launch encoder takes: one block of four waves per graph wins while every
   // phase of a graph is a single pass of its waves (measured: 51-node graphs, 9 to 144 of them,
